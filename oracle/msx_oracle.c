@@ -1,0 +1,314 @@
+/*
+ * CPU oracle for the emulated-rank collective hot path (TEST INFRASTRUCTURE ONLY).
+ *
+ * This file is the slow, single-threaded, obviously-correct statement of what each
+ * collective computes.  It is used only by the tests, by the smoke check and by the
+ * benchmark's CPU-baseline leg; the product library never links, loads or calls it,
+ * and it shares no code, header, table or helper with the HIP implementation.
+ *
+ * Everything here is a plain definition written out:
+ *   - AllReduce / ReduceScatter / AllGather follow the problem statement in the paper's
+ *     "Collective Communications" background section (AllReduce sums the inputs of all
+ *     ranks and every rank gets the result; ReduceScatter sums and hands each rank an
+ *     equal share; AllGather concatenates the shares on every rank).
+ *   - The LL unit follows the MemoryChannel "Protocols" paragraph: a data word and a
+ *     flag travel in one store; a reader accepts the data only when the flag matches.
+ *   - The token dispatch follows the expert-parallel setting the paper evaluates
+ *     (hidden 7168, top-8 of 256 experts); the paper does not define the packing order,
+ *     so the order used here (source rank ascending, then token ascending, one copy per
+ *     distinct destination rank) is this build's reading.
+ *
+ * Readings of points the paper leaves open (reduction order, accumulator width,
+ * rounding) are: fp32 accumulator, ranks added in order 0,1,...,N-1 starting from rank
+ * 0's value, one round-to-nearest-even conversion to bf16 at the end.
+ *
+ * Every function is pinned by tests that do not re-use its own formula (closed forms,
+ * exact integer sums, a library column-sum, permutation identities, brute force).
+ * Performance figures have no pin: the paper prints no number for emulated ranks.
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+
+/* ---------- bf16 <-> fp32 (IEEE binary32 truncated to its top 16 bits) ---------- */
+
+float orc_bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* round-to-nearest, ties-to-even; NaN stays NaN (quiet bit forced, sign kept) */
+uint16_t orc_f32_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t lsb = (u >> 16) & 1u;
+    u += 0x7fffu + lsb;
+    return (uint16_t)(u >> 16);
+}
+
+void orc_bf16_to_f32_buf(const uint16_t *in, float *out, size_t count)
+{
+    for (size_t i = 0; i < count; ++i)
+        out[i] = orc_bf16_to_f32(in[i]);
+}
+
+void orc_f32_to_bf16_buf(const float *in, uint16_t *out, size_t count)
+{
+    for (size_t i = 0; i < count; ++i)
+        out[i] = orc_f32_to_bf16(in[i]);
+}
+
+/* ---------- AllReduce (sum) ---------- */
+
+/* in: [n][count] rank-major.  out: [count] (the value every rank must hold). */
+void orc_allreduce_f32(const float *in, float *out, int n, size_t count)
+{
+    for (size_t i = 0; i < count; ++i) {
+        float acc = in[i];
+        for (int r = 1; r < n; ++r)
+            acc += in[(size_t)r * count + i];
+        out[i] = acc;
+    }
+}
+
+/* exact integer sum of integer-valued fp32 inputs (order-free check for config 1).
+ * returns 0 if every input was an integer of magnitude < 2^31, else 1. */
+int orc_allreduce_f32_as_i64(const float *in, int64_t *out, int n, size_t count)
+{
+    int bad = 0;
+    for (size_t i = 0; i < count; ++i) {
+        int64_t acc = 0;
+        for (int r = 0; r < n; ++r) {
+            float v = in[(size_t)r * count + i];
+            if (!(v > -2147483648.0f && v < 2147483648.0f) || (float)(int64_t)v != v)
+                bad = 1;
+            else
+                acc += (int64_t)v;
+        }
+        out[i] = acc;
+    }
+    return bad;
+}
+
+/* in: [n][count] bf16 bit patterns.  out: [count] bf16.  ref64 (nullable): [count]
+ * the same sum accumulated in double, unrounded. */
+void orc_allreduce_bf16(const uint16_t *in, uint16_t *out, double *ref64, int n, size_t count)
+{
+    for (size_t i = 0; i < count; ++i) {
+        float acc = orc_bf16_to_f32(in[i]);
+        double wide = (double)acc;
+        for (int r = 1; r < n; ++r) {
+            float v = orc_bf16_to_f32(in[(size_t)r * count + i]);
+            acc += v;
+            wide += (double)v;
+        }
+        out[i] = orc_f32_to_bf16(acc);
+        if (ref64)
+            ref64[i] = wide;
+    }
+}
+
+/* AllReduce fused with a residual add, as seen by ONE rank whose residual is res:
+ * out[i] = bf16( (sum over ranks in fp32) + fp32(res[i]) ), a single rounding. */
+void orc_allreduce_residual_bf16(const uint16_t *in, const uint16_t *res, uint16_t *out,
+                                 double *ref64, int n, size_t count)
+{
+    for (size_t i = 0; i < count; ++i) {
+        float acc = orc_bf16_to_f32(in[i]);
+        double wide = (double)acc;
+        for (int r = 1; r < n; ++r) {
+            float v = orc_bf16_to_f32(in[(size_t)r * count + i]);
+            acc += v;
+            wide += (double)v;
+        }
+        float rv = orc_bf16_to_f32(res[i]);
+        acc += rv;
+        wide += (double)rv;
+        out[i] = orc_f32_to_bf16(acc);
+        if (ref64)
+            ref64[i] = wide;
+    }
+}
+
+void orc_allreduce_residual_f32(const float *in, const float *res, float *out, int n, size_t count)
+{
+    for (size_t i = 0; i < count; ++i) {
+        float acc = in[i];
+        for (int r = 1; r < n; ++r)
+            acc += in[(size_t)r * count + i];
+        acc += res[i];
+        out[i] = acc;
+    }
+}
+
+/* ---------- ReduceScatter (sum): rank r receives the sum of everybody's share r ---------- */
+
+/* in: [n][count], count divisible by n.  out: [n][count/n]; row r = rank r's result. */
+void orc_reducescatter_f32(const float *in, float *out, int n, size_t count)
+{
+    size_t c = count / (size_t)n;
+    for (int r = 0; r < n; ++r)
+        for (size_t k = 0; k < c; ++k) {
+            float acc = in[(size_t)r * c + k];
+            for (int j = 1; j < n; ++j)
+                acc += in[(size_t)j * count + (size_t)r * c + k];
+            out[(size_t)r * c + k] = acc;
+        }
+}
+
+void orc_reducescatter_bf16(const uint16_t *in, uint16_t *out, int n, size_t count)
+{
+    size_t c = count / (size_t)n;
+    for (int r = 0; r < n; ++r)
+        for (size_t k = 0; k < c; ++k) {
+            float acc = orc_bf16_to_f32(in[(size_t)r * c + k]);
+            for (int j = 1; j < n; ++j)
+                acc += orc_bf16_to_f32(in[(size_t)j * count + (size_t)r * c + k]);
+            out[(size_t)r * c + k] = orc_f32_to_bf16(acc);
+        }
+}
+
+/* ---------- AllGather / equal AllToAll: pure byte movement ---------- */
+
+/* in: [n][cbytes] (rank j's contribution).  out: [n][n*cbytes]; every row is the
+ * concatenation of the contributions in rank order. */
+void orc_allgather(const uint8_t *in, uint8_t *out, int n, size_t cbytes)
+{
+    for (int r = 0; r < n; ++r)
+        for (int j = 0; j < n; ++j)
+            for (size_t b = 0; b < cbytes; ++b)
+                out[((size_t)r * n + j) * cbytes + b] = in[(size_t)j * cbytes + b];
+}
+
+/* in: [n][n*cbytes]; slot d of row s is what s sends to d.  out: [n][n*cbytes];
+ * slot s of row d is what d received from s. */
+void orc_alltoall(const uint8_t *in, uint8_t *out, int n, size_t cbytes)
+{
+    for (int d = 0; d < n; ++d)
+        for (int s = 0; s < n; ++s)
+            for (size_t b = 0; b < cbytes; ++b)
+                out[((size_t)d * n + s) * cbytes + b] = in[((size_t)s * n + d) * cbytes + b];
+}
+
+/* ---------- LL units ---------- */
+
+/* one 8-byte unit: data word in the low half, flag in the high half (little endian:
+ * bytes 0-3 data, bytes 4-7 flag, i.e. the flag is the last element of the unit). */
+uint64_t orc_ll_encode(uint32_t data, uint32_t flag)
+{
+    return ((uint64_t)flag << 32) | (uint64_t)data;
+}
+
+/* returns 1 and stores the data word if the unit carries the expected flag, else 0 */
+int orc_ll_decode(uint64_t unit, uint32_t expect, uint32_t *data)
+{
+    if ((uint32_t)(unit >> 32) != expect)
+        return 0;
+    *data = (uint32_t)unit;
+    return 1;
+}
+
+/* Encode nbytes of payload into 16-byte packets (two units each).  The payload is
+ * taken as little-endian 32-bit words; a final partial word and a missing second word
+ * are padded with zero data.  units must hold 2*ceil(nbytes/8) entries.
+ * Returns the number of units written. */
+size_t orc_ll_encode_buf(const uint8_t *payload, size_t nbytes, uint32_t flag, uint64_t *units)
+{
+    size_t npackets = (nbytes + 7) / 8;
+    for (size_t p = 0; p < npackets; ++p)
+        for (int h = 0; h < 2; ++h) {
+            uint32_t w = 0;
+            for (int b = 0; b < 4; ++b) {
+                size_t pos = p * 8 + (size_t)h * 4 + (size_t)b;
+                if (pos < nbytes)
+                    w |= (uint32_t)payload[pos] << (8 * b);
+            }
+            units[2 * p + (size_t)h] = orc_ll_encode(w, flag);
+        }
+    return 2 * npackets;
+}
+
+/* Decode: returns 1 and fills payload[0..nbytes) iff EVERY unit carries the flag. */
+int orc_ll_decode_buf(const uint64_t *units, size_t nbytes, uint32_t flag, uint8_t *payload)
+{
+    size_t npackets = (nbytes + 7) / 8;
+    for (size_t u = 0; u < 2 * npackets; ++u) {
+        uint32_t w;
+        if (!orc_ll_decode(units[u], flag, &w))
+            return 0;
+        for (int b = 0; b < 4; ++b) {
+            size_t pos = u * 4 + (size_t)b;
+            if (pos < nbytes)
+                payload[pos] = (uint8_t)(w >> (8 * b));
+        }
+    }
+    return 1;
+}
+
+/* ---------- token-routed dispatch ---------- */
+
+/*
+ * tokens   : [n][T][row_bytes]   source rows
+ * topk     : [n][T][K]           expert ids in [0, n_experts); experts are split evenly,
+ *                                expert e lives on rank e / (n_experts / n)
+ * recv     : [n][cap][row_bytes] destination buffers (cap rows each); rows beyond the
+ *                                received count are left untouched
+ * recv_src : [n][cap]            s*T + t of each received row (nullable)
+ * counts   : [n dst][n src]      rows destination d received from source s
+ * Returns 0, or -1 if some destination would overflow cap (nothing more is written to
+ * that destination), or -2 on an out-of-range expert id.
+ * A token goes ONCE to each distinct destination rank among its K experts.  Order in a
+ * destination buffer: by source rank ascending, then by token index ascending.
+ */
+int orc_moe_dispatch(const uint8_t *tokens, const int32_t *topk, int n, int T, int K,
+                     int n_experts, size_t row_bytes, uint8_t *recv, int32_t *recv_src,
+                     int32_t *counts, size_t cap)
+{
+    int per = n_experts / n;
+    int rc = 0;
+    for (int d = 0; d < n; ++d) {
+        size_t fill = 0;
+        for (int s = 0; s < n; ++s) {
+            int32_t got = 0;
+            for (int t = 0; t < T; ++t) {
+                int hit = 0;
+                for (int k = 0; k < K; ++k) {
+                    int32_t e = topk[((size_t)s * T + t) * K + k];
+                    if (e < 0 || e >= n_experts)
+                        return -2;
+                    if (e / per == d)
+                        hit = 1;
+                }
+                if (!hit)
+                    continue;
+                if (fill >= cap) {
+                    rc = -1;
+                    continue;
+                }
+                memcpy(recv + ((size_t)d * cap + fill) * row_bytes,
+                       tokens + ((size_t)s * T + t) * row_bytes, row_bytes);
+                if (recv_src)
+                    recv_src[(size_t)d * cap + fill] = (int32_t)(s * T + t);
+                ++fill;
+                ++got;
+            }
+            counts[d * n + s] = got;
+        }
+    }
+    return rc;
+}
+
+/* ---------- semaphore bookkeeping (the integer side of signal / wait) ---------- */
+
+/* wait() is satisfied when the counter has reached the expected value; counters only
+ * ever grow and wrap modulo 2^32, so "reached" is a signed distance test. */
+int orc_sem_reached(uint32_t sem, uint32_t expected)
+{
+    return (int32_t)(sem - expected) >= 0;
+}

@@ -1,0 +1,412 @@
+"""Pins for the CPU oracle: each check rests on something other than the oracle's own
+formula (closed forms, exact integer arithmetic, a library routine, permutation identities,
+brute force in Python integers/fractions, hand-worked bit patterns)."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_09014_amd import synth
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+COUNTS = [0, 1, 2, 3, 7, 8, 9, 15, 16, 17, 63, 64, 65, 1023, 1024, 1025]
+RANKS = [1, 2, 3, 4, 8]
+
+
+def _read_table(name):
+    rows = []
+    with open(os.path.join(GOLD, name)) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if line:
+                rows.append(line.split())
+    return rows
+
+
+# ---------------------------------------------------------------- bf16 conversion
+
+def test_bf16_golden_cases(orc):
+    for f32_hex, bf_hex in _read_table("bf16_rne_cases.txt"):
+        x = np.array([int(f32_hex, 16)], np.uint32).view(np.float32)
+        got = int(orc.f32_to_bf16(x)[0])
+        assert got == int(bf_hex, 16), (f32_hex, hex(got), bf_hex)
+
+
+def test_bf16_roundtrip_exhaustive(orc):
+    bits = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    f = orc.bf16_to_f32(bits)
+    assert np.array_equal(f.view(np.uint32), bits.astype(np.uint32) << 16)   # widening is a shift
+    back = orc.f32_to_bf16(f)
+    nan = np.isnan(f)
+    assert np.array_equal(back[~nan], bits[~nan])
+    assert np.all(np.isnan(orc.bf16_to_f32(back[nan])))
+
+
+def test_bf16_matches_torch_library_rounding(orc):
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn(1_000_000, generator=g) * torch.exp(torch.randn(1_000_000, generator=g) * 8)
+    raw = torch.randint(0, 2 ** 31 - 1, (200_000,), generator=g, dtype=torch.int32).view(torch.float32)
+    x = torch.cat([x, raw[torch.isfinite(raw)], -raw[torch.isfinite(raw)]])
+    want = x.bfloat16().view(torch.uint16).numpy()
+    got = orc.f32_to_bf16(x.numpy())
+    assert np.array_equal(got, want)
+
+
+# ---------------------------------------------------------------- AllReduce fp32
+
+@pytest.mark.parametrize("n", RANKS)
+def test_allreduce_f32_closed_forms(orc, n):
+    count = 1000
+    i = np.arange(count)
+    tri = n * (n + 1) // 2
+    x = np.stack([np.full(count, r + 1, np.float32) for r in range(n)])
+    assert np.array_equal(orc.allreduce_f32(x), np.full(count, tri, np.float32))
+    x = np.stack([((i % 251) * (r + 1)).astype(np.float32) for r in range(n)])
+    assert np.array_equal(orc.allreduce_f32(x), (tri * (i % 251)).astype(np.float32))
+    x = np.stack([(i == r).astype(np.float32) for r in range(n)])
+    assert np.array_equal(orc.allreduce_f32(x), (i < n).astype(np.float32))
+
+
+@pytest.mark.parametrize("n", RANKS)
+@pytest.mark.parametrize("count", COUNTS)
+def test_allreduce_f32_bruteforce_integers(orc, n, count):
+    x = synth.int_valued_f32(n, count, seed=count + 100 * n).numpy()
+    want = [sum(int(x[r, i]) for r in range(n)) for i in range(count)]      # Python ints
+    got = orc.allreduce_f32(x)
+    assert got.shape == (count,)
+    assert [int(v) for v in got] == want
+    assert list(orc.allreduce_f32_as_i64(x)) == want
+
+
+def test_allreduce_f32_is_column_sum_library(orc):
+    x = synth.int_valued_f32(8, 262144, seed=0).numpy()                      # config-1 shape
+    want = np.sum(x.astype(np.float64), axis=0)                              # library routine, exact here
+    got = orc.allreduce_f32(x)
+    assert np.array_equal(got.astype(np.float64), want)
+    assert np.array_equal(orc.allreduce_f32_as_i64(x), want.astype(np.int64))
+    assert np.abs(want).max() <= 8000
+
+
+def test_allreduce_f32_linearity_and_rank_permutation(orc):
+    a = synth.int_valued_f32(8, 4097, seed=1).numpy()
+    b = synth.int_valued_f32(8, 4097, seed=2).numpy()
+    assert np.array_equal(orc.allreduce_f32(a + b), orc.allreduce_f32(a) + orc.allreduce_f32(b))
+    perm = np.array([3, 7, 0, 5, 1, 6, 2, 4])
+    assert np.array_equal(orc.allreduce_f32(a[perm]), orc.allreduce_f32(a))
+
+
+def test_allreduce_f32_rank_order_and_accumulator_width(orc):
+    # 2^24 + 1 is not representable in fp32 (ties to even -> 2^24), so the canonical order
+    # ((x0 + x1) + x2) loses the 1, any order that cancels first keeps it, and a wider
+    # accumulator keeps it too.  Worked by hand from the binary32 format.
+    big = float(2 ** 24)
+    x = np.array([[big], [1.0], [-big]], np.float32)
+    assert orc.allreduce_f32(x)[0] == 0.0
+    assert orc.allreduce_f32(x[[0, 2, 1]])[0] == 1.0
+    assert orc.allreduce_f32(x[[1, 0, 2]])[0] == 0.0        # (1 + 2^24) also rounds to 2^24
+
+
+def test_allreduce_f32_rejects_non_integers_in_exact_check(orc):
+    with pytest.raises(ValueError):
+        orc.allreduce_f32_as_i64(np.array([[0.5], [1.0]], np.float32))
+
+
+def test_allreduce_f32_ieee_specials(orc):
+    nz = np.float32(-0.0)
+    out = orc.allreduce_f32(np.array([[nz, np.inf, np.inf, np.nan, 0.0]] * 1 +
+                                     [[nz, 1.0, -np.inf, 1.0, nz]], np.float32))
+    assert np.signbit(out[0]) and out[0] == 0.0             # -0 + -0 = -0
+    assert out[1] == np.inf and np.isnan(out[2]) and np.isnan(out[3])
+    assert out[4] == 0.0 and not np.signbit(out[4])         # +0 + -0 = +0
+
+
+# ---------------------------------------------------------------- AllReduce bf16
+
+def _ulp_bf16(v):
+    """spacing of bf16 numbers around |v| (8 significand bits), for finite v != 0."""
+    v = np.abs(np.asarray(v, np.float64))
+    e = np.floor(np.log2(np.maximum(v, 2.0 ** -126)))
+    return 2.0 ** (e - 7)
+
+
+@pytest.mark.parametrize("n", RANKS)
+def test_allreduce_bf16_within_one_ulp_of_fp64(orc, n):
+    x = synth.normal(n, 50_001, seed=3)
+    bits = synth.bf16_bits(x)
+    out, ref = orc.allreduce_bf16(bits, want_ref64=True)
+    want64 = np.sum(x.double().numpy(), axis=0)             # library column sum in fp64
+    assert np.allclose(ref, want64, rtol=0, atol=1e-12)
+    got = orc.bf16_to_f32(out).astype(np.float64)
+    absmax = np.abs(x.double().numpy()).max(axis=0)
+    # one bf16 ulp at the result, plus fp32 accumulation error (n ulps of fp32 at the
+    # largest partial sum), which matters only when the sum nearly cancels
+    tol = _ulp_bf16(want64) + n * absmax * n * 2.0 ** -24
+    assert np.all(np.abs(got - want64) <= tol)
+
+
+def test_allreduce_bf16_small_integers_exact_any_order(orc):
+    g = torch.Generator().manual_seed(11)
+    xi = torch.randint(-16, 17, (8, 9999), generator=g)      # |sum| <= 128: exact in bf16
+    bits = synth.bf16_bits(xi.to(torch.bfloat16))
+    want = synth.bf16_bits(xi.sum(0).to(torch.bfloat16))
+    assert np.array_equal(orc.allreduce_bf16(bits), want)
+    perm = np.array([5, 2, 7, 0, 3, 6, 1, 4])
+    assert np.array_equal(orc.allreduce_bf16(bits[perm]), want)
+
+
+def test_allreduce_bf16_one_and_two_ranks_vs_torch(orc):
+    x = synth.normal(2, 100_003, seed=4)
+    bits = synth.bf16_bits(x)
+    assert np.array_equal(orc.allreduce_bf16(bits[:1]), bits[0])                     # N = 1: identity
+    want = synth.bf16_bits((x[0].float() + x[1].float()).bfloat16())                  # library ops
+    assert np.array_equal(orc.allreduce_bf16(bits), want)
+
+
+def test_allreduce_bf16_order_accumulator_and_single_rounding(orc):
+    f = lambda *v: synth.bf16_bits(torch.tensor(v, dtype=torch.float32).bfloat16().view(-1, 1))
+    one = 0x3F80
+    # fp32 accumulator, canonical order: (2^24 + 1) -> 2^24, then - 2^24 -> 0
+    assert orc.allreduce_bf16(f(2.0 ** 24, 1.0, -2.0 ** 24))[0] == 0x0000
+    assert orc.allreduce_bf16(f(2.0 ** 24, -2.0 ** 24, 1.0))[0] == one
+    # single rounding at the end: 1 + 2^-8 + 2^-8 = 1 + 2^-7 exactly (one bf16 ulp above 1);
+    # rounding to bf16 after every add would give 1 (each 2^-8 is a tie that goes to even)
+    assert orc.allreduce_bf16(f(1.0, 2.0 ** -8, 2.0 ** -8))[0] == one + 1
+    # accumulating in bf16-width would be wrong here, a wider-than-fp32 accumulator not needed
+
+
+@pytest.mark.parametrize("n", [2, 3, 8])
+@pytest.mark.parametrize("count", [1, 5, 64, 257])
+def test_allreduce_bf16_bruteforce_fractions(orc, n, count):
+    # fp32 accumulation replayed with exact rationals rounded to 24 bits at each step
+    x = synth.normal(n, count, seed=20 + n)
+    bits = synth.bf16_bits(x)
+    out = orc.allreduce_bf16(bits)
+
+    def rnd(fr, p):
+        """round a Fraction to p significand bits, ties to even (no overflow/underflow here)"""
+        if fr == 0:
+            return fr
+        s = -1 if fr < 0 else 1
+        a = abs(fr)
+        e = math.floor(math.log2(float(a)))
+        while Fraction(2) ** e > a:
+            e -= 1
+        while Fraction(2) ** (e + 1) <= a:
+            e += 1
+        q = Fraction(2) ** (e - p + 1)
+        k = a / q
+        lo = k.numerator // k.denominator
+        rem = k - lo
+        if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and lo % 2 == 1):
+            lo += 1
+        return s * lo * q
+
+    for i in range(count):
+        acc = Fraction(float(x[0, i]))
+        for r in range(1, n):
+            acc = rnd(acc + Fraction(float(x[r, i])), 24)
+        want = float(rnd(acc, 8))
+        got = float(orc.bf16_to_f32(out[i:i + 1])[0])
+        assert got == want, (i, got, want)
+
+
+# ---------------------------------------------------------------- residual fusion
+
+def test_residual_zero_and_zero_input(orc):
+    x, res = synth.decode_activations(8, 2, hidden=512, seed=6)
+    xb, rb = synth.bf16_bits(x), synth.bf16_bits(res)
+    zero = np.zeros_like(rb)
+    assert np.array_equal(orc.allreduce_residual_bf16(xb, zero), orc.allreduce_bf16(xb))
+    assert np.array_equal(orc.allreduce_residual_bf16(np.zeros_like(xb), rb), rb)
+    # single rounding: equals torch's fp32 chain rounded once
+    acc = x[0].float()
+    for r in range(1, 8):
+        acc = acc + x[r].float()
+    want = synth.bf16_bits((acc + res.float()).bfloat16())
+    assert np.array_equal(orc.allreduce_residual_bf16(xb, rb), want)
+    xf = x.float().numpy()
+    assert np.array_equal(orc.allreduce_residual_f32(xf, res.float().numpy()),
+                          (acc + res.float()).numpy())
+
+
+# ---------------------------------------------------------------- ReduceScatter / AllGather / AllToAll
+
+@pytest.mark.parametrize("n", RANKS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_allgather_of_reducescatter_is_allreduce(orc, n, dtype):
+    count = n * 333
+    if dtype == "f32":
+        x = synth.int_valued_f32(n, count, seed=8).numpy()
+        ar = orc.allreduce_f32(x)
+    else:
+        x = synth.bf16_bits(synth.normal(n, count, seed=8))
+        ar = orc.allreduce_bf16(x)
+    rs = orc.reducescatter(x)
+    assert rs.shape == (n, count // n)
+    ag = orc.allgather(rs)
+    for r in range(n):
+        assert np.array_equal(ag[r], ar)
+
+
+@pytest.mark.parametrize("n", RANKS)
+def test_reducescatter_bruteforce(orc, n):
+    c = 5
+    x = synth.int_valued_f32(n, n * c, seed=9).numpy()
+    rs = orc.reducescatter(x)
+    for r in range(n):
+        for k in range(c):
+            assert int(rs[r, k]) == sum(int(x[j, r * c + k]) for j in range(n))
+    with pytest.raises(ValueError):
+        orc.reducescatter(np.zeros((3, 4), np.float32))
+
+
+@pytest.mark.parametrize("n", RANKS)
+def test_allgather_alltoall_are_attributable_permutations(orc, n):
+    c = 37
+    # every element names its rank and position, so a misplaced one is attributable
+    x = (np.arange(n)[:, None].astype(np.uint32) << 24) | np.arange(c, dtype=np.uint32)[None, :]
+    ag = orc.allgather(x)
+    for r in range(n):
+        for j in range(n):
+            assert np.array_equal(ag[r, j * c:(j + 1) * c], x[j])
+    y = (np.arange(n)[:, None].astype(np.uint32) << 24) | np.arange(n * c, dtype=np.uint32)[None, :]
+    a2a = orc.alltoall(y)
+    for d in range(n):
+        for s in range(n):
+            assert np.array_equal(a2a[d, s * c:(s + 1) * c], y[s, d * c:(d + 1) * c])
+    assert np.array_equal(orc.alltoall(a2a), y)             # involution
+    y16 = y.astype(np.uint16)
+    assert np.array_equal(orc.alltoall(orc.alltoall(y16)), y16)
+    # numpy library form of the same block transpose
+    want = y.reshape(n, n, c).transpose(1, 0, 2).reshape(n, n * c)
+    assert np.array_equal(a2a, want)
+
+
+# ---------------------------------------------------------------- LL units
+
+def test_ll_unit_byte_layout_golden(orc):
+    for data_hex, flag_hex, *mem in _read_table("ll_unit_layout.txt"):
+        unit = orc.ll_encode(int(data_hex, 16), int(flag_hex, 16))
+        got = list(np.array([unit], np.uint64).view(np.uint8))
+        assert got == [int(b, 16) for b in mem]
+
+
+def test_ll_roundtrip_and_flag_mismatch(orc):
+    g = np.random.default_rng(3)
+    words = [0, 1, 0xFFFFFFFF, 0x80000000, 0x7FFFFFFF] + [int(v) for v in g.integers(0, 2 ** 32, 200)]
+    flags = [1, 2, 0x7FFFFFFF, 0xFFFFFFFF]
+    for w in words:
+        for fl in flags:
+            u = orc.ll_encode(w, fl)
+            assert orc.ll_decode(u, fl) == (True, w)
+            assert orc.ll_decode(u, (fl + 1) & 0xFFFFFFFF) == (False, None)
+            assert orc.ll_decode(u, fl ^ 0x80000000) == (False, None)
+    # zero-initialised scratch never validates for a non-zero flag, whatever the data
+    for fl in flags:
+        assert orc.ll_decode(0, fl) == (False, None)
+
+
+@pytest.mark.parametrize("nbytes", [0, 1, 3, 4, 5, 8, 9, 15, 16, 17, 1024, 1027])
+def test_ll_buffer_encode_decode(orc, nbytes):
+    g = np.random.default_rng(nbytes)
+    payload = g.integers(0, 256, nbytes, dtype=np.uint8)
+    flag = 0x1234
+    units = orc.ll_encode_buf(payload, flag)
+    assert units.size == 2 * ((nbytes + 7) // 8)
+    ok, back = orc.ll_decode_buf(units, nbytes, flag)
+    assert ok and np.array_equal(back, payload)
+    raw = units.view(np.uint8).reshape(-1, 8)
+    assert np.all(raw[:, 4:].view(np.uint32) == flag)        # every unit carries the flag
+    padded = np.zeros(units.size * 4, np.uint8)
+    padded[:nbytes] = payload
+    assert np.array_equal(raw[:, :4].reshape(-1), padded)    # data words in order, zero padded
+    if units.size:
+        # a packet is ready only when BOTH of its units carry the flag
+        for victim in (0, units.size - 1):
+            broken = units.copy()
+            broken[victim] = orc.ll_encode(int(broken[victim]) & 0xFFFFFFFF, flag - 1)
+            assert orc.ll_decode_buf(broken, nbytes, flag) == (False, None)
+
+
+# ---------------------------------------------------------------- token dispatch
+
+def _dest_sets(topk, n, n_experts):
+    per = n_experts // n
+    return [[sorted({int(e) // per for e in tok}) for tok in rank] for rank in topk]
+
+
+def test_moe_dispatch_properties(orc):
+    n, T, H, K, E = 8, 96, 24, 8, 256
+    tokens = synth.bf16_bits(synth.moe_tokens(n, T, H, seed=1))
+    topk = synth.moe_routing(n, T, K, E, seed=1).numpy()
+    recv, src, counts, rc = orc.moe_dispatch(tokens, topk, E)
+    assert rc == 0
+    dests = _dest_sets(topk, n, E)
+    # conservation per source
+    for s in range(n):
+        assert counts[:, s].sum() == sum(len(d) for d in dests[s])
+    # brute-force expected order, built independently in Python
+    for d in range(n):
+        want = [(s, t) for s in range(n) for t in range(T) if d in dests[s][t]]
+        got = src[d, :len(want)]
+        assert [int(v) for v in got] == [s * T + t for s, t in want]
+        assert np.all(src[d, len(want):] == -1)
+        for slot, (s, t) in enumerate(want):
+            assert np.array_equal(recv[d, slot], tokens[s, t])
+        for s in range(n):
+            assert counts[d, s] == sum(1 for (ss, _) in want if ss == s)
+
+
+def test_moe_dispatch_special_cases(orc):
+    n, T, H, E = 8, 40, 8, 256
+    tokens = synth.bf16_bits(synth.moe_tokens(n, T, H, seed=2))
+    # K = 1: every token appears exactly once overall
+    topk1 = synth.moe_routing(n, T, 1, E, seed=2).numpy()
+    _, src, counts, rc = orc.moe_dispatch(tokens, topk1, E)
+    assert rc == 0 and counts.sum() == n * T
+    seen = sorted(int(v) for v in src[src >= 0])
+    assert seen == list(range(n * T))
+    # all experts of every token on rank 3: a plain gather to rank 3
+    topk3 = np.tile(np.arange(96, 104, dtype=np.int32), (n, T, 1))
+    recv, src, counts, rc = orc.moe_dispatch(tokens, topk3, E)
+    assert rc == 0 and counts[3].tolist() == [T] * n and counts.sum() == n * T
+    assert np.array_equal(recv[3, :n * T].reshape(n, T, H), tokens)
+    # one expert on every rank: full replication == AllGather of the token blocks
+    topk_all = np.tile(np.arange(0, 256, 32, dtype=np.int32), (n, T, 1))
+    recv, src, counts, rc = orc.moe_dispatch(tokens, topk_all, E)
+    ag = orc.allgather(tokens.reshape(n, T * H))
+    assert rc == 0 and np.all(counts == T)
+    assert np.array_equal(recv.reshape(n, n * T * H), ag)
+    # duplicates of one expert or one rank do not duplicate the row
+    topk_dup = np.zeros((n, T, 8), np.int32)
+    _, _, counts, _ = orc.moe_dispatch(tokens, topk_dup, E)
+    assert counts[0].tolist() == [T] * n and counts[1:].sum() == 0
+    # capacity overflow and bad expert ids are reported
+    assert orc.moe_dispatch(tokens, topk_all, E, cap=T)[3] == -1
+    bad = topk_all.copy()
+    bad[0, 0, 0] = 256
+    assert orc.moe_dispatch(tokens, bad, E)[3] == -2
+
+
+def test_moe_expected_fanout_of_the_seeded_routing():
+    n, T, K, E = 8, 4096, 8, 256
+    topk = synth.moe_routing(n, T, K, E, seed=0).numpy()
+    assert np.all(np.sort(topk, axis=2)[:, :, 1:] != np.sort(topk, axis=2)[:, :, :-1])   # distinct
+    fan = np.mean([len(set((tok // 32).tolist())) for rank in topk for tok in rank])
+    p_miss = math.comb(224, 8) / math.comb(256, 8)
+    expect = 8 * (1 - p_miss)
+    assert abs(expect - 5.295) < 1e-3
+    assert abs(fan - expect) < 0.03
+
+
+# ---------------------------------------------------------------- semaphore counter
+
+def test_sem_reached_is_wrap_safe(orc):
+    assert orc.sem_reached(5, 5) and orc.sem_reached(6, 5) and not orc.sem_reached(4, 5)
+    assert orc.sem_reached(1, 0xFFFFFFFE)                    # counter wrapped past the target
+    assert not orc.sem_reached(0xFFFFFFFE, 1)                # target is ahead across the wrap
+    assert orc.sem_reached(0, 0) and not orc.sem_reached(0, 1)
