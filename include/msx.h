@@ -1,0 +1,202 @@
+/*
+ * msx - collective data-movement kernels for N emulated ranks inside ONE MI355X.
+ *
+ * The N "GPUs" of the paper are N rank buffers in this GPU's HBM; rank r's work is done
+ * by the workgroups b with b % N == r of a single kernel launch, and ranks talk to each
+ * other only through device-scope flags in HBM (semaphores and LL packet flags).
+ *
+ * General rules for every entry point
+ *   - C ABI, no exceptions, never exits.  Returns MSX_OK (0) or a negative msx_error.
+ *   - Every `void* stream` is a hipStream_t (NULL = the default stream).  Calls enqueue
+ *     work on that stream and return without waiting for it (the first call on a device
+ *     also allocates the library's scratch and semaphores, which blocks once).
+ *   - Data pointers are DEVICE pointers, 16-byte aligned, owned by the caller and kept
+ *     alive until the stream has run the call.  Pointer TABLES (`const void* const*`)
+ *     are HOST arrays of `nranks` device pointers; they are read during the call only.
+ *   - nranks is 1..8.  count == 0 is a successful no-op.
+ *   - All calls share one per-device context (flag epoch, semaphore counters): issue
+ *     them on one stream, or order them yourself.
+ *   - A device-side wait that does not finish within the spin budget makes its workgroup
+ *     record {rank, site, expected, seen} and carry on; nothing hangs.  msx_status()
+ *     reports it.  After a timeout call msx_reset().
+ */
+#ifndef MSX_H
+#define MSX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { MSX_F32 = 0, MSX_BF16 = 1 } msx_dtype;
+typedef enum { MSX_SUM = 0 } msx_op;
+
+typedef enum {
+    MSX_OK = 0,
+    MSX_ERR_ARG = -1,          /* null / misaligned pointer, bad nranks, bad count, bad dtype */
+    MSX_ERR_UNSUPPORTED = -2,  /* valid request this build does not implement */
+    MSX_ERR_HIP = -3,          /* a HIP runtime call failed (msx_last_hip_error has the code) */
+    MSX_ERR_TIMEOUT = -4,      /* a device-side wait ran out of its spin budget */
+    MSX_ERR_NOMEM = -5,        /* scratch too small for the request / allocation failed */
+    MSX_ERR_CAPACITY = -6      /* token dispatch: a destination buffer overflowed */
+} msx_error;
+
+/* AllReduce algorithms (Collectives Library section: one-phase and two-phase all-pairs). */
+typedef enum {
+    MSX_ALGO_AUTO = 0,      /* pick by message size */
+    MSX_ALGO_1PA_LL = 1,    /* one-phase all-pairs over LL packets */
+    MSX_ALGO_2PA_LL = 2,    /* two-phase all-pairs over LL packets, rotating scratch */
+    MSX_ALGO_2PA_HB = 3,    /* two-phase all-pairs, HB protocol, reduce and put fused in registers */
+    MSX_ALGO_2PA_HB_2PHASE = 4 /* same, but reduce-scatter to memory, barrier, all-gather put */
+} msx_algo;
+
+/* ------------------------------------------------------------------------------------
+ * Collectives in the paper's problem statement (Background, "Collective Communications").
+ * These four take ONE rank-major contiguous device buffer and work IN PLACE.
+ * ---------------------------------------------------------------------------------- */
+
+/* AllReduce: buf is [nranks][count]; afterwards every row holds the elementwise sum of
+ * the rows.  count*elemsize must be a multiple of 16 when nranks > 1 (rows stay aligned);
+ * msx_allreduce_ex takes any count.  Sum is taken in fp32 in rank order 0..nranks-1 and
+ * rounded once. */
+int msx_allreduce(void* buf, size_t count, int dtype, int op, int nranks, void* stream);
+
+/* ReduceScatter: buf is [nranks][count], count % nranks == 0, c = count / nranks.
+ * Afterwards elements [r*c, (r+1)*c) of row r hold the sum over rows of that range;
+ * every other element is left as it was. */
+int msx_reducescatter(void* buf, size_t count, int dtype, int op, int nranks, void* stream);
+
+/* AllGather: buf is [nranks][nranks*count]; on entry row r holds its contribution in
+ * elements [r*count, (r+1)*count); afterwards every row is the concatenation.  op ignored. */
+int msx_allgather(void* buf, size_t count, int dtype, int op, int nranks, void* stream);
+
+/* AllToAll (equal blocks): buf is [nranks][count], count % nranks == 0, c = count/nranks.
+ * Afterwards block s of row d holds what block d of row s held.  op ignored. */
+int msx_alltoall(void* buf, size_t count, int dtype, int op, int nranks, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Out-of-place forms with one pointer per rank (send[r], recv[r] are rank r's buffers).
+ * send[r] == recv[r] is allowed for allreduce and reducescatter-with-full-rows only.
+ * ---------------------------------------------------------------------------------- */
+
+/* AllReduce, optionally fused with a residual add (tensor-parallel decode epilogue):
+ * recv[r][i] = round( fp32 sum_j send[j][i] (rank order) + fp32 residual[r][i] ).
+ * residual may be NULL (no add); its entries may all be the same pointer.
+ * algo is an msx_algo.  LL algorithms need count*elemsize <= the LL limit (msx_get_option
+ * "ll_max_bytes"), else MSX_ERR_NOMEM. */
+int msx_allreduce_ex(const void* const* send, void* const* recv, const void* const* residual,
+                     size_t count, int dtype, int op, int nranks, int algo, void* stream);
+
+/* ReduceScatter: send[r] is [count]; recv[r] is [count/nranks] = sum_j send[j][r*c + k]. */
+int msx_reducescatter_ex(const void* const* send, void* const* recv, size_t count, int dtype,
+                         int op, int nranks, void* stream);
+
+/* AllGather: send[r] is [count]; recv[r] is [nranks*count], block j = send[j]. */
+int msx_allgather_ex(const void* const* send, void* const* recv, size_t count, int dtype,
+                     int nranks, void* stream);
+
+/* AllToAll: send[r], recv[r] are [count], count % nranks == 0; recv[d] block s = send[s] block d.
+ * send and recv must not overlap. */
+int msx_alltoall_ex(const void* const* send, void* const* recv, size_t count, int dtype,
+                    int nranks, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Token-routed all-to-all (expert-parallel dispatch, the setting of the paper's DeepEP
+ * experiment: hidden 7168, top-8 of 256 experts).  Expert e lives on rank
+ * e / (n_experts / nranks).  Each token row goes ONCE to every distinct rank that owns one
+ * of its K experts.  recv_tokens[d] is filled by source rank ascending, then token index
+ * ascending.
+ *   tokens[s]        device [T][H] elements of dtype (H*elemsize % 16 == 0)
+ *   topk_idx[s]      device [T][K] int32 expert ids, 0 <= id < n_experts
+ *   recv_tokens[d]   device [recv_capacity_tokens][H]
+ *   recv_src_token[d] device [recv_capacity_tokens] int32 = s*T + t of each row, or the
+ *                    whole table may be NULL
+ *   recv_counts      device [nranks dst][nranks src] int32 (rows received per source)
+ * Rows that would exceed recv_capacity_tokens are dropped and msx_status() then reports
+ * MSX_ERR_CAPACITY; recv_counts still holds the true counts.  T <= 65534, K <= 32.
+ * ---------------------------------------------------------------------------------- */
+int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, int T, int H,
+                     int K, int n_experts, int dtype, int nranks, void* const* recv_tokens,
+                     int32_t* const* recv_src_token, int32_t* recv_counts,
+                     size_t recv_capacity_tokens, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * MemoryChannel primitives on their own (Primitive API figure and MemoryChannel section:
+ * put / signal / wait / flush, LL put / read).  Small kernels that exercise exactly one
+ * primitive pair between two emulated ranks; used by tests and by the latency table.
+ * ---------------------------------------------------------------------------------- */
+
+/* signal/wait ping-pong: workgroup block_a and workgroup block_b of a `grid_blocks`-wide
+ * launch bounce a semaphore `iters` times.  ns_out (device, 1 double) = ns per round trip. */
+int msx_prim_pingpong(int iters, int grid_blocks, int block_a, int block_b, double* ns_out,
+                      void* stream);
+
+/* `rounds` all-to-all barriers among nranks x blocks_per_rank workgroups (every rank signals
+ * all peers, then waits on all peers).  sem_out (device, [nranks][nranks] uint32, nullable)
+ * receives how far each semaphore of channel 0 advanced during the call. */
+int msx_prim_barrier(int rounds, int nranks, int blocks_per_rank, uint32_t* sem_out, void* stream);
+
+/* HB hand-off: rank 0 put()s src -> staging with 16-byte copies and signals; rank 1 waits,
+ * then copies staging -> dst.  All three are device buffers of nbytes (any size). */
+int msx_prim_put_signal_wait(const void* src, void* staging, void* dst, size_t nbytes,
+                             int blocks_per_rank, void* stream);
+
+/* LL encode only: write ceil(nbytes/8) 16-byte packets {w0, flag, w1, flag} for src into
+ * packets_out (device, 16-byte aligned, 16*ceil(nbytes/8) bytes). */
+int msx_prim_ll_encode(const void* src, size_t nbytes, uint32_t flag, void* packets_out,
+                       void* stream);
+
+/* LL hand-off: rank 0 encodes src into the library scratch with the current flag, rank 1
+ * polls every packet until both flags match and writes the payload to dst. */
+int msx_prim_ll_roundtrip(const void* src, void* dst, size_t nbytes, int blocks_per_rank,
+                          void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Context, options, status
+ * ---------------------------------------------------------------------------------- */
+
+/* Create the current device's context now (otherwise the first call does). */
+int msx_init(void);
+
+/* Re-zero scratch, semaphores and the flag epoch of the current device's context.
+ * Synchronises the device. */
+int msx_reset(void);
+
+/* Free the current device's context.  Synchronises the device. */
+int msx_finalize(void);
+
+/* Options (strings; numbers in decimal):
+ *   "algo"            auto | 1pa_ll | 2pa_ll | 2pa_hb | 2pa_hb_2phase  (for the in-place forms)
+ *   "ll_1pa_max_bytes", "ll_2pa_max_bytes"   size thresholds of the automatic choice
+ *   "ll_max_bytes"    largest per-rank message the LL scratch is sized for (set before init)
+ *   "hb_blocks_per_rank", "ll_blocks_per_rank", "threads"   0 = automatic
+ *   "hb_unroll"       1 | 2 | 4
+ *   "hb_barriers"     0 | 1   start/end rank barriers in the HB kernels
+ *   "spin_limit"      polls before a wait gives up
+ *   "drop_rank"       -1, or a rank whose workgroups return at once (failure-path tests)
+ *   "chaos"           0, or a seed: workgroups sleep pseudo-random times before they signal
+ *   "epoch"           next LL flag value (tests of wrap-around)
+ *   "sem_base"        set every semaphore and expected value to this number (wrap tests; syncs)
+ * Unknown key or bad value -> MSX_ERR_ARG. */
+int msx_set_option(const char* key, const char* value);
+int msx_get_option(const char* key, char* value_out, size_t value_len);
+
+/* Wait for `stream`, then report and clear the device-side status.  info (nullable) gets
+ * {code, rank, site, expected, seen, block}.  Returns MSX_OK, MSX_ERR_TIMEOUT or
+ * MSX_ERR_CAPACITY. */
+int msx_status(void* stream, uint32_t info[6]);
+
+/* Name and launch shape of the kernel the last call on this thread launched
+ * (for profiles): grid blocks, block threads, algorithm chosen. */
+int msx_last_launch(int* grid, int* block, int* algo);
+
+int msx_last_hip_error(void);
+const char* msx_strerror(int err);
+const char* msx_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MSX_H */

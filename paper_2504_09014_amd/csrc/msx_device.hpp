@@ -1,0 +1,244 @@
+// Device-side MemoryChannel primitives for ranks emulated inside one gfx950 GPU.
+//
+// A "rank" is the set of workgroups b of a launch with b % nranks == rank; workgroup
+// b / nranks of a rank is its "channel".  Workgroups are dealt round-robin to the 8 XCDs,
+// so with 8 ranks every rank lives on its own XCD and its own L2; anything another rank
+// must see therefore has to be made visible at device (agent) scope.
+//
+//   signal / wait / rank barrier : MemoryChannel "Synchronization" paragraph
+//   HB put (16-byte copies)      : MemoryChannel "Data Transfer" paragraph
+//   LL packet store / poll       : MemoryChannel "Protocols" paragraph, item (ii)
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace msx {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kMaxRanks = 8;
+constexpr int kMaxChannels = 256;
+constexpr int kSemStrideWords = 32;  // one semaphore per 128-byte line
+
+// status.code values written by the device
+constexpr unsigned kStatusOk = 0;
+constexpr unsigned kStatusTimeout = 1;
+constexpr unsigned kStatusCapacity = 2;
+
+// Everything a kernel needs from the per-device context; passed by value.
+struct DevCtx {
+    unsigned* sem;        // [kMaxRanks recv][kMaxRanks send][kMaxChannels] x kSemStrideWords
+    unsigned* expected;   // [kMaxRanks recv][kMaxRanks send][kMaxChannels] value the next wait needs
+    unsigned* status;     // 8 words: code, rank, site, expected, seen, block
+    void* ll;             // LL scratch, ll_bytes long: [rank][rotation][...]
+    unsigned ll_bytes;
+    unsigned ll_rank_stride;
+    unsigned ll_rot_stride;
+    unsigned spin_limit;
+    int drop_rank;        // failure-path tests: this rank's workgroups leave at once (-1: none)
+    unsigned chaos;       // 0, or a seed for pseudo-random delays before signalling
+};
+
+__device__ __forceinline__ unsigned sem_index(int recv, int send, int chan)
+{
+    return (unsigned)((recv * kMaxRanks + send) * kMaxChannels + chan);
+}
+
+__device__ __forceinline__ void report(const DevCtx& c, unsigned code, unsigned rank, unsigned site,
+                                       unsigned expected, unsigned seen)
+{
+    if (atomicCAS(c.status, 0u, code) == 0u) {
+        c.status[1] = rank;
+        c.status[2] = site;
+        c.status[3] = expected;
+        c.status[4] = seen;
+        c.status[5] = blockIdx.x;
+    }
+}
+
+// Pseudo-random pause (tests only): makes workgroups arrive at their signals in scrambled order.
+__device__ __forceinline__ void chaos_delay(const DevCtx& c, unsigned site)
+{
+    if (c.chaos == 0) return;
+    unsigned h = (c.chaos * 2654435761u) ^ (blockIdx.x * 40503u + site * 9176u + 0x9e3779b9u);
+    h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
+    unsigned n = h & 1023u;
+    for (unsigned i = 0; i < n; ++i) __builtin_amdgcn_s_sleep(8);
+}
+
+// ---- semaphores ---------------------------------------------------------------------
+
+// signal(): make every earlier store of this workgroup visible device-wide, then bump the
+// receiver's counter.  Call from ONE thread, after a workgroup barrier if other threads
+// of the workgroup produced the data.
+__device__ __forceinline__ void sem_signal(unsigned* sem)
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __hip_atomic_fetch_add(sem, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// The spinning half of wait(): one thread polls until the counter has reached `expected`
+// (signed distance, so the 32-bit counter may wrap), then acquires.  Returns false and
+// records the timeout when the spin budget runs out.
+__device__ __forceinline__ bool sem_spin(const DevCtx& c, unsigned* sem, unsigned expected,
+                                         unsigned rank, unsigned site)
+{
+    unsigned seen = 0;
+    bool ok = false;
+    for (unsigned spins = 0; spins <= c.spin_limit; ++spins) {
+        seen = __hip_atomic_load(sem, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((int)(seen - expected) >= 0) { ok = true; break; }
+        __builtin_amdgcn_s_sleep(1);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    if (!ok) report(c, kStatusTimeout, rank, site, expected, seen);
+    return ok;
+}
+
+// One-directional hand-off helpers for a (sender rank -> receiver rank) channel.
+// Both are workgroup-collective: every thread of the workgroup must call them.
+__device__ __forceinline__ void channel_signal(const DevCtx& c, int me, int peer, int chan, unsigned site)
+{
+    __syncthreads();   // all threads' puts are issued and complete before the release below
+    if (threadIdx.x == 0) {
+        chaos_delay(c, site);
+        sem_signal(c.sem + (size_t)sem_index(peer, me, chan) * kSemStrideWords);
+    }
+}
+
+__device__ __forceinline__ void channel_wait(const DevCtx& c, int me, int peer, int chan, unsigned site)
+{
+    if (threadIdx.x == 0) {
+        unsigned idx = sem_index(me, peer, chan);
+        unsigned want = c.expected[idx] + 1u;
+        c.expected[idx] = want;
+        sem_spin(c, c.sem + (size_t)idx * kSemStrideWords, want, (unsigned)me, site);
+    }
+    __syncthreads();   // the first thread waited for everybody
+}
+
+// Barrier among all ranks on one channel: signal every peer, then wait for every peer.
+// Threads 0..n-2 each serve one peer so the n-1 hops overlap.  Workgroup-collective.
+__device__ __forceinline__ void rank_barrier(const DevCtx& c, int me, int n, int chan, unsigned site)
+{
+    __syncthreads();
+    const int t = (int)threadIdx.x;
+    if (t < n - 1) {
+        int peer = me + 1 + t;
+        if (peer >= n) peer -= n;
+        chaos_delay(c, site + (unsigned)t);
+        sem_signal(c.sem + (size_t)sem_index(peer, me, chan) * kSemStrideWords);
+        unsigned idx = sem_index(me, peer, chan);
+        unsigned want = c.expected[idx] + 1u;
+        c.expected[idx] = want;
+        sem_spin(c, c.sem + (size_t)idx * kSemStrideWords, want, (unsigned)me, site);
+    }
+    __syncthreads();
+}
+
+// ---- HB protocol: cooperative 16-byte copy ---------------------------------------------
+
+// put(): threads tid of tids copy nbytes from src to dst (both 16-byte aligned when
+// nbytes >= 16; a tail shorter than 16 bytes is moved bytewise by the first threads).
+__device__ __forceinline__ void hb_put(void* dst, const void* src, size_t nbytes, size_t tid, size_t tids)
+{
+    const u32x4* s = (const u32x4*)src;
+    u32x4* d = (u32x4*)dst;
+    const size_t nvec = nbytes >> 4;
+    size_t i = tid;
+    for (; i + 3 * tids < nvec; i += 4 * tids) {
+        u32x4 a = __builtin_nontemporal_load(s + i);
+        u32x4 b = __builtin_nontemporal_load(s + i + tids);
+        u32x4 e = __builtin_nontemporal_load(s + i + 2 * tids);
+        u32x4 f = __builtin_nontemporal_load(s + i + 3 * tids);
+        __builtin_nontemporal_store(a, d + i);
+        __builtin_nontemporal_store(b, d + i + tids);
+        __builtin_nontemporal_store(e, d + i + 2 * tids);
+        __builtin_nontemporal_store(f, d + i + 3 * tids);
+    }
+    for (; i < nvec; i += tids) __builtin_nontemporal_store(__builtin_nontemporal_load(s + i), d + i);
+    const size_t done = nvec << 4;
+    for (size_t b = done + tid; b < nbytes; b += tids)
+        ((unsigned char*)dst)[b] = ((const unsigned char*)src)[b];
+}
+
+// ---- LL protocol: 16-byte packets = two 8-byte units {data, flag} -------------------------
+
+// The LL scratch is addressed through one buffer descriptor: accesses carry the device
+// (agent) scope bit so that a packet store goes straight to memory the other XCDs see and
+// a poll never reads a stale line; out-of-range offsets are dropped by the hardware
+// range check instead of faulting.
+constexpr int kAuxAgentScope = 1 << 4;      // "sc1" on this target
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t ll_resource(const DevCtx& c)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(c.ll, 0, (int)c.ll_bytes, 0x00020000);
+}
+
+__device__ __forceinline__ void ll_store(__amdgpu_buffer_rsrc_t r, unsigned byte_off, unsigned w0,
+                                         unsigned w1, unsigned flag)
+{
+    u32x4 p = {w0, flag, w1, flag};
+    __builtin_amdgcn_raw_buffer_store_b128(p, r, (int)byte_off, 0, kAuxAgentScope);
+}
+
+__device__ __forceinline__ u32x4 ll_load(__amdgpu_buffer_rsrc_t r, unsigned byte_off)
+{
+    return __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, kAuxAgentScope);
+}
+
+__device__ __forceinline__ bool ll_ready(u32x4 p, unsigned flag)
+{
+    return p.y == flag && p.w == flag;   // both units of the packet must carry the flag
+}
+
+// Keeps the compiler from hoisting a poll out of its retry loop.
+__device__ __forceinline__ void poll_fence() { asm volatile("" ::: "memory"); }
+
+// ---- element arithmetic -------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest even, NaN kept quiet
+__device__ __forceinline__ unsigned bf16_round(float f)
+{
+    unsigned u = __float_as_uint(f);
+    unsigned r = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+    unsigned q = (u >> 16) | 0x40u;
+    return ((u & 0x7fffffffu) > 0x7f800000u) ? q : r;
+}
+
+// Accumulator for the elements held in one 32-bit word: 1 x fp32 or 2 x bf16.
+template <int DT> struct WordAcc;
+template <> struct WordAcc<0> {   // fp32
+    float a;
+    __device__ __forceinline__ void set(unsigned w) { a = __uint_as_float(w); }
+    __device__ __forceinline__ void add(unsigned w) { a += __uint_as_float(w); }
+    __device__ __forceinline__ unsigned pack() const { return __float_as_uint(a); }
+};
+template <> struct WordAcc<1> {   // bf16 pair
+    float lo, hi;
+    __device__ __forceinline__ void set(unsigned w) { lo = bf16_lo(w); hi = bf16_hi(w); }
+    __device__ __forceinline__ void add(unsigned w) { lo += bf16_lo(w); hi += bf16_hi(w); }
+    __device__ __forceinline__ unsigned pack() const { return bf16_round(lo) | (bf16_round(hi) << 16); }
+};
+
+template <int DT> struct VecAcc {
+    WordAcc<DT> w[4];
+    __device__ __forceinline__ void set(u32x4 v) { w[0].set(v.x); w[1].set(v.y); w[2].set(v.z); w[3].set(v.w); }
+    __device__ __forceinline__ void add(u32x4 v) { w[0].add(v.x); w[1].add(v.y); w[2].add(v.z); w[3].add(v.w); }
+    __device__ __forceinline__ u32x4 pack() const { return u32x4{w[0].pack(), w[1].pack(), w[2].pack(), w[3].pack()}; }
+};
+
+__device__ __forceinline__ u32x4 ld16(const void* base, size_t vec_index)
+{
+    return __builtin_nontemporal_load((const u32x4*)base + vec_index);
+}
+__device__ __forceinline__ void st16(void* base, size_t vec_index, u32x4 v)
+{
+    __builtin_nontemporal_store(v, (u32x4*)base + vec_index);
+}
+
+}  // namespace msx

@@ -1,0 +1,887 @@
+// Host side of libmsx: per-device context, options, argument checks, algorithm choice and
+// launches behind the C ABI declared in include/msx.h.  Every launch is sized so that all
+// of its workgroups are resident at once (ranks wait on each other inside one kernel).
+#include "../../include/msx.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <utility>
+
+#include "msx_device.hpp"
+#include "msx_kernels_hb.hpp"
+#include "msx_kernels_ll.hpp"
+#include "msx_kernels_moe.hpp"
+#include "msx_kernels_prim.hpp"
+
+using namespace msx;
+
+namespace {
+
+struct Options {
+    int algo = MSX_ALGO_AUTO;
+    size_t ll_1pa_max = 32u << 10;
+    size_t ll_2pa_max = 512u << 10;
+    size_t ll_max_bytes = 4u << 20;
+    int hb_blocks = 0, ll_blocks = 0, threads = 0;
+    int hb_unroll = 2;
+    int hb_barriers = 1;
+    int peer_outer = 0;
+    unsigned spin_limit = 1u << 20;
+    int drop_rank = -1;
+    unsigned chaos = 0;
+};
+
+struct Ctx {
+    int device = -1;
+    DevCtx d{};
+    unsigned epoch = 0;        // last LL flag handed out
+    unsigned calls = 0;        // LL calls so far (rotation)
+    int cus = 0;
+    double ns_per_tick = 10.0;
+    void* moe_slots = nullptr;
+    size_t moe_slots_bytes = 0;
+    unsigned* moe_base = nullptr;
+    unsigned* snap = nullptr;  // small device scratch for snapshots
+    size_t ll_limit = 0;       // ll_max_bytes this context was sized for
+    std::map<std::pair<const void*, int>, int> occ;   // (kernel, threads) -> resident blocks per CU
+};
+
+std::mutex g_mu;
+Options g_opt;
+Ctx* g_ctx[64] = {};
+thread_local int t_hip_err = 0;
+thread_local int t_grid = 0, t_block = 0, t_algo = 0;
+
+int hip_fail(hipError_t e)
+{
+    t_hip_err = (int)e;
+    return MSX_ERR_HIP;
+}
+#define HIPCHK(x)                                    \
+    do {                                             \
+        hipError_t e_ = (x);                         \
+        if (e_ != hipSuccess) return hip_fail(e_);   \
+    } while (0)
+
+size_t elem_size(int dtype) { return dtype == MSX_F32 ? 4 : 2; }
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int destroy_ctx(Ctx* c)
+{
+    if (!c) return MSX_OK;
+    (void)hipDeviceSynchronize();
+    if (c->d.sem) (void)hipFree(c->d.sem);
+    if (c->d.expected) (void)hipFree(c->d.expected);
+    if (c->d.status) (void)hipFree(c->d.status);
+    if (c->d.ll) (void)hipFree(c->d.ll);
+    if (c->moe_slots) (void)hipFree(c->moe_slots);
+    if (c->moe_base) (void)hipFree(c->moe_base);
+    if (c->snap) (void)hipFree(c->snap);
+    delete c;
+    return MSX_OK;
+}
+
+// Context of the current device, created on first use.  Caller holds g_mu.
+int get_ctx(Ctx** out)
+{
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return MSX_ERR_ARG;
+    if (g_ctx[dev]) { *out = g_ctx[dev]; return MSX_OK; }
+    Ctx* c = new Ctx();
+    c->device = dev;
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDeviceProperties(&prop, dev);
+    if (e != hipSuccess) { delete c; return hip_fail(e); }
+    c->cus = prop.multiProcessorCount;
+    int khz = 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
+        c->ns_per_tick = 1.0e6 / (double)khz;
+
+    const size_t sem_bytes = (size_t)kMaxRanks * kMaxRanks * kMaxChannels * kSemStrideWords * 4;
+    const size_t exp_bytes = (size_t)kMaxRanks * kMaxRanks * kMaxChannels * 4;
+    // one rotation half holds either 1PA's n slots of P packets (P <= ll_max/4/8) or 2PA's
+    // 2 phases x n slots of ceil(P/n) packets (P <= ll_max/8): both at most 4*ll_max (+ slack)
+    size_t ll_max = g_opt.ll_max_bytes;
+    if (ll_max < 4096) ll_max = 4096;
+    if (ll_max > (16u << 20)) ll_max = 16u << 20;
+    const size_t rot = 4 * ll_max + 4096;
+    const size_t rank_stride = 2 * rot;
+    const size_t ll_bytes = rank_stride * kMaxRanks;
+    c->ll_limit = ll_max;
+
+    bool ok = hipMalloc((void**)&c->d.sem, sem_bytes) == hipSuccess &&
+              hipMalloc((void**)&c->d.expected, exp_bytes) == hipSuccess &&
+              hipMalloc((void**)&c->d.status, 64) == hipSuccess &&
+              hipMalloc((void**)&c->d.ll, ll_bytes) == hipSuccess &&
+              hipMalloc((void**)&c->moe_base, 64 * 4) == hipSuccess &&
+              hipMalloc((void**)&c->snap, 4096) == hipSuccess;
+    ok = ok && hipMemset(c->d.sem, 0, sem_bytes) == hipSuccess &&
+         hipMemset(c->d.expected, 0, exp_bytes) == hipSuccess &&
+         hipMemset(c->d.status, 0, 64) == hipSuccess &&
+         hipMemset(c->d.ll, 0, ll_bytes) == hipSuccess &&
+         hipMemset(c->moe_base, 0, 64 * 4) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) { destroy_ctx(c); t_hip_err = (int)hipErrorOutOfMemory; return MSX_ERR_NOMEM; }
+    c->d.ll_bytes = (unsigned)ll_bytes;
+    c->d.ll_rank_stride = (unsigned)rank_stride;
+    c->d.ll_rot_stride = (unsigned)rot;
+    g_ctx[dev] = c;
+    *out = c;
+    return MSX_OK;
+}
+
+// kernel-argument copy of the device context with the current test hooks applied
+DevCtx dev_ctx(const Ctx* c)
+{
+    DevCtx d = c->d;
+    d.spin_limit = g_opt.spin_limit;
+    d.drop_rank = g_opt.drop_rank;
+    d.chaos = g_opt.chaos;
+    return d;
+}
+
+unsigned next_flag(Ctx* c)
+{
+    if (++c->epoch == 0) c->epoch = 1;   // 0 is what untouched scratch holds
+    return c->epoch;
+}
+
+// how many workgroups of `threads` threads of kernel k can be resident on the whole GPU
+int resident_blocks(Ctx* c, const void* k, int threads, int* out)
+{
+    auto key = std::make_pair(k, threads);
+    auto it = c->occ.find(key);
+    int per_cu = 0;
+    if (it == c->occ.end()) {
+        HIPCHK(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k, threads, 0));
+        c->occ[key] = per_cu;
+    } else {
+        per_cu = it->second;
+    }
+    *out = per_cu * c->cus;
+    return MSX_OK;
+}
+
+// channels (workgroups per rank) for `work` items per rank handled `per_thread` at a time
+int pick_channels(Ctx* c, const void* k, int threads, int n, size_t work, size_t per_thread, int want,
+                  int cap, int* chans)
+{
+    int resident = 0;
+    int rc = resident_blocks(c, k, threads, &resident);
+    if (rc) return rc;
+    int limit = resident / n;
+    if (limit > kMaxChannels) limit = kMaxChannels;
+    if (limit < 1) return MSX_ERR_UNSUPPORTED;
+    int ch = want;
+    if (ch <= 0) {
+        const size_t per_block = (size_t)threads * per_thread;
+        size_t need = (work + per_block - 1) / per_block;
+        if (need < 1) need = 1;
+        ch = need > (size_t)cap ? cap : (int)need;
+    }
+    if (ch > limit) ch = limit;
+    *chans = ch;
+    return MSX_OK;
+}
+
+int check_common(int dtype, int op, int nranks)
+{
+    if (dtype != MSX_F32 && dtype != MSX_BF16) return MSX_ERR_ARG;
+    if (op != MSX_SUM) return MSX_ERR_UNSUPPORTED;
+    if (nranks < 1 || nranks > kMaxRanks) return MSX_ERR_ARG;
+    return MSX_OK;
+}
+
+int check_table(const void* const* t, int n)
+{
+    if (!t) return MSX_ERR_ARG;
+    for (int i = 0; i < n; ++i)
+        if (!t[i] || !aligned16(t[i])) return MSX_ERR_ARG;
+    return MSX_OK;
+}
+
+void note_launch(int grid, int block, int algo) { t_grid = grid; t_block = block; t_algo = algo; }
+
+template <typename K, typename... A>
+int launch(K k, int grid, int block, hipStream_t s, A... args)
+{
+    if (grid <= 0 || block <= 0) return MSX_ERR_ARG;
+    hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3((unsigned)block), 0, s, args...);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e);
+    return MSX_OK;
+}
+
+// ---- AllReduce ------------------------------------------------------------------------------
+
+typedef void (*HbKernel)(HbArgs, DevCtx);
+typedef void (*LlKernel)(LlArgs, DevCtx);
+
+HbKernel hb_fused_kernel(int dt, int u, int n)
+{
+#define MSX_ROW(DT, U) (n == 8 ? (HbKernel)k_allreduce_hb_fused<DT, U, 8> : (HbKernel)k_allreduce_hb_fused<DT, U, 0>)
+    if (dt == MSX_F32) return u >= 4 ? MSX_ROW(0, 4) : u == 2 ? MSX_ROW(0, 2) : MSX_ROW(0, 1);
+    return u >= 4 ? MSX_ROW(1, 4) : u == 2 ? MSX_ROW(1, 2) : MSX_ROW(1, 1);
+#undef MSX_ROW
+}
+HbKernel hb_2phase_kernel(int dt, int u, int n)
+{
+#define MSX_ROW(DT, U) (n == 8 ? (HbKernel)k_allreduce_hb_2phase<DT, U, 8> : (HbKernel)k_allreduce_hb_2phase<DT, U, 0>)
+    if (dt == MSX_F32) return u >= 2 ? MSX_ROW(0, 2) : MSX_ROW(0, 1);
+    return u >= 2 ? MSX_ROW(1, 2) : MSX_ROW(1, 1);
+#undef MSX_ROW
+}
+LlKernel ll_1pa_kernel(int dt, int n)
+{
+    if (dt == MSX_F32) return n == 8 ? (LlKernel)k_allreduce_1pa_ll<0, 8> : (LlKernel)k_allreduce_1pa_ll<0, 0>;
+    return n == 8 ? (LlKernel)k_allreduce_1pa_ll<1, 8> : (LlKernel)k_allreduce_1pa_ll<1, 0>;
+}
+LlKernel ll_2pa_kernel(int dt, int n)
+{
+    if (dt == MSX_F32) return n == 8 ? (LlKernel)k_allreduce_2pa_ll<0, 8> : (LlKernel)k_allreduce_2pa_ll<0, 0>;
+    return n == 8 ? (LlKernel)k_allreduce_2pa_ll<1, 8> : (LlKernel)k_allreduce_2pa_ll<1, 0>;
+}
+
+int ll_block_threads(size_t work)
+{
+    if (g_opt.threads > 0) {
+        int t = (g_opt.threads + 63) / 64 * 64;
+        return t > 1024 ? 1024 : t;
+    }
+    size_t t = (work + 63) / 64 * 64;
+    if (t < 64) t = 64;
+    if (t > 512) t = 512;
+    return (int)t;
+}
+
+int allreduce_impl(const void* const* send, void* const* recv, const void* const* residual, size_t count,
+                   int dtype, int op, int nranks, int algo, hipStream_t stream)
+{
+    int rc = check_common(dtype, op, nranks);
+    if (rc) return rc;
+    if (algo < MSX_ALGO_AUTO || algo > MSX_ALGO_2PA_HB_2PHASE) return MSX_ERR_ARG;
+    if ((rc = check_table(send, nranks))) return rc;
+    if ((rc = check_table((const void* const*)recv, nranks))) return rc;
+    if (residual && (rc = check_table(residual, nranks))) return rc;
+    if (count == 0) return MSX_OK;
+    const size_t nbytes = count * elem_size(dtype);
+
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    if ((rc = get_ctx(&c))) return rc;
+    const int n = nranks;
+
+    bool res_shared = residual != nullptr;
+    if (residual)
+        for (int i = 1; i < n; ++i) res_shared = res_shared && residual[i] == residual[0];
+
+    if (algo == MSX_ALGO_AUTO) algo = g_opt.algo;
+    if (algo == MSX_ALGO_AUTO) {
+        const size_t cap1 = c->ll_limit / 4, cap2 = c->ll_limit;
+        if (n == 1) algo = MSX_ALGO_2PA_HB;
+        else if (nbytes <= g_opt.ll_1pa_max && nbytes <= cap1) algo = MSX_ALGO_1PA_LL;
+        else if (nbytes <= g_opt.ll_2pa_max && nbytes <= cap2) algo = MSX_ALGO_2PA_LL;
+        else algo = MSX_ALGO_2PA_HB;
+    }
+
+    if (algo == MSX_ALGO_1PA_LL || algo == MSX_ALGO_2PA_LL) {
+        const size_t P = (nbytes + 7) / 8;
+        const size_t cp = (P + (size_t)n - 1) / (size_t)n;
+        const size_t need = algo == MSX_ALGO_1PA_LL ? (size_t)n * P * 16 : 2 * (size_t)n * cp * 16;
+        if (need > c->d.ll_rot_stride) return MSX_ERR_NOMEM;
+        const size_t work = algo == MSX_ALGO_1PA_LL ? P : cp;
+        LlKernel k = algo == MSX_ALGO_1PA_LL ? ll_1pa_kernel(dtype, n) : ll_2pa_kernel(dtype, n);
+        const int threads = ll_block_threads(work);
+        int chans = 1;
+        if ((rc = pick_channels(c, (const void*)k, threads, n, work, 1, g_opt.ll_blocks, 32, &chans))) return rc;
+        LlArgs a{};
+        for (int i = 0; i < n; ++i) {
+            a.in[i] = send[i];
+            a.out[i] = recv[i];
+            a.res[i] = residual ? residual[i] : nullptr;
+        }
+        a.nbytes = nbytes;
+        a.n = n;
+        a.chans = chans;
+        a.has_res = residual ? 1 : 0;
+        a.res_shared = res_shared ? 1 : 0;
+        a.flag = next_flag(c);
+        a.rot = c->calls++ & 1u;
+        note_launch(n * chans, threads, algo);
+        return launch(k, n * chans, threads, stream, a, dev_ctx(c));
+    }
+
+    // HB protocol
+    const int U = g_opt.hb_unroll;
+    if (algo == MSX_ALGO_2PA_HB_2PHASE && residual && !res_shared) return MSX_ERR_UNSUPPORTED;
+    HbKernel k = algo == MSX_ALGO_2PA_HB ? hb_fused_kernel(dtype, U, n) : hb_2phase_kernel(dtype, U, n);
+    const int threads = 256;
+    const size_t vecs = nbytes / 16;
+    const size_t per_rank = (vecs + (size_t)n - 1) / (size_t)n;
+    int chans = 1;
+    if ((rc = pick_channels(c, (const void*)k, threads, n, per_rank, (size_t)(U < 1 ? 1 : U), g_opt.hb_blocks,
+                            kMaxChannels, &chans)))
+        return rc;
+    HbArgs a{};
+    for (int i = 0; i < n; ++i) {
+        a.in[i] = send[i];
+        a.out[i] = recv[i];
+        a.res[i] = residual ? residual[i] : nullptr;
+    }
+    a.count = count;
+    a.n = n;
+    a.chans = chans;
+    a.has_res = residual ? 1 : 0;
+    a.res_shared = res_shared ? 1 : 0;
+    a.barriers = g_opt.hb_barriers;
+    a.peer_outer = g_opt.peer_outer;
+    note_launch(n * chans, threads, algo);
+    return launch(k, n * chans, threads, stream, a, dev_ctx(c));
+}
+
+// ---- the other HB collectives: a.count semantics differ per kernel -----------------------------
+
+enum HbOther { kRS, kAG, kA2A, kA2AInplace };
+
+int hb_other(HbOther which, const void* const* in, void* const* out, size_t count_or_bytes, int dtype,
+             int nranks, int vec, size_t work_units, hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = get_ctx(&c);
+    if (rc) return rc;
+    const int n = nranks, threads = 256;
+    const void* kp = nullptr;
+    switch (which) {
+        case kRS: kp = dtype == MSX_F32 ? (const void*)k_reducescatter_hb<0, 2> : (const void*)k_reducescatter_hb<1, 2>; break;
+        case kAG: kp = (const void*)k_allgather_hb; break;
+        case kA2A: kp = (const void*)k_alltoall_hb; break;
+        case kA2AInplace: kp = (const void*)k_alltoall_inplace; break;
+    }
+    int chans = 1;
+    if ((rc = pick_channels(c, kp, threads, n, work_units, 2, g_opt.hb_blocks, kMaxChannels, &chans))) return rc;
+    HbArgs a{};
+    for (int i = 0; i < n; ++i) {
+        a.in[i] = in ? in[i] : nullptr;
+        a.out[i] = out[i];
+    }
+    a.count = count_or_bytes;
+    a.n = n;
+    a.chans = chans;
+    a.barriers = g_opt.hb_barriers;
+    note_launch(n * chans, threads, MSX_ALGO_2PA_HB);
+    const DevCtx d = dev_ctx(c);
+    switch (which) {
+        case kRS:
+            if (dtype == MSX_F32) return launch(k_reducescatter_hb<0, 2>, n * chans, threads, stream, a, d, vec);
+            return launch(k_reducescatter_hb<1, 2>, n * chans, threads, stream, a, d, vec);
+        case kAG: return launch(k_allgather_hb, n * chans, threads, stream, a, d, vec);
+        case kA2A: return launch(k_alltoall_hb, n * chans, threads, stream, a, d, vec);
+        case kA2AInplace: return launch(k_alltoall_inplace, n * chans, threads, stream, a, d, vec);
+    }
+    return MSX_ERR_ARG;
+}
+
+bool parse_u64(const char* s, unsigned long long* v)
+{
+    if (!s || !*s) return false;
+    char* end = nullptr;
+    unsigned long long x = strtoull(s, &end, 10);
+    if (*end) return false;
+    *v = x;
+    return true;
+}
+
+}  // namespace
+
+// =============================================================================================
+// C ABI
+// =============================================================================================
+
+extern "C" {
+
+int msx_allreduce_ex(const void* const* send, void* const* recv, const void* const* residual, size_t count,
+                     int dtype, int op, int nranks, int algo, void* stream)
+{
+    return allreduce_impl(send, recv, residual, count, dtype, op, nranks, algo, (hipStream_t)stream);
+}
+
+int msx_allreduce(void* buf, size_t count, int dtype, int op, int nranks, void* stream)
+{
+    int rc = check_common(dtype, op, nranks);
+    if (rc) return rc;
+    if (count == 0) return MSX_OK;
+    if (!buf || !aligned16(buf)) return MSX_ERR_ARG;
+    const size_t row = count * elem_size(dtype);
+    if (nranks > 1 && (row & 15u)) return MSX_ERR_ARG;   // every row must start 16-byte aligned
+    const void* in[kMaxRanks];
+    void* out[kMaxRanks];
+    for (int r = 0; r < nranks; ++r) in[r] = out[r] = (char*)buf + (size_t)r * row;
+    return allreduce_impl(in, out, nullptr, count, dtype, op, nranks, MSX_ALGO_AUTO, (hipStream_t)stream);
+}
+
+int msx_reducescatter_ex(const void* const* send, void* const* recv, size_t count, int dtype, int op, int nranks,
+                         void* stream)
+{
+    int rc = check_common(dtype, op, nranks);
+    if (rc) return rc;
+    if ((rc = check_table(send, nranks))) return rc;
+    if (!recv) return MSX_ERR_ARG;
+    if (count % (size_t)nranks) return MSX_ERR_ARG;
+    if (count == 0) return MSX_OK;
+    const size_t c = count / (size_t)nranks, esz = elem_size(dtype);
+    int vec = (c * esz) % 16 == 0;
+    for (int r = 0; r < nranks; ++r) {
+        if (!recv[r]) return MSX_ERR_ARG;
+        if (!aligned16(recv[r])) vec = 0;
+        if ((uintptr_t)recv[r] % esz) return MSX_ERR_ARG;
+    }
+    const size_t work = vec ? c * esz / 16 : c;
+    return hb_other(kRS, send, recv, c, dtype, nranks, vec, work, (hipStream_t)stream);
+}
+
+int msx_reducescatter(void* buf, size_t count, int dtype, int op, int nranks, void* stream)
+{
+    int rc = check_common(dtype, op, nranks);
+    if (rc) return rc;
+    if (count % (size_t)nranks) return MSX_ERR_ARG;
+    if (count == 0) return MSX_OK;
+    if (!buf || !aligned16(buf)) return MSX_ERR_ARG;
+    const size_t esz = elem_size(dtype), row = count * esz, c = count / (size_t)nranks;
+    if (nranks > 1 && (row & 15u)) return MSX_ERR_ARG;
+    const void* in[kMaxRanks];
+    void* out[kMaxRanks];
+    for (int r = 0; r < nranks; ++r) {
+        in[r] = (char*)buf + (size_t)r * row;
+        out[r] = (char*)buf + (size_t)r * row + (size_t)r * c * esz;   // rank r's own share, in place
+    }
+    return msx_reducescatter_ex(in, out, count, dtype, op, nranks, stream);
+}
+
+int msx_allgather_ex(const void* const* send, void* const* recv, size_t count, int dtype, int nranks, void* stream)
+{
+    int rc = check_common(dtype, MSX_SUM, nranks);
+    if (rc) return rc;
+    if (!send || !recv) return MSX_ERR_ARG;
+    if (count == 0) return MSX_OK;
+    const size_t nbytes = count * elem_size(dtype);
+    int vec = nbytes % 16 == 0;
+    for (int r = 0; r < nranks; ++r) {
+        if (!send[r] || !recv[r]) return MSX_ERR_ARG;
+        if (!aligned16(send[r]) || !aligned16(recv[r])) vec = 0;
+    }
+    const size_t work = vec ? nbytes / 16 : nbytes;
+    return hb_other(kAG, send, recv, nbytes, dtype, nranks, vec, work, (hipStream_t)stream);
+}
+
+int msx_allgather(void* buf, size_t count, int dtype, int op, int nranks, void* stream)
+{
+    (void)op;
+    int rc = check_common(dtype, MSX_SUM, nranks);
+    if (rc) return rc;
+    if (count == 0) return MSX_OK;
+    if (!buf) return MSX_ERR_ARG;
+    const size_t nbytes = count * elem_size(dtype), row = nbytes * (size_t)nranks;
+    const void* in[kMaxRanks];
+    void* out[kMaxRanks];
+    for (int r = 0; r < nranks; ++r) {
+        out[r] = (char*)buf + (size_t)r * row;
+        in[r] = (char*)out[r] + (size_t)r * nbytes;   // rank r's contribution already sits in its slot
+    }
+    return msx_allgather_ex(in, out, count, dtype, nranks, stream);
+}
+
+int msx_alltoall_ex(const void* const* send, void* const* recv, size_t count, int dtype, int nranks, void* stream)
+{
+    int rc = check_common(dtype, MSX_SUM, nranks);
+    if (rc) return rc;
+    if (!send || !recv) return MSX_ERR_ARG;
+    if (count % (size_t)nranks) return MSX_ERR_ARG;
+    if (count == 0) return MSX_OK;
+    const size_t row = count * elem_size(dtype);
+    const size_t nbytes = row / (size_t)nranks;
+    int vec = nbytes % 16 == 0;
+    for (int r = 0; r < nranks; ++r) {
+        if (!send[r] || !recv[r]) return MSX_ERR_ARG;
+        if (!aligned16(send[r]) || !aligned16(recv[r])) vec = 0;
+        for (int q = 0; q < nranks; ++q) {   // send and recv must not overlap
+            const char *s0 = (const char*)send[q], *r0 = (const char*)recv[r];
+            if (s0 < r0 + row && r0 < s0 + row) return MSX_ERR_ARG;
+        }
+    }
+    const size_t work = vec ? nbytes / 16 : nbytes;
+    return hb_other(kA2A, send, recv, nbytes, dtype, nranks, vec, work, (hipStream_t)stream);
+}
+
+int msx_alltoall(void* buf, size_t count, int dtype, int op, int nranks, void* stream)
+{
+    (void)op;
+    int rc = check_common(dtype, MSX_SUM, nranks);
+    if (rc) return rc;
+    if (count % (size_t)nranks) return MSX_ERR_ARG;
+    if (count == 0) return MSX_OK;
+    if (!buf) return MSX_ERR_ARG;
+    const size_t row = count * elem_size(dtype), nbytes = row / (size_t)nranks;
+    void* out[kMaxRanks];
+    for (int r = 0; r < nranks; ++r) out[r] = (char*)buf + (size_t)r * row;
+    const int vec = aligned16(buf) && nbytes % 16 == 0;
+    const size_t work = (vec ? nbytes / 16 : nbytes) * (size_t)(nranks > 1 ? nranks - 1 : 1) / 2 + 1;
+    return hb_other(kA2AInplace, nullptr, out, nbytes, dtype, nranks, vec, work, (hipStream_t)stream);
+}
+
+int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, int T, int H, int K, int n_experts,
+                     int dtype, int nranks, void* const* recv_tokens, int32_t* const* recv_src_token,
+                     int32_t* recv_counts, size_t recv_capacity_tokens, void* stream)
+{
+    int rc = check_common(dtype, MSX_SUM, nranks);
+    if (rc) return rc;
+    if ((rc = check_table(tokens, nranks))) return rc;
+    if ((rc = check_table((const void* const*)topk_idx, nranks))) return rc;
+    if ((rc = check_table((const void* const*)recv_tokens, nranks))) return rc;
+    if (!recv_counts) return MSX_ERR_ARG;
+    if (recv_src_token)
+        for (int r = 0; r < nranks; ++r)
+            if (!recv_src_token[r]) return MSX_ERR_ARG;
+    if (T < 0 || H <= 0 || K <= 0 || K > 32 || n_experts <= 0 || n_experts % nranks) return MSX_ERR_ARG;
+    if (T > 65534) return MSX_ERR_UNSUPPORTED;
+    const size_t row_bytes = (size_t)H * elem_size(dtype);
+    if (row_bytes % 16) return MSX_ERR_ARG;
+    if (recv_capacity_tokens > 0xffffffffull) recv_capacity_tokens = 0xffffffffull;
+    const hipStream_t s = (hipStream_t)stream;
+
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    if ((rc = get_ctx(&c))) return rc;
+    const int n = nranks;
+    const size_t need = (size_t)kMaxRanks * (size_t)(T > 0 ? T : 1) * 16;
+    if (need > c->moe_slots_bytes) {
+        if (c->moe_slots) { HIPCHK(hipDeviceSynchronize()); HIPCHK(hipFree(c->moe_slots)); c->moe_slots = nullptr; c->moe_slots_bytes = 0; }
+        HIPCHK(hipMalloc(&c->moe_slots, need));
+        c->moe_slots_bytes = need;
+    }
+    MoeArgs a{};
+    for (int i = 0; i < n; ++i) {
+        a.tokens[i] = tokens[i];
+        a.topk[i] = topk_idx[i];
+        a.recv[i] = recv_tokens[i];
+        a.recv_src[i] = recv_src_token ? recv_src_token[i] : nullptr;
+    }
+    a.recv_counts = recv_counts;
+    a.slots = (unsigned short*)c->moe_slots;
+    a.base = c->moe_base;
+    a.T = T;
+    a.K = K;
+    a.n = n;
+    a.per_rank = n_experts / n;
+    a.n_experts = n_experts;
+    a.row_vecs = (unsigned)(row_bytes / 16);
+    a.cap = (unsigned)recv_capacity_tokens;
+    a.has_src = recv_src_token ? 1 : 0;
+    a.flag = next_flag(c);
+    a.rot = c->calls++ & 1u;
+    const DevCtx d = dev_ctx(c);
+
+    int resident = 0;
+    if ((rc = resident_blocks(c, (const void*)k_moe_plan, kPlanThreads, &resident))) return rc;
+    if (resident < n) return MSX_ERR_UNSUPPORTED;
+    a.chans = 1;
+    if ((rc = launch(k_moe_plan, n, kPlanThreads, s, a, d))) return rc;
+
+    int chans = 1;
+    if ((rc = pick_channels(c, (const void*)k_moe_pack, 256, n, (size_t)T, 1, g_opt.hb_blocks, kMaxChannels, &chans)))
+        return rc;   // work unit: one wave per token, 4 waves per workgroup
+    a.chans = chans;
+    note_launch(n * chans, 256, MSX_ALGO_2PA_HB);
+    return launch(k_moe_pack, n * chans, 256, s, a, d);
+}
+
+// ---- primitives -------------------------------------------------------------------------------
+
+int msx_prim_pingpong(int iters, int grid_blocks, int block_a, int block_b, double* ns_out, void* stream)
+{
+    if (iters < 0 || grid_blocks < 2 || block_a < 0 || block_b < 0 || block_a >= grid_blocks ||
+        block_b >= grid_blocks || block_a == block_b || !ns_out)
+        return MSX_ERR_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = get_ctx(&c);
+    if (rc) return rc;
+    int resident = 0;
+    if ((rc = resident_blocks(c, (const void*)k_pingpong, 64, &resident))) return rc;
+    if (grid_blocks > resident) return MSX_ERR_ARG;
+    note_launch(grid_blocks, 64, 0);
+    return launch(k_pingpong, grid_blocks, 64, (hipStream_t)stream, dev_ctx(c), iters, block_a, block_b,
+                  c->ns_per_tick, ns_out);
+}
+
+int msx_prim_barrier(int rounds, int nranks, int blocks_per_rank, uint32_t* sem_out, void* stream)
+{
+    if (rounds < 0 || nranks < 1 || nranks > kMaxRanks || blocks_per_rank < 1 || blocks_per_rank > kMaxChannels)
+        return MSX_ERR_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = get_ctx(&c);
+    if (rc) return rc;
+    int resident = 0;
+    if ((rc = resident_blocks(c, (const void*)k_barrier_rounds, 256, &resident))) return rc;
+    if (nranks * blocks_per_rank > resident) return MSX_ERR_ARG;
+    const DevCtx d = dev_ctx(c);
+    if (rounds > 0 && nranks > 1) {
+        note_launch(nranks * blocks_per_rank, 256, 0);
+        if ((rc = launch(k_barrier_rounds, nranks * blocks_per_rank, 256, (hipStream_t)stream, d, nranks, rounds)))
+            return rc;
+    }
+    if (sem_out) return launch(k_sem_snapshot, 1, 64, (hipStream_t)stream, d, nranks, (unsigned*)sem_out);
+    return MSX_OK;
+}
+
+int msx_prim_put_signal_wait(const void* src, void* staging, void* dst, size_t nbytes, int blocks_per_rank,
+                             void* stream)
+{
+    if (!src || !staging || !dst || !aligned16(src) || !aligned16(staging) || !aligned16(dst)) return MSX_ERR_ARG;
+    if (blocks_per_rank < 1 || blocks_per_rank > kMaxChannels) return MSX_ERR_ARG;
+    if (nbytes == 0) return MSX_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = get_ctx(&c);
+    if (rc) return rc;
+    int resident = 0;
+    if ((rc = resident_blocks(c, (const void*)k_put_signal_wait, 256, &resident))) return rc;
+    if (2 * blocks_per_rank > resident) return MSX_ERR_ARG;
+    note_launch(2 * blocks_per_rank, 256, 0);
+    return launch(k_put_signal_wait, 2 * blocks_per_rank, 256, (hipStream_t)stream, dev_ctx(c), src, staging, dst,
+                  nbytes, blocks_per_rank);
+}
+
+int msx_prim_ll_encode(const void* src, size_t nbytes, uint32_t flag, void* packets_out, void* stream)
+{
+    if (nbytes == 0) return MSX_OK;
+    if (!src || !packets_out || !aligned16(packets_out)) return MSX_ERR_ARG;
+    const size_t P = (nbytes + 7) / 8;
+    size_t grid = (P + 255) / 256;
+    if (grid > 1024) grid = 1024;
+    note_launch((int)grid, 256, 0);
+    return launch(k_ll_encode, (int)grid, 256, (hipStream_t)stream, src, nbytes, (unsigned)flag, (u32x4*)packets_out);
+}
+
+int msx_prim_ll_roundtrip(const void* src, void* dst, size_t nbytes, int blocks_per_rank, void* stream)
+{
+    if (nbytes == 0) return MSX_OK;
+    if (!src || !dst) return MSX_ERR_ARG;
+    if (blocks_per_rank < 1 || blocks_per_rank > kMaxChannels) return MSX_ERR_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = get_ctx(&c);
+    if (rc) return rc;
+    const size_t P = (nbytes + 7) / 8;
+    if (P * 16 > c->d.ll_rot_stride) return MSX_ERR_NOMEM;
+    int resident = 0;
+    if ((rc = resident_blocks(c, (const void*)k_ll_roundtrip, 256, &resident))) return rc;
+    if (2 * blocks_per_rank > resident) return MSX_ERR_ARG;
+    const unsigned flag = next_flag(c);
+    const unsigned rot = c->calls++ & 1u;
+    note_launch(2 * blocks_per_rank, 256, 0);
+    return launch(k_ll_roundtrip, 2 * blocks_per_rank, 256, (hipStream_t)stream, dev_ctx(c), src, dst, nbytes,
+                  blocks_per_rank, flag, rot);
+}
+
+// ---- context, options, status ---------------------------------------------------------------
+
+int msx_init(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    return get_ctx(&c);
+}
+
+int msx_reset(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = get_ctx(&c);
+    if (rc) return rc;
+    HIPCHK(hipDeviceSynchronize());
+    HIPCHK(hipMemset(c->d.sem, 0, (size_t)kMaxRanks * kMaxRanks * kMaxChannels * kSemStrideWords * 4));
+    HIPCHK(hipMemset(c->d.expected, 0, (size_t)kMaxRanks * kMaxRanks * kMaxChannels * 4));
+    HIPCHK(hipMemset(c->d.status, 0, 64));
+    HIPCHK(hipMemset(c->d.ll, 0, c->d.ll_bytes));
+    HIPCHK(hipDeviceSynchronize());
+    c->epoch = 0;
+    c->calls = 0;
+    return MSX_OK;
+}
+
+int msx_finalize(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return MSX_ERR_ARG;
+    Ctx* c = g_ctx[dev];
+    g_ctx[dev] = nullptr;
+    return destroy_ctx(c);
+}
+
+int msx_set_option(const char* key, const char* value)
+{
+    if (!key || !value) return MSX_ERR_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    const std::string k(key), v(value);
+    unsigned long long u = 0;
+    if (k == "algo") {
+        if (v == "auto") g_opt.algo = MSX_ALGO_AUTO;
+        else if (v == "1pa_ll") g_opt.algo = MSX_ALGO_1PA_LL;
+        else if (v == "2pa_ll") g_opt.algo = MSX_ALGO_2PA_LL;
+        else if (v == "2pa_hb") g_opt.algo = MSX_ALGO_2PA_HB;
+        else if (v == "2pa_hb_2phase") g_opt.algo = MSX_ALGO_2PA_HB_2PHASE;
+        else return MSX_ERR_ARG;
+        return MSX_OK;
+    }
+    if (k == "drop_rank") {
+        if (v == "-1") { g_opt.drop_rank = -1; return MSX_OK; }
+        if (!parse_u64(value, &u) || u >= (unsigned)kMaxRanks) return MSX_ERR_ARG;
+        g_opt.drop_rank = (int)u;
+        return MSX_OK;
+    }
+    if (!parse_u64(value, &u)) return MSX_ERR_ARG;
+    if (k == "ll_1pa_max_bytes") g_opt.ll_1pa_max = (size_t)u;
+    else if (k == "ll_2pa_max_bytes") g_opt.ll_2pa_max = (size_t)u;
+    else if (k == "ll_max_bytes") {
+        if (u < 4096 || u > (16u << 20)) return MSX_ERR_ARG;
+        g_opt.ll_max_bytes = (size_t)u;
+    } else if (k == "hb_blocks_per_rank") {
+        if (u > (unsigned)kMaxChannels) return MSX_ERR_ARG;
+        g_opt.hb_blocks = (int)u;
+    } else if (k == "ll_blocks_per_rank") {
+        if (u > (unsigned)kMaxChannels) return MSX_ERR_ARG;
+        g_opt.ll_blocks = (int)u;
+    } else if (k == "threads") {
+        if (u > 1024) return MSX_ERR_ARG;
+        g_opt.threads = (int)u;
+    } else if (k == "hb_unroll") {
+        if (u != 1 && u != 2 && u != 4) return MSX_ERR_ARG;
+        g_opt.hb_unroll = (int)u;
+    } else if (k == "hb_barriers") {
+        if (u > 1) return MSX_ERR_ARG;
+        g_opt.hb_barriers = (int)u;
+    } else if (k == "peer_outer") {
+        if (u > 1) return MSX_ERR_ARG;
+        g_opt.peer_outer = (int)u;
+    } else if (k == "spin_limit") {
+        if (u < 1 || u > 0x7fffffffu) return MSX_ERR_ARG;
+        g_opt.spin_limit = (unsigned)u;
+    } else if (k == "chaos") {
+        g_opt.chaos = (unsigned)u;
+    } else if (k == "epoch") {
+        Ctx* c = nullptr;
+        int rc = get_ctx(&c);
+        if (rc) return rc;
+        c->epoch = (unsigned)u - 1u;   // the next call uses exactly u (or 1 if u is 0)
+    } else if (k == "sem_base") {
+        Ctx* c = nullptr;
+        int rc = get_ctx(&c);
+        if (rc) return rc;
+        HIPCHK(hipDeviceSynchronize());
+        const size_t ns = (size_t)kMaxRanks * kMaxRanks * kMaxChannels;
+        unsigned* host = (unsigned*)malloc(ns * kSemStrideWords * 4);
+        if (!host) return MSX_ERR_NOMEM;
+        for (size_t i = 0; i < ns * kSemStrideWords; ++i) host[i] = (unsigned)u;
+        hipError_t e1 = hipMemcpy(c->d.sem, host, ns * kSemStrideWords * 4, hipMemcpyHostToDevice);
+        hipError_t e2 = hipMemcpy(c->d.expected, host, ns * 4, hipMemcpyHostToDevice);
+        free(host);
+        HIPCHK(e1);
+        HIPCHK(e2);
+        HIPCHK(hipDeviceSynchronize());
+    } else {
+        return MSX_ERR_ARG;
+    }
+    return MSX_OK;
+}
+
+int msx_get_option(const char* key, char* value_out, size_t value_len)
+{
+    if (!key || !value_out || value_len == 0) return MSX_ERR_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    const std::string k(key);
+    unsigned long long u = 0;
+    if (k == "algo") {
+        static const char* names[] = {"auto", "1pa_ll", "2pa_ll", "2pa_hb", "2pa_hb_2phase"};
+        snprintf(value_out, value_len, "%s", names[g_opt.algo]);
+        return MSX_OK;
+    }
+    if (k == "drop_rank") { snprintf(value_out, value_len, "%d", g_opt.drop_rank); return MSX_OK; }
+    if (k == "ll_1pa_max_bytes") u = g_opt.ll_1pa_max;
+    else if (k == "ll_2pa_max_bytes") u = g_opt.ll_2pa_max;
+    else if (k == "ll_max_bytes") {
+        int dev = 0;
+        u = g_opt.ll_max_bytes;
+        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && g_ctx[dev]) u = g_ctx[dev]->ll_limit;
+    } else if (k == "hb_blocks_per_rank") u = (unsigned)g_opt.hb_blocks;
+    else if (k == "ll_blocks_per_rank") u = (unsigned)g_opt.ll_blocks;
+    else if (k == "threads") u = (unsigned)g_opt.threads;
+    else if (k == "hb_unroll") u = (unsigned)g_opt.hb_unroll;
+    else if (k == "hb_barriers") u = (unsigned)g_opt.hb_barriers;
+    else if (k == "peer_outer") u = (unsigned)g_opt.peer_outer;
+    else if (k == "spin_limit") u = g_opt.spin_limit;
+    else if (k == "chaos") u = g_opt.chaos;
+    else if (k == "epoch") {
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && g_ctx[dev]) u = g_ctx[dev]->epoch;
+    } else return MSX_ERR_ARG;
+    snprintf(value_out, value_len, "%llu", u);
+    return MSX_OK;
+}
+
+int msx_status(void* stream, uint32_t info[6])
+{
+    HIPCHK(hipStreamSynchronize((hipStream_t)stream));
+    std::lock_guard<std::mutex> lk(g_mu);
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return MSX_ERR_ARG;
+    Ctx* c = g_ctx[dev];
+    uint32_t h[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (c) {
+        HIPCHK(hipMemcpy(h, c->d.status, 32, hipMemcpyDeviceToHost));
+        if (h[0] != 0) HIPCHK(hipMemset(c->d.status, 0, 32));
+    }
+    if (info)
+        for (int i = 0; i < 6; ++i) info[i] = h[i];
+    if (h[0] == kStatusTimeout) return MSX_ERR_TIMEOUT;
+    if (h[0] == kStatusCapacity) return MSX_ERR_CAPACITY;
+    return MSX_OK;
+}
+
+int msx_last_launch(int* grid, int* block, int* algo)
+{
+    if (grid) *grid = t_grid;
+    if (block) *block = t_block;
+    if (algo) *algo = t_algo;
+    return MSX_OK;
+}
+
+int msx_last_hip_error(void) { return t_hip_err; }
+
+const char* msx_strerror(int err)
+{
+    switch (err) {
+        case MSX_OK: return "ok";
+        case MSX_ERR_ARG: return "invalid argument";
+        case MSX_ERR_UNSUPPORTED: return "unsupported request";
+        case MSX_ERR_HIP: return "HIP runtime error";
+        case MSX_ERR_TIMEOUT: return "device-side wait timed out";
+        case MSX_ERR_NOMEM: return "scratch too small or allocation failed";
+        case MSX_ERR_CAPACITY: return "token dispatch receive buffer overflow";
+        default: return "unknown error";
+    }
+}
+
+const char* msx_version(void) { return "msx 0.1 (gfx950)"; }
+
+}  // extern "C"

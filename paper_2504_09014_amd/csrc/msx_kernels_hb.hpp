@@ -1,0 +1,347 @@
+// HB-protocol kernels: two-phase all-pairs AllReduce (fused and two-phase), standalone
+// ReduceScatter / AllGather / AllToAll.  Collectives Library section (2PA) and the
+// MemoryChannel HB protocol: move large chunks with 16-byte accesses and synchronise once
+// per chunk.  One workgroup set per rank; a thread reads the same vector from ALL ranks at
+// once (no per-peer synchronisation inside the reduction) and, following the paper's
+// note for peer-to-peer meshes, writes to all peers inside the element loop.
+#pragma once
+#include "msx_device.hpp"
+
+namespace msx {
+
+struct HbArgs {
+    const void* in[kMaxRanks];
+    void* out[kMaxRanks];
+    const void* res[kMaxRanks];
+    size_t count;       // elements per rank (allreduce) / per block (others)
+    int n;              // ranks
+    int chans;          // workgroups per rank
+    int has_res;        // add a residual
+    int res_shared;     // all residual pointers are the same buffer
+    int barriers;       // run the start / end rank barriers
+    int peer_outer;     // two-phase all-gather: one hb_put per peer instead of peer-inner
+};
+
+template <int DT> __device__ __forceinline__ float load_elem(const void* p, size_t e)
+{
+    if constexpr (DT == 0) return ((const float*)p)[e];
+    else return __uint_as_float((unsigned)((const unsigned short*)p)[e] << 16);
+}
+template <int DT> __device__ __forceinline__ void store_elem(void* p, size_t e, float v)
+{
+    if constexpr (DT == 0) ((float*)p)[e] = v;
+    else ((unsigned short*)p)[e] = (unsigned short)bf16_round(v);
+}
+
+// Elements past the last whole 16-byte vector: summed and written to every rank by the
+// first threads of rank 0, channel 0.
+template <int DT>
+__device__ __forceinline__ void allreduce_tail(const HbArgs& a, int n, size_t first, size_t count)
+{
+    for (size_t e = first + threadIdx.x; e < count; e += blockDim.x) {
+        float acc = load_elem<DT>(a.in[0], e);
+#pragma unroll
+        for (int j = 1; j < kMaxRanks; ++j)
+            if (j < n) acc += load_elem<DT>(a.in[j], e);
+        float r[kMaxRanks];
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p)
+            r[p] = (p < n && a.has_res) ? load_elem<DT>(a.res[a.res_shared ? 0 : p], e) : 0.0f;
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p)
+            if (p < n) store_elem<DT>(a.out[p], e, a.has_res ? acc + r[p] : acc);
+    }
+}
+
+// Sum of vector idx over all ranks in rank order, from registers loaded up front.
+#define MSX_LOAD_ALL(v, ptrs, idx)                                   \
+    _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)            \
+        if (j < n) v[j] = ld16(ptrs[j], idx);
+
+#define MSX_SUM_ALL(acc, v)                                          \
+    acc.set(v[0]);                                                   \
+    _Pragma("unroll") for (int j = 1; j < kMaxRanks; ++j)            \
+        if (j < n) acc.add(v[j]);
+
+// ---- fused two-phase all-pairs: reduce chunk `rank` in registers and put it to everyone ----
+// (reduce-scatter chunk-sum feeding the all-gather copy with no memory round trip; the
+// fused "reduce then put" operation of the DSL's Operation Fusion paragraph, widened from
+// two local buffers to all N ranks.)  In place is safe: chunk r of every row is read and
+// written by rank r's threads only, and a thread loads all N values before it stores.
+template <int DT, int U, int NR>
+__global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
+{
+    const int n = NR ? NR : a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    constexpr size_t epv = DT == 0 ? 4 : 8;
+    const size_t V = a.count / epv;
+
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 10);   // every peer's input is ready
+
+    const size_t lo = V * (size_t)rank / (size_t)n;
+    const size_t hi = V * (size_t)(rank + 1) / (size_t)n;
+    const size_t RT = (size_t)a.chans * blockDim.x;
+    const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
+
+    for (size_t i = lo + rt; i < hi; i += RT * U) {
+        u32x4 v[U][kMaxRanks];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t idx = i + (size_t)u * RT;
+            if (idx < hi) { MSX_LOAD_ALL(v[u], a.in, idx) }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t idx = i + (size_t)u * RT;
+            if (idx < hi) {
+                VecAcc<DT> acc;
+                MSX_SUM_ALL(acc, v[u])
+                if (!a.has_res || a.res_shared) {
+                    if (a.has_res) acc.add(ld16(a.res[0], idx));
+                    const u32x4 o = acc.pack();
+#pragma unroll
+                    for (int p = 0; p < kMaxRanks; ++p)
+                        if (p < n) st16(a.out[p], idx, o);
+                } else {
+#pragma unroll
+                    for (int p = 0; p < kMaxRanks; ++p)
+                        if (p < n) {
+                            VecAcc<DT> t = acc;
+                            t.add(ld16(a.res[p], idx));
+                            st16(a.out[p], idx, t.pack());
+                        }
+                }
+            }
+        }
+    }
+    if (rank == 0 && chan == 0) allreduce_tail<DT>(a, n, V * epv, a.count);
+
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 11);   // every peer's puts into my output landed
+}
+
+// ---- two-phase form: reduce-scatter to memory, rank barrier, all-gather by put ---------------
+template <int DT, int U, int NR>
+__global__ __launch_bounds__(256) void k_allreduce_hb_2phase(HbArgs a, DevCtx c)
+{
+    const int n = NR ? NR : a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    constexpr size_t epv = DT == 0 ? 4 : 8;
+    const size_t V = a.count / epv;
+
+    if (n > 1) rank_barrier(c, rank, n, chan, 20);
+
+    const size_t lo = V * (size_t)rank / (size_t)n;
+    const size_t hi = V * (size_t)(rank + 1) / (size_t)n;
+    const size_t RT = (size_t)a.chans * blockDim.x;
+    const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
+
+    // phase 1: chunk-sum into my own output
+    for (size_t i = lo + rt; i < hi; i += RT * U) {
+        u32x4 v[U][kMaxRanks];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t idx = i + (size_t)u * RT;
+            if (idx < hi) { MSX_LOAD_ALL(v[u], a.in, idx) }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t idx = i + (size_t)u * RT;
+            if (idx < hi) {
+                VecAcc<DT> acc;
+                MSX_SUM_ALL(acc, v[u])
+                if (a.has_res) acc.add(ld16(a.res[0], idx));   // shared residual only (host checks)
+                st16(a.out[rank], idx, acc.pack());
+            }
+        }
+    }
+
+    // phase boundary: all ranks have finished reading the inputs (so an in-place all-gather
+    // may overwrite them) and have their chunk reduced
+    if (n > 1) rank_barrier(c, rank, n, chan, 21);
+
+    // phase 2: put my reduced chunk into every peer's output
+    if (a.peer_outer) {
+        const char* src = (const char*)a.out[rank] + lo * 16;
+        for (int k = 1; k < n; ++k) {
+            int p = rank + k; if (p >= n) p -= n;
+            hb_put((char*)a.out[p] + lo * 16, src, (hi - lo) * 16, rt, RT);
+        }
+    } else {
+        for (size_t idx = lo + rt; idx < hi; idx += RT) {
+            const u32x4 o = ld16(a.out[rank], idx);
+#pragma unroll
+            for (int p = 0; p < kMaxRanks; ++p)
+                if (p < n && p != rank) st16(a.out[p], idx, o);
+        }
+    }
+    if (rank == 0 && chan == 0) allreduce_tail<DT>(a, n, V * epv, a.count);
+
+    if (n > 1) rank_barrier(c, rank, n, chan, 22);
+}
+
+// ---- standalone ReduceScatter: out[r][k] = sum_j in[j][r*c + k], k < c = count ---------------
+// a.count is c (elements per block); a.in[j] is rank j's full row; a.out[r] points at the c
+// results of rank r.  vec != 0 when c*elemsize is a multiple of 16 (so every block is
+// 16-byte aligned); otherwise an element-wise path is used.
+template <int DT, int U>
+__global__ __launch_bounds__(256) void k_reducescatter_hb(HbArgs a, DevCtx c, int vec)
+{
+    const int n = a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    constexpr size_t epv = DT == 0 ? 4 : 8;
+    constexpr size_t esz = DT == 0 ? 4 : 2;
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 30);
+    const size_t RT = (size_t)a.chans * blockDim.x;
+    const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
+    const size_t blk = a.count;
+    if (vec) {
+        const size_t cv = blk / epv;
+        const void* src[kMaxRanks];
+#pragma unroll
+        for (int j = 0; j < kMaxRanks; ++j) src[j] = j < n ? (const char*)a.in[j] + (size_t)rank * blk * esz : nullptr;
+        for (size_t i = rt; i < cv; i += RT * U) {
+            u32x4 v[U][kMaxRanks];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const size_t idx = i + (size_t)u * RT;
+                if (idx < cv) { MSX_LOAD_ALL(v[u], src, idx) }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const size_t idx = i + (size_t)u * RT;
+                if (idx < cv) {
+                    VecAcc<DT> acc;
+                    MSX_SUM_ALL(acc, v[u])
+                    st16(a.out[rank], idx, acc.pack());
+                }
+            }
+        }
+    } else {
+        for (size_t k = rt; k < blk; k += RT) {
+            const size_t e = (size_t)rank * blk + k;
+            float acc = load_elem<DT>(a.in[0], e);
+            for (int j = 1; j < n; ++j) acc += load_elem<DT>(a.in[j], e);
+            store_elem<DT>(a.out[rank], k, acc);
+        }
+    }
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 31);   // peers are done reading my input
+}
+
+// ---- standalone AllGather: out[p] block r = in[r]; a.count = bytes per block ------------------
+// Put-based: rank r reads its block once and writes it into every rank's output (peer loop
+// inside the element loop).  A destination equal to the source (in-place) is skipped.
+__global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int vec)
+{
+    const int n = a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    const size_t RT = (size_t)a.chans * blockDim.x;
+    const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
+    const size_t nbytes = a.count;
+    const char* src = (const char*)a.in[rank];
+    char* dst[kMaxRanks];
+#pragma unroll
+    for (int p = 0; p < kMaxRanks; ++p) dst[p] = p < n ? (char*)a.out[p] + (size_t)rank * nbytes : nullptr;
+    if (vec) {
+        const size_t nv = nbytes >> 4;
+        for (size_t i = rt; i < nv; i += RT * 2) {
+            const size_t i1 = i + RT;
+            const u32x4 v0 = ld16(src, i);
+            u32x4 v1 = v0;
+            if (i1 < nv) v1 = ld16(src, i1);
+#pragma unroll
+            for (int p = 0; p < kMaxRanks; ++p)
+                if (p < n && dst[p] != src) {
+                    st16(dst[p], i, v0);
+                    if (i1 < nv) st16(dst[p], i1, v1);
+                }
+        }
+    } else {
+        for (size_t b = rt; b < nbytes; b += RT) {
+            const char v = src[b];
+            for (int p = 0; p < n; ++p)
+                if (dst[p] != src) dst[p][b] = v;
+        }
+    }
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 40);   // all blocks have landed in my output
+}
+
+// ---- standalone AllToAll (out of place): out[d] block s = in[s] block d; a.count = bytes/block ---
+__global__ __launch_bounds__(256) void k_alltoall_hb(HbArgs a, DevCtx c, int vec)
+{
+    const int n = a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    const size_t RT = (size_t)a.chans * blockDim.x;
+    const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
+    const size_t nbytes = a.count;
+    const char* src = (const char*)a.in[rank];
+    if (vec) {
+        const size_t nv = nbytes >> 4;
+        for (size_t i = rt; i < nv; i += RT) {
+            u32x4 v[kMaxRanks];
+#pragma unroll
+            for (int d = 0; d < kMaxRanks; ++d)
+                if (d < n) v[d] = ld16(src + (size_t)d * nbytes, i);
+#pragma unroll
+            for (int d = 0; d < kMaxRanks; ++d)
+                if (d < n) st16((char*)a.out[d] + (size_t)rank * nbytes, i, v[d]);
+        }
+    } else {
+        for (int d = 0; d < n; ++d) {
+            char* dp = (char*)a.out[d] + (size_t)rank * nbytes;
+            const char* sp = src + (size_t)d * nbytes;
+            for (size_t b = rt; b < nbytes; b += RT) dp[b] = sp[b];
+        }
+    }
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 50);
+}
+
+// ---- AllToAll in place: block (s,d) and block (d,s) swap through registers --------------------
+// For a pair s<d the lower rank swaps the first half of the vectors and the higher rank the
+// second half, so each vector of each pair is loaded and stored by exactly one thread.
+__global__ __launch_bounds__(256) void k_alltoall_inplace(HbArgs a, DevCtx c, int vec)
+{
+    const int n = a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 60);
+    const size_t RT = (size_t)a.chans * blockDim.x;
+    const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
+    const size_t nbytes = a.count;
+    const size_t units = vec ? (nbytes >> 4) : nbytes;
+    const size_t half = units / 2;
+    for (int k = 1; k < n; ++k) {
+        int peer = rank + k; if (peer >= n) peer -= n;
+        const size_t lo = rank < peer ? 0 : half;
+        const size_t hi = rank < peer ? half : units;
+        char* mine = (char*)a.out[rank] + (size_t)peer * nbytes;
+        char* theirs = (char*)a.out[peer] + (size_t)rank * nbytes;
+        if (vec) {
+            for (size_t i = lo + rt; i < hi; i += RT) {
+                const u32x4 x = ld16(mine, i);
+                const u32x4 y = ld16(theirs, i);
+                st16(mine, i, y);
+                st16(theirs, i, x);
+            }
+        } else {
+            for (size_t b = lo + rt; b < hi; b += RT) {
+                const char x = mine[b], y = theirs[b];
+                mine[b] = y;
+                theirs[b] = x;
+            }
+        }
+    }
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 61);
+}
+
+}  // namespace msx

@@ -1,0 +1,212 @@
+// LL-protocol AllReduce kernels: one-phase all-pairs (1PA) and two-phase all-pairs (2PA)
+// over 16-byte packets {w0, flag, w1, flag} in each receiver's scratch.  Collectives
+// Library section (1PA, 2PA with rotating buffers) and MemoryChannel LL protocol.
+//
+// No semaphore and no fence is used here: a packet is complete when both flags match.
+// A thread always works on the same packet index in every phase, so no workgroup barrier
+// is needed either.  The scratch has two rotating halves (picked by the call counter) so a
+// rank may start the next call while a slow peer still reads the previous call's packets.
+#pragma once
+#include "msx_device.hpp"
+
+namespace msx {
+
+struct LlArgs {
+    const void* in[kMaxRanks];
+    void* out[kMaxRanks];
+    const void* res[kMaxRanks];
+    size_t nbytes;      // payload bytes per rank
+    int n;
+    int chans;
+    int has_res;
+    int res_shared;
+    unsigned flag;      // this call's flag (never 0)
+    unsigned rot;       // which half of the rotating scratch
+};
+
+// payload words of packet k (bytes [8k, 8k+8)), zero padded past nbytes; nbytes is even
+__device__ __forceinline__ u32x2 load_words(const void* base, size_t k, size_t nbytes)
+{
+    const size_t off = k * 8;
+    if (off + 8 <= nbytes) return *(const u32x2*)((const char*)base + off);
+    unsigned h[4] = {0, 0, 0, 0};
+    for (int i = 0; i < 4; ++i)
+        if (off + 2 * i + 2 <= nbytes) h[i] = *(const unsigned short*)((const char*)base + off + 2 * i);
+    return u32x2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
+}
+
+__device__ __forceinline__ void store_words(void* base, size_t k, size_t nbytes, u32x2 w)
+{
+    const size_t off = k * 8;
+    if (off + 8 <= nbytes) { *(u32x2*)((char*)base + off) = w; return; }
+    const unsigned h[4] = {w.x & 0xffffu, w.x >> 16, w.y & 0xffffu, w.y >> 16};
+    for (int i = 0; i < 4; ++i)
+        if (off + 2 * i + 2 <= nbytes) *(unsigned short*)((char*)base + off + 2 * i) = (unsigned short)h[i];
+}
+
+// Poll packet `pos` of slots j != me (j < n) of my scratch until all carry the flag.
+#define MSX_LL_POLL_ALL(v, base_off, slot_stride, pos)                                        \
+    {                                                                                         \
+        bool ready = false;                                                                   \
+        for (unsigned spins = 0; !ready && spins <= c.spin_limit; ++spins) {                  \
+            poll_fence();                                                                     \
+            ready = true;                                                                     \
+            _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)                             \
+                if (j < n && j != rank) v[j] = ll_load(rs, (base_off) + (unsigned)j * (slot_stride) + (unsigned)(pos) * 16u); \
+            _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)                             \
+                if (j < n && j != rank) ready = ready && ll_ready(v[j], a.flag);              \
+        }                                                                                     \
+        if (!ready) report(c, kStatusTimeout, (unsigned)rank, 100u, a.flag, 0u);              \
+    }
+
+// ---- 1PA: every rank sends ALL its data to every peer, then reduces everything itself --------
+template <int DT, int NR>
+__global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
+{
+    const int n = NR ? NR : a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
+    const unsigned P = (unsigned)((a.nbytes + 7) / 8);          // packets per rank
+    const unsigned RT = (unsigned)a.chans * blockDim.x;
+    const unsigned rt = (unsigned)chan * blockDim.x + threadIdx.x;
+    const unsigned slot_stride = P * 16u;
+    const unsigned rot_off = a.rot * c.ll_rot_stride;
+    chaos_delay(c, 70);
+
+    // send: my packet k goes to slot `rank` of every peer, all peers before any wait
+    for (unsigned k = rt; k < P; k += RT) {
+        const u32x2 w = load_words(a.in[rank], k, a.nbytes);
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p)
+            if (p < n && p != rank)
+                ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + k * 16u,
+                         w.x, w.y, a.flag);
+    }
+    // receive + reduce in rank order 0..n-1 (identical bits on every rank)
+    const unsigned my_off = (unsigned)rank * c.ll_rank_stride + rot_off;
+    for (unsigned k = rt; k < P; k += RT) {
+        const u32x2 own = load_words(a.in[rank], k, a.nbytes);
+        u32x4 v[kMaxRanks];
+        MSX_LL_POLL_ALL(v, my_off, slot_stride, k)
+        WordAcc<DT> a0, a1;
+#pragma unroll
+        for (int j = 0; j < kMaxRanks; ++j)
+            if (j < n) {
+                const unsigned w0 = j == rank ? own.x : v[j].x;
+                const unsigned w1 = j == rank ? own.y : v[j].z;
+                if (j == 0) { a0.set(w0); a1.set(w1); } else { a0.add(w0); a1.add(w1); }
+            }
+        if (a.has_res) {
+            const u32x2 r = load_words(a.res[rank], k, a.nbytes);
+            a0.add(r.x); a1.add(r.y);
+        }
+        store_words(a.out[rank], k, a.nbytes, u32x2{a0.pack(), a1.pack()});
+    }
+}
+
+// ---- 2PA: reduce-scatter over packets, then all-gather over packets ----------------------------
+// Packets are split into n chunks of cp = ceil(P/n); rank r owns chunk r.
+//   scratch of rank p, phase 1: slot j (source rank) at (j*cp + q)*16
+//                      phase 2: n*cp*16 + (j*cp + q)*16
+template <int DT, int NR>
+__global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
+{
+    const int n = NR ? NR : a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
+    const unsigned P = (unsigned)((a.nbytes + 7) / 8);
+    const unsigned cp = (P + (unsigned)n - 1) / (unsigned)n;
+    const unsigned RT = (unsigned)a.chans * blockDim.x;
+    const unsigned rt = (unsigned)chan * blockDim.x + threadIdx.x;
+    const unsigned slot_stride = cp * 16u;
+    const unsigned rot_off = a.rot * c.ll_rot_stride;
+    const unsigned ph2 = (unsigned)n * slot_stride;
+    const unsigned my_off = (unsigned)rank * c.ll_rank_stride + rot_off;
+    chaos_delay(c, 80);
+
+    // phase 1 send: packet q of chunk p goes to slot `rank` of rank p
+    for (unsigned q = rt; q < cp; q += RT) {
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p)
+            if (p < n && p != rank) {
+                const unsigned k = (unsigned)p * cp + q;
+                if (k < P) {
+                    const u32x2 w = load_words(a.in[rank], k, a.nbytes);
+                    ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + q * 16u,
+                             w.x, w.y, a.flag);
+                }
+            }
+    }
+    // phase 1 receive + reduce my chunk, phase 2 send the result to every peer
+    for (unsigned q = rt; q < cp; q += RT) {
+        const unsigned k = (unsigned)rank * cp + q;
+        if (k >= P) break;
+        const u32x2 own = load_words(a.in[rank], k, a.nbytes);
+        u32x4 v[kMaxRanks];
+        MSX_LL_POLL_ALL(v, my_off, slot_stride, q)
+        WordAcc<DT> a0, a1;
+#pragma unroll
+        for (int j = 0; j < kMaxRanks; ++j)
+            if (j < n) {
+                const unsigned w0 = j == rank ? own.x : v[j].x;
+                const unsigned w1 = j == rank ? own.y : v[j].z;
+                if (j == 0) { a0.set(w0); a1.set(w1); } else { a0.add(w0); a1.add(w1); }
+            }
+        if (!a.has_res || a.res_shared) {
+            if (a.has_res) {
+                const u32x2 r = load_words(a.res[0], k, a.nbytes);
+                a0.add(r.x); a1.add(r.y);
+            }
+            const u32x2 o = {a0.pack(), a1.pack()};
+#pragma unroll
+            for (int p = 0; p < kMaxRanks; ++p)
+                if (p < n && p != rank)
+                    ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + ph2 + (unsigned)rank * slot_stride + q * 16u,
+                             o.x, o.y, a.flag);
+            store_words(a.out[rank], k, a.nbytes, o);
+        } else {
+            // every destination adds its own residual before the single rounding
+#pragma unroll
+            for (int p = 0; p < kMaxRanks; ++p)
+                if (p < n) {
+                    const u32x2 r = load_words(a.res[p], k, a.nbytes);
+                    WordAcc<DT> t0 = a0, t1 = a1;
+                    t0.add(r.x); t1.add(r.y);
+                    const u32x2 o = {t0.pack(), t1.pack()};
+                    if (p != rank)
+                        ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + ph2 + (unsigned)rank * slot_stride + q * 16u,
+                                 o.x, o.y, a.flag);
+                    else
+                        store_words(a.out[rank], k, a.nbytes, o);
+                }
+        }
+    }
+    // phase 2 receive: the other chunks, reduced by their owners
+    for (unsigned q = rt; q < cp; q += RT) {
+        u32x4 v[kMaxRanks];
+        // only slots whose packet exists were sent: the last chunks may be short or empty
+        bool ready = false;
+        for (unsigned spins = 0; !ready && spins <= c.spin_limit; ++spins) {
+            poll_fence();
+            ready = true;
+#pragma unroll
+            for (int j = 0; j < kMaxRanks; ++j)
+                if (j < n && j != rank && (unsigned)j * cp + q < P)
+                    v[j] = ll_load(rs, my_off + ph2 + (unsigned)j * slot_stride + q * 16u);
+#pragma unroll
+            for (int j = 0; j < kMaxRanks; ++j)
+                if (j < n && j != rank && (unsigned)j * cp + q < P) ready = ready && ll_ready(v[j], a.flag);
+        }
+        if (!ready) report(c, kStatusTimeout, (unsigned)rank, 101u, a.flag, 0u);
+#pragma unroll
+        for (int j = 0; j < kMaxRanks; ++j)
+            if (j < n && j != rank && (unsigned)j * cp + q < P)
+                store_words(a.out[rank], (size_t)j * cp + q, a.nbytes, u32x2{v[j].x, v[j].z});
+    }
+}
+
+}  // namespace msx

@@ -1,0 +1,203 @@
+// Token-routed all-to-all (expert-parallel dispatch).  The paper evaluates this exchange
+// in its DeepEP experiment (hidden 7168, top-8 of 256 experts) but does not describe the
+// packing; the order built here is: destination buffer d holds rows by source rank
+// ascending, then by token index ascending, one row per (token, distinct destination).
+//
+//   plan  : one workgroup per source rank.  Marks each token's destination ranks, turns
+//           the marks into stable per-destination slots with a workgroup prefix sum,
+//           exchanges the 8 per-destination counts with all peers over LL packets, and
+//           derives where this source's rows start inside every destination buffer.
+//   pack  : many workgroups per rank, one wave per token: the row is read once and put
+//           into every destination (peer loop inside the row loop), then a rank barrier.
+#pragma once
+#include "msx_device.hpp"
+
+namespace msx {
+
+struct MoeArgs {
+    const void* tokens[kMaxRanks];
+    const int* topk[kMaxRanks];
+    void* recv[kMaxRanks];
+    int* recv_src[kMaxRanks];
+    int* recv_counts;       // [n dst][n src]
+    unsigned short* slots;  // plan scratch: [n src][T][8] slot of the token in destination d, 0xFFFF = not sent
+    unsigned* base;         // plan scratch: [n src][8] first row of source s inside destination d
+    int T, K, n, per_rank;  // per_rank = experts per rank
+    int n_experts;
+    unsigned row_vecs;      // 16-byte vectors per row
+    unsigned cap;           // rows per destination buffer
+    int chans;
+    int has_src;
+    unsigned flag;
+    unsigned rot;
+};
+
+constexpr int kPlanThreads = 1024;
+
+// workgroup-wide exclusive prefix sum of two packed counters (4 x 16-bit fields each)
+__device__ __forceinline__ void block_exscan2(unsigned long long& x, unsigned long long& y,
+                                              unsigned long long* lds, unsigned long long& tx,
+                                              unsigned long long& ty)
+{
+    const int lane = (int)(threadIdx.x & 63u), wave = (int)(threadIdx.x >> 6);
+    unsigned long long ix = x, iy = y;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        unsigned long long ux = __shfl_up(ix, d, 64), uy = __shfl_up(iy, d, 64);
+        if (lane >= d) { ix += ux; iy += uy; }
+    }
+    if (lane == 63) { lds[wave * 2] = ix; lds[wave * 2 + 1] = iy; }
+    __syncthreads();
+    unsigned long long bx = 0, by = 0, sx = 0, sy = 0;
+    const int nw = (int)(blockDim.x >> 6);
+    for (int w = 0; w < nw; ++w) {
+        if (w == wave) { bx = sx; by = sy; }
+        sx += lds[w * 2]; sy += lds[w * 2 + 1];
+    }
+    tx = sx; ty = sy;                  // totals
+    x = bx + ix - x; y = by + iy - y;  // exclusive
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
+{
+    const int n = a.n;
+    const int rank = (int)blockIdx.x;           // one workgroup per source rank
+    if (rank == c.drop_rank) return;
+    __shared__ unsigned long long scan_lds[2 * (kPlanThreads / 64)];
+    __shared__ unsigned cnt[kMaxRanks][kMaxRanks];   // [src][dst]
+    const int T = a.T, K = a.K;
+    const int per_thread = (T + (int)blockDim.x - 1) / (int)blockDim.x;
+    const int t0 = (int)threadIdx.x * per_thread;
+    const int t1 = min(T, t0 + per_thread);
+    const int* topk = a.topk[rank];
+
+    // pass 1: my tokens' destination marks, counted per destination (16-bit fields)
+    unsigned long long cx = 0, cy = 0;
+    for (int t = t0; t < t1; ++t) {
+        unsigned mask = 0;
+        for (int k = 0; k < K; ++k) {
+            const int e = topk[(size_t)t * K + k];
+            if (e >= 0 && e < a.n_experts) mask |= 1u << (e / a.per_rank);
+        }
+        for (int d = 0; d < 4; ++d) {
+            cx += (unsigned long long)((mask >> d) & 1u) << (16 * d);
+            cy += (unsigned long long)((mask >> (d + 4)) & 1u) << (16 * d);
+        }
+    }
+    unsigned long long totx, toty;
+    block_exscan2(cx, cy, scan_lds, totx, toty);   // cx, cy now hold the slots my first token gets
+
+    // pass 2: stable slots
+    unsigned short* slots = a.slots + ((size_t)rank * T) * 8;
+    for (int t = t0; t < t1; ++t) {
+        unsigned mask = 0;
+        for (int k = 0; k < K; ++k) {
+            const int e = topk[(size_t)t * K + k];
+            if (e >= 0 && e < a.n_experts) mask |= 1u << (e / a.per_rank);
+        }
+        unsigned s[8];
+        for (int d = 0; d < 4; ++d) {
+            const unsigned b0 = (mask >> d) & 1u, b1 = (mask >> (d + 4)) & 1u;
+            s[d] = b0 ? (unsigned)((cx >> (16 * d)) & 0xffffu) : 0xffffu;
+            s[d + 4] = b1 ? (unsigned)((cy >> (16 * d)) & 0xffffu) : 0xffffu;
+            cx += (unsigned long long)b0 << (16 * d);
+            cy += (unsigned long long)b1 << (16 * d);
+        }
+        u32x4 pk = {s[0] | (s[1] << 16), s[2] | (s[3] << 16), s[4] | (s[5] << 16), s[6] | (s[7] << 16)};
+        *(u32x4*)(slots + (size_t)t * 8) = pk;
+    }
+
+    // exchange counts: my 8 per-destination counts go to every peer as 4 LL packets
+    const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
+    const unsigned rot_off = a.rot * c.ll_rot_stride;
+    const unsigned tid = threadIdx.x;
+    if (tid < 8) cnt[rank][tid] = (unsigned)(((tid < 4 ? totx : toty) >> (16 * (tid & 3))) & 0xffffu);
+    __syncthreads();
+    if (tid < (unsigned)n * 4u) {
+        const int p = (int)(tid >> 2);
+        const unsigned q = tid & 3u;
+        if (p != rank)
+            ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + ((unsigned)rank * 4u + q) * 16u,
+                     cnt[rank][2 * q], cnt[rank][2 * q + 1], a.flag);
+    }
+    if (tid < (unsigned)n * 4u) {
+        const int j = (int)(tid >> 2);
+        const unsigned q = tid & 3u;
+        if (j != rank) {
+            u32x4 v = {0, 0, 0, 0};
+            bool ready = false;
+            for (unsigned spins = 0; !ready && spins <= c.spin_limit; ++spins) {
+                poll_fence();
+                v = ll_load(rs, (unsigned)rank * c.ll_rank_stride + rot_off + ((unsigned)j * 4u + q) * 16u);
+                ready = ll_ready(v, a.flag);
+            }
+            if (!ready) report(c, kStatusTimeout, (unsigned)rank, 200u, a.flag, v.y);
+            cnt[j][2 * q] = v.x;
+            cnt[j][2 * q + 1] = v.z;
+        }
+    }
+    __syncthreads();
+    // where my rows start in destination d: after the rows of all lower source ranks
+    if (tid < 8) {
+        unsigned b = 0;
+        for (int s = 0; s < rank; ++s) b += cnt[s][tid];
+        a.base[rank * 8 + (int)tid] = (int)tid < n ? b : 0u;
+    }
+    // as a destination I publish how many rows each source sends me
+    if (tid < (unsigned)n) a.recv_counts[rank * n + (int)tid] = (int)cnt[tid][rank];
+    // overflow check for my own buffer
+    if (tid == 0) {
+        unsigned tot = 0;
+        for (int s = 0; s < n; ++s) tot += cnt[s][rank];
+        if (tot > a.cap) report(c, kStatusCapacity, (unsigned)rank, 201u, a.cap, tot);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_moe_pack(MoeArgs a, DevCtx c)
+{
+    const int n = a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    const int lane = (int)(threadIdx.x & 63u);
+    const int waves = (int)(blockDim.x >> 6);
+    const int wave = chan * waves + (int)(threadIdx.x >> 6);
+    const int total_waves = a.chans * waves;
+    unsigned base[kMaxRanks];
+#pragma unroll
+    for (int d = 0; d < kMaxRanks; ++d) base[d] = a.base[rank * 8 + d];
+    const char* tokens = (const char*)a.tokens[rank];
+    const size_t row_bytes = (size_t)a.row_vecs * 16;
+
+    for (int t = wave; t < a.T; t += total_waves) {
+        const u32x4 pk = *(const u32x4*)(a.slots + ((size_t)rank * a.T + t) * 8);
+        unsigned row[kMaxRanks];
+        row[0] = pk.x & 0xffffu; row[1] = pk.x >> 16; row[2] = pk.y & 0xffffu; row[3] = pk.y >> 16;
+        row[4] = pk.z & 0xffffu; row[5] = pk.z >> 16; row[6] = pk.w & 0xffffu; row[7] = pk.w >> 16;
+        char* dst[kMaxRanks];
+#pragma unroll
+        for (int d = 0; d < kMaxRanks; ++d) {
+            const unsigned r = base[d] + row[d];
+            const bool go = d < n && row[d] != 0xffffu && r < a.cap;
+            dst[d] = go ? (char*)a.recv[d] + (size_t)r * row_bytes : nullptr;
+            if (go && a.has_src && lane == 0) a.recv_src[d][r] = rank * a.T + t;
+        }
+        const char* src = tokens + (size_t)t * row_bytes;
+        for (unsigned i = (unsigned)lane; i < a.row_vecs; i += 128u) {
+            const unsigned i1 = i + 64u;
+            const u32x4 v0 = ld16(src, i);
+            u32x4 v1 = v0;
+            if (i1 < a.row_vecs) v1 = ld16(src, i1);
+#pragma unroll
+            for (int d = 0; d < kMaxRanks; ++d)
+                if (dst[d]) {
+                    st16(dst[d], i, v0);
+                    if (i1 < a.row_vecs) st16(dst[d], i1, v1);
+                }
+        }
+    }
+    if (n > 1) rank_barrier(c, rank, n, chan, 210);   // all rows destined to me have landed
+}
+
+}  // namespace msx

@@ -1,0 +1,200 @@
+"""GPU parity tests of ReduceScatter, AllGather, AllToAll (in-place and per-rank forms) and
+of the token-routed dispatch, against the CPU oracle.  All comparisons are bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_09014_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def msx():
+    import paper_2504_09014_amd as m
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: there is no fallback path")
+    m.init()
+    yield m
+    m.set_option("chaos", "0")
+
+
+def _bits(t):
+    t = t.detach().cpu().contiguous()
+    return t.view(torch.uint16).numpy() if t.dtype == torch.bfloat16 else t.numpy()
+
+
+def _data(n, count, dtype, seed):
+    if dtype == torch.float32:
+        return synth.int_valued_f32(n, count, seed=seed)
+    return synth.normal(n, count, seed=seed)
+
+
+def _tagged(n, count):
+    """every element names its row and column: a misplaced one is attributable"""
+    return ((torch.arange(n, dtype=torch.int64)[:, None] << 24) | torch.arange(count, dtype=torch.int64)[None, :]) \
+        .to(torch.int32).view(torch.float32)
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("c", [1, 3, 8, 64, 1000, 4096, 65536 + 8])
+def test_reducescatter_matches_oracle(msx, orc, n, dtype, c):
+    count = n * c
+    x = _data(n, count, dtype, seed=c)
+    want = orc.reducescatter(_bits(x))
+    send = [x[r].clone().cuda() for r in range(n)]
+    recv = [torch.zeros(c, dtype=dtype, device="cuda") for _ in range(n)]
+    msx.reducescatter_ex(send, recv)
+    msx.check_status()
+    for r in range(n):
+        assert np.array_equal(_bits(recv[r]), want[r]), (n, c, r)
+    esz = 4 if dtype == torch.float32 else 2
+    if (count * esz) % 16 == 0:
+        buf = x.clone().cuda()
+        msx.reducescatter(buf)
+        msx.check_status()
+        got, orig = _bits(buf), _bits(x)
+        for r in range(n):
+            assert np.array_equal(got[r, r * c:(r + 1) * c], want[r])
+            mask = np.ones(count, bool)
+            mask[r * c:(r + 1) * c] = False
+            assert np.array_equal(got[r, mask], orig[r, mask])          # the rest is untouched
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("c", [1, 5, 8, 1000, 4096, 65536 + 24])
+def test_allgather_matches_oracle(msx, orc, n, dtype, c):
+    x = _tagged(n, c) if dtype == torch.float32 else synth.normal(n, c, seed=c)
+    want = orc.allgather(_bits(x))
+    send = [x[r].clone().cuda() for r in range(n)]
+    recv = [torch.zeros(n * c, dtype=dtype, device="cuda") for _ in range(n)]
+    msx.allgather_ex(send, recv)
+    msx.check_status()
+    for r in range(n):
+        assert np.array_equal(_bits(recv[r]).view(np.uint8), want[r].view(np.uint8)), (n, c, r)
+    # in place: row r holds its block in slot r, the rest is garbage to be overwritten
+    buf = torch.full((n, n * c), 7.0, dtype=dtype)
+    for r in range(n):
+        buf[r, r * c:(r + 1) * c] = x[r]
+    buf = buf.cuda()
+    msx.allgather(buf)
+    msx.check_status()
+    assert np.array_equal(_bits(buf).view(np.uint8), want.view(np.uint8))
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("c", [1, 5, 8, 1000, 4096, 65536 + 24])
+def test_alltoall_matches_oracle(msx, orc, n, dtype, c):
+    count = n * c
+    x = _tagged(n, count) if dtype == torch.float32 else synth.normal(n, count, seed=c + 1)
+    want = orc.alltoall(_bits(x))
+    send = [x[r].clone().cuda() for r in range(n)]
+    recv = [torch.zeros(count, dtype=dtype, device="cuda") for _ in range(n)]
+    msx.alltoall_ex(send, recv)
+    msx.check_status()
+    for r in range(n):
+        assert np.array_equal(_bits(recv[r]).view(np.uint8), want[r].view(np.uint8)), (n, c, r)
+    buf = x.clone().cuda()
+    msx.alltoall(buf)
+    msx.check_status()
+    assert np.array_equal(_bits(buf).view(np.uint8), want.view(np.uint8))
+    msx.alltoall(buf)                                   # applying it twice restores the input
+    msx.check_status()
+    assert np.array_equal(_bits(buf).view(np.uint8), _bits(x).view(np.uint8))
+
+
+def test_allgather_of_reducescatter_equals_allreduce_on_gpu(msx, orc):
+    n, c = 8, 12345 * 8
+    x = synth.normal(n, n * c, seed=42)
+    send = [x[r].clone().cuda() for r in range(n)]
+    part = [torch.zeros(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    full = [torch.zeros(n * c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    msx.set_option("chaos", "3")
+    msx.reducescatter_ex(send, part)
+    msx.allgather_ex(part, full)
+    msx.set_option("chaos", "0")
+    msx.check_status()
+    want = orc.allreduce_bf16(_bits(x))
+    for r in range(n):
+        assert np.array_equal(_bits(full[r]), want)
+
+
+# ---------------------------------------------------------------- token dispatch
+
+def _dispatch(msx, tokens, topk, n_experts, cap):
+    n, T, H = tokens.shape
+    tok = [tokens[r].clone().cuda() for r in range(n)]
+    idx = [topk[r].clone().cuda() for r in range(n)]
+    recv = [torch.zeros((cap, H), dtype=tokens.dtype, device="cuda") for _ in range(n)]
+    src = [torch.full((cap,), -1, dtype=torch.int32, device="cuda") for _ in range(n)]
+    counts = torch.full((n, n), -1, dtype=torch.int32, device="cuda")
+    msx.moe_dispatch(tok, idx, n_experts, recv, counts, src)
+    rc, info = msx.status()
+    return recv, src, counts, rc, info
+
+
+@pytest.mark.parametrize("n,T,H,K,E", [(8, 96, 24, 8, 256), (8, 1000, 64, 8, 256), (4, 333, 8, 2, 16),
+                                       (2, 5000, 40, 1, 2), (8, 1, 8, 8, 256), (1, 77, 16, 4, 8)])
+def test_moe_dispatch_small_shapes(msx, orc, n, T, H, K, E):
+    tokens = synth.moe_tokens(n, T, H, seed=T)
+    topk = synth.moe_routing(n, T, K, E, seed=T)
+    cap = n * T
+    want_recv, want_src, want_counts, orc_rc = orc.moe_dispatch(_bits(tokens), topk.numpy(), E, cap)
+    assert orc_rc == 0
+    recv, src, counts, rc, info = _dispatch(msx, tokens, topk, E, cap)
+    assert rc == 0, info
+    assert np.array_equal(counts.cpu().numpy(), want_counts)
+    for d in range(n):
+        assert np.array_equal(src[d].cpu().numpy(), want_src[d]), d
+        assert np.array_equal(_bits(recv[d]), want_recv[d]), d
+
+
+def test_moe_dispatch_special_routings(msx, orc):
+    n, T, H, E = 8, 200, 32, 256
+    tokens = synth.moe_tokens(n, T, H, seed=5)
+    routes = {
+        "all to rank 3": torch.arange(96, 104, dtype=torch.int32).repeat(n, T, 1),
+        "one expert per rank": torch.arange(0, 256, 32, dtype=torch.int32).repeat(n, T, 1),
+        "duplicates": torch.zeros((n, T, 8), dtype=torch.int32),
+    }
+    for name, topk in routes.items():
+        want_recv, want_src, want_counts, _ = orc.moe_dispatch(_bits(tokens), topk.numpy(), E, n * T)
+        recv, src, counts, rc, info = _dispatch(msx, tokens, topk, E, n * T)
+        assert rc == 0, (name, info)
+        assert np.array_equal(counts.cpu().numpy(), want_counts), name
+        for d in range(n):
+            assert np.array_equal(src[d].cpu().numpy(), want_src[d]), (name, d)
+            assert np.array_equal(_bits(recv[d]), want_recv[d]), (name, d)
+
+
+def test_moe_dispatch_reports_overflow_and_keeps_true_counts(msx, orc):
+    n, T, H, E = 8, 64, 8, 256
+    tokens = synth.moe_tokens(n, T, H, seed=6)
+    topk = torch.arange(0, 256, 32, dtype=torch.int32).repeat(n, T, 1)      # everything everywhere
+    cap = T * 3                                                            # needs T * 8
+    want_recv, _, _, orc_rc = orc.moe_dispatch(_bits(tokens), topk.numpy(), E, cap)
+    assert orc_rc == -1
+    recv, src, counts, rc, info = _dispatch(msx, tokens, topk, E, cap)
+    assert rc == -6 and info[0] == 2
+    assert np.all(counts.cpu().numpy() == T)
+    for d in range(n):
+        assert np.array_equal(_bits(recv[d]), want_recv[d])                 # the rows that fit are right
+
+
+def test_config5_moe_dispatch_full_size(msx, orc):
+    n, T, H, K, E = 8, 4096, 7168, 8, 256
+    tokens = synth.moe_tokens(n, T, H, seed=0)
+    topk = synth.moe_routing(n, T, K, E, seed=0)
+    cap = 24576                                                            # expected 21.7k rows per rank
+    want_recv, want_src, want_counts, orc_rc = orc.moe_dispatch(_bits(tokens), topk.numpy(), E, cap)
+    assert orc_rc == 0
+    recv, src, counts, rc, info = _dispatch(msx, tokens, topk, E, cap)
+    assert rc == 0, info
+    assert np.array_equal(counts.cpu().numpy(), want_counts)
+    assert abs(want_counts.sum() / (n * T) - 5.295) < 0.03
+    for d in range(n):
+        assert np.array_equal(src[d].cpu().numpy(), want_src[d]), d
+        assert np.array_equal(_bits(recv[d]), want_recv[d]), d

@@ -1,0 +1,85 @@
+"""Config 3: bandwidth-path AllReduce at 64 MiB, 256 MiB and 1 GiB per rank (bf16, 8 ranks,
+out of place), in the launch configuration the benchmark times.
+
+64 MiB is compared with the oracle in full.  At 256 MiB and 1 GiB the oracle runs on
+deterministic windows (start and end of every rank's chunk, a band around every chunk
+boundary, 48 seeded 64 KiB windows) and an on-GPU comparison checks that all 8 outputs are
+bitwise identical, so a fault anywhere outside the windows still shows on at least the
+cross-rank check or as a wrong window."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_09014_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def msx():
+    import paper_2504_09014_amd as m
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: there is no fallback path")
+    m.init()
+    return m
+
+
+def _bits(t):
+    return t.detach().cpu().contiguous().view(torch.uint16).numpy()
+
+
+def _windows(count, n, rng):
+    w = 32768                                              # 64 KiB of bf16
+    spans = []
+    chunk = count // n
+    for r in range(n):
+        lo = r * chunk
+        spans += [(lo, min(count, lo + (1 << 19))), (max(0, lo + chunk - (1 << 19)), lo + chunk),
+                  (max(0, lo - 2048), min(count, lo + 2048))]
+    for s in rng.integers(0, count - w, 48):
+        spans.append((int(s), int(s) + w))
+    spans.append((count - 4096, count))
+    return spans
+
+
+@pytest.mark.parametrize("mib,algo", [(64, 3), (64, 4), (256, 3), (1024, 3)])
+def test_config3_large_allreduce(msx, orc, mib, algo):
+    n = 8
+    count = mib * (1 << 20) // 2
+    x = synth.normal(n, count, seed=mib, device="cuda")     # generated on the GPU by torch
+    send = [x[r] for r in range(n)]
+    recv = [torch.empty(count, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    msx.allreduce_ex(send, recv, None, algo=algo)
+    msx.check_status()
+    for r in range(1, n):
+        assert torch.equal(recv[r].view(torch.int16), recv[0].view(torch.int16)), r
+    if mib <= 64:
+        want = orc.allreduce_bf16(_bits(x))
+        assert np.array_equal(_bits(recv[0]), want)
+        assert np.array_equal(_bits(recv[5]), want)
+    else:
+        rng = np.random.default_rng(mib)
+        for lo, hi in _windows(count, n, rng):
+            want = orc.allreduce_bf16(_bits(x[:, lo:hi]))
+            assert np.array_equal(_bits(recv[0][lo:hi]), want), (lo, hi)
+            assert np.array_equal(_bits(recv[6][lo:hi]), want), (lo, hi)
+    del x, send, recv
+    torch.cuda.empty_cache()
+
+
+def test_large_in_place_allreduce_256mib(msx, orc):
+    n, count = 8, 128 << 20
+    x = synth.normal(n, count, seed=7, device="cuda")
+    keep = {}
+    rng = np.random.default_rng(1)
+    spans = _windows(count, n, rng)
+    for lo, hi in spans:
+        keep[(lo, hi)] = orc.allreduce_bf16(_bits(x[:, lo:hi]))
+    msx.allreduce(x)
+    msx.check_status()
+    for r in range(1, n):
+        assert torch.equal(x[r].view(torch.int16), x[0].view(torch.int16)), r
+    for (lo, hi), want in keep.items():
+        assert np.array_equal(_bits(x[3, lo:hi]), want), (lo, hi)
+    del x
+    torch.cuda.empty_cache()
