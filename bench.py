@@ -1,0 +1,282 @@
+#!/usr/bin/env python3
+"""Benchmark of the emulated 8-rank AllReduce hot path on one MI355X.
+
+A step is one bandwidth-path AllReduce (two-phase all-pairs, HB protocol, reduce and put
+fused) of 1 GiB of bf16 per rank over 8 emulated ranks, out of place: start barrier over the
+semaphore layer, chunk-sum of 8 input streams, put into 8 output streams, end barrier.
+Inputs are resident in HBM before the timed region.
+
+One JSON line on stdout.  `value` is HBM GB/s over the algorithmic bytes (every input read
+once, every output written once = 16 x S per step) measured by wall clock over all timed
+steps; `roofline` repeats it from HIP-event kernel times; `extras` carries the small-message
+latencies (LL path), the decode-shaped fused-residual sizes and the token dispatch.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_calls(torch, fn, iters, warmup):
+    """(mean wall us per call issued back to back, list of per-call HIP-event us)"""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    t0 = time.perf_counter()
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) / iters * 1e6
+    return wall, [a.elapsed_time(b) * 1e3 for a, b in evs]
+
+
+def back_to_back_us(torch, fn, iters, warmup):
+    """mean us per call when `iters` calls are queued with nothing in between"""
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(iters):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e3 / iters
+
+
+def median(v):
+    s = sorted(v)
+    return s[len(s) // 2]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--mib", type=int, default=1024, help="bf16 MiB per rank of the headline AllReduce")
+    ap.add_argument("--no-extras", action="store_true", help="skip latency / decode / dispatch tables")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, to scale "
+                         "hardware byte counters against)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build emulates its 8 ranks inside ONE GPU; --gpus must be 1 "
+              "(nothing here runs on a second GPU)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2504_09014_amd as msx
+    from paper_2504_09014_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the library has no CPU path", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    msx.init()
+    n = 8
+
+    # ---------------------------------------------------------------- headline: config 3
+    count = args.mib * (1 << 20) // 2
+    S = count * 2
+    log(f"[bench] generating {n} x {args.mib} MiB bf16 on the GPU")
+    x = synth.normal(n, count, seed=3, device="cuda")
+    send = [x[r] for r in range(n)]
+    recv = [torch.empty(count, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+
+    def step():
+        msx.allreduce_ex(send, recv, None, algo=msx.ALGO_AUTO)
+
+    for _ in range(args.warmup):
+        step()
+    msx.check_status()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b in evs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    msx.check_status()
+    grid, block, algo = msx.last_launch()
+    ms_per_step = wall / args.steps * 1e3
+    kern_ms = [a.elapsed_time(b) for a, b in evs]
+    kern_avg = sum(kern_ms) / len(kern_ms)
+    alg_bytes = 2 * n * S                      # n inputs read once + n outputs written once
+    value = alg_bytes / (wall / args.steps) / 1e9
+    achieved = alg_bytes / (kern_avg * 1e-3) / 1e9
+    log(f"[bench] AllReduce {args.mib} MiB/rank: {ms_per_step:.3f} ms/step wall, {kern_avg:.3f} ms kernel, "
+        f"{achieved:.0f} GB/s, algBW {S / (kern_avg * 1e-3) / 1e9:.0f} GB/s, grid {grid}x{block}")
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            t = json.load(open(tpath)).get(f"allreduce_hb_fused_{args.mib}MiB")
+            if t:
+                traffic = t["fetch_bytes"] + t["write_bytes"]
+        except Exception:
+            traffic = None
+
+    out = {
+        "metric": "emulated 8-rank AllReduce GB/s (% HBM roofline) + small-msg latency us",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {
+            "workload": f"AllReduce-sum 2PA-HB fused, 8 emulated ranks, bf16 N(0,1), {args.mib} MiB per rank, "
+                        f"out of place ({n * S >> 20} MiB in + {n * S >> 20} MiB out)",
+            "nranks": n, "bytes_per_rank": S, "algo": algo, "grid": grid, "block": block,
+            "algbw_GBps": round(S / (wall / args.steps) / 1e9, 1),
+            "busbw_GBps": round(S / (wall / args.steps) / 1e9 * 2 * (n - 1) / n, 1),
+            "pct_hbm_roofline": round(100 * value / HBM_PEAK_GBPS, 1),
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+            "kernel": "k_allreduce_hb_fused<bf16>", "algorithmic_bytes": alg_bytes,
+            "kernel_ms_avg": round(kern_avg, 4), "kernel_ms_min": round(min(kern_ms), 4),
+        },
+    }
+
+    if args.calibrate:
+        a_ = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        b_ = torch.empty_like(a_)
+        torch.cuda.synchronize()
+        b_.copy_(a_)                        # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a_, b_
+
+    # ---------------------------------------------------------------- CPU oracle baseline
+    if not args.no_cpu:
+        import numpy as np
+        import oracle
+        sample = min(count, 256 << 20)                     # at most 512 MiB per rank
+        log(f"[bench] CPU oracle on the first {sample * 2 >> 20} MiB of every rank (single thread)")
+        host = np.empty((n, sample), np.uint16)
+        for r in range(n):
+            host[r] = x[r, :sample].cpu().view(torch.uint16).numpy()
+        t0 = time.perf_counter()
+        want = oracle.allreduce_bf16(host)
+        dt = time.perf_counter() - t0
+        got = recv[n - 1][:sample].cpu().view(torch.uint16).numpy()
+        if not np.array_equal(got, want):
+            print("bench.py: GPU result differs from the oracle on the sampled range", file=sys.stderr)
+            sys.exit(1)
+        out["cpu_baseline"] = {
+            "value": round(2 * n * sample * 2 / dt / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {sample * 2 >> 20} MiB of each of the 8 rank buffers of the same workload, "
+                      f"{dt:.1f} s, GPU output checked bit-exact against it",
+            "host_cpus": os.cpu_count(),
+        }
+        del host, want, got
+    del x, send, recv
+    torch.cuda.empty_cache()
+
+    # ---------------------------------------------------------------- extras
+    if not args.no_extras:
+        extras = {}
+        lat = {}
+        for kib in [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024]:
+            c = kib * 1024 // 2
+            xs = synth.normal(n, c, seed=kib)
+            s_ = [xs[r].clone().cuda() for r in range(n)]
+            r_ = [torch.empty_like(t) for t in s_]
+            fn = lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO)
+            _, ev = time_calls(torch, fn, 200, 20)
+            b2b = back_to_back_us(torch, fn, 500, 20)
+            g, b, a = msx.last_launch()
+            lat[f"{kib}KiB"] = {"us_back_to_back": round(b2b, 2), "us_event_median": round(median(ev), 2),
+                                "algo": a, "grid": g, "block": b}
+        msx.check_status()
+        extras["config2_bf16_latency"] = lat
+        dec = {}
+        for T in [1, 8, 32, 128, 256]:
+            xs, res = synth.decode_activations(n, T, seed=T)
+            s_ = [xs[r].clone().cuda() for r in range(n)]
+            r_ = [torch.empty_like(t) for t in s_]
+            rr = [res.cuda()] * n
+            fn = lambda: msx.allreduce_ex(s_, r_, rr, algo=msx.ALGO_AUTO)
+            b2b = back_to_back_us(torch, fn, 300, 20)
+            g, b, a = msx.last_launch()
+            dec[f"T{T}"] = {"us_back_to_back": round(b2b, 2), "algo": a, "grid": g}
+        msx.check_status()
+        extras["config4_decode_residual"] = dec
+        # config 1
+        xi = synth.int_valued_f32(n, 262144, seed=0)
+        s_ = [xi[r].clone().cuda() for r in range(n)]
+        r_ = [torch.empty_like(t) for t in s_]
+        c1 = {}
+        for name, a in [("1pa_ll", 1), ("2pa_ll", 2), ("2pa_hb", 3), ("2pa_hb_2phase", 4)]:
+            fn = lambda: msx.allreduce_ex(s_, r_, None, algo=a)
+            c1[name] = round(back_to_back_us(torch, fn, 200, 20), 2)
+        msx.check_status()
+        extras["config1_fp32_1MiB_us"] = c1
+        # other HB sizes of config 3
+        c3 = {}
+        for mib in [64, 256]:
+            c = mib * (1 << 20) // 2
+            xs = synth.normal(n, c, seed=mib, device="cuda")
+            s_ = [xs[r] for r in range(n)]
+            r_ = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            fn = lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO)
+            _, ev = time_calls(torch, fn, 20, 5)
+            ms = sum(ev) / len(ev) / 1e3
+            c3[f"{mib}MiB"] = {"ms": round(ms, 4), "GBps": round(16 * c * 2 / ms / 1e6, 1),
+                               "pct_roofline": round(16 * c * 2 / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+            del xs, s_, r_
+            torch.cuda.empty_cache()
+        msx.check_status()
+        extras["config3_other_sizes"] = c3
+        # config 5
+        T, H, K, E = 4096, 7168, 8, 256
+        tok = synth.moe_tokens(n, T, H, seed=0, device="cuda")
+        topk = synth.moe_routing(n, T, K, E, seed=0, device="cuda")
+        cap = 24576
+        rt = [torch.empty((cap, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        rs = [torch.empty((cap,), dtype=torch.int32, device="cuda") for _ in range(n)]
+        cnt = torch.zeros((n, n), dtype=torch.int32, device="cuda")
+        tk = [tok[r] for r in range(n)]
+        ix = [topk[r].contiguous() for r in range(n)]
+        fn = lambda: msx.moe_dispatch(tk, ix, E, rt, cnt, rs)
+        _, ev = time_calls(torch, fn, 20, 5)
+        msx.check_status()
+        rows = int(cnt.sum().item())
+        ms = sum(ev) / len(ev) / 1e3
+        moved = n * T * H * 2 + rows * H * 2
+        extras["config5_moe_dispatch"] = {"ms": round(ms, 4), "rows_sent": rows, "GBps": round(moved / ms / 1e6, 1),
+                                          "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+        extras["hop_ns"] = {"signal_wait_round_trip_cross_xcd": round(msx.prim_pingpong(2000, 16, 0, 1), 1),
+                            "signal_wait_round_trip_same_xcd": round(msx.prim_pingpong(2000, 16, 0, 8), 1)}
+        out["extras"] = extras
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

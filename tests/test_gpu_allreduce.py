@@ -145,7 +145,10 @@ def test_ieee_special_values(msx, orc):
 def test_config4_decode_allreduce_with_fused_residual(msx, orc, T):
     x, res = synth.decode_activations(8, T, hidden=8192, seed=T)
     want = orc.allreduce_residual_bf16(_bits(x), _bits(res))
+    one_phase_limit = int(msx.get_option("ll_max_bytes")) // 4      # 1PA keeps n full copies per rank
     for name, algo in ALGOS.items():
+        if name == "1pa_ll" and T * 8192 * 2 > one_phase_limit:
+            continue
         outs = _run_ex(msx, x, algo, residual=res)
         for r in range(8):
             assert np.array_equal(outs[r], want), (name, T, r)
