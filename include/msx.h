@@ -15,7 +15,9 @@
  *     are HOST arrays of `nranks` device pointers; they are read during the call only.
  *   - nranks is 1..8.  count == 0 is a successful no-op.
  *   - All calls share one per-device context (flag epoch, semaphore counters): issue
- *     them on one stream, or order them yourself.
+ *     them on one stream, or order them yourself.  That state lives in device memory and
+ *     is advanced by the kernels, so calls may be captured into a HIP graph and replayed
+ *     (create the context with msx_init or a first call before capturing).
  *   - A device-side wait that does not finish within the spin budget makes its workgroup
  *     record {rank, site, expected, seen} and carry on; nothing hangs.  msx_status()
  *     reports it.  After a timeout call msx_reset().
@@ -177,7 +179,7 @@ int msx_finalize(void);
  *   "spin_limit"      polls before a wait gives up
  *   "drop_rank"       -1, or a rank whose workgroups return at once (failure-path tests)
  *   "chaos"           0, or a seed: workgroups sleep pseudo-random times before they signal
- *   "epoch"           next LL flag value (tests of wrap-around)
+ *   "epoch"           next LL flag value (tests of wrap-around; synchronises the device)
  *   "sem_base"        set every semaphore and expected value to this number (wrap tests; syncs)
  * Unknown key or bad value -> MSX_ERR_ARG. */
 int msx_set_option(const char* key, const char* value);

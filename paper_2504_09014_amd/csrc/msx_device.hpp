@@ -31,6 +31,7 @@ struct DevCtx {
     unsigned* sem;        // [kMaxRanks recv][kMaxRanks send][kMaxChannels] x kSemStrideWords
     unsigned* expected;   // [kMaxRanks recv][kMaxRanks send][kMaxChannels] value the next wait needs
     unsigned* status;     // 8 words: code, rank, site, expected, seen, block
+    unsigned* call_state; // {last LL flag handed out, LL calls so far, workgroups finished this call}
     void* ll;             // LL scratch, ll_bytes long: [rank][rotation][...]
     unsigned ll_bytes;
     unsigned ll_rank_stride;
@@ -71,10 +72,11 @@ __device__ __forceinline__ void chaos_delay(const DevCtx& c, unsigned site)
 
 // signal(): make every earlier store of this workgroup visible device-wide, then bump the
 // receiver's counter.  Call from ONE thread, after a workgroup barrier if other threads
-// of the workgroup produced the data.
-__device__ __forceinline__ void sem_signal(unsigned* sem)
+// of the workgroup produced the data.  release = false skips the fence: for a signal that
+// publishes no data of this launch ("I have arrived", "I am done reading").
+__device__ __forceinline__ void sem_signal(unsigned* sem, bool release = true)
 {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    if (release) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
     __hip_atomic_fetch_add(sem, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
@@ -82,7 +84,7 @@ __device__ __forceinline__ void sem_signal(unsigned* sem)
 // (signed distance, so the 32-bit counter may wrap), then acquires.  Returns false and
 // records the timeout when the spin budget runs out.
 __device__ __forceinline__ bool sem_spin(const DevCtx& c, unsigned* sem, unsigned expected,
-                                         unsigned rank, unsigned site)
+                                         unsigned rank, unsigned site, bool acquire = true)
 {
     unsigned seen = 0;
     bool ok = false;
@@ -91,7 +93,7 @@ __device__ __forceinline__ bool sem_spin(const DevCtx& c, unsigned* sem, unsigne
         if ((int)(seen - expected) >= 0) { ok = true; break; }
         __builtin_amdgcn_s_sleep(1);
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    if (acquire) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     if (!ok) report(c, kStatusTimeout, rank, site, expected, seen);
     return ok;
 }
@@ -120,7 +122,12 @@ __device__ __forceinline__ void channel_wait(const DevCtx& c, int me, int peer, 
 
 // Barrier among all ranks on one channel: signal every peer, then wait for every peer.
 // Threads 0..n-2 each serve one peer so the n-1 hops overlap.  Workgroup-collective.
-__device__ __forceinline__ void rank_barrier(const DevCtx& c, int me, int n, int chan, unsigned site)
+//   release: this workgroup wrote data the peers (or their next kernel) will read
+//   acquire: this workgroup is about to read data the peers wrote
+// A device-scope release writes the whole L2 of this XCD back and an acquire invalidates it,
+// and those operations queue up per XCD, so each barrier asks only for what it needs.
+__device__ __forceinline__ void rank_barrier(const DevCtx& c, int me, int n, int chan, unsigned site,
+                                             bool release = true, bool acquire = true)
 {
     __syncthreads();
     const int t = (int)threadIdx.x;
@@ -128,13 +135,41 @@ __device__ __forceinline__ void rank_barrier(const DevCtx& c, int me, int n, int
         int peer = me + 1 + t;
         if (peer >= n) peer -= n;
         chaos_delay(c, site + (unsigned)t);
-        sem_signal(c.sem + (size_t)sem_index(peer, me, chan) * kSemStrideWords);
+        sem_signal(c.sem + (size_t)sem_index(peer, me, chan) * kSemStrideWords, release);
         unsigned idx = sem_index(me, peer, chan);
         unsigned want = c.expected[idx] + 1u;
         c.expected[idx] = want;
-        sem_spin(c, c.sem + (size_t)idx * kSemStrideWords, want, (unsigned)me, site);
+        sem_spin(c, c.sem + (size_t)idx * kSemStrideWords, want, (unsigned)me, site, acquire);
     }
     __syncthreads();
+}
+
+// ---- per-call flag and scratch rotation for the LL protocol -----------------------------------
+// The flag of a call and the scratch half it uses come from device memory, not from kernel
+// arguments, so a captured launch can be replayed: every workgroup reads the state when it
+// starts, and the LAST workgroup to finish advances it (all others have read it by then).
+struct CallTag { unsigned flag; unsigned rot; };
+
+__device__ __forceinline__ CallTag call_begin(const DevCtx& c)
+{
+    const unsigned e = c.call_state[0], k = c.call_state[1];
+    unsigned f = e + 1u;
+    if (f == 0u) f = 1u;            // 0 is what untouched scratch holds
+    return CallTag{f, k & 1u};
+}
+
+// Workgroup-collective; every workgroup of the launch must call it exactly once, at its end.
+__device__ __forceinline__ void call_end(const DevCtx& c, CallTag tag)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned done = __hip_atomic_fetch_add(c.call_state + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (done == gridDim.x - 1u) {
+            __hip_atomic_store(c.call_state + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(c.call_state + 0, tag.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(c.call_state + 1, c.call_state[1] + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 }
 
 // ---- HB protocol: cooperative 16-byte copy ---------------------------------------------

@@ -40,8 +40,6 @@ struct Options {
 struct Ctx {
     int device = -1;
     DevCtx d{};
-    unsigned epoch = 0;        // last LL flag handed out
-    unsigned calls = 0;        // LL calls so far (rotation)
     int cus = 0;
     double ns_per_tick = 10.0;
     void* moe_slots = nullptr;
@@ -79,6 +77,7 @@ int destroy_ctx(Ctx* c)
     if (c->d.sem) (void)hipFree(c->d.sem);
     if (c->d.expected) (void)hipFree(c->d.expected);
     if (c->d.status) (void)hipFree(c->d.status);
+    if (c->d.call_state) (void)hipFree(c->d.call_state);
     if (c->d.ll) (void)hipFree(c->d.ll);
     if (c->moe_slots) (void)hipFree(c->moe_slots);
     if (c->moe_base) (void)hipFree(c->moe_base);
@@ -119,12 +118,14 @@ int get_ctx(Ctx** out)
     bool ok = hipMalloc((void**)&c->d.sem, sem_bytes) == hipSuccess &&
               hipMalloc((void**)&c->d.expected, exp_bytes) == hipSuccess &&
               hipMalloc((void**)&c->d.status, 64) == hipSuccess &&
+              hipMalloc((void**)&c->d.call_state, 64) == hipSuccess &&
               hipMalloc((void**)&c->d.ll, ll_bytes) == hipSuccess &&
               hipMalloc((void**)&c->moe_base, 64 * 4) == hipSuccess &&
               hipMalloc((void**)&c->snap, 4096) == hipSuccess;
     ok = ok && hipMemset(c->d.sem, 0, sem_bytes) == hipSuccess &&
          hipMemset(c->d.expected, 0, exp_bytes) == hipSuccess &&
          hipMemset(c->d.status, 0, 64) == hipSuccess &&
+         hipMemset(c->d.call_state, 0, 64) == hipSuccess &&
          hipMemset(c->d.ll, 0, ll_bytes) == hipSuccess &&
          hipMemset(c->moe_base, 0, 64 * 4) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
     if (!ok) { destroy_ctx(c); t_hip_err = (int)hipErrorOutOfMemory; return MSX_ERR_NOMEM; }
@@ -144,12 +145,6 @@ DevCtx dev_ctx(const Ctx* c)
     d.drop_rank = g_opt.drop_rank;
     d.chaos = g_opt.chaos;
     return d;
-}
-
-unsigned next_flag(Ctx* c)
-{
-    if (++c->epoch == 0) c->epoch = 1;   // 0 is what untouched scratch holds
-    return c->epoch;
 }
 
 // how many workgroups of `threads` threads of kernel k can be resident on the whole GPU
@@ -311,8 +306,6 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
         a.chans = chans;
         a.has_res = residual ? 1 : 0;
         a.res_shared = res_shared ? 1 : 0;
-        a.flag = next_flag(c);
-        a.rot = c->calls++ & 1u;
         note_launch(n * chans, threads, algo);
         return launch(k, n * chans, threads, stream, a, dev_ctx(c));
     }
@@ -583,8 +576,6 @@ int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, 
     a.row_vecs = (unsigned)(row_bytes / 16);
     a.cap = (unsigned)recv_capacity_tokens;
     a.has_src = recv_src_token ? 1 : 0;
-    a.flag = next_flag(c);
-    a.rot = c->calls++ & 1u;
     const DevCtx d = dev_ctx(c);
 
     int resident = 0;
@@ -684,11 +675,9 @@ int msx_prim_ll_roundtrip(const void* src, void* dst, size_t nbytes, int blocks_
     int resident = 0;
     if ((rc = resident_blocks(c, (const void*)k_ll_roundtrip, 256, &resident))) return rc;
     if (2 * blocks_per_rank > resident) return MSX_ERR_ARG;
-    const unsigned flag = next_flag(c);
-    const unsigned rot = c->calls++ & 1u;
     note_launch(2 * blocks_per_rank, 256, 0);
     return launch(k_ll_roundtrip, 2 * blocks_per_rank, 256, (hipStream_t)stream, dev_ctx(c), src, dst, nbytes,
-                  blocks_per_rank, flag, rot);
+                  blocks_per_rank);
 }
 
 // ---- context, options, status ---------------------------------------------------------------
@@ -710,10 +699,9 @@ int msx_reset(void)
     HIPCHK(hipMemset(c->d.sem, 0, (size_t)kMaxRanks * kMaxRanks * kMaxChannels * kSemStrideWords * 4));
     HIPCHK(hipMemset(c->d.expected, 0, (size_t)kMaxRanks * kMaxRanks * kMaxChannels * 4));
     HIPCHK(hipMemset(c->d.status, 0, 64));
+    HIPCHK(hipMemset(c->d.call_state, 0, 64));
     HIPCHK(hipMemset(c->d.ll, 0, c->d.ll_bytes));
     HIPCHK(hipDeviceSynchronize());
-    c->epoch = 0;
-    c->calls = 0;
     return MSX_OK;
 }
 
@@ -782,7 +770,9 @@ int msx_set_option(const char* key, const char* value)
         Ctx* c = nullptr;
         int rc = get_ctx(&c);
         if (rc) return rc;
-        c->epoch = (unsigned)u - 1u;   // the next call uses exactly u (or 1 if u is 0)
+        HIPCHK(hipDeviceSynchronize());
+        const unsigned last = (unsigned)u - 1u;   // the next call uses exactly u (or 1 if u is 0)
+        HIPCHK(hipMemcpy(c->d.call_state, &last, 4, hipMemcpyHostToDevice));
     } else if (k == "sem_base") {
         Ctx* c = nullptr;
         int rc = get_ctx(&c);
@@ -832,7 +822,12 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
     else if (k == "chaos") u = g_opt.chaos;
     else if (k == "epoch") {
         int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && g_ctx[dev]) u = g_ctx[dev]->epoch;
+        if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && g_ctx[dev]) {
+            unsigned last = 0;
+            HIPCHK(hipDeviceSynchronize());
+            HIPCHK(hipMemcpy(&last, g_ctx[dev]->d.call_state, 4, hipMemcpyDeviceToHost));
+            u = last;
+        }
     } else return MSX_ERR_ARG;
     snprintf(value_out, value_len, "%llu", u);
     return MSX_OK;

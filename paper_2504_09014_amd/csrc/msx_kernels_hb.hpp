@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
     constexpr size_t epv = DT == 0 ? 4 : 8;
     const size_t V = a.count / epv;
 
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 10);   // every peer's input is ready
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 10, false, true);   // every peer's input is ready
 
     const size_t lo = V * (size_t)rank / (size_t)n;
     const size_t hi = V * (size_t)(rank + 1) / (size_t)n;
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
     }
     if (rank == 0 && chan == 0) allreduce_tail<DT>(a, n, V * epv, a.count);
 
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 11);   // every peer's puts into my output landed
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 11, true, false);   // every peer's puts into my output landed
 }
 
 // ---- two-phase form: reduce-scatter to memory, rank barrier, all-gather by put ---------------
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_2phase(HbArgs a, DevCtx c)
     constexpr size_t epv = DT == 0 ? 4 : 8;
     const size_t V = a.count / epv;
 
-    if (n > 1) rank_barrier(c, rank, n, chan, 20);
+    if (n > 1) rank_barrier(c, rank, n, chan, 20, false, true);
 
     const size_t lo = V * (size_t)rank / (size_t)n;
     const size_t hi = V * (size_t)(rank + 1) / (size_t)n;
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_2phase(HbArgs a, DevCtx c)
     }
     if (rank == 0 && chan == 0) allreduce_tail<DT>(a, n, V * epv, a.count);
 
-    if (n > 1) rank_barrier(c, rank, n, chan, 22);
+    if (n > 1) rank_barrier(c, rank, n, chan, 22, true, false);
 }
 
 // ---- standalone ReduceScatter: out[r][k] = sum_j in[j][r*c + k], k < c = count ---------------
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(256) void k_reducescatter_hb(HbArgs a, DevCtx c, in
     if (rank == c.drop_rank) return;
     constexpr size_t epv = DT == 0 ? 4 : 8;
     constexpr size_t esz = DT == 0 ? 4 : 2;
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 30);
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 30, false, true);
     const size_t RT = (size_t)a.chans * blockDim.x;
     const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
     const size_t blk = a.count;
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256) void k_reducescatter_hb(HbArgs a, DevCtx c, in
             store_elem<DT>(a.out[rank], k, acc);
         }
     }
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 31);   // peers are done reading my input
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 31, false, false);   // peers are done reading my input: nothing to publish
 }
 
 // ---- standalone AllGather: out[p] block r = in[r]; a.count = bytes per block ------------------
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int ve
                 if (dst[p] != src) dst[p][b] = v;
         }
     }
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 40);   // all blocks have landed in my output
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 40, true, false);   // all blocks have landed in my output
 }
 
 // ---- standalone AllToAll (out of place): out[d] block s = in[s] block d; a.count = bytes/block ---
@@ -302,7 +302,7 @@ __global__ __launch_bounds__(256) void k_alltoall_hb(HbArgs a, DevCtx c, int vec
             for (size_t b = rt; b < nbytes; b += RT) dp[b] = sp[b];
         }
     }
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 50);
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 50, true, false);
 }
 
 // ---- AllToAll in place: block (s,d) and block (d,s) swap through registers --------------------
@@ -314,7 +314,7 @@ __global__ __launch_bounds__(256) void k_alltoall_inplace(HbArgs a, DevCtx c, in
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
     if (rank == c.drop_rank) return;
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 60);
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 60, false, true);
     const size_t RT = (size_t)a.chans * blockDim.x;
     const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
     const size_t nbytes = a.count;
@@ -341,7 +341,7 @@ __global__ __launch_bounds__(256) void k_alltoall_inplace(HbArgs a, DevCtx c, in
             }
         }
     }
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 61);
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 61, true, false);
 }
 
 }  // namespace msx

@@ -6,6 +6,8 @@
 // A thread always works on the same packet index in every phase, so no workgroup barrier
 // is needed either.  The scratch has two rotating halves (picked by the call counter) so a
 // rank may start the next call while a slow peer still reads the previous call's packets.
+// The flag and the half come from device memory (call_begin / call_end), so a launch can be
+// captured in a HIP graph and replayed.
 #pragma once
 #include "msx_device.hpp"
 
@@ -20,8 +22,6 @@ struct LlArgs {
     int chans;
     int has_res;
     int res_shared;
-    unsigned flag;      // this call's flag (never 0)
-    unsigned rot;       // which half of the rotating scratch
 };
 
 // payload words of packet k (bytes [8k, 8k+8)), zero padded past nbytes; nbytes is even
@@ -54,9 +54,9 @@ __device__ __forceinline__ void store_words(void* base, size_t k, size_t nbytes,
             _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)                             \
                 if (j < n && j != rank) v[j] = ll_load(rs, (base_off) + (unsigned)j * (slot_stride) + (unsigned)(pos) * 16u); \
             _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)                             \
-                if (j < n && j != rank) ready = ready && ll_ready(v[j], a.flag);              \
+                if (j < n && j != rank) ready = ready && ll_ready(v[j], tag.flag);              \
         }                                                                                     \
-        if (!ready) report(c, kStatusTimeout, (unsigned)rank, 100u, a.flag, 0u);              \
+        if (!ready) report(c, kStatusTimeout, (unsigned)rank, 100u, tag.flag, 0u);              \
     }
 
 // ---- 1PA: every rank sends ALL its data to every peer, then reduces everything itself --------
@@ -66,13 +66,14 @@ __global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
     const int n = NR ? NR : a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
-    if (rank == c.drop_rank) return;
+    const CallTag tag = call_begin(c);
+    if (rank == c.drop_rank) { call_end(c, tag); return; }
     const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
     const unsigned P = (unsigned)((a.nbytes + 7) / 8);          // packets per rank
     const unsigned RT = (unsigned)a.chans * blockDim.x;
     const unsigned rt = (unsigned)chan * blockDim.x + threadIdx.x;
     const unsigned slot_stride = P * 16u;
-    const unsigned rot_off = a.rot * c.ll_rot_stride;
+    const unsigned rot_off = tag.rot * c.ll_rot_stride;
     chaos_delay(c, 70);
 
     // send: my packet k goes to slot `rank` of every peer, all peers before any wait
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
         for (int p = 0; p < kMaxRanks; ++p)
             if (p < n && p != rank)
                 ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + k * 16u,
-                         w.x, w.y, a.flag);
+                         w.x, w.y, tag.flag);
     }
     // receive + reduce in rank order 0..n-1 (identical bits on every rank)
     const unsigned my_off = (unsigned)rank * c.ll_rank_stride + rot_off;
@@ -104,6 +105,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
         }
         store_words(a.out[rank], k, a.nbytes, u32x2{a0.pack(), a1.pack()});
     }
+    call_end(c, tag);
 }
 
 // ---- 2PA: reduce-scatter over packets, then all-gather over packets ----------------------------
@@ -116,14 +118,15 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
     const int n = NR ? NR : a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
-    if (rank == c.drop_rank) return;
+    const CallTag tag = call_begin(c);
+    if (rank == c.drop_rank) { call_end(c, tag); return; }
     const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
     const unsigned P = (unsigned)((a.nbytes + 7) / 8);
     const unsigned cp = (P + (unsigned)n - 1) / (unsigned)n;
     const unsigned RT = (unsigned)a.chans * blockDim.x;
     const unsigned rt = (unsigned)chan * blockDim.x + threadIdx.x;
     const unsigned slot_stride = cp * 16u;
-    const unsigned rot_off = a.rot * c.ll_rot_stride;
+    const unsigned rot_off = tag.rot * c.ll_rot_stride;
     const unsigned ph2 = (unsigned)n * slot_stride;
     const unsigned my_off = (unsigned)rank * c.ll_rank_stride + rot_off;
     chaos_delay(c, 80);
@@ -137,7 +140,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
                 if (k < P) {
                     const u32x2 w = load_words(a.in[rank], k, a.nbytes);
                     ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + q * 16u,
-                             w.x, w.y, a.flag);
+                             w.x, w.y, tag.flag);
                 }
             }
     }
@@ -166,7 +169,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
             for (int p = 0; p < kMaxRanks; ++p)
                 if (p < n && p != rank)
                     ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + ph2 + (unsigned)rank * slot_stride + q * 16u,
-                             o.x, o.y, a.flag);
+                             o.x, o.y, tag.flag);
             store_words(a.out[rank], k, a.nbytes, o);
         } else {
             // every destination adds its own residual before the single rounding
@@ -179,7 +182,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
                     const u32x2 o = {t0.pack(), t1.pack()};
                     if (p != rank)
                         ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + ph2 + (unsigned)rank * slot_stride + q * 16u,
-                                 o.x, o.y, a.flag);
+                                 o.x, o.y, tag.flag);
                     else
                         store_words(a.out[rank], k, a.nbytes, o);
                 }
@@ -199,14 +202,15 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
                     v[j] = ll_load(rs, my_off + ph2 + (unsigned)j * slot_stride + q * 16u);
 #pragma unroll
             for (int j = 0; j < kMaxRanks; ++j)
-                if (j < n && j != rank && (unsigned)j * cp + q < P) ready = ready && ll_ready(v[j], a.flag);
+                if (j < n && j != rank && (unsigned)j * cp + q < P) ready = ready && ll_ready(v[j], tag.flag);
         }
-        if (!ready) report(c, kStatusTimeout, (unsigned)rank, 101u, a.flag, 0u);
+        if (!ready) report(c, kStatusTimeout, (unsigned)rank, 101u, tag.flag, 0u);
 #pragma unroll
         for (int j = 0; j < kMaxRanks; ++j)
             if (j < n && j != rank && (unsigned)j * cp + q < P)
                 store_words(a.out[rank], (size_t)j * cp + q, a.nbytes, u32x2{v[j].x, v[j].z});
     }
+    call_end(c, tag);
 }
 
 }  // namespace msx

@@ -28,8 +28,6 @@ struct MoeArgs {
     unsigned cap;           // rows per destination buffer
     int chans;
     int has_src;
-    unsigned flag;
-    unsigned rot;
 };
 
 constexpr int kPlanThreads = 1024;
@@ -63,7 +61,8 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
 {
     const int n = a.n;
     const int rank = (int)blockIdx.x;           // one workgroup per source rank
-    if (rank == c.drop_rank) return;
+    const CallTag tag = call_begin(c);
+    if (rank == c.drop_rank) { call_end(c, tag); return; }
     __shared__ unsigned long long scan_lds[2 * (kPlanThreads / 64)];
     __shared__ unsigned cnt[kMaxRanks][kMaxRanks];   // [src][dst]
     const int T = a.T, K = a.K;
@@ -110,7 +109,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
 
     // exchange counts: my 8 per-destination counts go to every peer as 4 LL packets
     const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
-    const unsigned rot_off = a.rot * c.ll_rot_stride;
+    const unsigned rot_off = tag.rot * c.ll_rot_stride;
     const unsigned tid = threadIdx.x;
     if (tid < 8) cnt[rank][tid] = (unsigned)(((tid < 4 ? totx : toty) >> (16 * (tid & 3))) & 0xffffu);
     __syncthreads();
@@ -119,7 +118,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
         const unsigned q = tid & 3u;
         if (p != rank)
             ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + ((unsigned)rank * 4u + q) * 16u,
-                     cnt[rank][2 * q], cnt[rank][2 * q + 1], a.flag);
+                     cnt[rank][2 * q], cnt[rank][2 * q + 1], tag.flag);
     }
     if (tid < (unsigned)n * 4u) {
         const int j = (int)(tid >> 2);
@@ -130,9 +129,9 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
             for (unsigned spins = 0; !ready && spins <= c.spin_limit; ++spins) {
                 poll_fence();
                 v = ll_load(rs, (unsigned)rank * c.ll_rank_stride + rot_off + ((unsigned)j * 4u + q) * 16u);
-                ready = ll_ready(v, a.flag);
+                ready = ll_ready(v, tag.flag);
             }
-            if (!ready) report(c, kStatusTimeout, (unsigned)rank, 200u, a.flag, v.y);
+            if (!ready) report(c, kStatusTimeout, (unsigned)rank, 200u, tag.flag, v.y);
             cnt[j][2 * q] = v.x;
             cnt[j][2 * q + 1] = v.z;
         }
@@ -152,6 +151,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
         for (int s = 0; s < n; ++s) tot += cnt[s][rank];
         if (tot > a.cap) report(c, kStatusCapacity, (unsigned)rank, 201u, a.cap, tot);
     }
+    call_end(c, tag);
 }
 
 __global__ __launch_bounds__(256) void k_moe_pack(MoeArgs a, DevCtx c)
@@ -197,7 +197,7 @@ __global__ __launch_bounds__(256) void k_moe_pack(MoeArgs a, DevCtx c)
                 }
         }
     }
-    if (n > 1) rank_barrier(c, rank, n, chan, 210);   // all rows destined to me have landed
+    if (n > 1) rank_barrier(c, rank, n, chan, 210, true, false);   // all rows destined to me have landed
 }
 
 }  // namespace msx

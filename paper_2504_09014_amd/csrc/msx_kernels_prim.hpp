@@ -89,11 +89,13 @@ __global__ __launch_bounds__(256) void k_ll_encode(const void* src, size_t nbyte
 // LL hand-off through the library scratch: rank 0 writes packets into rank 1's slot 0,
 // rank 1 polls each packet and writes the payload out.
 __global__ __launch_bounds__(256) void k_ll_roundtrip(DevCtx c, const void* src, void* dst, size_t nbytes,
-                                                       int chans, unsigned flag, unsigned rot)
+                                                       int chans)
 {
     const int rank = (int)(blockIdx.x & 1u);
     const int chan = (int)(blockIdx.x >> 1);
-    if (rank == c.drop_rank) return;
+    const CallTag tag = call_begin(c);
+    const unsigned flag = tag.flag, rot = tag.rot;
+    if (rank == c.drop_rank) { call_end(c, tag); return; }
     const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
     const unsigned P = (unsigned)((nbytes + 7) / 8);
     const unsigned RT = (unsigned)chans * blockDim.x;
@@ -121,6 +123,7 @@ __global__ __launch_bounds__(256) void k_ll_roundtrip(DevCtx c, const void* src,
                 if (off + (size_t)b < nbytes) ((unsigned char*)dst)[off + b] = (unsigned char)(w[b >> 2] >> (8 * (b & 3)));
         }
     }
+    call_end(c, tag);
 }
 
 }  // namespace msx

@@ -242,3 +242,40 @@ def test_ll_request_larger_than_scratch_is_refused(msx):
     assert e.value.code == -5
     with pytest.raises(msx.MsxError):
         msx.allreduce_ex(send, send, None, algo=1)
+
+
+def test_calls_captured_in_a_hip_graph_replay_correctly(msx, orc):
+    # flags, scratch rotation and expected semaphore values live in device memory, so a captured
+    # sequence of calls can be replayed; inputs change between replays, eager calls run in between
+    n, count = 8, 6000
+    xs = [synth.normal(n, count, seed=200 + i) for i in range(4)]
+    send = [xs[0][r].clone().cuda() for r in range(n)]
+    outs = {a: [torch.zeros(count, dtype=torch.bfloat16, device="cuda") for _ in range(n)] for a in ALGOS.values()}
+    for a in ALGOS.values():                                  # warm-up outside the capture
+        msx.allreduce_ex(send, outs[a], None, algo=a)
+    msx.check_status()
+    st = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(g, stream=st):
+            for _ in range(3):
+                for a in ALGOS.values():
+                    msx.allreduce_ex(send, outs[a], None, algo=a)
+    torch.cuda.synchronize()
+    for i, x in enumerate(xs):
+        for r in range(n):
+            send[r].copy_(x[r])
+        for a in ALGOS.values():
+            for t in outs[a]:
+                t.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        msx.check_status()
+        want = _oracle(orc, x)
+        for a in ALGOS.values():
+            for r in (0, 4, 7):
+                assert np.array_equal(_bits(outs[a][r]), want), (i, a, r)
+        # eager calls between replays share the same device-side call state
+        assert np.array_equal(_run_ex(msx, x, 2)[1], want)
+        assert np.array_equal(_run_ex(msx, x, 1)[6], want)
