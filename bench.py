@@ -175,6 +175,7 @@ def main():
             "workload": f"AllReduce-sum 2PA-HB fused, 8 emulated ranks, bf16 N(0,1), {args.mib} MiB per rank, "
                         f"out of place ({n * S >> 20} MiB in + {n * S >> 20} MiB out)",
             "nranks": n, "bytes_per_rank": S, "algo": algo, "grid": grid, "block": block,
+            "gpu": torch.cuda.get_device_name(0), "gpu_uuid": str(getattr(torch.cuda.get_device_properties(0), "uuid", "")),
             "algbw_GBps": round(S / (wall / args.steps) / 1e9, 1),
             "busbw_GBps": round(S / (wall / args.steps) / 1e9 * 2 * (n - 1) / n, 1),
             "pct_hbm_roofline": round(100 * value / HBM_PEAK_GBPS, 1),
@@ -230,12 +231,13 @@ def main():
             xs = synth.normal(n, c, seed=kib)
             s_ = [xs[r].clone().cuda() for r in range(n)]
             r_ = [torch.empty_like(t) for t in s_]
-            fn = lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO)
-            b2b = back_to_back_us(torch, fn, 300, 20)
-            gus = graph_us(torch, fn)
+            ll_algo = msx.ALGO_1PA_LL if kib <= 32 else msx.ALGO_2PA_LL     # the paper's split on A100
+            row = {}
+            for name, a in [("ll_us", ll_algo), ("hb_us", msx.ALGO_2PA_HB), ("auto_us", msx.ALGO_AUTO)]:
+                row[name] = round(graph_us(torch, lambda: msx.allreduce_ex(s_, r_, None, algo=a)), 2)
             g, b, a = msx.last_launch()
-            lat[f"{kib}KiB"] = {"us_in_graph": round(gus, 2), "us_eager_python": round(b2b, 2),
-                                "algo": a, "grid": g, "block": b}
+            row.update({"ll_algo": ll_algo, "auto_algo": a, "auto_grid": g, "auto_block": b})
+            lat[f"{kib}KiB"] = row
         msx.check_status()
         extras["config2_bf16_latency"] = lat
         dec = {}

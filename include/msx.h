@@ -176,6 +176,8 @@ int msx_finalize(void);
  *   "hb_blocks_per_rank", "ll_blocks_per_rank", "threads"   0 = automatic
  *   "hb_unroll"       1 | 2 | 4
  *   "hb_barriers"     0 | 1   start/end rank barriers in the HB kernels
+ *   "peer_outer"      0 | 1   two-phase HB all-gather: one put per peer instead of peer-inner
+ *   "barrier_fences"  0..3    msx_prim_barrier only: bit 0 release fence, bit 1 acquire fence
  *   "spin_limit"      polls before a wait gives up
  *   "drop_rank"       -1, or a rank whose workgroups return at once (failure-path tests)
  *   "chaos"           0, or a seed: workgroups sleep pseudo-random times before they signal

@@ -25,13 +25,17 @@ namespace {
 
 struct Options {
     int algo = MSX_ALGO_AUTO;
-    size_t ll_1pa_max = 32u << 10;
-    size_t ll_2pa_max = 512u << 10;
+    // Automatic choice, from the per-size sweep on MI355X: inside one chip a peer's buffer is as
+    // close as the rank's own, so the fused HB kernel (two flag hops, 16 S bytes) beats the packet
+    // protocols from 4 KiB up; 1PA-LL ties with it below.  2PA-LL is reachable by request only.
+    size_t ll_1pa_max = 2u << 10;
+    size_t ll_2pa_max = 0;
     size_t ll_max_bytes = 4u << 20;
     int hb_blocks = 0, ll_blocks = 0, threads = 0;
-    int hb_unroll = 2;
+    int hb_unroll = 0;        // 0 = by size
     int hb_barriers = 1;
     int peer_outer = 0;
+    int barrier_fences = 3;   // msx_prim_barrier only: bit 0 release, bit 1 acquire
     unsigned spin_limit = 1u << 20;
     int drop_rank = -1;
     unsigned chaos = 0;
@@ -218,12 +222,14 @@ int launch(K k, int grid, int block, hipStream_t s, A... args)
 typedef void (*HbKernel)(HbArgs, DevCtx);
 typedef void (*LlKernel)(LlArgs, DevCtx);
 
-HbKernel hb_fused_kernel(int dt, int u, int n)
+HbKernel hb_fused_kernel(int dt, int u, int n, int res)
 {
-#define MSX_ROW(DT, U) (n == 8 ? (HbKernel)k_allreduce_hb_fused<DT, U, 8> : (HbKernel)k_allreduce_hb_fused<DT, U, 0>)
-    if (dt == MSX_F32) return u >= 4 ? MSX_ROW(0, 4) : u == 2 ? MSX_ROW(0, 2) : MSX_ROW(0, 1);
-    return u >= 4 ? MSX_ROW(1, 4) : u == 2 ? MSX_ROW(1, 2) : MSX_ROW(1, 1);
-#undef MSX_ROW
+#define MSX_N(DT, U, RES) (n == 8 ? (HbKernel)k_allreduce_hb_fused<DT, U, 8, RES> : (HbKernel)k_allreduce_hb_fused<DT, U, 0, RES>)
+#define MSX_R(DT, U) (res == 0 ? MSX_N(DT, U, 0) : res == 1 ? MSX_N(DT, U, 1) : MSX_N(DT, U, 2))
+    if (dt == MSX_F32) return u >= 4 ? MSX_R(0, 4) : u == 2 ? MSX_R(0, 2) : MSX_R(0, 1);
+    return u >= 4 ? MSX_R(1, 4) : u == 2 ? MSX_R(1, 2) : MSX_R(1, 1);
+#undef MSX_R
+#undef MSX_N
 }
 HbKernel hb_2phase_kernel(int dt, int u, int n)
 {
@@ -310,16 +316,27 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
         return launch(k, n * chans, threads, stream, a, dev_ctx(c));
     }
 
-    // HB protocol
-    const int U = g_opt.hb_unroll;
+    // HB protocol.  Launch shape by size (from a sweep on MI355X): small messages want every
+    // thread to issue all its loads at once (more unrolling, one pass); large ones want many
+    // plain workgroups.  Options override.
     if (algo == MSX_ALGO_2PA_HB_2PHASE && residual && !res_shared) return MSX_ERR_UNSUPPORTED;
-    HbKernel k = algo == MSX_ALGO_2PA_HB ? hb_fused_kernel(dtype, U, n) : hb_2phase_kernel(dtype, U, n);
     const int threads = 256;
     const size_t vecs = nbytes / 16;
     const size_t per_rank = (vecs + (size_t)n - 1) / (size_t)n;
+    int U = g_opt.hb_unroll;
+    int want = g_opt.hb_blocks;
+    if (U == 0) U = per_rank <= 32768 ? 2 : 1;
+    if (algo == MSX_ALGO_2PA_HB_2PHASE && U > 2) U = 2;
+    if (want == 0) {
+        if (per_rank <= 32768) want = (int)((per_rank + (size_t)threads * U - 1) / ((size_t)threads * U));
+        else if (per_rank <= 262144) want = 32;   // up to 4 MiB of chunk per rank
+        else want = 128;
+        if (want < 1) want = 1;
+    }
+    HbKernel k = algo == MSX_ALGO_2PA_HB ? hb_fused_kernel(dtype, U, n, !residual ? 0 : res_shared ? 1 : 2)
+                                         : hb_2phase_kernel(dtype, U, n);
     int chans = 1;
-    if ((rc = pick_channels(c, (const void*)k, threads, n, per_rank, (size_t)(U < 1 ? 1 : U), g_opt.hb_blocks,
-                            kMaxChannels, &chans)))
+    if ((rc = pick_channels(c, (const void*)k, threads, n, per_rank, (size_t)U, want, kMaxChannels, &chans)))
         return rc;
     HbArgs a{};
     for (int i = 0; i < n; ++i) {
@@ -585,8 +602,9 @@ int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, 
     if ((rc = launch(k_moe_plan, n, kPlanThreads, s, a, d))) return rc;
 
     int chans = 1;
-    if ((rc = pick_channels(c, (const void*)k_moe_pack, 256, n, (size_t)T, 1, g_opt.hb_blocks, kMaxChannels, &chans)))
-        return rc;   // work unit: one wave per token, 4 waves per workgroup
+    // one wave per token row, 4 waves per workgroup, a few rows per wave
+    if ((rc = pick_channels(c, (const void*)k_moe_pack, 256, n, (size_t)T * 64, 4, g_opt.hb_blocks, 128, &chans)))
+        return rc;
     a.chans = chans;
     note_launch(n * chans, 256, MSX_ALGO_2PA_HB);
     return launch(k_moe_pack, n * chans, 256, s, a, d);
@@ -625,7 +643,8 @@ int msx_prim_barrier(int rounds, int nranks, int blocks_per_rank, uint32_t* sem_
     const DevCtx d = dev_ctx(c);
     if (rounds > 0 && nranks > 1) {
         note_launch(nranks * blocks_per_rank, 256, 0);
-        if ((rc = launch(k_barrier_rounds, nranks * blocks_per_rank, 256, (hipStream_t)stream, d, nranks, rounds)))
+        if ((rc = launch(k_barrier_rounds, nranks * blocks_per_rank, 256, (hipStream_t)stream, d, nranks, rounds,
+                         g_opt.barrier_fences)))
             return rc;
     }
     if (sem_out) return launch(k_sem_snapshot, 1, 64, (hipStream_t)stream, d, nranks, (unsigned*)sem_out);
@@ -753,7 +772,7 @@ int msx_set_option(const char* key, const char* value)
         if (u > 1024) return MSX_ERR_ARG;
         g_opt.threads = (int)u;
     } else if (k == "hb_unroll") {
-        if (u != 1 && u != 2 && u != 4) return MSX_ERR_ARG;
+        if (u != 0 && u != 1 && u != 2 && u != 4) return MSX_ERR_ARG;
         g_opt.hb_unroll = (int)u;
     } else if (k == "hb_barriers") {
         if (u > 1) return MSX_ERR_ARG;
@@ -761,6 +780,9 @@ int msx_set_option(const char* key, const char* value)
     } else if (k == "peer_outer") {
         if (u > 1) return MSX_ERR_ARG;
         g_opt.peer_outer = (int)u;
+    } else if (k == "barrier_fences") {
+        if (u > 3) return MSX_ERR_ARG;
+        g_opt.barrier_fences = (int)u;
     } else if (k == "spin_limit") {
         if (u < 1 || u > 0x7fffffffu) return MSX_ERR_ARG;
         g_opt.spin_limit = (unsigned)u;
@@ -818,6 +840,7 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
     else if (k == "hb_unroll") u = (unsigned)g_opt.hb_unroll;
     else if (k == "hb_barriers") u = (unsigned)g_opt.hb_barriers;
     else if (k == "peer_outer") u = (unsigned)g_opt.peer_outer;
+    else if (k == "barrier_fences") u = (unsigned)g_opt.barrier_fences;
     else if (k == "spin_limit") u = g_opt.spin_limit;
     else if (k == "chaos") u = g_opt.chaos;
     else if (k == "epoch") {

@@ -4,6 +4,13 @@
 // per chunk.  One workgroup set per rank; a thread reads the same vector from ALL ranks at
 // once (no per-peer synchronisation inside the reduction) and, following the paper's
 // note for peer-to-peer meshes, writes to all peers inside the element loop.
+//
+// Synchronisation policy.  The barrier at the START of a kernel only orders execution
+// ("every peer has entered this call, so what earlier launches wrote into its buffers is
+// final"): data written by earlier launches is already visible when a launch starts, so that
+// barrier carries no fence.  The barrier at the END publishes the puts of this launch; the puts
+// are write-through (st16_wt + put_drain), so it needs no L2 write-back either, except in the
+// workgroups that also wrote with ordinary stores (a scalar tail, an unaligned byte path).
 #pragma once
 #include "msx_device.hpp"
 
@@ -34,7 +41,7 @@ template <int DT> __device__ __forceinline__ void store_elem(void* p, size_t e, 
 }
 
 // Elements past the last whole 16-byte vector: summed and written to every rank by the
-// first threads of rank 0, channel 0.
+// first threads of rank 0, channel 0 (ordinary stores: that workgroup releases for real).
 template <int DT>
 __device__ __forceinline__ void allreduce_tail(const HbArgs& a, int n, size_t first, size_t count)
 {
@@ -53,7 +60,6 @@ __device__ __forceinline__ void allreduce_tail(const HbArgs& a, int n, size_t fi
     }
 }
 
-// Sum of vector idx over all ranks in rank order, from registers loaded up front.
 #define MSX_LOAD_ALL(v, ptrs, idx)                                   \
     _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)            \
         if (j < n) v[j] = ld16(ptrs[j], idx);
@@ -68,7 +74,8 @@ __device__ __forceinline__ void allreduce_tail(const HbArgs& a, int n, size_t fi
 // fused "reduce then put" operation of the DSL's Operation Fusion paragraph, widened from
 // two local buffers to all N ranks.)  In place is safe: chunk r of every row is read and
 // written by rank r's threads only, and a thread loads all N values before it stores.
-template <int DT, int U, int NR>
+// RES: 0 no residual, 1 one residual shared by all ranks, 2 one residual per destination.
+template <int DT, int U, int NR, int RES>
 __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
 {
     const int n = NR ? NR : a.n;
@@ -78,7 +85,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
     constexpr size_t epv = DT == 0 ? 4 : 8;
     const size_t V = a.count / epv;
 
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 10, false, true);   // every peer's input is ready
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 10, false, false);   // every peer has entered the call
 
     const size_t lo = V * (size_t)rank / (size_t)n;
     const size_t hi = V * (size_t)(rank + 1) / (size_t)n;
@@ -98,27 +105,29 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
             if (idx < hi) {
                 VecAcc<DT> acc;
                 MSX_SUM_ALL(acc, v[u])
-                if (!a.has_res || a.res_shared) {
-                    if (a.has_res) acc.add(ld16(a.res[0], idx));
+                if constexpr (RES != 2) {
+                    if constexpr (RES == 1) acc.add(ld16(a.res[0], idx));
                     const u32x4 o = acc.pack();
 #pragma unroll
                     for (int p = 0; p < kMaxRanks; ++p)
-                        if (p < n) st16(a.out[p], idx, o);
+                        if (p < n) st16_wt(a.out[p], idx, o);
                 } else {
 #pragma unroll
                     for (int p = 0; p < kMaxRanks; ++p)
                         if (p < n) {
                             VecAcc<DT> t = acc;
                             t.add(ld16(a.res[p], idx));
-                            st16(a.out[p], idx, t.pack());
+                            st16_wt(a.out[p], idx, t.pack());
                         }
                 }
             }
         }
     }
-    if (rank == 0 && chan == 0) allreduce_tail<DT>(a, n, V * epv, a.count);
+    const bool tail = rank == 0 && chan == 0 && V * epv < a.count;
+    if (tail) allreduce_tail<DT>(a, n, V * epv, a.count);
 
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 11, true, false);   // every peer's puts into my output landed
+    put_drain();
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 11, tail, false);   // my puts have landed everywhere
 }
 
 // ---- two-phase form: reduce-scatter to memory, rank barrier, all-gather by put ---------------
@@ -132,7 +141,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_2phase(HbArgs a, DevCtx c)
     constexpr size_t epv = DT == 0 ? 4 : 8;
     const size_t V = a.count / epv;
 
-    if (n > 1) rank_barrier(c, rank, n, chan, 20, false, true);
+    if (n > 1) rank_barrier(c, rank, n, chan, 20, false, false);
 
     const size_t lo = V * (size_t)rank / (size_t)n;
     const size_t hi = V * (size_t)(rank + 1) / (size_t)n;
@@ -159,9 +168,9 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_2phase(HbArgs a, DevCtx c)
         }
     }
 
-    // phase boundary: all ranks have finished reading the inputs (so an in-place all-gather
-    // may overwrite them) and have their chunk reduced
-    if (n > 1) rank_barrier(c, rank, n, chan, 21);
+    // phase boundary: every rank has finished reading the inputs, so an in-place all-gather may
+    // overwrite them.  No data changes hands here (a thread re-reads only what it wrote itself).
+    if (n > 1) rank_barrier(c, rank, n, chan, 21, false, false);
 
     // phase 2: put my reduced chunk into every peer's output
     if (a.peer_outer) {
@@ -175,11 +184,13 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_2phase(HbArgs a, DevCtx c)
             const u32x4 o = ld16(a.out[rank], idx);
 #pragma unroll
             for (int p = 0; p < kMaxRanks; ++p)
-                if (p < n && p != rank) st16(a.out[p], idx, o);
+                if (p < n && p != rank) st16_wt(a.out[p], idx, o);
         }
     }
     if (rank == 0 && chan == 0) allreduce_tail<DT>(a, n, V * epv, a.count);
 
+    // phase 1 and hb_put use ordinary streaming stores: this form releases for real
+    put_drain();
     if (n > 1) rank_barrier(c, rank, n, chan, 22, true, false);
 }
 
@@ -196,7 +207,7 @@ __global__ __launch_bounds__(256) void k_reducescatter_hb(HbArgs a, DevCtx c, in
     if (rank == c.drop_rank) return;
     constexpr size_t epv = DT == 0 ? 4 : 8;
     constexpr size_t esz = DT == 0 ? 4 : 2;
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 30, false, true);
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 30, false, false);
     const size_t RT = (size_t)a.chans * blockDim.x;
     const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
     const size_t blk = a.count;
@@ -230,7 +241,8 @@ __global__ __launch_bounds__(256) void k_reducescatter_hb(HbArgs a, DevCtx c, in
             store_elem<DT>(a.out[rank], k, acc);
         }
     }
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 31, false, false);   // peers are done reading my input: nothing to publish
+    // peers are done reading my input; my result is local, nothing to publish
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 31, false, false);
 }
 
 // ---- standalone AllGather: out[p] block r = in[r]; a.count = bytes per block ------------------
@@ -259,8 +271,8 @@ __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int ve
 #pragma unroll
             for (int p = 0; p < kMaxRanks; ++p)
                 if (p < n && dst[p] != src) {
-                    st16(dst[p], i, v0);
-                    if (i1 < nv) st16(dst[p], i1, v1);
+                    st16_wt(dst[p], i, v0);
+                    if (i1 < nv) st16_wt(dst[p], i1, v1);
                 }
         }
     } else {
@@ -270,7 +282,8 @@ __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int ve
                 if (dst[p] != src) dst[p][b] = v;
         }
     }
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 40, true, false);   // all blocks have landed in my output
+    put_drain();
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 40, !vec, false);   // my block has landed everywhere
 }
 
 // ---- standalone AllToAll (out of place): out[d] block s = in[s] block d; a.count = bytes/block ---
@@ -293,7 +306,7 @@ __global__ __launch_bounds__(256) void k_alltoall_hb(HbArgs a, DevCtx c, int vec
                 if (d < n) v[d] = ld16(src + (size_t)d * nbytes, i);
 #pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)
-                if (d < n) st16((char*)a.out[d] + (size_t)rank * nbytes, i, v[d]);
+                if (d < n) st16_wt((char*)a.out[d] + (size_t)rank * nbytes, i, v[d]);
         }
     } else {
         for (int d = 0; d < n; ++d) {
@@ -302,7 +315,8 @@ __global__ __launch_bounds__(256) void k_alltoall_hb(HbArgs a, DevCtx c, int vec
             for (size_t b = rt; b < nbytes; b += RT) dp[b] = sp[b];
         }
     }
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 50, true, false);
+    put_drain();
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 50, !vec, false);
 }
 
 // ---- AllToAll in place: block (s,d) and block (d,s) swap through registers --------------------
@@ -314,7 +328,7 @@ __global__ __launch_bounds__(256) void k_alltoall_inplace(HbArgs a, DevCtx c, in
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
     if (rank == c.drop_rank) return;
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 60, false, true);
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 60, false, false);
     const size_t RT = (size_t)a.chans * blockDim.x;
     const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
     const size_t nbytes = a.count;
@@ -330,8 +344,8 @@ __global__ __launch_bounds__(256) void k_alltoall_inplace(HbArgs a, DevCtx c, in
             for (size_t i = lo + rt; i < hi; i += RT) {
                 const u32x4 x = ld16(mine, i);
                 const u32x4 y = ld16(theirs, i);
-                st16(mine, i, y);
-                st16(theirs, i, x);
+                st16_wt(mine, i, y);
+                st16_wt(theirs, i, x);
             }
         } else {
             for (size_t b = lo + rt; b < hi; b += RT) {
@@ -341,7 +355,8 @@ __global__ __launch_bounds__(256) void k_alltoall_inplace(HbArgs a, DevCtx c, in
             }
         }
     }
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 61, true, false);
+    put_drain();
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 61, !vec, false);
 }
 
 }  // namespace msx

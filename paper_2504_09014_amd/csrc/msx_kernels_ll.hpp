@@ -131,18 +131,18 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
     const unsigned my_off = (unsigned)rank * c.ll_rank_stride + rot_off;
     chaos_delay(c, 80);
 
-    // phase 1 send: packet q of chunk p goes to slot `rank` of rank p
+    // phase 1 send: packet q of chunk p goes to slot `rank` of rank p.  All loads first, then
+    // all stores, so the n-1 input reads overlap instead of queueing behind each other.
     for (unsigned q = rt; q < cp; q += RT) {
+        u32x2 w[kMaxRanks];
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
-            if (p < n && p != rank) {
-                const unsigned k = (unsigned)p * cp + q;
-                if (k < P) {
-                    const u32x2 w = load_words(a.in[rank], k, a.nbytes);
-                    ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + q * 16u,
-                             w.x, w.y, tag.flag);
-                }
-            }
+            if (p < n && p != rank && (unsigned)p * cp + q < P) w[p] = load_words(a.in[rank], (size_t)p * cp + q, a.nbytes);
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p)
+            if (p < n && p != rank && (unsigned)p * cp + q < P)
+                ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + q * 16u,
+                         w[p].x, w[p].y, tag.flag);
     }
     // phase 1 receive + reduce my chunk, phase 2 send the result to every peer
     for (unsigned q = rt; q < cp; q += RT) {

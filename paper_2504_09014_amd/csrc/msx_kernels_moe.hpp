@@ -181,23 +181,26 @@ __global__ __launch_bounds__(256) void k_moe_pack(MoeArgs a, DevCtx c)
             const unsigned r = base[d] + row[d];
             const bool go = d < n && row[d] != 0xffffu && r < a.cap;
             dst[d] = go ? (char*)a.recv[d] + (size_t)r * row_bytes : nullptr;
-            if (go && a.has_src && lane == 0) a.recv_src[d][r] = rank * a.T + t;
+            if (go && a.has_src && lane == 0) st32_wt(a.recv_src[d] + r, (unsigned)(rank * a.T + t));
         }
         const char* src = tokens + (size_t)t * row_bytes;
-        for (unsigned i = (unsigned)lane; i < a.row_vecs; i += 128u) {
-            const unsigned i1 = i + 64u;
-            const u32x4 v0 = ld16(src, i);
-            u32x4 v1 = v0;
-            if (i1 < a.row_vecs) v1 = ld16(src, i1);
+        // four vectors per lane in flight; the row is read once and stored to every destination
+        for (unsigned i = (unsigned)lane; i < a.row_vecs; i += 256u) {
+            u32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i + 64u * u < a.row_vecs) v[u] = ld16(src, i + 64u * u);
 #pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)
                 if (dst[d]) {
-                    st16(dst[d], i, v0);
-                    if (i1 < a.row_vecs) st16(dst[d], i1, v1);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (i + 64u * u < a.row_vecs) st16_wt(dst[d], i + 64u * u, v[u]);
                 }
         }
     }
-    if (n > 1) rank_barrier(c, rank, n, chan, 210, true, false);   // all rows destined to me have landed
+    put_drain();
+    if (n > 1) rank_barrier(c, rank, n, chan, 210, false, false);   // write-through puts: all rows destined to me have landed
 }
 
 }  // namespace msx

@@ -31,13 +31,13 @@ __global__ __launch_bounds__(64) void k_pingpong(DevCtx c, int iters, int block_
     }
 }
 
-// `rounds` rank barriers on every channel
-__global__ __launch_bounds__(256) void k_barrier_rounds(DevCtx c, int n, int rounds)
+// `rounds` rank barriers on every channel; fences bit 0 = release, bit 1 = acquire
+__global__ __launch_bounds__(256) void k_barrier_rounds(DevCtx c, int n, int rounds, int fences)
 {
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
     if (rank == c.drop_rank) return;
-    for (int r = 0; r < rounds; ++r) rank_barrier(c, rank, n, chan, 310);
+    for (int r = 0; r < rounds; ++r) rank_barrier(c, rank, n, chan, 310, (fences & 1) != 0, (fences & 2) != 0);
 }
 
 // channel-0 semaphore values, [n recv][n send]
