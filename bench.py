@@ -278,6 +278,26 @@ def main():
             torch.cuda.empty_cache()
         msx.check_status()
         extras["config3_other_sizes"] = c3
+        # standalone ReduceScatter / AllGather / AllToAll (HB protocol), 256 MiB rows
+        other = {}
+        c = 128 << 20                                   # elements per full row (256 MiB of bf16)
+        full = synth.normal(n, c, seed=11, device="cuda")
+        rows_ = [full[r] for r in range(n)]
+        part = [torch.empty(c // n, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        full2 = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        for name, fn, moved in [
+            ("reducescatter", lambda: msx.reducescatter_ex(rows_, part), n * c * 2 + c * 2),
+            ("allgather", lambda: msx.allgather_ex(part, full2), c * 2 + n * c * 2),
+            ("alltoall", lambda: msx.alltoall_ex(rows_, full2), 2 * n * c * 2),
+        ]:
+            _, ev = time_calls(torch, fn, 10, 3)
+            ms = median(ev) / 1e3
+            other[name] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
+                           "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+        msx.check_status()
+        del full, rows_, part, full2
+        torch.cuda.empty_cache()
+        extras["standalone_256MiB_rows"] = other
         # config 5
         T, H, K, E = 4096, 7168, 8, 256
         tok = synth.moe_tokens(n, T, H, seed=0, device="cuda")

@@ -374,8 +374,11 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
         case kA2A: kp = (const void*)k_alltoall_hb; break;
         case kA2AInplace: kp = (const void*)k_alltoall_inplace; break;
     }
+    // workgroups per rank for large inputs, from a sweep: the read-heavy reduce-scatter runs best
+    // with few workgroups per rank, the write-heavy copies with many
+    const int cap = which == kRS ? 32 : 128;
     int chans = 1;
-    if ((rc = pick_channels(c, kp, threads, n, work_units, 2, g_opt.hb_blocks, kMaxChannels, &chans))) return rc;
+    if ((rc = pick_channels(c, kp, threads, n, work_units, 2, g_opt.hb_blocks, cap, &chans))) return rc;
     HbArgs a{};
     for (int i = 0; i < n; ++i) {
         a.in[i] = in ? in[i] : nullptr;
