@@ -298,6 +298,36 @@ def main():
         del full, rows_, part, full2
         torch.cuda.empty_cache()
         extras["standalone_256MiB_rows"] = other
+        # AllGather / ReduceScatter size sweeps (row = the full buffer of one rank), both protocols
+        sweep = {}
+        for row_kib in [8, 64, 1024, 16384, 262144, 1048576]:
+            c = row_kib * 1024 // 2
+            full = synth.normal(n, c, seed=row_kib, device="cuda")
+            rows_ = [full[r] for r in range(n)]
+            part = [torch.empty(c // n, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            full2 = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            row = {}
+            for proto in ("hb", "ll"):
+                if proto == "ll" and row_kib > 1024:      # packets of larger blocks exceed the LL scratch
+                    continue
+                msx.set_option("coll_algo", proto)
+                for name, fn in [("allgather", lambda: msx.allgather_ex(part, full2)),
+                                 ("reducescatter", lambda: msx.reducescatter_ex(rows_, part))]:
+                    if row_kib <= 16384:
+                        us = graph_us(torch, fn, calls=20, replays=5)
+                    else:
+                        us = median(time_calls(torch, fn, 8, 2)[1])
+                    row[f"{name}_{proto}_us"] = round(us, 2)
+            msx.set_option("coll_algo", "auto")
+            moved_ag = c * 2 + n * c * 2
+            moved_rs = n * c * 2 + c * 2
+            row["allgather_hb_GBps"] = round(moved_ag / row["allgather_hb_us"] / 1e3, 1)
+            row["reducescatter_hb_GBps"] = round(moved_rs / row["reducescatter_hb_us"] / 1e3, 1)
+            sweep[f"{row_kib}KiB"] = row
+            del full, rows_, part, full2
+            torch.cuda.empty_cache()
+        msx.check_status()
+        extras["allgather_reducescatter_sweep"] = sweep
         # config 5
         T, H, K, E = 4096, 7168, 8, 256
         tok = synth.moe_tokens(n, T, H, seed=0, device="cuda")

@@ -172,6 +172,9 @@ int msx_finalize(void);
 /* Options (strings; numbers in decimal):
  *   "algo"            auto | 1pa_ll | 2pa_ll | 2pa_hb | 2pa_hb_2phase  (for the in-place forms)
  *   "ll_1pa_max_bytes", "ll_2pa_max_bytes"   size thresholds of the automatic choice
+ *   "coll_algo"       auto | ll | hb   protocol of allgather / reducescatter (LL needs blocks that
+ *                     are multiples of 8 bytes and fit the LL scratch; "ll" fails otherwise)
+ *   "coll_ll_max_bytes"   auto: LL up to this many bytes per block
  *   "ll_max_bytes"    largest per-rank message the LL scratch is sized for (set before init)
  *   "hb_blocks_per_rank", "ll_blocks_per_rank", "threads"   0 = automatic
  *   "hb_unroll"       1 | 2 | 4

@@ -36,6 +36,8 @@ struct Options {
     int hb_barriers = 1;
     int peer_outer = 0;
     int barrier_fences = 3;   // msx_prim_barrier only: bit 0 release, bit 1 acquire
+    int coll_algo = 0;        // allgather / reducescatter: 0 auto, 1 LL packets, 2 HB
+    size_t coll_ll_max = 0;   // auto: LL up to this many bytes per block (0: never; HB wins on one chip)
     unsigned spin_limit = 1u << 20;
     int drop_rank = -1;
     unsigned chaos = 0;
@@ -355,6 +357,47 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     return launch(k, n * chans, threads, stream, a, dev_ctx(c));
 }
 
+
+// AllGather / ReduceScatter over LL packets.  nbytes = bytes per block (multiple of 8).
+int ll_coll(bool gather, const void* const* in, void* const* out, size_t nbytes, int dtype, int nranks,
+            hipStream_t stream)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = get_ctx(&c);
+    if (rc) return rc;
+    const int n = nranks;
+    const size_t P = nbytes / 8;
+    if ((size_t)n * P * 16 > c->d.ll_rot_stride) return MSX_ERR_NOMEM;
+    const void* kp;
+    if (gather) kp = n == 8 ? (const void*)k_allgather_ll<8> : (const void*)k_allgather_ll<0>;
+    else if (dtype == MSX_F32) kp = n == 8 ? (const void*)k_reducescatter_ll<0, 8> : (const void*)k_reducescatter_ll<0, 0>;
+    else kp = n == 8 ? (const void*)k_reducescatter_ll<1, 8> : (const void*)k_reducescatter_ll<1, 0>;
+    const int threads = ll_block_threads(P);
+    int chans = 1;
+    if ((rc = pick_channels(c, kp, threads, n, P, 1, g_opt.ll_blocks, 32, &chans))) return rc;
+    LlCollArgs a{};
+    for (int i = 0; i < n; ++i) {
+        a.in[i] = in[i];
+        a.out[i] = out[i];
+    }
+    a.nbytes = nbytes;
+    a.n = n;
+    a.chans = chans;
+    note_launch(n * chans, threads, gather ? MSX_ALGO_1PA_LL : MSX_ALGO_2PA_LL);
+    typedef void (*K)(LlCollArgs, DevCtx);
+    return launch((K)kp, n * chans, threads, stream, a, dev_ctx(c));
+}
+
+// 1: use the LL kernels, 0: use the HB kernels, < 0: LL was demanded but cannot serve this request
+int use_ll_coll(size_t nbytes, bool aligned8)
+{
+    const bool can = aligned8 && nbytes % 8 == 0;
+    if (g_opt.coll_algo == 1) return can ? 1 : MSX_ERR_UNSUPPORTED;
+    if (g_opt.coll_algo == 2 || !can) return 0;
+    return nbytes <= g_opt.coll_ll_max ? 1 : 0;
+}
+
 // ---- the other HB collectives: a.count semantics differ per kernel -----------------------------
 
 enum HbOther { kRS, kAG, kA2A, kA2AInplace };
@@ -455,6 +498,16 @@ int msx_reducescatter_ex(const void* const* send, void* const* recv, size_t coun
         if (!aligned16(recv[r])) vec = 0;
         if ((uintptr_t)recv[r] % esz) return MSX_ERR_ARG;
     }
+    if (nranks > 1) {
+        bool al8 = true;
+        for (int r = 0; r < nranks; ++r) al8 = al8 && ((uintptr_t)recv[r] & 7u) == 0;
+        const int ll = use_ll_coll(c * esz, al8);
+        if (ll < 0) return ll;
+        if (ll) {
+            const int rc2 = ll_coll(false, send, recv, c * esz, dtype, nranks, (hipStream_t)stream);
+            if (rc2 != MSX_ERR_NOMEM || g_opt.coll_algo == 1) return rc2;
+        }
+    }
     const size_t work = vec ? c * esz / 16 : c;
     return hb_other(kRS, send, recv, c, dtype, nranks, vec, work, (hipStream_t)stream);
 }
@@ -488,6 +541,17 @@ int msx_allgather_ex(const void* const* send, void* const* recv, size_t count, i
     for (int r = 0; r < nranks; ++r) {
         if (!send[r] || !recv[r]) return MSX_ERR_ARG;
         if (!aligned16(send[r]) || !aligned16(recv[r])) vec = 0;
+    }
+    if (nranks > 1) {
+        bool al8 = true;
+        for (int r = 0; r < nranks; ++r)
+            al8 = al8 && ((uintptr_t)send[r] & 7u) == 0 && ((uintptr_t)recv[r] & 7u) == 0;
+        const int ll = use_ll_coll(nbytes, al8);
+        if (ll < 0) return ll;
+        if (ll) {
+            const int rc2 = ll_coll(true, send, recv, nbytes, dtype, nranks, (hipStream_t)stream);
+            if (rc2 != MSX_ERR_NOMEM || g_opt.coll_algo == 1) return rc2;
+        }
     }
     const size_t work = vec ? nbytes / 16 : nbytes;
     return hb_other(kAG, send, recv, nbytes, dtype, nranks, vec, work, (hipStream_t)stream);
@@ -753,6 +817,13 @@ int msx_set_option(const char* key, const char* value)
         else return MSX_ERR_ARG;
         return MSX_OK;
     }
+    if (k == "coll_algo") {
+        if (v == "auto") g_opt.coll_algo = 0;
+        else if (v == "ll") g_opt.coll_algo = 1;
+        else if (v == "hb") g_opt.coll_algo = 2;
+        else return MSX_ERR_ARG;
+        return MSX_OK;
+    }
     if (k == "drop_rank") {
         if (v == "-1") { g_opt.drop_rank = -1; return MSX_OK; }
         if (!parse_u64(value, &u) || u >= (unsigned)kMaxRanks) return MSX_ERR_ARG;
@@ -762,6 +833,7 @@ int msx_set_option(const char* key, const char* value)
     if (!parse_u64(value, &u)) return MSX_ERR_ARG;
     if (k == "ll_1pa_max_bytes") g_opt.ll_1pa_max = (size_t)u;
     else if (k == "ll_2pa_max_bytes") g_opt.ll_2pa_max = (size_t)u;
+    else if (k == "coll_ll_max_bytes") g_opt.coll_ll_max = (size_t)u;
     else if (k == "ll_max_bytes") {
         if (u < 4096 || u > (16u << 20)) return MSX_ERR_ARG;
         g_opt.ll_max_bytes = (size_t)u;
@@ -830,9 +902,15 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
         snprintf(value_out, value_len, "%s", names[g_opt.algo]);
         return MSX_OK;
     }
+    if (k == "coll_algo") {
+        static const char* cn[] = {"auto", "ll", "hb"};
+        snprintf(value_out, value_len, "%s", cn[g_opt.coll_algo]);
+        return MSX_OK;
+    }
     if (k == "drop_rank") { snprintf(value_out, value_len, "%d", g_opt.drop_rank); return MSX_OK; }
     if (k == "ll_1pa_max_bytes") u = g_opt.ll_1pa_max;
     else if (k == "ll_2pa_max_bytes") u = g_opt.ll_2pa_max;
+    else if (k == "coll_ll_max_bytes") u = g_opt.coll_ll_max;
     else if (k == "ll_max_bytes") {
         int dev = 0;
         u = g_opt.ll_max_bytes;

@@ -213,4 +213,101 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
     call_end(c, tag);
 }
 
+// ---- AllGather and ReduceScatter over LL packets (small messages) -------------------------------
+// The two halves of 2PA on their own: the paper evaluates AllGather as a collective of its
+// own and says its algorithms mirror the AllReduce ones.  nbytes = bytes per block, a
+// multiple of 8 (the host sends other sizes down the HB path).
+struct LlCollArgs {
+    const void* in[kMaxRanks];
+    void* out[kMaxRanks];
+    size_t nbytes;
+    int n;
+    int chans;
+};
+
+// AllGather: rank r's block travels as packets to slot r of every peer's scratch; every rank
+// decodes the n-1 foreign slots into its output and copies its own block directly.
+template <int NR>
+__global__ __launch_bounds__(1024) void k_allgather_ll(LlCollArgs a, DevCtx c)
+{
+    const int n = NR ? NR : a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    const CallTag tag = call_begin(c);
+    if (rank == c.drop_rank) { call_end(c, tag); return; }
+    const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
+    const unsigned P = (unsigned)(a.nbytes / 8);
+    const unsigned RT = (unsigned)a.chans * blockDim.x;
+    const unsigned rt = (unsigned)chan * blockDim.x + threadIdx.x;
+    const unsigned slot_stride = P * 16u;
+    const unsigned rot_off = tag.rot * c.ll_rot_stride;
+    const unsigned my_off = (unsigned)rank * c.ll_rank_stride + rot_off;
+    char* const mine = (char*)a.out[rank] + (size_t)rank * a.nbytes;
+    chaos_delay(c, 90);
+    for (unsigned k = rt; k < P; k += RT) {
+        const u32x2 w = load_words(a.in[rank], k, a.nbytes);
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p)
+            if (p < n && p != rank)
+                ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + k * 16u,
+                         w.x, w.y, tag.flag);
+        if ((const void*)mine != a.in[rank]) store_words(mine, k, a.nbytes, w);
+    }
+    for (unsigned k = rt; k < P; k += RT) {
+        u32x4 v[kMaxRanks];
+        MSX_LL_POLL_ALL(v, my_off, slot_stride, k)
+#pragma unroll
+        for (int j = 0; j < kMaxRanks; ++j)
+            if (j < n && j != rank)
+                store_words((char*)a.out[rank] + (size_t)j * a.nbytes, k, a.nbytes, u32x2{v[j].x, v[j].z});
+    }
+    call_end(c, tag);
+}
+
+// ReduceScatter: rank r sends block p of its input to slot r of rank p; rank r sums the n-1
+// received copies of block r with its own, in rank order, into out[r].
+template <int DT, int NR>
+__global__ __launch_bounds__(1024) void k_reducescatter_ll(LlCollArgs a, DevCtx c)
+{
+    const int n = NR ? NR : a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    const CallTag tag = call_begin(c);
+    if (rank == c.drop_rank) { call_end(c, tag); return; }
+    const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
+    const unsigned P = (unsigned)(a.nbytes / 8);
+    const unsigned RT = (unsigned)a.chans * blockDim.x;
+    const unsigned rt = (unsigned)chan * blockDim.x + threadIdx.x;
+    const unsigned slot_stride = P * 16u;
+    const unsigned rot_off = tag.rot * c.ll_rot_stride;
+    const unsigned my_off = (unsigned)rank * c.ll_rank_stride + rot_off;
+    chaos_delay(c, 95);
+    for (unsigned k = rt; k < P; k += RT) {
+        u32x2 w[kMaxRanks];
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p)
+            if (p < n && p != rank) w[p] = load_words((const char*)a.in[rank] + (size_t)p * a.nbytes, k, a.nbytes);
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p)
+            if (p < n && p != rank)
+                ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + k * 16u,
+                         w[p].x, w[p].y, tag.flag);
+    }
+    for (unsigned k = rt; k < P; k += RT) {
+        const u32x2 own = load_words((const char*)a.in[rank] + (size_t)rank * a.nbytes, k, a.nbytes);
+        u32x4 v[kMaxRanks];
+        MSX_LL_POLL_ALL(v, my_off, slot_stride, k)
+        WordAcc<DT> a0, a1;
+#pragma unroll
+        for (int j = 0; j < kMaxRanks; ++j)
+            if (j < n) {
+                const unsigned w0 = j == rank ? own.x : v[j].x;
+                const unsigned w1 = j == rank ? own.y : v[j].z;
+                if (j == 0) { a0.set(w0); a1.set(w1); } else { a0.add(w0); a1.add(w1); }
+            }
+        store_words(a.out[rank], k, a.nbytes, u32x2{a0.pack(), a1.pack()});
+    }
+    call_end(c, tag);
+}
+
 }  // namespace msx

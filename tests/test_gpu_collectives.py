@@ -17,6 +17,7 @@ def msx():
     m.init()
     yield m
     m.set_option("chaos", "0")
+    m.set_option("coll_algo", "auto")
 
 
 def _bits(t):
@@ -104,6 +105,64 @@ def test_alltoall_matches_oracle(msx, orc, n, dtype, c):
     msx.alltoall(buf)                                   # applying it twice restores the input
     msx.check_status()
     assert np.array_equal(_bits(buf).view(np.uint8), _bits(x).view(np.uint8))
+
+
+@pytest.mark.parametrize("n", [2, 3, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("c", [4, 8, 100, 4096, 65536 + 8, 262144])
+def test_ll_packet_allgather_and_reducescatter(msx, orc, n, dtype, c):
+    esz = 4 if dtype == torch.float32 else 2
+    msx.set_option("coll_algo", "ll")
+    msx.set_option("chaos", "13")
+    try:
+        # ReduceScatter over packets
+        x = _data(n, n * c, dtype, seed=c + 3)
+        send = [x[r].clone().cuda() for r in range(n)]
+        recv = [torch.zeros(c, dtype=dtype, device="cuda") for _ in range(n)]
+        msx.reducescatter_ex(send, recv)
+        msx.check_status()
+        assert msx.last_launch()[2] == 2                      # really the packet kernel
+        want = orc.reducescatter(_bits(x))
+        for r in range(n):
+            assert np.array_equal(_bits(recv[r]), want[r]), (n, c, r)
+        # AllGather over packets, out of place and in place
+        y = _tagged(n, c) if dtype == torch.float32 else synth.normal(n, c, seed=c)
+        want = orc.allgather(_bits(y))
+        send = [y[r].clone().cuda() for r in range(n)]
+        recv = [torch.zeros(n * c, dtype=dtype, device="cuda") for _ in range(n)]
+        msx.allgather_ex(send, recv)
+        msx.check_status()
+        assert msx.last_launch()[2] == 1
+        for r in range(n):
+            assert np.array_equal(_bits(recv[r]).view(np.uint8), want[r].view(np.uint8)), (n, c, r)
+        buf = torch.full((n, n * c), 7.0, dtype=dtype)
+        for r in range(n):
+            buf[r, r * c:(r + 1) * c] = y[r]
+        buf = buf.cuda()
+        msx.allgather(buf)
+        msx.check_status()
+        assert np.array_equal(_bits(buf).view(np.uint8), want.view(np.uint8))
+    finally:
+        msx.set_option("coll_algo", "auto")
+        msx.set_option("chaos", "0")
+
+
+def test_ll_packet_collectives_refuse_what_they_cannot_serve(msx):
+    msx.set_option("coll_algo", "ll")
+    try:
+        send = [torch.zeros(3, dtype=torch.bfloat16, device="cuda") for _ in range(8)]      # 6-byte blocks
+        recv = [torch.zeros(24, dtype=torch.bfloat16, device="cuda") for _ in range(8)]
+        with pytest.raises(msx.MsxError) as e:
+            msx.allgather_ex(send, recv)
+        assert e.value.code == -2
+        big = int(msx.get_option("ll_max_bytes"))                                            # too large for the scratch
+        send = [torch.zeros(big, dtype=torch.bfloat16, device="cuda") for _ in range(8)]
+        recv = [torch.zeros(8 * big, dtype=torch.bfloat16, device="cuda") for _ in range(8)]
+        with pytest.raises(msx.MsxError) as e:
+            msx.allgather_ex(send, recv)
+        assert e.value.code == -5
+    finally:
+        msx.set_option("coll_algo", "auto")
 
 
 def test_allgather_of_reducescatter_equals_allreduce_on_gpu(msx, orc):
