@@ -304,6 +304,57 @@ int orc_moe_dispatch(const uint8_t *tokens, const int32_t *topk, int n, int T, i
     return rc;
 }
 
+/*
+ * Combine: the way back of the dispatch.  y[d] holds one processed row for every row that
+ * destination d received, in the order the dispatch delivered them.  Every source token
+ * gets the sum of its rows over the destination ranks it was sent to, added in fp32 in
+ * ascending rank order starting from the first one, rounded once to bf16.
+ *   y   : [n][cap][H] bf16 bits        out : [n][T][H] bf16 bits
+ * The paper names the operation (dispatch and combine of its expert-parallel experiment)
+ * but not the arithmetic; plain unweighted sum in rank order is this build's reading.
+ * Returns 0, -1 if a destination would overflow cap, -2 on a bad expert id.
+ */
+int orc_moe_combine_bf16(const uint16_t *y, const int32_t *topk, int n, int T, int K, int n_experts,
+                         size_t H, size_t cap, uint16_t *out, float *acc /* scratch [n*T*H] */,
+                         uint8_t *seen /* scratch [n*T] */)
+{
+    int per = n_experts / n;
+    memset(seen, 0, (size_t)n * T);
+    for (int d = 0; d < n; ++d) {
+        size_t fill = 0;
+        for (int s = 0; s < n; ++s)
+            for (int t = 0; t < T; ++t) {
+                int hit = 0;
+                for (int k = 0; k < K; ++k) {
+                    int32_t e = topk[((size_t)s * T + t) * K + k];
+                    if (e < 0 || e >= n_experts)
+                        return -2;
+                    if (e / per == d)
+                        hit = 1;
+                }
+                if (!hit)
+                    continue;
+                if (fill >= cap)
+                    return -1;
+                const uint16_t *row = y + ((size_t)d * cap + fill) * H;
+                float *a = acc + ((size_t)s * T + t) * H;
+                if (!seen[(size_t)s * T + t]) {
+                    for (size_t h = 0; h < H; ++h)
+                        a[h] = orc_bf16_to_f32(row[h]);
+                    seen[(size_t)s * T + t] = 1;
+                } else {
+                    for (size_t h = 0; h < H; ++h)
+                        a[h] += orc_bf16_to_f32(row[h]);
+                }
+                ++fill;
+            }
+    }
+    for (size_t i = 0; i < (size_t)n * T; ++i)
+        for (size_t h = 0; h < H; ++h)
+            out[i * H + h] = seen[i] ? orc_f32_to_bf16(acc[i * H + h]) : 0;
+    return 0;
+}
+
 /* ---------- semaphore bookkeeping (the integer side of signal / wait) ---------- */
 
 /* wait() is satisfied when the counter has reached the expected value; counters only

@@ -56,6 +56,8 @@ def lib():
         L.orc_ll_decode_buf.restype = i32
         L.orc_moe_dispatch.argtypes = [vp, vp, i32, i32, i32, i32, sz, vp, vp, vp, sz]
         L.orc_moe_dispatch.restype = i32
+        L.orc_moe_combine_bf16.argtypes = [vp, vp, i32, i32, i32, i32, sz, sz, vp, vp, vp]
+        L.orc_moe_combine_bf16.restype = i32
         L.orc_sem_reached.argtypes = [u32, u32]
         L.orc_sem_reached.restype = i32
         _lib = L
@@ -221,6 +223,21 @@ def moe_dispatch(tokens, topk, n_experts, cap=None):
     rc = lib().orc_moe_dispatch(_p(tokens), _p(topk), n, T, K, n_experts,
                                 H * tokens.dtype.itemsize, _p(recv), _p(src), _p(counts), cap)
     return recv, src, counts, rc
+
+
+def moe_combine_bf16(y, topk, n_experts, T=None):
+    """y: [n, cap, H] uint16 (bf16 bits) rows in dispatch order; topk: [n, T, K] int32.
+    Returns (out [n, T, H] uint16, rc)."""
+    y = _c(y, np.uint16)
+    topk = _c(topk, np.int32)
+    n, cap, H = y.shape
+    T = topk.shape[1]
+    K = topk.shape[2]
+    out = np.zeros((n, T, H), np.uint16)
+    acc = np.zeros(n * T * H, np.float32)
+    seen = np.zeros(n * T, np.uint8)
+    rc = lib().orc_moe_combine_bf16(_p(y), _p(topk), n, T, K, n_experts, H, cap, _p(out), _p(acc), _p(seen))
+    return out, rc
 
 
 def sem_reached(sem, expected):

@@ -392,6 +392,61 @@ def test_moe_dispatch_special_cases(orc):
     assert orc.moe_dispatch(tokens, bad, E)[3] == -2
 
 
+def test_moe_combine_properties(orc):
+    n, T, H, K, E = 8, 64, 16, 8, 256
+    tokens = synth.moe_tokens(n, T, H, seed=3)
+    tb = synth.bf16_bits(tokens)
+    topk = synth.moe_routing(n, T, K, E, seed=3).numpy()
+    recv, src, counts, rc = orc.moe_dispatch(tb, topk, E)
+    assert rc == 0
+    dests = _dest_sets(topk, n, E)
+    fan = np.array([[len(d) for d in rank] for rank in dests])
+    # 1. combine of the dispatched rows themselves = fan-out x token, built independently with torch:
+    #    repeated fp32 addition of the same value, one rounding
+    out, rc = orc.moe_combine_bf16(recv, topk, E)
+    assert rc == 0
+    want = torch.zeros(n, T, H)
+    tf = tokens.float()
+    for k in range(1, 9):
+        acc = tf.clone()
+        for _ in range(k - 1):
+            acc = acc + tf
+        m = torch.from_numpy(fan == k)
+        want[m] = acc[m]
+    assert np.array_equal(out, synth.bf16_bits(want.bfloat16()))
+    # 2. rows that carry their destination rank as value: result = sum of the destination ids,
+    #    which pins WHICH rows are summed for each token
+    y = np.zeros_like(recv)
+    for d in range(n):
+        y[d] = synth.bf16_bits(torch.full((1,), float(d + 1)).bfloat16())[0]
+    out, _ = orc.moe_combine_bf16(y, topk, E)
+    want_ids = np.array([[sum(d + 1 for d in ds) for ds in rank] for rank in dests], np.float32)
+    got = orc.bf16_to_f32(out)
+    assert np.array_equal(got, np.repeat(want_ids[:, :, None], H, axis=2))
+    # 3. rows that carry their source position: every summed row must be the token's own
+    y = np.zeros_like(recv)
+    for d in range(n):
+        for slot in range(int(counts[d].sum())):
+            y[d, slot] = synth.bf16_bits(torch.full((1,), float(src[d, slot] % 31)).bfloat16())[0]
+    out, _ = orc.moe_combine_bf16(y, topk, E)
+    idx = (np.arange(n)[:, None] * T + np.arange(T)[None, :]) % 31
+    assert np.array_equal(orc.bf16_to_f32(out)[:, :, 0], (idx * fan).astype(np.float32))   # <= 240: exact in bf16
+    # 4. order and single rounding: ranks 0,1,2 deliver 2^24*2^-16.. use the probe 256, 1, -256 scaled to bf16
+    topk3 = np.tile(np.array([0, 32, 64, 1, 2, 3, 4, 5], np.int32), (n, T, 1))             # ranks 0,1,2
+    recv3, _, counts3, _ = orc.moe_dispatch(tb, topk3, E)
+    y = np.zeros_like(recv3)
+    vals = {0: 2.0 ** 24, 1: 1.0, 2: -(2.0 ** 24)}
+    for d, v in vals.items():
+        y[d, :int(counts3[d].sum())] = synth.bf16_bits(torch.full((1,), v).bfloat16())[0]
+    out, _ = orc.moe_combine_bf16(y, topk3, E)
+    assert np.all(out == 0)                                   # (2^24 + 1) - 2^24 = 0 in fp32, rank order
+    # 5. capacity and id errors are reported
+    assert orc.moe_combine_bf16(recv[:, :10], topk, E)[1] == -1
+    bad = topk.copy()
+    bad[1, 2, 3] = -1
+    assert orc.moe_combine_bf16(recv, bad, E)[1] == -2
+
+
 def test_moe_expected_fanout_of_the_seeded_routing():
     n, T, K, E = 8, 4096, 8, 256
     topk = synth.moe_routing(n, T, K, E, seed=0).numpy()
