@@ -346,6 +346,14 @@ def main():
         moved = n * T * H * 2 + rows * H * 2
         extras["config5_moe_dispatch"] = {"ms": round(ms, 4), "rows_sent": rows, "GBps": round(moved / ms / 1e6, 1),
                                           "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+        outs = [torch.empty((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        fnc = lambda: msx.moe_combine(rt, outs)
+        _, ev = time_calls(torch, fnc, 20, 5)
+        msx.check_status()
+        ms = median(ev) / 1e3
+        moved = rows * H * 2 + n * T * H * 2
+        extras["config5_moe_combine"] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
+                                         "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
         extras["hop_ns"] = {"signal_wait_round_trip_cross_xcd": round(msx.prim_pingpong(2000, 16, 0, 1), 1),
                             "signal_wait_round_trip_same_xcd": round(msx.prim_pingpong(2000, 16, 0, 8), 1)}
         out["extras"] = extras

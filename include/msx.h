@@ -124,6 +124,17 @@ int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, 
                      int32_t* const* recv_src_token, int32_t* recv_counts,
                      size_t recv_capacity_tokens, void* stream);
 
+/* Combine, the way back of msx_moe_dispatch (the paper's expert-parallel experiment runs
+ * "dispatch and combine").  Uses the routing of the LAST msx_moe_dispatch on this device, which
+ * must have had the same T and nranks (else MSX_ERR_ARG).
+ *   expert_out[d]  device [capacity_tokens][H]: one processed row per row destination d received,
+ *                  in the order the dispatch delivered them
+ *   out_tokens[s]  device [T][H]: out[s][t] = round( sum over the destination ranks of token (s,t),
+ *                  ascending, in fp32 starting from the first, of its row in expert_out[d] )
+ * Rows the dispatch dropped for lack of capacity are left out of the sum. */
+int msx_moe_combine(const void* const* expert_out, void* const* out_tokens, int T, int H, int dtype,
+                    int nranks, size_t capacity_tokens, void* stream);
+
 /* ------------------------------------------------------------------------------------
  * MemoryChannel primitives on their own (Primitive API figure and MemoryChannel section:
  * put / signal / wait / flush, LL put / read).  Small kernels that exercise exactly one

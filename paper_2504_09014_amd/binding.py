@@ -13,7 +13,7 @@ __all__ = [
     "MsxError", "lib", "lib_path", "init", "reset", "finalize", "set_option", "get_option", "status",
     "check_status", "last_launch", "version", "strerror",
     "allreduce", "reducescatter", "allgather", "alltoall",
-    "allreduce_ex", "reducescatter_ex", "allgather_ex", "alltoall_ex", "moe_dispatch",
+    "allreduce_ex", "reducescatter_ex", "allgather_ex", "alltoall_ex", "moe_dispatch", "moe_combine",
     "prim_pingpong", "prim_barrier", "prim_put_signal_wait", "prim_ll_encode", "prim_ll_roundtrip",
     "EXPORTS",
 ]
@@ -25,7 +25,7 @@ ALGO_AUTO, ALGO_1PA_LL, ALGO_2PA_LL, ALGO_2PA_HB, ALGO_2PA_HB_2PHASE = 0, 1, 2, 
 EXPORTS = [
     "msx_allreduce", "msx_reducescatter", "msx_allgather", "msx_alltoall",
     "msx_allreduce_ex", "msx_reducescatter_ex", "msx_allgather_ex", "msx_alltoall_ex",
-    "msx_moe_dispatch",
+    "msx_moe_dispatch", "msx_moe_combine",
     "msx_prim_pingpong", "msx_prim_barrier", "msx_prim_put_signal_wait", "msx_prim_ll_encode",
     "msx_prim_ll_roundtrip",
     "msx_init", "msx_reset", "msx_finalize", "msx_set_option", "msx_get_option", "msx_status",
@@ -67,6 +67,7 @@ def lib():
         L.msx_allgather_ex.argtypes = [pp, pp, sz, i, i, vp]
         L.msx_alltoall_ex.argtypes = [pp, pp, sz, i, i, vp]
         L.msx_moe_dispatch.argtypes = [pp, pp, i, i, i, i, i, i, pp, pp, vp, sz, vp]
+        L.msx_moe_combine.argtypes = [pp, pp, i, i, i, i, sz, vp]
         L.msx_prim_pingpong.argtypes = [i, i, i, i, vp, vp]
         L.msx_prim_barrier.argtypes = [i, i, i, vp, vp]
         L.msx_prim_put_signal_wait.argtypes = [vp, vp, vp, sz, i, vp]
@@ -251,6 +252,18 @@ def moe_dispatch(tokens, topk_idx, n_experts, recv_tokens, recv_counts, recv_src
     _ck(lib().msx_moe_dispatch(_table(tokens), _table(topk_idx), T, H, K, n_experts, _dtype(tokens[0]), n,
                                _table(recv_tokens), _table(recv_src_token), C.c_void_p(recv_counts.data_ptr()),
                                cap, _stream(stream)), "msx_moe_dispatch")
+
+
+def moe_combine(expert_out, out_tokens, stream=None):
+    """expert_out[d]: [cap, H] processed rows in dispatch order; out_tokens[s]: [T, H].
+    Uses the routing of the last moe_dispatch."""
+    n = len(expert_out)
+    cap, H = expert_out[0].shape
+    T = out_tokens[0].shape[0]
+    for t in list(expert_out) + list(out_tokens):
+        _dev(t, "tensor")
+    _ck(lib().msx_moe_combine(_table(expert_out), _table(out_tokens), T, H, _dtype(expert_out[0]), n, cap,
+                              _stream(stream)), "msx_moe_combine")
 
 
 # ---- primitives ------------------------------------------------------------------------------------

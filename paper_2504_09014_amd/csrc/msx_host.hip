@@ -51,6 +51,7 @@ struct Ctx {
     void* moe_slots = nullptr;
     size_t moe_slots_bytes = 0;
     unsigned* moe_base = nullptr;
+    int plan_T = -1, plan_n = 0;   // shape of the routing plan the last dispatch left behind
     unsigned* snap = nullptr;  // small device scratch for snapshots
     size_t ll_limit = 0;       // ll_max_bytes this context was sized for
     std::map<std::pair<const void*, int>, int> occ;   // (kernel, threads) -> resident blocks per CU
@@ -673,8 +674,48 @@ int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, 
     if ((rc = pick_channels(c, (const void*)k_moe_pack, 256, n, (size_t)T * 64, 4, g_opt.hb_blocks, 128, &chans)))
         return rc;
     a.chans = chans;
+    c->plan_T = T;
+    c->plan_n = n;
     note_launch(n * chans, 256, MSX_ALGO_2PA_HB);
     return launch(k_moe_pack, n * chans, 256, s, a, d);
+}
+
+int msx_moe_combine(const void* const* expert_out, void* const* out_tokens, int T, int H, int dtype, int nranks,
+                    size_t capacity_tokens, void* stream)
+{
+    int rc = check_common(dtype, MSX_SUM, nranks);
+    if (rc) return rc;
+    if ((rc = check_table(expert_out, nranks))) return rc;
+    if ((rc = check_table((const void* const*)out_tokens, nranks))) return rc;
+    if (T < 0 || H <= 0) return MSX_ERR_ARG;
+    const size_t row_bytes = (size_t)H * elem_size(dtype);
+    if (row_bytes % 16) return MSX_ERR_ARG;
+    if (capacity_tokens > 0xffffffffull) capacity_tokens = 0xffffffffull;
+
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    if ((rc = get_ctx(&c))) return rc;
+    if (c->plan_T != T || c->plan_n != nranks || !c->moe_slots) return MSX_ERR_ARG;   // no matching dispatch before
+    if (T == 0) return MSX_OK;
+    const int n = nranks;
+    MoeArgs a{};
+    for (int i = 0; i < n; ++i) {
+        a.recv[i] = const_cast<void*>(expert_out[i]);
+        a.tokens[i] = out_tokens[i];
+    }
+    a.slots = (unsigned short*)c->moe_slots;
+    a.base = c->moe_base;
+    a.T = T;
+    a.n = n;
+    a.row_vecs = (unsigned)(row_bytes / 16);
+    a.cap = (unsigned)capacity_tokens;
+    const void* kp = dtype == MSX_F32 ? (const void*)k_moe_combine<0> : (const void*)k_moe_combine<1>;
+    int chans = 1;
+    if ((rc = pick_channels(c, kp, 256, n, (size_t)T * 64, 4, g_opt.hb_blocks, 128, &chans))) return rc;
+    a.chans = chans;
+    note_launch(n * chans, 256, MSX_ALGO_2PA_HB);
+    typedef void (*K)(MoeArgs, DevCtx);
+    return launch((K)kp, n * chans, 256, (hipStream_t)stream, a, dev_ctx(c));
 }
 
 // ---- primitives -------------------------------------------------------------------------------

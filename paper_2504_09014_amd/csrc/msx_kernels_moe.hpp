@@ -203,4 +203,67 @@ __global__ __launch_bounds__(256) void k_moe_pack(MoeArgs a, DevCtx c)
     if (n > 1) rank_barrier(c, rank, n, chan, 210, false, false);   // write-through puts: all rows destined to me have landed
 }
 
+// ---- combine: the way back ------------------------------------------------------------------------
+// Source rank s gathers, for each of its tokens, the processed rows from the destination ranks the
+// token was sent to (same plan as the dispatch) and sums them in fp32 in ascending rank order,
+// starting from the first, with one rounding.  A get-style read of the peers' buffers: every row is
+// read once and every output row written once.  a.recv[] are the peers' processed rows (read),
+// a.tokens[] (cast away const by the host) the per-source outputs.
+template <int DT>
+__global__ __launch_bounds__(256) void k_moe_combine(MoeArgs a, DevCtx c)
+{
+    const int n = a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    if (n > 1) rank_barrier(c, rank, n, chan, 220, false, false);   // every peer's rows are final
+    const int lane = (int)(threadIdx.x & 63u);
+    const int waves = (int)(blockDim.x >> 6);
+    const int wave = chan * waves + (int)(threadIdx.x >> 6);
+    const int total_waves = a.chans * waves;
+    unsigned base[kMaxRanks];
+#pragma unroll
+    for (int d = 0; d < kMaxRanks; ++d) base[d] = a.base[rank * 8 + d];
+    char* out = (char*)a.tokens[rank];
+    const size_t row_bytes = (size_t)a.row_vecs * 16;
+
+    for (int t = wave; t < a.T; t += total_waves) {
+        const u32x4 pk = *(const u32x4*)(a.slots + ((size_t)rank * a.T + t) * 8);
+        unsigned row[kMaxRanks];
+        row[0] = pk.x & 0xffffu; row[1] = pk.x >> 16; row[2] = pk.y & 0xffffu; row[3] = pk.y >> 16;
+        row[4] = pk.z & 0xffffu; row[5] = pk.z >> 16; row[6] = pk.w & 0xffffu; row[7] = pk.w >> 16;
+        const char* src[kMaxRanks];
+#pragma unroll
+        for (int d = 0; d < kMaxRanks; ++d) {
+            const unsigned r = base[d] + row[d];
+            const bool go = d < n && row[d] != 0xffffu && r < a.cap;
+            src[d] = go ? (const char*)a.recv[d] + (size_t)r * row_bytes : nullptr;
+        }
+        char* dst = out + (size_t)t * row_bytes;
+        for (unsigned i = (unsigned)lane; i < a.row_vecs; i += 128u) {
+            const unsigned i1 = i + 64u;
+            const bool two = i1 < a.row_vecs;
+            u32x4 v0[kMaxRanks], v1[kMaxRanks];
+#pragma unroll
+            for (int d = 0; d < kMaxRanks; ++d)
+                if (src[d]) {
+                    v0[d] = ld16(src[d], i);
+                    if (two) v1[d] = ld16(src[d], i1);
+                }
+            VecAcc<DT> a0, a1;
+            bool first = true;
+#pragma unroll
+            for (int d = 0; d < kMaxRanks; ++d)
+                if (src[d]) {
+                    if (first) { a0.set(v0[d]); if (two) a1.set(v1[d]); first = false; }
+                    else { a0.add(v0[d]); if (two) a1.add(v1[d]); }
+                }
+            const u32x4 zero = {0, 0, 0, 0};
+            st16(dst, i, first ? zero : a0.pack());
+            if (two) st16(dst, i1, first ? zero : a1.pack());
+        }
+    }
+    if (n > 1) rank_barrier(c, rank, n, chan, 221, false, false);   // peers are done reading my rows
+}
+
 }  // namespace msx

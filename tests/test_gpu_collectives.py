@@ -257,3 +257,52 @@ def test_config5_moe_dispatch_full_size(msx, orc):
     for d in range(n):
         assert np.array_equal(src[d].cpu().numpy(), want_src[d]), d
         assert np.array_equal(_bits(recv[d]), want_recv[d]), d
+
+
+# ---------------------------------------------------------------- combine
+
+@pytest.mark.parametrize("n,T,H,K,E", [(8, 96, 24, 8, 256), (8, 1000, 64, 8, 256), (4, 333, 8, 2, 16), (1, 77, 16, 4, 8)])
+def test_moe_combine_small_shapes(msx, orc, n, T, H, K, E):
+    tokens = synth.moe_tokens(n, T, H, seed=T + 1)
+    topk = synth.moe_routing(n, T, K, E, seed=T + 1)
+    cap = n * T
+    recv, src, counts, rc, info = _dispatch(msx, tokens, topk, E, cap)
+    assert rc == 0, info
+    # "expert output": fresh random rows, so the sum is not just a multiple of the token
+    y = synth.normal(n, cap * H, seed=77).view(n, cap, H)
+    ydev = [y[d].clone().cuda() for d in range(n)]
+    out = [torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    msx.set_option("chaos", "21")
+    msx.moe_combine(ydev, out)
+    msx.set_option("chaos", "0")
+    msx.check_status()
+    want, orc_rc = orc.moe_combine_bf16(_bits(y), topk.numpy(), E)
+    assert orc_rc == 0
+    for s in range(n):
+        assert np.array_equal(_bits(out[s]), want[s]), s
+
+
+def test_moe_combine_needs_a_matching_dispatch(msx):
+    y = [torch.zeros((16, 8), dtype=torch.bfloat16, device="cuda") for _ in range(8)]
+    out = [torch.zeros((12345, 8), dtype=torch.bfloat16, device="cuda") for _ in range(8)]
+    with pytest.raises(msx.MsxError) as e:
+        msx.moe_combine(y, out)
+    assert e.value.code == -1
+
+
+def test_config5_moe_combine_full_size(msx, orc):
+    n, T, H, K, E = 8, 4096, 7168, 8, 256
+    tokens = synth.moe_tokens(n, T, H, seed=0)
+    topk = synth.moe_routing(n, T, K, E, seed=0)
+    cap = 24576
+    recv, src, counts, rc, info = _dispatch(msx, tokens, topk, E, cap)
+    assert rc == 0, info
+    # combine what was dispatched (rows stay on the GPU): out = fan-out copies of the token summed
+    out = [torch.empty((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    msx.moe_combine(recv, out)
+    msx.check_status()
+    y = np.stack([_bits(r) for r in recv])
+    want, orc_rc = orc.moe_combine_bf16(y, topk.numpy(), E)
+    assert orc_rc == 0
+    for s in range(n):
+        assert np.array_equal(_bits(out[s]), want[s]), s
