@@ -304,6 +304,83 @@ int orc_moe_dispatch(const uint8_t *tokens, const int32_t *topk, int n, int T, i
     return rc;
 }
 
+/* ---------- FP8 (OCP E4M3: 1 sign, 4 exponent bits with bias 7, 3 mantissa bits; largest finite
+ * value 448 = 0x7E, 0x7F / 0xFF are NaN, there is no infinity) ---------- */
+
+float orc_e4m3_to_f32(uint8_t b)
+{
+    int sign = b >> 7, e = (b >> 3) & 15, m = b & 7;
+    float v;
+    if (e == 15 && m == 7) {
+        uint32_t q = 0x7fc00000u | ((uint32_t)sign << 31);
+        memcpy(&v, &q, 4);
+        return v;
+    }
+    if (e == 0)
+        v = (float)m / 8.0f / 64.0f;                 /* subnormal: m/8 * 2^-6 */
+    else {
+        v = 1.0f + (float)m / 8.0f;
+        for (int i = e; i < 7; ++i) v *= 0.5f;
+        for (int i = 7; i < e; ++i) v *= 2.0f;
+    }
+    return sign ? -v : v;
+}
+
+/* nearest representable value, ties to the even code, magnitudes beyond 448 saturate to 448,
+ * NaN -> 0x7F.  Written as a search over the 127 finite magnitudes so that it shares nothing
+ * with a bit-twiddling encoder. */
+uint8_t orc_f32_to_e4m3(float f)
+{
+    if (f != f)
+        return 0x7f;
+    uint8_t sign = 0;
+    if (f < 0.0f || (f == 0.0f && 1.0f / f < 0.0f)) {
+        sign = 0x80;
+        f = -f;
+    }
+    if (f >= 448.0f)
+        return (uint8_t)(sign | 0x7e);
+    int best = 0;
+    for (int code = 0; code < 0x7f; ++code) {        /* magnitudes ascend with the code */
+        float lo = orc_e4m3_to_f32((uint8_t)code), hi = orc_e4m3_to_f32((uint8_t)(code + 1));
+        if (code + 1 == 0x7f)
+            hi = 512.0f;                             /* the value the next code would have had */
+        if (f >= lo && f <= hi) {
+            double dl = (double)f - (double)lo, dh = (double)hi - (double)f;
+            if (dl < dh) best = code;
+            else if (dh < dl) best = code + 1;
+            else best = (code & 1) ? code + 1 : code;
+            break;
+        }
+    }
+    if (best >= 0x7f)
+        best = 0x7e;
+    return (uint8_t)(sign | best);
+}
+
+/* Row-wise quantisation in groups of 128 elements (the 1x128 tile scaling of the DeepSeek-V3
+ * setting the paper's expert-parallel experiment uses): amax = max(|x|, 1e-4) over the group,
+ * inv = 448 / amax, q = e4m3(x * inv), scale = amax / 448, all in fp32.
+ *   x : [rows][H] bf16 bits, H % 128 == 0     q : [rows][H] bytes     scales : [rows][H/128] */
+void orc_fp8_quantize_rows(const uint16_t *x, uint8_t *q, float *scales, size_t rows, size_t H)
+{
+    size_t groups = H / 128;
+    for (size_t r = 0; r < rows; ++r)
+        for (size_t g = 0; g < groups; ++g) {
+            const uint16_t *px = x + r * H + g * 128;
+            float amax = 1e-4f;
+            for (int i = 0; i < 128; ++i) {
+                float v = orc_bf16_to_f32(px[i]);
+                if (v < 0.0f) v = -v;
+                if (v > amax) amax = v;              /* NaN never wins the comparison */
+            }
+            float inv = 448.0f / amax;
+            scales[r * groups + g] = amax / 448.0f;
+            for (int i = 0; i < 128; ++i)
+                q[r * H + g * 128 + i] = orc_f32_to_e4m3(orc_bf16_to_f32(px[i]) * inv);
+        }
+}
+
 /*
  * Combine: the way back of the dispatch.  y[d] holds one processed row for every row that
  * destination d received, in the order the dispatch delivered them.  Every source token

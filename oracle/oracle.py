@@ -56,6 +56,12 @@ def lib():
         L.orc_ll_decode_buf.restype = i32
         L.orc_moe_dispatch.argtypes = [vp, vp, i32, i32, i32, i32, sz, vp, vp, vp, sz]
         L.orc_moe_dispatch.restype = i32
+        L.orc_e4m3_to_f32.argtypes = [C.c_uint8]
+        L.orc_e4m3_to_f32.restype = C.c_float
+        L.orc_f32_to_e4m3.argtypes = [C.c_float]
+        L.orc_f32_to_e4m3.restype = C.c_uint8
+        L.orc_fp8_quantize_rows.argtypes = [vp, vp, vp, sz, sz]
+        L.orc_fp8_quantize_rows.restype = None
         L.orc_moe_combine_bf16.argtypes = [vp, vp, i32, i32, i32, i32, sz, sz, vp, vp, vp]
         L.orc_moe_combine_bf16.restype = i32
         L.orc_sem_reached.argtypes = [u32, u32]
@@ -223,6 +229,25 @@ def moe_dispatch(tokens, topk, n_experts, cap=None):
     rc = lib().orc_moe_dispatch(_p(tokens), _p(topk), n, T, K, n_experts,
                                 H * tokens.dtype.itemsize, _p(recv), _p(src), _p(counts), cap)
     return recv, src, counts, rc
+
+
+def e4m3_to_f32(code):
+    return float(lib().orc_e4m3_to_f32(int(code) & 0xFF))
+
+
+def f32_to_e4m3(x):
+    return int(lib().orc_f32_to_e4m3(float(np.float32(x))))
+
+
+def fp8_quantize_rows(x):
+    """x: [rows, H] uint16 (bf16 bits), H % 128 == 0 -> (q [rows, H] uint8, scales [rows, H/128] float32)."""
+    x = _c(x, np.uint16)
+    rows, H = x.shape
+    assert H % 128 == 0
+    q = np.empty((rows, H), np.uint8)
+    scales = np.empty((rows, H // 128), np.float32)
+    lib().orc_fp8_quantize_rows(_p(x), _p(q), _p(scales), rows, H)
+    return q, scales
 
 
 def moe_combine_bf16(y, topk, n_experts, T=None):

@@ -458,6 +458,74 @@ def test_moe_expected_fanout_of_the_seeded_routing():
     assert abs(fan - expect) < 0.03
 
 
+# ---------------------------------------------------------------- FP8 E4M3
+
+def test_e4m3_decode_all_codes_closed_form_and_torch(orc):
+    codes = np.arange(256, dtype=np.uint8)
+    got = np.array([orc.e4m3_to_f32(c) for c in codes], np.float32)
+    for c in codes:
+        s, e, m = c >> 7, (c >> 3) & 15, c & 7
+        if e == 15 and m == 7:
+            assert np.isnan(got[c])
+            continue
+        want = (2.0 ** -6) * (m / 8.0) if e == 0 else (2.0 ** (int(e) - 7)) * (1 + m / 8.0)
+        assert got[c] == np.float32(-want if s else want), c
+    assert got[0x7E] == 448.0 and got[0x01] == 2.0 ** -9 and got[0x08] == 2.0 ** -6
+    lib = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).float().numpy()      # library decode
+    ok = ~np.isnan(lib)
+    assert np.array_equal(got[ok], lib[ok]) and np.all(np.isnan(got[~ok]))
+
+
+def test_e4m3_encode_roundtrip_ties_saturation_and_torch(orc):
+    for c in range(256):
+        v = orc.e4m3_to_f32(c)
+        if v != v:
+            assert orc.f32_to_e4m3(v) == 0x7F
+        else:
+            assert orc.f32_to_e4m3(v) == c, c                      # includes -0 -> 0x80
+    # hand-worked: spacing is 0.125 in [1,2): 1.0625 is the tie between 1.0 (0x38, even) and 1.125 (0x39)
+    assert orc.f32_to_e4m3(1.0625) == 0x38 and orc.f32_to_e4m3(1.1875) == 0x3A   # tie between 0x39 and 0x3A -> even
+    assert orc.f32_to_e4m3(1.07) == 0x39 and orc.f32_to_e4m3(1.05) == 0x38
+    assert orc.f32_to_e4m3(2.0 ** -10) == 0x00 and orc.f32_to_e4m3(2.0 ** -10 * 1.01) == 0x01   # subnormal tie / just above
+    assert orc.f32_to_e4m3(3 * 2.0 ** -10) == 0x02                                       # tie 1.5 ulp -> even (2)
+    assert orc.f32_to_e4m3(448.0) == 0x7E and orc.f32_to_e4m3(464.0) == 0x7E and orc.f32_to_e4m3(1e30) == 0x7E
+    assert orc.f32_to_e4m3(-1e30) == 0xFE and orc.f32_to_e4m3(float("inf")) == 0x7E
+    assert orc.f32_to_e4m3(440.0) == 0x7E                          # above the tie (432) between 416 and 448
+    assert orc.f32_to_e4m3(432.0) == 0x7E                          # the tie itself: 0x7D is odd -> up
+    assert orc.f32_to_e4m3(float("nan")) == 0x7F
+    g = torch.Generator().manual_seed(2)
+    x = torch.randn(20000, generator=g) * torch.exp(torch.randn(20000, generator=g) * 3)
+    x = x[x.abs() <= 448.0]
+    lib = x.to(torch.float8_e4m3fn).view(torch.uint8).numpy()                              # library encode (RNE)
+    got = np.array([orc.f32_to_e4m3(v) for v in x.numpy()], np.uint8)
+    assert np.array_equal(got, lib)
+
+
+def test_fp8_row_quantisation(orc):
+    x = synth.normal(6, 7168, seed=12)
+    x[2] *= 1000.0
+    x[3] = 0
+    x[4, :128] = 0.5                                                                      # a constant group
+    q, scales = orc.fp8_quantize_rows(synth.bf16_bits(x))
+    xf = x.float().view(6, 56, 128)
+    # IEEE fp32 division and multiplication with numpy (torch's scalar / tensor goes through a
+    # reciprocal and is not correctly rounded), torch's float8 type as the library encoder
+    xn = xf.numpy()
+    amax = np.maximum(np.abs(xn).max(axis=2), np.float32(1e-4)).astype(np.float32)
+    assert np.array_equal(scales, amax / np.float32(448.0))
+    scaled = xn * (np.float32(448.0) / amax)[:, :, None]
+    assert scaled.dtype == np.float32
+    lib = torch.from_numpy(scaled).to(torch.float8_e4m3fn).view(torch.uint8).view(6, 7168).numpy()
+    assert np.array_equal(q, lib)
+    assert np.all(q[3] == 0) and np.all(scales[3] == np.float32(1e-4) / np.float32(448.0))
+    assert np.all(q[4, :128] == 0x7E) and scales[4, 0] == np.float32(0.5) / np.float32(448.0)
+    # every group uses the top code at least once (the element that set amax), dequantisation is close
+    deq = np.array([[orc.e4m3_to_f32(c) for c in row] for row in q[:2]]).reshape(2, 56, 128) * scales[:2, :, None]
+    assert np.all((q[:2].reshape(2, 56, 128) & 0x7F).max(axis=2) == 0x7E)
+    err = np.abs(deq - xn[:2])
+    assert np.all(err <= 0.0625 * np.abs(xn[:2]) + scales[:2, :, None] * 2.0 ** -9 + 1e-7)
+
+
 # ---------------------------------------------------------------- semaphore counter
 
 def test_sem_reached_is_wrap_safe(orc):
