@@ -354,6 +354,16 @@ def main():
         moved = rows * H * 2 + n * T * H * 2
         extras["config5_moe_combine"] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
                                          "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+        rq = [torch.empty((cap, H), dtype=torch.uint8, device="cuda") for _ in range(n)]
+        rsc = [torch.empty((cap, H // 128), dtype=torch.float32, device="cuda") for _ in range(n)]
+        fn8 = lambda: msx.moe_dispatch_fp8(tk, ix, E, rq, rsc, cnt, rs)
+        _, ev = time_calls(torch, fn8, 20, 5)
+        msx.check_status()
+        ms = median(ev) / 1e3
+        moved = n * T * H * 2 + rows * (H + H // 128 * 4)
+        extras["config5_moe_dispatch_fp8"] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
+                                              "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+        del rq, rsc
         extras["hop_ns"] = {"signal_wait_round_trip_cross_xcd": round(msx.prim_pingpong(2000, 16, 0, 1), 1),
                             "signal_wait_round_trip_same_xcd": round(msx.prim_pingpong(2000, 16, 0, 8), 1)}
         out["extras"] = extras

@@ -124,6 +124,18 @@ int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, 
                      int32_t* const* recv_src_token, int32_t* recv_counts,
                      size_t recv_capacity_tokens, void* stream);
 
+/* The same dispatch with FP8 quantisation fused into the packing (the paper's setting is "FP8
+ * dispatch and BF16 combine"): tokens are bf16 [T][H], H % 128 == 0.  Each row is quantised in
+ * groups of 128 elements: amax = max(|x|, 1e-4), q = E4M3(x * (448 / amax)) (OCP E4M3, round to
+ * nearest even, saturating at 448), scale = amax / 448, all in fp32.
+ *   recv_q[d]       device [recv_capacity_tokens][H] bytes
+ *   recv_scales[d]  device [recv_capacity_tokens][H/128] float
+ * Everything else as in msx_moe_dispatch; msx_moe_combine may follow it. */
+int msx_moe_dispatch_fp8(const void* const* tokens, const int32_t* const* topk_idx, int T, int H,
+                         int K, int n_experts, int nranks, void* const* recv_q,
+                         float* const* recv_scales, int32_t* const* recv_src_token,
+                         int32_t* recv_counts, size_t recv_capacity_tokens, void* stream);
+
 /* Combine, the way back of msx_moe_dispatch (the paper's expert-parallel experiment runs
  * "dispatch and combine").  Uses the routing of the LAST msx_moe_dispatch on this device, which
  * must have had the same T and nranks (else MSX_ERR_ARG).

@@ -13,7 +13,7 @@ __all__ = [
     "MsxError", "lib", "lib_path", "init", "reset", "finalize", "set_option", "get_option", "status",
     "check_status", "last_launch", "version", "strerror",
     "allreduce", "reducescatter", "allgather", "alltoall",
-    "allreduce_ex", "reducescatter_ex", "allgather_ex", "alltoall_ex", "moe_dispatch", "moe_combine",
+    "allreduce_ex", "reducescatter_ex", "allgather_ex", "alltoall_ex", "moe_dispatch", "moe_dispatch_fp8", "moe_combine",
     "prim_pingpong", "prim_barrier", "prim_put_signal_wait", "prim_ll_encode", "prim_ll_roundtrip",
     "EXPORTS",
 ]
@@ -25,7 +25,7 @@ ALGO_AUTO, ALGO_1PA_LL, ALGO_2PA_LL, ALGO_2PA_HB, ALGO_2PA_HB_2PHASE = 0, 1, 2, 
 EXPORTS = [
     "msx_allreduce", "msx_reducescatter", "msx_allgather", "msx_alltoall",
     "msx_allreduce_ex", "msx_reducescatter_ex", "msx_allgather_ex", "msx_alltoall_ex",
-    "msx_moe_dispatch", "msx_moe_combine",
+    "msx_moe_dispatch", "msx_moe_dispatch_fp8", "msx_moe_combine",
     "msx_prim_pingpong", "msx_prim_barrier", "msx_prim_put_signal_wait", "msx_prim_ll_encode",
     "msx_prim_ll_roundtrip",
     "msx_init", "msx_reset", "msx_finalize", "msx_set_option", "msx_get_option", "msx_status",
@@ -67,6 +67,7 @@ def lib():
         L.msx_allgather_ex.argtypes = [pp, pp, sz, i, i, vp]
         L.msx_alltoall_ex.argtypes = [pp, pp, sz, i, i, vp]
         L.msx_moe_dispatch.argtypes = [pp, pp, i, i, i, i, i, i, pp, pp, vp, sz, vp]
+        L.msx_moe_dispatch_fp8.argtypes = [pp, pp, i, i, i, i, i, pp, pp, pp, vp, sz, vp]
         L.msx_moe_combine.argtypes = [pp, pp, i, i, i, i, sz, vp]
         L.msx_prim_pingpong.argtypes = [i, i, i, i, vp, vp]
         L.msx_prim_barrier.argtypes = [i, i, i, vp, vp]
@@ -252,6 +253,24 @@ def moe_dispatch(tokens, topk_idx, n_experts, recv_tokens, recv_counts, recv_src
     _ck(lib().msx_moe_dispatch(_table(tokens), _table(topk_idx), T, H, K, n_experts, _dtype(tokens[0]), n,
                                _table(recv_tokens), _table(recv_src_token), C.c_void_p(recv_counts.data_ptr()),
                                cap, _stream(stream)), "msx_moe_dispatch")
+
+
+def moe_dispatch_fp8(tokens, topk_idx, n_experts, recv_q, recv_scales, recv_counts, recv_src_token=None,
+                     stream=None):
+    """tokens[s]: [T, H] bf16; recv_q[d]: [cap, H] uint8; recv_scales[d]: [cap, H/128] float32."""
+    n = len(tokens)
+    T, H = tokens[0].shape
+    K = topk_idx[0].shape[1]
+    cap = recv_q[0].shape[0]
+    for t in (list(tokens) + list(topk_idx) + list(recv_q) + list(recv_scales) + list(recv_src_token or [])
+              + [recv_counts]):
+        _dev(t, "tensor")
+    if tokens[0].dtype != torch.bfloat16 or recv_q[0].dtype != torch.uint8 or recv_scales[0].dtype != torch.float32:
+        raise TypeError("tokens bf16, recv_q uint8, recv_scales float32")
+    _ck(lib().msx_moe_dispatch_fp8(_table(tokens), _table(topk_idx), T, H, K, n_experts, n, _table(recv_q),
+                                   _table(recv_scales), _table(recv_src_token),
+                                   C.c_void_p(recv_counts.data_ptr()), cap, _stream(stream)),
+        "msx_moe_dispatch_fp8")
 
 
 def moe_combine(expert_out, out_tokens, stream=None):

@@ -245,6 +245,25 @@ __device__ __forceinline__ unsigned bf16_round(float f)
     return ((u & 0x7fffffffu) > 0x7f800000u) ? q : r;
 }
 
+// fp32 -> OCP E4M3 code (1-4-3, bias 7, largest finite 448 = 0x7E, no infinity): round to nearest
+// even, magnitudes from 448 up (and infinities) saturate to 0x7E, NaN -> 0x7F.
+__device__ __forceinline__ unsigned e4m3_round(float f)
+{
+    const unsigned u = __float_as_uint(f);
+    const unsigned sign = (u >> 24) & 0x80u;
+    const unsigned a = u & 0x7fffffffu;
+    unsigned code;
+    if (a > 0x7f800000u) return 0x7fu;
+    if (a >= 0x43e00000u) code = 0x7eu;                       // |f| >= 448
+    else if (a >= 0x3c800000u) {                              // normal E4M3 range, |f| >= 2^-6
+        const unsigned r = a + 0x7ffffu + ((a >> 20) & 1u);   // round the mantissa to 3 bits
+        code = (((r >> 23) - 120u) << 3) | ((r >> 20) & 7u);
+    } else {
+        code = (unsigned)__float2int_rn(__uint_as_float(a) * 512.0f);   // multiples of 2^-9; 8 -> 0x08
+    }
+    return sign | code;
+}
+
 // Accumulator for the elements held in one 32-bit word: 1 x fp32 or 2 x bf16.
 template <int DT> struct WordAcc;
 template <> struct WordAcc<0> {   // fp32
@@ -291,6 +310,10 @@ __device__ __forceinline__ void st16_wt(void* base, size_t vec_index, u32x4 v)
 {
     u32x4* p = (u32x4*)base + vec_index;
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+}
+__device__ __forceinline__ void st8_wt(void* addr, u32x2 v)
+{
+    asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(addr), "v"(v) : "memory");
 }
 __device__ __forceinline__ void st32_wt(void* addr, unsigned v)
 {

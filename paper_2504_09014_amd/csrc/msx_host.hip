@@ -445,6 +445,85 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     return MSX_ERR_ARG;
 }
 
+// Token dispatch; recv_scales != nullptr selects the fused FP8 quantisation (tokens are bf16 then).
+int moe_dispatch_impl(const void* const* tokens, const int32_t* const* topk_idx, int T, int H, int K, int n_experts,
+                      int dtype, int nranks, void* const* recv_tokens, float* const* recv_scales,
+                      int32_t* const* recv_src_token, int32_t* recv_counts, size_t recv_capacity_tokens,
+                      hipStream_t s)
+{
+    int rc = check_common(dtype, MSX_SUM, nranks);
+    if (rc) return rc;
+    if ((rc = check_table(tokens, nranks))) return rc;
+    if ((rc = check_table((const void* const*)topk_idx, nranks))) return rc;
+    if ((rc = check_table((const void* const*)recv_tokens, nranks))) return rc;
+    if (!recv_counts) return MSX_ERR_ARG;
+    if (recv_src_token)
+        for (int r = 0; r < nranks; ++r)
+            if (!recv_src_token[r]) return MSX_ERR_ARG;
+    if (recv_scales)
+        for (int r = 0; r < nranks; ++r)
+            if (!recv_scales[r] || ((uintptr_t)recv_scales[r] & 3u)) return MSX_ERR_ARG;
+    if (T < 0 || H <= 0 || K <= 0 || K > 32 || n_experts <= 0 || n_experts % nranks) return MSX_ERR_ARG;
+    if (T > 65534) return MSX_ERR_UNSUPPORTED;
+    const size_t row_bytes = (size_t)H * elem_size(dtype);
+    if (row_bytes % 16) return MSX_ERR_ARG;
+    if (recv_capacity_tokens > 0xffffffffull) recv_capacity_tokens = 0xffffffffull;
+
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    if ((rc = get_ctx(&c))) return rc;
+    const int n = nranks;
+    const size_t need = (size_t)kMaxRanks * (size_t)(T > 0 ? T : 1) * 16;
+    if (need > c->moe_slots_bytes) {
+        if (c->moe_slots) { HIPCHK(hipDeviceSynchronize()); HIPCHK(hipFree(c->moe_slots)); c->moe_slots = nullptr; c->moe_slots_bytes = 0; }
+        HIPCHK(hipMalloc(&c->moe_slots, need));
+        c->moe_slots_bytes = need;
+    }
+    MoeArgs a{};
+    for (int i = 0; i < n; ++i) {
+        a.tokens[i] = tokens[i];
+        a.topk[i] = topk_idx[i];
+        a.recv[i] = recv_tokens[i];
+        a.recv_src[i] = recv_src_token ? recv_src_token[i] : nullptr;
+    }
+    a.recv_counts = recv_counts;
+    a.slots = (unsigned short*)c->moe_slots;
+    a.base = c->moe_base;
+    a.T = T;
+    a.K = K;
+    a.n = n;
+    a.per_rank = n_experts / n;
+    a.n_experts = n_experts;
+    a.row_vecs = (unsigned)(row_bytes / 16);
+    a.cap = (unsigned)recv_capacity_tokens;
+    a.has_src = recv_src_token ? 1 : 0;
+    const DevCtx d = dev_ctx(c);
+
+    int resident = 0;
+    if ((rc = resident_blocks(c, (const void*)k_moe_plan, kPlanThreads, &resident))) return rc;
+    if (resident < n) return MSX_ERR_UNSUPPORTED;
+    a.chans = 1;
+    if ((rc = launch(k_moe_plan, n, kPlanThreads, s, a, d))) return rc;
+
+    int chans = 1;
+    // one wave per token row, 4 waves per workgroup, a few rows per wave
+    if ((rc = pick_channels(c, (const void*)k_moe_pack, 256, n, (size_t)T * 64, 4, g_opt.hb_blocks, 128, &chans)))
+        return rc;
+    a.chans = chans;
+    c->plan_T = T;
+    c->plan_n = n;
+    note_launch(n * chans, 256, MSX_ALGO_2PA_HB);
+    if (recv_scales) {
+        MoeFp8Args f{};
+        for (int i = 0; i < n; ++i) f.recv_scales[i] = recv_scales[i];
+        f.groups = (unsigned)(H / 128);
+        return launch(k_moe_pack_fp8, n * chans, 256, s, a, f, d);
+    }
+    return launch(k_moe_pack, n * chans, 256, s, a, d);
+}
+
+
+
 bool parse_u64(const char* s, unsigned long long* v)
 {
     if (!s || !*s) return false;
@@ -617,67 +696,19 @@ int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, 
                      int dtype, int nranks, void* const* recv_tokens, int32_t* const* recv_src_token,
                      int32_t* recv_counts, size_t recv_capacity_tokens, void* stream)
 {
-    int rc = check_common(dtype, MSX_SUM, nranks);
-    if (rc) return rc;
-    if ((rc = check_table(tokens, nranks))) return rc;
-    if ((rc = check_table((const void* const*)topk_idx, nranks))) return rc;
-    if ((rc = check_table((const void* const*)recv_tokens, nranks))) return rc;
-    if (!recv_counts) return MSX_ERR_ARG;
-    if (recv_src_token)
-        for (int r = 0; r < nranks; ++r)
-            if (!recv_src_token[r]) return MSX_ERR_ARG;
-    if (T < 0 || H <= 0 || K <= 0 || K > 32 || n_experts <= 0 || n_experts % nranks) return MSX_ERR_ARG;
-    if (T > 65534) return MSX_ERR_UNSUPPORTED;
-    const size_t row_bytes = (size_t)H * elem_size(dtype);
-    if (row_bytes % 16) return MSX_ERR_ARG;
-    if (recv_capacity_tokens > 0xffffffffull) recv_capacity_tokens = 0xffffffffull;
-    const hipStream_t s = (hipStream_t)stream;
+    return moe_dispatch_impl(tokens, topk_idx, T, H, K, n_experts, dtype, nranks, recv_tokens, nullptr,
+                             recv_src_token, recv_counts, recv_capacity_tokens, (hipStream_t)stream);
+}
 
-    std::lock_guard<std::mutex> lk(g_mu);
-    Ctx* c = nullptr;
-    if ((rc = get_ctx(&c))) return rc;
-    const int n = nranks;
-    const size_t need = (size_t)kMaxRanks * (size_t)(T > 0 ? T : 1) * 16;
-    if (need > c->moe_slots_bytes) {
-        if (c->moe_slots) { HIPCHK(hipDeviceSynchronize()); HIPCHK(hipFree(c->moe_slots)); c->moe_slots = nullptr; c->moe_slots_bytes = 0; }
-        HIPCHK(hipMalloc(&c->moe_slots, need));
-        c->moe_slots_bytes = need;
-    }
-    MoeArgs a{};
-    for (int i = 0; i < n; ++i) {
-        a.tokens[i] = tokens[i];
-        a.topk[i] = topk_idx[i];
-        a.recv[i] = recv_tokens[i];
-        a.recv_src[i] = recv_src_token ? recv_src_token[i] : nullptr;
-    }
-    a.recv_counts = recv_counts;
-    a.slots = (unsigned short*)c->moe_slots;
-    a.base = c->moe_base;
-    a.T = T;
-    a.K = K;
-    a.n = n;
-    a.per_rank = n_experts / n;
-    a.n_experts = n_experts;
-    a.row_vecs = (unsigned)(row_bytes / 16);
-    a.cap = (unsigned)recv_capacity_tokens;
-    a.has_src = recv_src_token ? 1 : 0;
-    const DevCtx d = dev_ctx(c);
-
-    int resident = 0;
-    if ((rc = resident_blocks(c, (const void*)k_moe_plan, kPlanThreads, &resident))) return rc;
-    if (resident < n) return MSX_ERR_UNSUPPORTED;
-    a.chans = 1;
-    if ((rc = launch(k_moe_plan, n, kPlanThreads, s, a, d))) return rc;
-
-    int chans = 1;
-    // one wave per token row, 4 waves per workgroup, a few rows per wave
-    if ((rc = pick_channels(c, (const void*)k_moe_pack, 256, n, (size_t)T * 64, 4, g_opt.hb_blocks, 128, &chans)))
-        return rc;
-    a.chans = chans;
-    c->plan_T = T;
-    c->plan_n = n;
-    note_launch(n * chans, 256, MSX_ALGO_2PA_HB);
-    return launch(k_moe_pack, n * chans, 256, s, a, d);
+int msx_moe_dispatch_fp8(const void* const* tokens, const int32_t* const* topk_idx, int T, int H, int K,
+                         int n_experts, int nranks, void* const* recv_q, float* const* recv_scales,
+                         int32_t* const* recv_src_token, int32_t* recv_counts, size_t recv_capacity_tokens,
+                         void* stream)
+{
+    if (!recv_scales) return MSX_ERR_ARG;
+    if (H <= 0 || H % 128) return MSX_ERR_ARG;
+    return moe_dispatch_impl(tokens, topk_idx, T, H, K, n_experts, MSX_BF16, nranks, recv_q, recv_scales,
+                             recv_src_token, recv_counts, recv_capacity_tokens, (hipStream_t)stream);
 }
 
 int msx_moe_combine(const void* const* expert_out, void* const* out_tokens, int T, int H, int dtype, int nranks,

@@ -203,6 +203,84 @@ __global__ __launch_bounds__(256) void k_moe_pack(MoeArgs a, DevCtx c)
     if (n > 1) rank_barrier(c, rank, n, chan, 210, false, false);   // write-through puts: all rows destined to me have landed
 }
 
+// ---- pack with FP8 quantisation ---------------------------------------------------------------------
+// The "FP8 dispatch" of the paper's expert-parallel setting: the bf16 row is read once, quantised
+// in registers to E4M3 in groups of 128 elements (amax = max(|x|, 1e-4), q = e4m3(x * (448/amax)),
+// scale = amax/448, fp32 throughout) and the 1-byte row plus its fp32 scales are put into every
+// destination.  A lane holds 8 elements; the 16 lanes of a group share their maximum by shuffles.
+// a.recv[d] = quantised rows [cap][H] bytes, a.recv_scales[d] = [cap][H/128] floats.
+struct MoeFp8Args {
+    float* recv_scales[kMaxRanks];
+    unsigned groups;        // H / 128
+};
+
+__global__ __launch_bounds__(256) void k_moe_pack_fp8(MoeArgs a, MoeFp8Args f, DevCtx c)
+{
+    const int n = a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    const int lane = (int)(threadIdx.x & 63u);
+    const int waves = (int)(blockDim.x >> 6);
+    const int wave = chan * waves + (int)(threadIdx.x >> 6);
+    const int total_waves = a.chans * waves;
+    unsigned base[kMaxRanks];
+#pragma unroll
+    for (int d = 0; d < kMaxRanks; ++d) base[d] = a.base[rank * 8 + d];
+    const char* tokens = (const char*)a.tokens[rank];
+    const unsigned row_vecs = a.row_vecs;                    // 16-byte vectors of the bf16 row = H / 8
+    const size_t src_row = (size_t)row_vecs * 16, q_row = (size_t)row_vecs * 8;
+
+    for (int t = wave; t < a.T; t += total_waves) {
+        const u32x4 pk = *(const u32x4*)(a.slots + ((size_t)rank * a.T + t) * 8);
+        unsigned row[kMaxRanks];
+        row[0] = pk.x & 0xffffu; row[1] = pk.x >> 16; row[2] = pk.y & 0xffffu; row[3] = pk.y >> 16;
+        row[4] = pk.z & 0xffffu; row[5] = pk.z >> 16; row[6] = pk.w & 0xffffu; row[7] = pk.w >> 16;
+        char* dq[kMaxRanks];
+        float* ds[kMaxRanks];
+#pragma unroll
+        for (int d = 0; d < kMaxRanks; ++d) {
+            const unsigned r = base[d] + row[d];
+            const bool go = d < n && row[d] != 0xffffu && r < a.cap;
+            dq[d] = go ? (char*)a.recv[d] + (size_t)r * q_row : nullptr;
+            ds[d] = go ? f.recv_scales[d] + (size_t)r * f.groups : nullptr;
+            if (go && a.has_src && lane == 0) st32_wt(a.recv_src[d] + r, (unsigned)(rank * a.T + t));
+        }
+        const char* src = tokens + (size_t)t * src_row;
+        for (unsigned i = (unsigned)lane; i < row_vecs; i += 64u) {
+            const u32x4 v = ld16(src, i);
+            float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
+                          bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+            float amax = 1e-4f;
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const float m = fabsf(x[k]);
+                amax = m > amax ? m : amax;                  // a NaN never wins the comparison
+            }
+#pragma unroll
+            for (int m = 8; m >= 1; m >>= 1) {
+                const float o = __shfl_xor(amax, m, 64);
+                amax = o > amax ? o : amax;
+            }
+            const float inv = 448.0f / amax;
+            unsigned b[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) b[k] = e4m3_round(x[k] * inv);
+            const u32x2 q = {b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24),
+                             b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24)};
+            const float scale = amax / 448.0f;
+#pragma unroll
+            for (int d = 0; d < kMaxRanks; ++d)
+                if (dq[d]) {
+                    st8_wt(dq[d] + (size_t)i * 8, q);
+                    if ((lane & 15) == 0) st32_wt(ds[d] + (i >> 4), __float_as_uint(scale));
+                }
+        }
+    }
+    put_drain();
+    if (n > 1) rank_barrier(c, rank, n, chan, 230, false, false);
+}
+
 // ---- combine: the way back ------------------------------------------------------------------------
 // Source rank s gathers, for each of its tokens, the processed rows from the destination ranks the
 // token was sent to (same plan as the dispatch) and sums them in fp32 in ascending rank order,

@@ -306,3 +306,67 @@ def test_config5_moe_combine_full_size(msx, orc):
     assert orc_rc == 0
     for s in range(n):
         assert np.array_equal(_bits(out[s]), want[s]), s
+
+
+# ---------------------------------------------------------------- FP8 dispatch
+
+@pytest.mark.parametrize("n,T,H,K,E", [(8, 96, 128, 8, 256), (8, 500, 512, 8, 256), (4, 333, 256, 2, 16), (8, 64, 7168, 8, 256)])
+def test_moe_dispatch_fp8_matches_quantise_then_dispatch(msx, orc, n, T, H, K, E):
+    tokens = synth.moe_tokens(n, T, H, seed=T + 5)
+    tokens[0, 0, :128] = 0                                      # an all-zero group (amax clamps at 1e-4)
+    tokens[0, 1, 5] = 1000.0                                    # an outlier that sets its group's scale
+    tokens[1 % n, 2, 7] = float("inf")
+    topk = synth.moe_routing(n, T, K, E, seed=T + 5)
+    cap = n * T
+    tb = _bits(tokens)
+    q, scales = orc.fp8_quantize_rows(tb.reshape(n * T, H))
+    want_q, want_src, want_counts, orc_rc = orc.moe_dispatch(q.reshape(n, T, H), topk.numpy(), E, cap)
+    want_s, _, _, _ = orc.moe_dispatch(scales.reshape(n, T, H // 128), topk.numpy(), E, cap)
+    assert orc_rc == 0
+    tok = [tokens[r].clone().cuda() for r in range(n)]
+    idx = [topk[r].clone().cuda() for r in range(n)]
+    rq = [torch.zeros((cap, H), dtype=torch.uint8, device="cuda") for _ in range(n)]
+    rs = [torch.zeros((cap, H // 128), dtype=torch.float32, device="cuda") for _ in range(n)]
+    src = [torch.full((cap,), -1, dtype=torch.int32, device="cuda") for _ in range(n)]
+    counts = torch.zeros((n, n), dtype=torch.int32, device="cuda")
+    msx.moe_dispatch_fp8(tok, idx, E, rq, rs, counts, src)
+    msx.check_status()
+    assert np.array_equal(counts.cpu().numpy(), want_counts)
+    for d in range(n):
+        assert np.array_equal(src[d].cpu().numpy(), want_src[d]), d
+        assert np.array_equal(rq[d].cpu().numpy(), want_q[d]), d
+        assert np.array_equal(rs[d].cpu().numpy().view(np.uint32), want_s[d].view(np.uint32)), d
+
+
+def test_e4m3_encoder_on_gpu_covers_every_code_and_tie(msx, orc):
+    # one row whose groups hold hand-picked values scaled so that x * (448 / amax) hits exact
+    # codes, ties and the subnormal range: group amax is pinned to 448 by one element
+    vals = [orc.e4m3_to_f32(c) for c in range(0x7F)]
+    probes = []
+    for a, b in zip(vals[:-1], vals[1:]):
+        probes += [a, (a + b) / 2]                               # every code and every tie
+    probes += [448.0, -448.0, 0.0, -0.0]
+    probes = [p for p in probes if float(torch.tensor(p).bfloat16()) == p]     # representable in bf16
+    H = 128 * ((len(probes) + 126) // 127)
+    row = torch.zeros(H)
+    k = 0
+    for g in range(H // 128):
+        row[g * 128] = 448.0
+        for j in range(1, 128):
+            if k < len(probes):
+                row[g * 128 + j] = probes[k]
+                k += 1
+    tokens = row.bfloat16().view(1, 1, H).repeat(8, 1, 1)
+    topk = torch.arange(0, 256, 32, dtype=torch.int32).repeat(8, 1, 1)
+    q, scales = orc.fp8_quantize_rows(_bits(tokens).reshape(8, H))
+    tok = [tokens[r].clone().cuda() for r in range(8)]
+    idx = [topk[r].clone().cuda() for r in range(8)]
+    rq = [torch.zeros((8, H), dtype=torch.uint8, device="cuda") for _ in range(8)]
+    rs = [torch.zeros((8, H // 128), dtype=torch.float32, device="cuda") for _ in range(8)]
+    counts = torch.zeros((8, 8), dtype=torch.int32, device="cuda")
+    msx.moe_dispatch_fp8(tok, idx, 256, rq, rs, counts)
+    msx.check_status()
+    assert np.all(counts.cpu().numpy() == 1)
+    assert np.all(scales == 1.0)
+    for d in range(8):
+        assert np.array_equal(rq[d].cpu().numpy(), q), d
