@@ -278,6 +278,22 @@ def main():
             torch.cuda.empty_cache()
         msx.check_status()
         extras["config3_other_sizes"] = c3
+        # two-phase ring over put/signal/wait hand-offs, next to the all-pairs form
+        ring = {}
+        for mib in [1, 64, 256]:
+            c = mib * (1 << 20) // 2
+            xs = synth.normal(n, c, seed=mib + 1, device="cuda")
+            s_ = [xs[r] for r in range(n)]
+            r_ = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            row = {}
+            for name, a in [("ring_2pr_us", msx.ALGO_2PR_HB), ("allpairs_2pa_us", msx.ALGO_2PA_HB)]:
+                fn = lambda: msx.allreduce_ex(s_, r_, None, algo=a)
+                row[name] = round(median(time_calls(torch, fn, 10, 3)[1]), 1)
+            ring[f"{mib}MiB"] = row
+            del xs, s_, r_
+            torch.cuda.empty_cache()
+        msx.check_status()
+        extras["ring_vs_allpairs"] = ring
         # standalone ReduceScatter / AllGather / AllToAll (HB protocol), 256 MiB rows
         other = {}
         c = 128 << 20                                   # elements per full row (256 MiB of bf16)

@@ -51,7 +51,12 @@ typedef enum {
     MSX_ALGO_1PA_LL = 1,    /* one-phase all-pairs over LL packets */
     MSX_ALGO_2PA_LL = 2,    /* two-phase all-pairs over LL packets, rotating scratch */
     MSX_ALGO_2PA_HB = 3,    /* two-phase all-pairs, HB protocol, reduce and put fused in registers */
-    MSX_ALGO_2PA_HB_2PHASE = 4 /* same, but reduce-scatter to memory, barrier, all-gather put */
+    MSX_ALGO_2PA_HB_2PHASE = 4, /* same, but reduce-scatter to memory, barrier, all-gather put */
+    MSX_ALGO_2PR_HB = 5     /* two-phase ring over put/signal/wait hand-offs; count*elemsize must be a
+                               multiple of 16*nranks, no residual.  Partial sums travel in the element
+                               type (rounded at every hop) and chunk k is summed in the order k, k+1, ...,
+                               so results differ from the other algorithms in the last bits.  The first
+                               call of a new size (re)allocates the ring scratch and blocks. */
 } msx_algo;
 
 /* ------------------------------------------------------------------------------------
@@ -193,7 +198,7 @@ int msx_reset(void);
 int msx_finalize(void);
 
 /* Options (strings; numbers in decimal):
- *   "algo"            auto | 1pa_ll | 2pa_ll | 2pa_hb | 2pa_hb_2phase  (for the in-place forms)
+ *   "algo"            auto | 1pa_ll | 2pa_ll | 2pa_hb | 2pa_hb_2phase | 2pr_hb  (for the in-place forms)
  *   "ll_1pa_max_bytes", "ll_2pa_max_bytes"   size thresholds of the automatic choice
  *   "coll_algo"       auto | ll | hb   protocol of allgather / reducescatter (LL needs blocks that
  *                     are multiples of 8 bytes and fit the LL scratch; "ll" fails otherwise)

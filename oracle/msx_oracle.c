@@ -147,6 +147,38 @@ void orc_allreduce_residual_f32(const float *in, const float *res, float *out, i
     }
 }
 
+/* ---------- ring order (two-phase ring AllReduce, Collectives Library section, 2PR) ----------
+ * The buffer is cut into n equal chunks; chunk k starts at rank k and travels k -> k+1 -> ... ->
+ * k-1 (mod n); every rank on the way adds its own values in fp32 and passes the partial sum on
+ * in the element type, so the partial is rounded to that type at every hop.  The all-gather
+ * phase then copies the finished chunk to everybody.  count % n == 0.  out: [count]. */
+void orc_allreduce_ring_bf16(const uint16_t *in, uint16_t *out, int n, size_t count)
+{
+    size_t c = count / (size_t)n;
+    for (int k = 0; k < n; ++k)
+        for (size_t i = (size_t)k * c; i < (size_t)(k + 1) * c; ++i) {
+            uint16_t part = in[(size_t)k * count + i];
+            for (int h = 1; h < n; ++h) {
+                int r = (k + h) % n;
+                float acc = orc_bf16_to_f32(part) + orc_bf16_to_f32(in[(size_t)r * count + i]);
+                part = orc_f32_to_bf16(acc);
+            }
+            out[i] = part;
+        }
+}
+
+void orc_allreduce_ring_f32(const float *in, float *out, int n, size_t count)
+{
+    size_t c = count / (size_t)n;
+    for (int k = 0; k < n; ++k)
+        for (size_t i = (size_t)k * c; i < (size_t)(k + 1) * c; ++i) {
+            float part = in[(size_t)k * count + i];
+            for (int h = 1; h < n; ++h)
+                part = part + in[(size_t)((k + h) % n) * count + i];
+            out[i] = part;
+        }
+}
+
 /* ---------- ReduceScatter (sum): rank r receives the sum of everybody's share r ---------- */
 
 /* in: [n][count], count divisible by n.  out: [n][count/n]; row r = rank r's result. */

@@ -38,6 +38,10 @@ def lib():
         L.orc_allreduce_residual_bf16.restype = None
         L.orc_allreduce_residual_f32.argtypes = [vp, vp, vp, i32, sz]
         L.orc_allreduce_residual_f32.restype = None
+        L.orc_allreduce_ring_bf16.argtypes = [vp, vp, i32, sz]
+        L.orc_allreduce_ring_bf16.restype = None
+        L.orc_allreduce_ring_f32.argtypes = [vp, vp, i32, sz]
+        L.orc_allreduce_ring_f32.restype = None
         L.orc_reducescatter_f32.argtypes = [vp, vp, i32, sz]
         L.orc_reducescatter_f32.restype = None
         L.orc_reducescatter_bf16.argtypes = [vp, vp, i32, sz]
@@ -145,6 +149,23 @@ def allreduce_residual_f32(x, res):
     assert res.shape == (count,)
     out = np.empty(count, np.float32)
     lib().orc_allreduce_residual_f32(_p(x), _p(res), _p(out), n, count)
+    return out
+
+
+def allreduce_ring(x):
+    """Ring-order AllReduce (partial sums rounded to the element type at every hop).
+    x: [n, count] float32 or uint16 (bf16 bits), count % n == 0 -> [count]."""
+    x = np.ascontiguousarray(x)
+    n, count = x.shape
+    if count % n:
+        raise ValueError("count must be divisible by the number of ranks")
+    out = np.empty(count, x.dtype)
+    if x.dtype == np.float32:
+        lib().orc_allreduce_ring_f32(_p(x), _p(out), n, count)
+    elif x.dtype == np.uint16:
+        lib().orc_allreduce_ring_bf16(_p(x), _p(out), n, count)
+    else:
+        raise TypeError(x.dtype)
     return out
 
 

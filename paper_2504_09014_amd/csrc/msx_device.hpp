@@ -100,12 +100,15 @@ __device__ __forceinline__ bool sem_spin(const DevCtx& c, unsigned* sem, unsigne
 
 // One-directional hand-off helpers for a (sender rank -> receiver rank) channel.
 // Both are workgroup-collective: every thread of the workgroup must call them.
-__device__ __forceinline__ void channel_signal(const DevCtx& c, int me, int peer, int chan, unsigned site)
+// release = false is for puts made with write-through stores and drained by every wave
+// (st16_wt + put_drain): they are already visible device-wide when the workgroup barrier ends.
+__device__ __forceinline__ void channel_signal(const DevCtx& c, int me, int peer, int chan, unsigned site,
+                                               bool release = true)
 {
     __syncthreads();   // all threads' puts are issued and complete before the release below
     if (threadIdx.x == 0) {
         chaos_delay(c, site);
-        sem_signal(c.sem + (size_t)sem_index(peer, me, chan) * kSemStrideWords);
+        sem_signal(c.sem + (size_t)sem_index(peer, me, chan) * kSemStrideWords, release);
     }
 }
 

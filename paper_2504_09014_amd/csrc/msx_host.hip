@@ -52,6 +52,8 @@ struct Ctx {
     size_t moe_slots_bytes = 0;
     unsigned* moe_base = nullptr;
     int plan_T = -1, plan_n = 0;   // shape of the routing plan the last dispatch left behind
+    void* ring = nullptr;          // ring AllReduce: per-rank receive scratch, grown on demand
+    size_t ring_bytes = 0;
     unsigned* snap = nullptr;  // small device scratch for snapshots
     size_t ll_limit = 0;       // ll_max_bytes this context was sized for
     std::map<std::pair<const void*, int>, int> occ;   // (kernel, threads) -> resident blocks per CU
@@ -87,6 +89,7 @@ int destroy_ctx(Ctx* c)
     if (c->d.call_state) (void)hipFree(c->d.call_state);
     if (c->d.ll) (void)hipFree(c->d.ll);
     if (c->moe_slots) (void)hipFree(c->moe_slots);
+    if (c->ring) (void)hipFree(c->ring);
     if (c->moe_base) (void)hipFree(c->moe_base);
     if (c->snap) (void)hipFree(c->snap);
     delete c;
@@ -269,7 +272,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
 {
     int rc = check_common(dtype, op, nranks);
     if (rc) return rc;
-    if (algo < MSX_ALGO_AUTO || algo > MSX_ALGO_2PA_HB_2PHASE) return MSX_ERR_ARG;
+    if (algo < MSX_ALGO_AUTO || algo > MSX_ALGO_2PR_HB) return MSX_ERR_ARG;
     if ((rc = check_table(send, nranks))) return rc;
     if ((rc = check_table((const void* const*)recv, nranks))) return rc;
     if (residual && (rc = check_table(residual, nranks))) return rc;
@@ -317,6 +320,35 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
         a.res_shared = res_shared ? 1 : 0;
         note_launch(n * chans, threads, algo);
         return launch(k, n * chans, threads, stream, a, dev_ctx(c));
+    }
+
+    if (algo == MSX_ALGO_2PR_HB && n == 1) algo = MSX_ALGO_2PA_HB;
+    if (algo == MSX_ALGO_2PR_HB) {
+        // two-phase ring: n equal chunks of whole 16-byte vectors, no residual
+        if (residual) return MSX_ERR_UNSUPPORTED;
+        if (nbytes % (16 * (size_t)n)) return MSX_ERR_UNSUPPORTED;
+        const size_t need = nbytes * (size_t)n;
+        if (need > c->ring_bytes) {
+            HIPCHK(hipDeviceSynchronize());
+            if (c->ring) { HIPCHK(hipFree(c->ring)); c->ring = nullptr; c->ring_bytes = 0; }
+            if (hipMalloc(&c->ring, need) != hipSuccess) return MSX_ERR_NOMEM;
+            c->ring_bytes = need;
+        }
+        const void* kp = dtype == MSX_F32 ? (const void*)k_allreduce_ring<0> : (const void*)k_allreduce_ring<1>;
+        RingArgs a{};
+        for (int i = 0; i < n; ++i) {
+            a.in[i] = send[i];
+            a.out[i] = recv[i];
+            a.scratch[i] = (char*)c->ring + (size_t)i * nbytes;
+        }
+        a.chunk_vecs = nbytes / 16 / (size_t)n;
+        a.n = n;
+        int chans = 1;
+        if ((rc = pick_channels(c, kp, 256, n, a.chunk_vecs, 4, g_opt.hb_blocks, 64, &chans))) return rc;
+        a.chans = chans;
+        note_launch(n * chans, 256, algo);
+        typedef void (*K)(RingArgs, DevCtx);
+        return launch((K)kp, n * chans, 256, stream, a, dev_ctx(c));
     }
 
     // HB protocol.  Launch shape by size (from a sweep on MI355X): small messages want every
@@ -886,6 +918,7 @@ int msx_set_option(const char* key, const char* value)
         else if (v == "2pa_ll") g_opt.algo = MSX_ALGO_2PA_LL;
         else if (v == "2pa_hb") g_opt.algo = MSX_ALGO_2PA_HB;
         else if (v == "2pa_hb_2phase") g_opt.algo = MSX_ALGO_2PA_HB_2PHASE;
+        else if (v == "2pr_hb") g_opt.algo = MSX_ALGO_2PR_HB;
         else return MSX_ERR_ARG;
         return MSX_OK;
     }
@@ -970,7 +1003,7 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
     const std::string k(key);
     unsigned long long u = 0;
     if (k == "algo") {
-        static const char* names[] = {"auto", "1pa_ll", "2pa_ll", "2pa_hb", "2pa_hb_2phase"};
+        static const char* names[] = {"auto", "1pa_ll", "2pa_ll", "2pa_hb", "2pa_hb_2phase", "2pr_hb"};
         snprintf(value_out, value_len, "%s", names[g_opt.algo]);
         return MSX_OK;
     }

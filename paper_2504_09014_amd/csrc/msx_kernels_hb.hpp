@@ -359,4 +359,84 @@ __global__ __launch_bounds__(256) void k_alltoall_inplace(HbArgs a, DevCtx c, in
     if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 61, !vec, false);
 }
 
+// ---- two-phase ring (2PR) over the MemoryChannel ---------------------------------------------------
+// Collectives Library section, 2PR, and the overlapped ring reduce-scatter example of the DSL
+// section: n chunks travel around the ring; in the reduce-scatter phase a rank adds its own
+// values to the partial sum it received and passes it on (fused reduce-then-put, so the partial
+// never goes through local memory), in the all-gather phase it forwards finished chunks.  Every
+// hop is a real put -> signal || wait -> read hand-off: puts are write-through, the wait acquires.
+// The partial sum travels in the element type, i.e. it is rounded at every hop; chunk k is
+// summed in the order k, k+1, ..., k-1 (mod n).  The paper's version runs over the DMA engine
+// and splits chunks in halves to overlap copy and reduction; with thread copies the same
+// threads do both, so there is nothing to overlap and chunks are not split.  Inside one chip a
+// ring moves 5(n-1)/n S bytes per rank against 2 S for all-pairs: this path is for comparison.
+struct RingArgs {
+    const void* in[kMaxRanks];
+    void* out[kMaxRanks];
+    void* scratch[kMaxRanks];   // per rank: n chunks of partial sums received from the previous rank
+    size_t chunk_vecs;          // 16-byte vectors per chunk
+    int n;
+    int chans;
+};
+
+template <int DT>
+__global__ __launch_bounds__(256) void k_allreduce_ring(RingArgs a, DevCtx c)
+{
+    const int n = a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    if (rank == c.drop_rank) return;
+    const int next = rank + 1 == n ? 0 : rank + 1;
+    const int prev = rank == 0 ? n - 1 : rank - 1;
+    const size_t cv = a.chunk_vecs;
+    const size_t lo = cv * (size_t)chan / (size_t)a.chans, hi = cv * (size_t)(chan + 1) / (size_t)a.chans;
+    const size_t tid = threadIdx.x, bd = blockDim.x;
+
+    rank_barrier(c, rank, n, chan, 70, false, false);   // everybody is done with the previous call's scratch
+
+    // step 0: my own chunk starts its trip
+    for (size_t i = lo + tid; i < hi; i += bd) {
+        const size_t idx = (size_t)rank * cv + i;
+        st16_wt(a.scratch[next], idx, ld16(a.in[rank], idx));
+    }
+    put_drain();
+    channel_signal(c, rank, next, chan, 71, false);
+
+    // reduce-scatter: n-1 hops; the last one produces my finished chunk and starts the all-gather
+    for (int s = 0; s + 1 < n; ++s) {
+        int j = rank - 1 - s; if (j < 0) j += n;
+        const bool last = s + 2 == n;
+        channel_wait(c, rank, prev, chan, 72);
+        for (size_t i = lo + tid; i < hi; i += bd) {
+            const size_t idx = (size_t)j * cv + i;
+            VecAcc<DT> acc;
+            acc.set(ld16(a.scratch[rank], idx));
+            acc.add(ld16(a.in[rank], idx));
+            const u32x4 o = acc.pack();
+            if (last) {
+                st16(a.out[rank], idx, o);
+                st16_wt(a.out[next], idx, o);
+            } else {
+                st16_wt(a.scratch[next], idx, o);
+            }
+        }
+        put_drain();
+        channel_signal(c, rank, next, chan, 73, false);
+    }
+
+    // all-gather: n-1 chunks arrive from the previous rank; all but the last are passed on
+    for (int s = 0; s + 1 < n; ++s) {
+        int j = rank - s; if (j < 0) j += n;
+        channel_wait(c, rank, prev, chan, 74);
+        if (s + 2 < n) {
+            for (size_t i = lo + tid; i < hi; i += bd) {
+                const size_t idx = (size_t)j * cv + i;
+                st16_wt(a.out[next], idx, ld16(a.out[rank], idx));
+            }
+            put_drain();
+            channel_signal(c, rank, next, chan, 75, false);
+        }
+    }
+}
+
 }  // namespace msx

@@ -219,7 +219,7 @@ def test_dead_rank_times_out_and_context_recovers(msx, orc):
     msx.set_option("spin_limit", "2000")
     msx.set_option("drop_rank", "5")
     try:
-        for algo in ALGOS.values():
+        for algo in list(ALGOS.values()) + [5]:
             send = [x[r].clone().cuda() for r in range(8)]
             recv = [torch.empty_like(s) for s in send]
             msx.allreduce_ex(send, recv, None, algo=algo)
@@ -279,3 +279,51 @@ def test_calls_captured_in_a_hip_graph_replay_correctly(msx, orc):
         # eager calls between replays share the same device-side call state
         assert np.array_equal(_run_ex(msx, x, 2)[1], want)
         assert np.array_equal(_run_ex(msx, x, 1)[6], want)
+
+
+# ---------------------------------------------------------------- two-phase ring
+
+@pytest.mark.parametrize("n", [2, 3, 5, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_ring_allreduce_matches_ring_order_oracle(msx, orc, n, dtype):
+    esz = 4 if dtype == torch.float32 else 2
+    for vecs_per_chunk in [1, 3, 64, 1000, 16385]:
+        count = vecs_per_chunk * n * 16 // esz
+        if dtype == torch.float32:
+            g = torch.Generator().manual_seed(count)
+            x = torch.randn(n, count, generator=g) * torch.exp(torch.randn(n, count, generator=g) * 3)
+        else:
+            x = synth.normal(n, count, seed=count)
+        want = orc.allreduce_ring(_bits(x))
+        msx.set_option("chaos", str(3 + vecs_per_chunk))
+        for inplace in (False, True):
+            outs = _run_ex(msx, x, 5, inplace=inplace)
+            for r in range(n):
+                assert np.array_equal(outs[r].view(np.uint8), want.view(np.uint8)), (n, count, r, inplace)
+        msx.set_option("chaos", "0")
+        # and within the any-order tolerance of the fp64 sum (bf16: 2e-2 relative plus the spacing at
+        # the largest partial sum, which covers sums that nearly cancel)
+        if dtype == torch.bfloat16:
+            ref = np.sum(x.double().numpy(), axis=0)
+            got = orc.bf16_to_f32(outs[0]).astype(np.float64)
+            absmax = np.abs(x.double().numpy()).max(axis=0)
+            ulp = 2.0 ** (np.floor(np.log2(np.maximum(n * absmax, 2.0 ** -126))) - 7)
+            assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + n * ulp)
+
+
+def test_ring_allreduce_integers_equal_the_other_algorithms(msx, orc):
+    x = synth.int_valued_f32(8, 262144, seed=0)                 # config 1: every order is exact
+    want = orc.allreduce_f32(x.numpy())
+    for o in _run_ex(msx, x, 5):
+        assert np.array_equal(o, want)
+
+
+def test_ring_allreduce_refuses_unsupported_requests(msx):
+    send = [torch.zeros(100, dtype=torch.bfloat16, device="cuda") for _ in range(8)]     # 200 B: not 16*8-divisible
+    with pytest.raises(msx.MsxError) as e:
+        msx.allreduce_ex(send, send, None, algo=5)
+    assert e.value.code == -2
+    send = [torch.zeros(1024, dtype=torch.bfloat16, device="cuda") for _ in range(8)]
+    with pytest.raises(msx.MsxError) as e:
+        msx.allreduce_ex(send, send, send, algo=5)
+    assert e.value.code == -2

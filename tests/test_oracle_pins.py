@@ -214,6 +214,37 @@ def test_allreduce_bf16_bruteforce_fractions(orc, n, count):
         assert got == want, (i, got, want)
 
 
+# ---------------------------------------------------------------- ring order
+
+@pytest.mark.parametrize("n", [1, 2, 3, 8])
+def test_ring_order_allreduce(orc, n):
+    c = 37
+    count = n * c
+    # integers: any order is exact
+    xi = synth.int_valued_f32(n, count, seed=n).numpy()
+    assert np.array_equal(orc.allreduce_ring(xi), orc.allreduce_f32(xi))
+    # fp32: chunk k in ring order = rank-order sum of the ranks rotated so that rank k comes first
+    g = torch.Generator().manual_seed(n)
+    xf = (torch.randn(n, count, generator=g) * torch.exp(torch.randn(n, count, generator=g) * 4)).numpy()
+    ring = orc.allreduce_ring(xf)
+    for k in range(n):
+        rolled = np.ascontiguousarray(np.roll(xf, -k, axis=0))
+        assert np.array_equal(ring[k * c:(k + 1) * c], orc.allreduce_f32(rolled)[k * c:(k + 1) * c]), k
+    # bf16: the partial is rounded at every hop; replay with torch's own conversions
+    xb = synth.normal(n, count, seed=40 + n)
+    ring = orc.allreduce_ring(synth.bf16_bits(xb))
+    for k in range(n):
+        part = xb[k, k * c:(k + 1) * c]
+        for h in range(1, n):
+            part = (part.float() + xb[(k + h) % n, k * c:(k + 1) * c].float()).bfloat16()
+        assert np.array_equal(ring[k * c:(k + 1) * c], synth.bf16_bits(part)), k
+    # and stays within the any-order tolerance of the fp64 sum
+    ref = np.sum(xb.double().numpy(), axis=0)
+    got = orc.bf16_to_f32(ring).astype(np.float64)
+    absmax = np.abs(xb.double().numpy()).max(axis=0)
+    assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + n * _ulp_bf16(n * absmax))
+
+
 # ---------------------------------------------------------------- residual fusion
 
 def test_residual_zero_and_zero_input(orc):
