@@ -294,6 +294,28 @@ def main():
             torch.cuda.empty_cache()
         msx.check_status()
         extras["ring_vs_allpairs"] = ring
+        # the same algorithms run by the plan-interpreter kernel: overhead over the hand-written kernels
+        interp = {}
+        for kib in [64, 1024, 65536, 262144]:
+            c = kib * 1024 // 2
+            xs = synth.normal(n, c, seed=kib + 2, device="cuda")
+            s_ = [xs[r] for r in range(n)]
+            r_ = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            row = {}
+            for name, a in [("hand_2pa_us", msx.ALGO_2PA_HB), ("plan_2pa_us", msx.ALGO_PLAN_2PA_HB),
+                            ("hand_2pr_us", msx.ALGO_2PR_HB), ("plan_2pr_us", msx.ALGO_PLAN_2PR_HB)]:
+                fn = lambda: msx.allreduce_ex(s_, r_, None, algo=a)
+                if kib <= 1024:
+                    row[name] = round(graph_us(torch, fn, calls=20, replays=5), 2)
+                else:
+                    row[name] = round(median(time_calls(torch, fn, 10, 3)[1]), 1)
+            row["overhead_2pa_pct"] = round(100 * (row["plan_2pa_us"] / row["hand_2pa_us"] - 1), 1)
+            row["overhead_2pr_pct"] = round(100 * (row["plan_2pr_us"] / row["hand_2pr_us"] - 1), 1)
+            interp[f"{kib}KiB"] = row
+            del xs, s_, r_
+            torch.cuda.empty_cache()
+        msx.check_status()
+        extras["plan_interpreter_vs_hand_kernels"] = interp
         # standalone ReduceScatter / AllGather / AllToAll (HB protocol), 256 MiB rows
         other = {}
         c = 128 << 20                                   # elements per full row (256 MiB of bf16)

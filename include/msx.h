@@ -52,11 +52,15 @@ typedef enum {
     MSX_ALGO_2PA_LL = 2,    /* two-phase all-pairs over LL packets, rotating scratch */
     MSX_ALGO_2PA_HB = 3,    /* two-phase all-pairs, HB protocol, reduce and put fused in registers */
     MSX_ALGO_2PA_HB_2PHASE = 4, /* same, but reduce-scatter to memory, barrier, all-gather put */
-    MSX_ALGO_2PR_HB = 5     /* two-phase ring over put/signal/wait hand-offs; count*elemsize must be a
+    MSX_ALGO_2PR_HB = 5,    /* two-phase ring over put/signal/wait hand-offs; count*elemsize must be a
                                multiple of 16*nranks, no residual.  Partial sums travel in the element
                                type (rounded at every hop) and chunk k is summed in the order k, k+1, ...,
                                so results differ from the other algorithms in the last bits.  The first
                                call of a new size (re)allocates the ring scratch and blocks. */
+    MSX_ALGO_PLAN_2PA_HB = 6, /* MSX_ALGO_2PA_HB run by the generic plan-interpreter kernel (the paper's */
+    MSX_ALGO_PLAN_2PR_HB = 7  /* Executor): same results as the hand-written kernel; count*elemsize must be a
+                               multiple of 16*nranks, no residual; the first call of a shape lowers and uploads
+                               the plan (blocks). */
 } msx_algo;
 
 /* ------------------------------------------------------------------------------------
@@ -198,7 +202,8 @@ int msx_reset(void);
 int msx_finalize(void);
 
 /* Options (strings; numbers in decimal):
- *   "algo"            auto | 1pa_ll | 2pa_ll | 2pa_hb | 2pa_hb_2phase | 2pr_hb  (for the in-place forms)
+ *   "algo"            auto | 1pa_ll | 2pa_ll | 2pa_hb | 2pa_hb_2phase | 2pr_hb | plan_2pa_hb | plan_2pr_hb
+ *                     (for the in-place forms)
  *   "ll_1pa_max_bytes", "ll_2pa_max_bytes"   size thresholds of the automatic choice
  *   "coll_algo"       auto | ll | hb   protocol of allgather / reducescatter (LL needs blocks that
  *                     are multiples of 8 bytes and fit the LL scratch; "ll" fails otherwise)

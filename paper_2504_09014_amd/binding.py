@@ -9,7 +9,7 @@ import os
 import torch
 
 __all__ = [
-    "F32", "BF16", "SUM", "ALGO_AUTO", "ALGO_1PA_LL", "ALGO_2PA_LL", "ALGO_2PA_HB", "ALGO_2PA_HB_2PHASE", "ALGO_2PR_HB",
+    "F32", "BF16", "SUM", "ALGO_AUTO", "ALGO_1PA_LL", "ALGO_2PA_LL", "ALGO_2PA_HB", "ALGO_2PA_HB_2PHASE", "ALGO_2PR_HB", "ALGO_PLAN_2PA_HB", "ALGO_PLAN_2PR_HB",
     "MsxError", "lib", "lib_path", "init", "reset", "finalize", "set_option", "get_option", "status",
     "check_status", "last_launch", "version", "strerror",
     "allreduce", "reducescatter", "allgather", "alltoall",
@@ -21,6 +21,7 @@ __all__ = [
 F32, BF16 = 0, 1
 SUM = 0
 ALGO_AUTO, ALGO_1PA_LL, ALGO_2PA_LL, ALGO_2PA_HB, ALGO_2PA_HB_2PHASE, ALGO_2PR_HB = 0, 1, 2, 3, 4, 5
+ALGO_PLAN_2PA_HB, ALGO_PLAN_2PR_HB = 6, 7
 
 EXPORTS = [
     "msx_allreduce", "msx_reducescatter", "msx_allgather", "msx_alltoall",

@@ -12,11 +12,13 @@
 #include <mutex>
 #include <string>
 #include <utility>
+#include <vector>
 
 #include "msx_device.hpp"
 #include "msx_kernels_hb.hpp"
 #include "msx_kernels_ll.hpp"
 #include "msx_kernels_moe.hpp"
+#include "msx_kernels_plan.hpp"
 #include "msx_kernels_prim.hpp"
 
 using namespace msx;
@@ -54,6 +56,8 @@ struct Ctx {
     int plan_T = -1, plan_n = 0;   // shape of the routing plan the last dispatch left behind
     void* ring = nullptr;          // ring AllReduce: per-rank receive scratch, grown on demand
     size_t ring_bytes = 0;
+    struct Plan { int algo, n, chans; size_t nbytes; PlanOp* ops; unsigned* start; };
+    std::vector<Plan> plans;       // lowered execution plans, kept on the device
     unsigned* snap = nullptr;  // small device scratch for snapshots
     size_t ll_limit = 0;       // ll_max_bytes this context was sized for
     std::map<std::pair<const void*, int>, int> occ;   // (kernel, threads) -> resident blocks per CU
@@ -90,6 +94,7 @@ int destroy_ctx(Ctx* c)
     if (c->d.ll) (void)hipFree(c->d.ll);
     if (c->moe_slots) (void)hipFree(c->moe_slots);
     if (c->ring) (void)hipFree(c->ring);
+    for (auto& p : c->plans) { (void)hipFree(p.ops); (void)hipFree(p.start); }
     if (c->moe_base) (void)hipFree(c->moe_base);
     if (c->snap) (void)hipFree(c->snap);
     delete c;
@@ -267,12 +272,142 @@ int ll_block_threads(size_t work)
     return (int)t;
 }
 
+
+// ---- lowering of an AllReduce to an execution plan (the host half of the Executor analogue) ------------
+
+PlanOp plan_op(int code, int peer = 0, int flags = 0)
+{
+    PlanOp o{};
+    o.code = code;
+    o.peer = peer;
+    o.flags = flags;
+    return o;
+}
+
+PlanOp plan_reduce_put(std::vector<PlanRef> src, std::vector<PlanRef> dst, int dst_wt, size_t first, size_t end,
+                       size_t step)
+{
+    PlanOp o{};
+    o.code = kOpReducePut;
+    o.nsrc = (int)src.size();
+    o.ndst = (int)dst.size();
+    for (size_t k = 0; k < src.size(); ++k) o.src[k] = src[k];
+    for (size_t k = 0; k < dst.size(); ++k) o.dst[k] = dst[k];
+    o.dst_wt = dst_wt;
+    o.first = first;
+    o.end = end;
+    o.step = step;
+    return o;
+}
+
+// Same steps as k_allreduce_hb_fused / k_allreduce_ring, written as data.  nvec = 16-byte vectors per rank.
+void lower_allreduce(int algo, int n, int chans, size_t nvec, int threads, std::vector<PlanOp>* ops,
+                     std::vector<unsigned>* start)
+{
+    start->assign((size_t)n * chans, 0);
+    const size_t cv = nvec / (size_t)n;
+    for (int b = 0; b < n * chans; ++b) {
+        const int rank = b % n, chan = b / n;
+        (*start)[b] = (unsigned)ops->size();
+        const short r = (short)rank;
+        if (algo == MSX_ALGO_PLAN_2PA_HB) {
+            std::vector<PlanRef> src, dst;
+            for (short j = 0; j < n; ++j) { src.push_back({kBufIn, j}); dst.push_back({kBufOut, j}); }
+            ops->push_back(plan_op(kOpBarrier));
+            ops->push_back(plan_reduce_put(src, dst, (1 << n) - 1, (size_t)rank * cv + (size_t)chan * threads,
+                                           (size_t)(rank + 1) * cv, (size_t)chans * threads));
+            ops->push_back(plan_op(kOpDrain));
+            ops->push_back(plan_op(kOpBarrier));
+        } else {
+            const short next = (short)((rank + 1) % n), prev = (short)((rank + n - 1) % n);
+            const size_t lo = cv * (size_t)chan / (size_t)chans, hi = cv * (size_t)(chan + 1) / (size_t)chans;
+            auto range = [&](int chunk, std::vector<PlanRef> s, std::vector<PlanRef> d, int wt) {
+                return plan_reduce_put(s, d, wt, (size_t)chunk * cv + lo, (size_t)chunk * cv + hi, (size_t)threads);
+            };
+            ops->push_back(plan_op(kOpBarrier));
+            ops->push_back(range(rank, {{kBufIn, r}}, {{kBufScratch, next}}, 1));
+            ops->push_back(plan_op(kOpDrain));
+            ops->push_back(plan_op(kOpSignal, next));
+            for (int s = 0; s + 1 < n; ++s) {
+                const int j = (rank - 1 - s + 2 * n) % n;
+                ops->push_back(plan_op(kOpWait, prev, 2));
+                if (s + 2 == n) ops->push_back(range(j, {{kBufScratch, r}, {kBufIn, r}}, {{kBufOut, r}, {kBufOut, next}}, 2));
+                else ops->push_back(range(j, {{kBufScratch, r}, {kBufIn, r}}, {{kBufScratch, next}}, 1));
+                ops->push_back(plan_op(kOpDrain));
+                ops->push_back(plan_op(kOpSignal, next));
+            }
+            for (int s = 0; s + 1 < n; ++s) {
+                const int j = (rank - s + n) % n;
+                ops->push_back(plan_op(kOpWait, prev, 2));
+                if (s + 2 < n) {
+                    ops->push_back(range(j, {{kBufOut, r}}, {{kBufOut, next}}, 1));
+                    ops->push_back(plan_op(kOpDrain));
+                    ops->push_back(plan_op(kOpSignal, next));
+                }
+            }
+        }
+        ops->push_back(plan_op(kOpEnd));
+    }
+}
+
+int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nbytes, int dtype, int n, int algo,
+                   hipStream_t stream)
+{
+    if (nbytes % (16 * (size_t)n)) return MSX_ERR_UNSUPPORTED;
+    const size_t nvec = nbytes / 16;
+    const void* kp = dtype == MSX_F32 ? (const void*)k_plan_executor<0> : (const void*)k_plan_executor<1>;
+    const int threads = 256;
+    int chans = 1, rc;
+    const bool ring = algo == MSX_ALGO_PLAN_2PR_HB;
+    int want = g_opt.hb_blocks;
+    const size_t per_rank = nvec / (size_t)n;
+    if (want == 0 && !ring) want = per_rank <= 32768 ? (int)((per_rank + 511) / 512) : per_rank <= 262144 ? 32 : 128;
+    if (want == 0 && !ring && want < 1) want = 1;
+    if ((rc = pick_channels(c, kp, threads, n, per_rank, 4, want, ring ? 64 : kMaxChannels, &chans))) return rc;
+    if (ring) {
+        const size_t need = nbytes * (size_t)n;
+        if (need > c->ring_bytes) {
+            HIPCHK(hipDeviceSynchronize());
+            if (c->ring) { HIPCHK(hipFree(c->ring)); c->ring = nullptr; c->ring_bytes = 0; }
+            if (hipMalloc(&c->ring, need) != hipSuccess) return MSX_ERR_NOMEM;
+            c->ring_bytes = need;
+        }
+    }
+    const Ctx::Plan* plan = nullptr;
+    for (const auto& p : c->plans)
+        if (p.algo == algo && p.n == n && p.chans == chans && p.nbytes == nbytes) plan = &p;
+    if (!plan) {
+        std::vector<PlanOp> ops;
+        std::vector<unsigned> start;
+        lower_allreduce(algo, n, chans, nvec, threads, &ops, &start);
+        Ctx::Plan p{algo, n, chans, nbytes, nullptr, nullptr};
+        if (hipMalloc((void**)&p.ops, ops.size() * sizeof(PlanOp)) != hipSuccess) return MSX_ERR_NOMEM;
+        if (hipMalloc((void**)&p.start, start.size() * sizeof(unsigned)) != hipSuccess) { (void)hipFree(p.ops); return MSX_ERR_NOMEM; }
+        HIPCHK(hipMemcpy(p.ops, ops.data(), ops.size() * sizeof(PlanOp), hipMemcpyHostToDevice));
+        HIPCHK(hipMemcpy(p.start, start.data(), start.size() * sizeof(unsigned), hipMemcpyHostToDevice));
+        c->plans.push_back(p);
+        plan = &c->plans.back();
+    }
+    PlanArgs a{};
+    for (int i = 0; i < n; ++i) {
+        a.in[i] = send[i];
+        a.out[i] = recv[i];
+        a.scratch[i] = ring ? (void*)((char*)c->ring + (size_t)i * nbytes) : nullptr;
+    }
+    a.ops = plan->ops;
+    a.start = plan->start;
+    a.n = n;
+    note_launch(n * chans, threads, algo);
+    typedef void (*K)(PlanArgs, DevCtx);
+    return launch((K)kp, n * chans, threads, stream, a, dev_ctx(c));
+}
+
 int allreduce_impl(const void* const* send, void* const* recv, const void* const* residual, size_t count,
                    int dtype, int op, int nranks, int algo, hipStream_t stream)
 {
     int rc = check_common(dtype, op, nranks);
     if (rc) return rc;
-    if (algo < MSX_ALGO_AUTO || algo > MSX_ALGO_2PR_HB) return MSX_ERR_ARG;
+    if (algo < MSX_ALGO_AUTO || algo > MSX_ALGO_PLAN_2PR_HB) return MSX_ERR_ARG;
     if ((rc = check_table(send, nranks))) return rc;
     if ((rc = check_table((const void* const*)recv, nranks))) return rc;
     if (residual && (rc = check_table(residual, nranks))) return rc;
@@ -322,6 +457,11 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
         return launch(k, n * chans, threads, stream, a, dev_ctx(c));
     }
 
+    if ((algo == MSX_ALGO_PLAN_2PA_HB || algo == MSX_ALGO_PLAN_2PR_HB) && n > 1) {
+        if (residual) return MSX_ERR_UNSUPPORTED;
+        return plan_allreduce(c, send, recv, nbytes, dtype, n, algo, stream);
+    }
+    if (algo == MSX_ALGO_PLAN_2PA_HB || algo == MSX_ALGO_PLAN_2PR_HB) algo = MSX_ALGO_2PA_HB;
     if (algo == MSX_ALGO_2PR_HB && n == 1) algo = MSX_ALGO_2PA_HB;
     if (algo == MSX_ALGO_2PR_HB) {
         // two-phase ring: n equal chunks of whole 16-byte vectors, no residual
@@ -919,6 +1059,8 @@ int msx_set_option(const char* key, const char* value)
         else if (v == "2pa_hb") g_opt.algo = MSX_ALGO_2PA_HB;
         else if (v == "2pa_hb_2phase") g_opt.algo = MSX_ALGO_2PA_HB_2PHASE;
         else if (v == "2pr_hb") g_opt.algo = MSX_ALGO_2PR_HB;
+        else if (v == "plan_2pa_hb") g_opt.algo = MSX_ALGO_PLAN_2PA_HB;
+        else if (v == "plan_2pr_hb") g_opt.algo = MSX_ALGO_PLAN_2PR_HB;
         else return MSX_ERR_ARG;
         return MSX_OK;
     }
@@ -1003,7 +1145,8 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
     const std::string k(key);
     unsigned long long u = 0;
     if (k == "algo") {
-        static const char* names[] = {"auto", "1pa_ll", "2pa_ll", "2pa_hb", "2pa_hb_2phase", "2pr_hb"};
+        static const char* names[] = {"auto", "1pa_ll", "2pa_ll", "2pa_hb", "2pa_hb_2phase", "2pr_hb",
+                                      "plan_2pa_hb", "plan_2pr_hb"};
         snprintf(value_out, value_len, "%s", names[g_opt.algo]);
         return MSX_OK;
     }

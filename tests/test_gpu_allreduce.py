@@ -327,3 +327,47 @@ def test_ring_allreduce_refuses_unsupported_requests(msx):
     with pytest.raises(msx.MsxError) as e:
         msx.allreduce_ex(send, send, send, algo=5)
     assert e.value.code == -2
+
+
+# ---------------------------------------------------------------- plan interpreter
+
+@pytest.mark.parametrize("n", [2, 3, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_plan_interpreter_runs_the_same_algorithms(msx, orc, n, dtype):
+    esz = 4 if dtype == torch.float32 else 2
+    for vecs_per_chunk in [1, 5, 64, 1000, 16385, 70001]:
+        count = vecs_per_chunk * n * 16 // esz
+        x = synth.int_valued_f32(n, count, seed=count) if dtype == torch.float32 else synth.normal(n, count, seed=count)
+        want_pairs = _oracle(orc, x)
+        want_ring = orc.allreduce_ring(_bits(x))
+        msx.set_option("chaos", str(1 + vecs_per_chunk))
+        for inplace in (False, True):
+            for r, o in enumerate(_run_ex(msx, x, 6, inplace=inplace)):
+                assert np.array_equal(o.view(np.uint8), want_pairs.view(np.uint8)), ("pairs", n, count, r, inplace)
+            for r, o in enumerate(_run_ex(msx, x, 7, inplace=inplace)):
+                assert np.array_equal(o.view(np.uint8), want_ring.view(np.uint8)), ("ring", n, count, r, inplace)
+        msx.set_option("chaos", "0")
+
+
+def test_plan_interpreter_argument_checks_and_dead_rank(msx, orc):
+    send = [torch.zeros(100, dtype=torch.bfloat16, device="cuda") for _ in range(8)]
+    for algo in (6, 7):
+        with pytest.raises(msx.MsxError) as e:
+            msx.allreduce_ex(send, send, None, algo=algo)
+        assert e.value.code == -2
+    x = synth.normal(8, 4096, seed=10)
+    msx.set_option("spin_limit", "2000")
+    msx.set_option("drop_rank", "2")
+    try:
+        for algo in (6, 7):
+            s_ = [x[r].clone().cuda() for r in range(8)]
+            r_ = [torch.empty_like(t) for t in s_]
+            msx.allreduce_ex(s_, r_, None, algo=algo)
+            rc, info = msx.status()
+            assert rc == -4, (algo, info)
+            msx.reset()
+    finally:
+        msx.set_option("drop_rank", "-1")
+        msx.set_option("spin_limit", str(1 << 20))
+        msx.reset()
+    assert np.array_equal(_run_ex(msx, x, 6)[0], _oracle(orc, x))
