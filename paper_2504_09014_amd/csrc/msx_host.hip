@@ -304,7 +304,7 @@ PlanOp plan_reduce_put(std::vector<PlanRef> src, std::vector<PlanRef> dst, int d
 void lower_allreduce(int algo, int n, int chans, size_t nvec, int threads, std::vector<PlanOp>* ops,
                      std::vector<unsigned>* start)
 {
-    start->assign((size_t)n * chans, 0);
+    start->assign((size_t)n * chans, 0);   // one more entry (the total) is appended at the end
     const size_t cv = nvec / (size_t)n;
     for (int b = 0; b < n * chans; ++b) {
         const int rank = b % n, chan = b / n;
@@ -348,6 +348,7 @@ void lower_allreduce(int algo, int n, int chans, size_t nvec, int threads, std::
         }
         ops->push_back(plan_op(kOpEnd));
     }
+    start->push_back((unsigned)ops->size());
 }
 
 int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nbytes, int dtype, int n, int algo,

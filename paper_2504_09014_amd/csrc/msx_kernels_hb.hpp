@@ -407,17 +407,23 @@ __global__ __launch_bounds__(256) void k_allreduce_ring(RingArgs a, DevCtx c)
         int j = rank - 1 - s; if (j < 0) j += n;
         const bool last = s + 2 == n;
         channel_wait(c, rank, prev, chan, 72);
-        for (size_t i = lo + tid; i < hi; i += bd) {
-            const size_t idx = (size_t)j * cv + i;
-            VecAcc<DT> acc;
-            acc.set(ld16(a.scratch[rank], idx));
-            acc.add(ld16(a.in[rank], idx));
-            const u32x4 o = acc.pack();
+        for (size_t i = lo + tid; i < hi; i += 2 * bd) {       // two vectors per thread in flight
+            const size_t idx = (size_t)j * cv + i, idx1 = idx + bd;
+            const bool two = i + bd < hi;
+            const u32x4 p0 = ld16(a.scratch[rank], idx), m0 = ld16(a.in[rank], idx);
+            u32x4 p1 = p0, m1 = m0;
+            if (two) { p1 = ld16(a.scratch[rank], idx1); m1 = ld16(a.in[rank], idx1); }
+            VecAcc<DT> a0, a1;
+            a0.set(p0); a0.add(m0);
+            a1.set(p1); a1.add(m1);
+            const u32x4 o0 = a0.pack(), o1 = a1.pack();
             if (last) {
-                st16(a.out[rank], idx, o);
-                st16_wt(a.out[next], idx, o);
+                st16(a.out[rank], idx, o0);
+                st16_wt(a.out[next], idx, o0);
+                if (two) { st16(a.out[rank], idx1, o1); st16_wt(a.out[next], idx1, o1); }
             } else {
-                st16_wt(a.scratch[next], idx, o);
+                st16_wt(a.scratch[next], idx, o0);
+                if (two) st16_wt(a.scratch[next], idx1, o1);
             }
         }
         put_drain();
