@@ -232,6 +232,17 @@ int msx_status(void* stream, uint32_t info[6]);
  * (for profiles): grid blocks, block threads, algorithm chosen. */
 int msx_last_launch(int* grid, int* block, int* algo);
 
+/* Host logic on its own (no device is touched; usable on a machine without a GPU).
+ * msx_debug_choose: what the automatic choice would run for `nbytes` per rank given an LL scratch
+ * sized for ll_limit bytes, and the HB launch shape (unroll, wanted workgroups per rank).
+ * msx_debug_lower_plan: the execution plan the interpreter algorithms run.  ops_out receives
+ * 128-byte records {int code, peer, flags, nsrc, ndst; {int16 kind, rank} src[9], dst[8]; int dst_wt;
+ * uint64 first, end, step} (see csrc/msx_kernels_plan.hpp), start_out the nranks*blocks_per_rank+1
+ * list offsets.  With ops_out == NULL only *ops_written is set. */
+int msx_debug_choose(size_t nbytes, int nranks, size_t ll_limit, int* algo, int* unroll, int* want_blocks);
+int msx_debug_lower_plan(int algo, int nranks, int blocks_per_rank, size_t vectors_per_rank, int threads,
+                         void* ops_out, size_t ops_capacity, uint32_t* start_out, size_t* ops_written);
+
 int msx_last_hip_error(void);
 const char* msx_strerror(int err);
 const char* msx_version(void);

@@ -31,6 +31,7 @@ EXPORTS = [
     "msx_prim_ll_roundtrip",
     "msx_init", "msx_reset", "msx_finalize", "msx_set_option", "msx_get_option", "msx_status",
     "msx_last_launch", "msx_last_hip_error", "msx_strerror", "msx_version",
+    "msx_debug_choose", "msx_debug_lower_plan",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -79,6 +80,8 @@ def lib():
         L.msx_get_option.argtypes = [C.c_char_p, C.c_char_p, sz]
         L.msx_status.argtypes = [vp, C.POINTER(u32)]
         L.msx_last_launch.argtypes = [C.POINTER(i), C.POINTER(i), C.POINTER(i)]
+        L.msx_debug_choose.argtypes = [sz, i, sz, C.POINTER(i), C.POINTER(i), C.POINTER(i)]
+        L.msx_debug_lower_plan.argtypes = [i, i, i, sz, i, vp, sz, C.POINTER(u32), C.POINTER(sz)]
         L.msx_strerror.argtypes = [i]
         L.msx_strerror.restype = C.c_char_p
         L.msx_version.restype = C.c_char_p

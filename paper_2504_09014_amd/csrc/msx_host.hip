@@ -273,6 +273,35 @@ int ll_block_threads(size_t work)
 }
 
 
+// ---- host-side choices (pure functions of sizes and options; no device needed) -------------------------
+
+// which algorithm the automatic choice runs for nbytes per rank; ll_limit = what the LL scratch holds
+int choose_algo(size_t nbytes, int n, size_t ll_limit)
+{
+    if (n == 1) return MSX_ALGO_2PA_HB;
+    if (nbytes <= g_opt.ll_1pa_max && nbytes <= ll_limit / 4) return MSX_ALGO_1PA_LL;
+    if (nbytes <= g_opt.ll_2pa_max && nbytes <= ll_limit) return MSX_ALGO_2PA_LL;
+    return MSX_ALGO_2PA_HB;
+}
+
+// launch shape of the HB AllReduce kernels: unroll and wanted workgroups per rank (before the
+// co-residency clamp).  Small messages: every thread issues all its loads at once, one pass;
+// large ones: many plain workgroups.
+void choose_hb_shape(size_t nbytes, int n, int threads, int* unroll, int* want)
+{
+    const size_t per_rank = (nbytes / 16 + (size_t)n - 1) / (size_t)n;
+    int U = g_opt.hb_unroll, w = g_opt.hb_blocks;
+    if (U == 0) U = per_rank <= 32768 ? 2 : 1;
+    if (w == 0) {
+        if (per_rank <= 32768) w = (int)((per_rank + (size_t)threads * U - 1) / ((size_t)threads * U));
+        else if (per_rank <= 262144) w = 32;   // up to 4 MiB of chunk per rank
+        else w = 128;
+        if (w < 1) w = 1;
+    }
+    *unroll = U;
+    *want = w;
+}
+
 // ---- lowering of an AllReduce to an execution plan (the host half of the Executor analogue) ------------
 
 PlanOp plan_op(int code, int peer = 0, int flags = 0)
@@ -360,10 +389,9 @@ int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nb
     const int threads = 256;
     int chans = 1, rc;
     const bool ring = algo == MSX_ALGO_PLAN_2PR_HB;
-    int want = g_opt.hb_blocks;
+    int want = g_opt.hb_blocks, unroll_unused = 1;
     const size_t per_rank = nvec / (size_t)n;
-    if (want == 0 && !ring) want = per_rank <= 32768 ? (int)((per_rank + 511) / 512) : per_rank <= 262144 ? 32 : 128;
-    if (want == 0 && !ring && want < 1) want = 1;
+    if (!ring) choose_hb_shape(nbytes, n, threads, &unroll_unused, &want);   // same shape as the hand kernel
     if ((rc = pick_channels(c, kp, threads, n, per_rank, 4, want, ring ? 64 : kMaxChannels, &chans))) return rc;
     if (ring) {
         const size_t need = nbytes * (size_t)n;
@@ -425,13 +453,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
         for (int i = 1; i < n; ++i) res_shared = res_shared && residual[i] == residual[0];
 
     if (algo == MSX_ALGO_AUTO) algo = g_opt.algo;
-    if (algo == MSX_ALGO_AUTO) {
-        const size_t cap1 = c->ll_limit / 4, cap2 = c->ll_limit;
-        if (n == 1) algo = MSX_ALGO_2PA_HB;
-        else if (nbytes <= g_opt.ll_1pa_max && nbytes <= cap1) algo = MSX_ALGO_1PA_LL;
-        else if (nbytes <= g_opt.ll_2pa_max && nbytes <= cap2) algo = MSX_ALGO_2PA_LL;
-        else algo = MSX_ALGO_2PA_HB;
-    }
+    if (algo == MSX_ALGO_AUTO) algo = choose_algo(nbytes, n, c->ll_limit);
 
     if (algo == MSX_ALGO_1PA_LL || algo == MSX_ALGO_2PA_LL) {
         const size_t P = (nbytes + 7) / 8;
@@ -499,16 +521,9 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     const int threads = 256;
     const size_t vecs = nbytes / 16;
     const size_t per_rank = (vecs + (size_t)n - 1) / (size_t)n;
-    int U = g_opt.hb_unroll;
-    int want = g_opt.hb_blocks;
-    if (U == 0) U = per_rank <= 32768 ? 2 : 1;
+    int U = 1, want = 1;
+    choose_hb_shape(nbytes, n, threads, &U, &want);
     if (algo == MSX_ALGO_2PA_HB_2PHASE && U > 2) U = 2;
-    if (want == 0) {
-        if (per_rank <= 32768) want = (int)((per_rank + (size_t)threads * U - 1) / ((size_t)threads * U));
-        else if (per_rank <= 262144) want = 32;   // up to 4 MiB of chunk per rank
-        else want = 128;
-        if (want < 1) want = 1;
-    }
     HbKernel k = algo == MSX_ALGO_2PA_HB ? hb_fused_kernel(dtype, U, n, !residual ? 0 : res_shared ? 1 : 2)
                                          : hb_2phase_kernel(dtype, U, n);
     int chans = 1;
@@ -1203,6 +1218,33 @@ int msx_status(void* stream, uint32_t info[6])
         for (int i = 0; i < 6; ++i) info[i] = h[i];
     if (h[0] == kStatusTimeout) return MSX_ERR_TIMEOUT;
     if (h[0] == kStatusCapacity) return MSX_ERR_CAPACITY;
+    return MSX_OK;
+}
+
+int msx_debug_choose(size_t nbytes, int nranks, size_t ll_limit, int* algo, int* unroll, int* want_blocks)
+{
+    if (nranks < 1 || nranks > kMaxRanks || !algo || !unroll || !want_blocks) return MSX_ERR_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    *algo = g_opt.algo != MSX_ALGO_AUTO ? g_opt.algo : choose_algo(nbytes, nranks, ll_limit);
+    choose_hb_shape(nbytes, nranks, 256, unroll, want_blocks);
+    return MSX_OK;
+}
+
+int msx_debug_lower_plan(int algo, int nranks, int blocks_per_rank, size_t vectors_per_rank, int threads,
+                         void* ops_out, size_t ops_capacity, uint32_t* start_out, size_t* ops_written)
+{
+    if ((algo != MSX_ALGO_PLAN_2PA_HB && algo != MSX_ALGO_PLAN_2PR_HB) || nranks < 2 || nranks > kMaxRanks ||
+        blocks_per_rank < 1 || blocks_per_rank > kMaxChannels || threads < 1 || !ops_written ||
+        vectors_per_rank % (size_t)nranks)
+        return MSX_ERR_ARG;
+    std::vector<PlanOp> ops;
+    std::vector<unsigned> start;
+    lower_allreduce(algo, nranks, blocks_per_rank, vectors_per_rank, threads, &ops, &start);
+    *ops_written = ops.size();
+    if (!ops_out || !start_out) return MSX_OK;           // size query
+    if (ops.size() > ops_capacity) return MSX_ERR_NOMEM;
+    memcpy(ops_out, ops.data(), ops.size() * sizeof(PlanOp));
+    memcpy(start_out, start.data(), start.size() * sizeof(unsigned));
     return MSX_OK;
 }
 

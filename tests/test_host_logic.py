@@ -1,0 +1,197 @@
+"""CPU tests of the library's host logic (no device is touched): the automatic algorithm choice,
+the launch shapes, and the lowering of AllReduce to execution plans.  A lowered plan is RUN here
+by a small sequential simulator over numpy buffers (one float per 16-byte vector), with a
+scheduler that advances workgroups until they block, so the test also shows that the plan cannot
+deadlock and that every wait is matched by exactly one signal."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+
+class PlanRef(C.Structure):
+    _fields_ = [("kind", C.c_int16), ("rank", C.c_int16)]
+
+
+class PlanOp(C.Structure):
+    _fields_ = [("code", C.c_int), ("peer", C.c_int), ("flags", C.c_int), ("nsrc", C.c_int), ("ndst", C.c_int),
+                ("src", PlanRef * 9), ("dst", PlanRef * 8), ("dst_wt", C.c_int),
+                ("first", C.c_uint64), ("end", C.c_uint64), ("step", C.c_uint64), ("_pad", C.c_uint64)]
+
+
+END, BARRIER, SIGNAL, WAIT, REDUCE_PUT, DRAIN = range(6)
+IN, OUT, SCRATCH = range(3)
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2504_09014_amd as msx
+    return msx.lib()
+
+
+def lower(L, algo, n, chans, vecs_per_rank, threads):
+    written = C.c_size_t(0)
+    assert L.msx_debug_lower_plan(algo, n, chans, vecs_per_rank, threads, None, 0, None, C.byref(written)) == 0
+    ops = (PlanOp * written.value)()
+    start = (C.c_uint32 * (n * chans + 1))()
+    assert C.sizeof(PlanOp) == 128
+    assert L.msx_debug_lower_plan(algo, n, chans, vecs_per_rank, threads, ops, written.value, start,
+                                  C.byref(written)) == 0
+    return ops, list(start)
+
+
+def simulate(ops, start, n, chans, threads, x, ring_order_rounding=None):
+    """x: [n, V] float64 'vectors'.  Returns out [n, V].  Each workgroup runs until it blocks."""
+    V = x.shape[1]
+    bufs = {IN: x.copy(), OUT: np.full((n, V), np.nan), SCRATCH: np.full((n, V), np.nan)}
+    sem = np.zeros((n, n, chans), np.int64)          # [recv][send][chan]
+    expected = np.zeros((n, n, chans), np.int64)
+    pc = [start[b] for b in range(n * chans)]
+    barrier_phase = [0] * (n * chans)                # 0: must signal, 1: waiting
+    done = [False] * (n * chans)
+    touched = np.zeros((3, n, V), np.int32)
+
+    def step(b):
+        """run workgroup b until it blocks or ends; return True if it made progress"""
+        rank, chan = b % n, b // n
+        progressed = False
+        while True:
+            op = ops[pc[b]]
+            if op.code == END:
+                done[b] = True
+                return True
+            if op.code == BARRIER:
+                if barrier_phase[b] == 0:
+                    for p in range(n):
+                        if p != rank:
+                            sem[p, rank, chan] += 1
+                    barrier_phase[b] = 1
+                    progressed = True
+                ok = all(sem[rank, p, chan] >= expected[rank, p, chan] + 1 for p in range(n) if p != rank)
+                if not ok:
+                    return progressed
+                for p in range(n):
+                    if p != rank:
+                        expected[rank, p, chan] += 1
+                barrier_phase[b] = 0
+            elif op.code == SIGNAL:
+                sem[op.peer, rank, chan] += 1
+            elif op.code == WAIT:
+                if sem[rank, op.peer, chan] < expected[rank, op.peer, chan] + 1:
+                    return progressed
+                expected[rank, op.peer, chan] += 1
+            elif op.code == REDUCE_PUT:
+                idx = np.concatenate([np.arange(op.first + t, op.end, op.step) for t in range(threads)]) \
+                    if op.first < op.end else np.zeros(0, np.int64)
+                idx = idx.astype(np.int64)
+                acc = bufs[op.src[0].kind][op.src[0].rank, idx].copy()
+                for k in range(1, op.nsrc):
+                    acc = acc + bufs[op.src[k].kind][op.src[k].rank, idx]
+                    if ring_order_rounding is not None:
+                        acc = ring_order_rounding(acc)
+                assert not np.any(np.isnan(acc)), "read of a vector nobody has written"
+                for k in range(op.ndst):
+                    d = op.dst[k]
+                    bufs[d.kind][d.rank, idx] = acc
+                    touched[d.kind, d.rank, idx] += 1
+                    # data another rank will read must be written through (no fence follows)
+                    if d.rank != rank:
+                        assert op.dst_wt & (1 << k), "remote destination written with an ordinary store"
+            elif op.code == DRAIN:
+                pass
+            else:
+                raise AssertionError(f"unknown op {op.code}")
+            pc[b] += 1
+            progressed = True
+
+    for _ in range(100000):
+        if all(done):
+            break
+        any_progress = False
+        for b in np.random.default_rng(len(ops)).permutation(n * chans):   # scrambled, deterministic order
+            if not done[b]:
+                any_progress |= step(int(b))
+        assert any_progress, "the plan deadlocks"
+    assert all(done)
+    # every signal was consumed by exactly one wait
+    off = ~np.eye(n, dtype=bool)
+    assert np.array_equal(sem[off], expected[off])
+    return bufs[OUT], touched
+
+
+@pytest.mark.parametrize("n", [2, 3, 8])
+@pytest.mark.parametrize("chans,threads,cv", [(1, 4, 1), (3, 4, 7), (2, 8, 64), (5, 16, 333)])
+def test_lowered_all_pairs_plan_computes_the_allreduce(L, n, chans, threads, cv):
+    V = cv * n
+    ops, start = lower(L, 6, n, chans, V, threads)
+    rng = np.random.default_rng(V)
+    x = rng.integers(-1000, 1001, (n, V)).astype(np.float64)
+    out, touched = simulate(ops, start, n, chans, threads, x)
+    assert np.array_equal(out, np.tile(x.sum(0), (n, 1)))
+    assert np.all(touched[OUT] == 1)                              # every output vector is written exactly once
+    assert np.all(touched[SCRATCH] == 0)
+
+
+@pytest.mark.parametrize("n", [2, 3, 8])
+@pytest.mark.parametrize("chans,threads,cv", [(1, 4, 1), (3, 4, 7), (2, 8, 64), (5, 16, 333)])
+def test_lowered_ring_plan_computes_the_allreduce_in_ring_order(L, n, chans, threads, cv):
+    V = cv * n
+    ops, start = lower(L, 7, n, chans, V, threads)
+    rng = np.random.default_rng(V + 1)
+    x = rng.standard_normal((n, V)) * np.exp(rng.standard_normal((n, V)) * 3)
+    x = x.astype(np.float32).astype(np.float64)
+    rnd = lambda a: a.astype(np.float32).astype(np.float64)        # partial sums travel as fp32
+    out, touched = simulate(ops, start, n, chans, threads, x, ring_order_rounding=rnd)
+    want = np.empty(V)
+    for k in range(n):                                            # chunk k: k, k+1, ..., k-1 (mod n)
+        sl = slice(k * cv, (k + 1) * cv)
+        acc = x[k, sl].astype(np.float32)
+        for h in range(1, n):
+            acc = (acc + x[(k + h) % n, sl].astype(np.float32)).astype(np.float32)
+        want[sl] = acc
+    assert np.array_equal(out, np.tile(want, (n, 1)))
+    assert np.all(touched[OUT] == 1)
+    # each rank's scratch receives every chunk but the one that ends its trip there... exactly n-1 chunks
+    assert np.all(touched[SCRATCH].reshape(n, n, cv).sum(axis=2) // cv <= 1)
+    assert np.all(touched[SCRATCH].sum(axis=1) == (n - 1) * cv)
+
+
+def test_lower_plan_argument_checks(L):
+    w = C.c_size_t(0)
+    assert L.msx_debug_lower_plan(3, 8, 1, 64, 256, None, 0, None, C.byref(w)) == -1      # not a plan algorithm
+    assert L.msx_debug_lower_plan(6, 1, 1, 64, 256, None, 0, None, C.byref(w)) == -1      # one rank
+    assert L.msx_debug_lower_plan(6, 8, 1, 63, 256, None, 0, None, C.byref(w)) == -1      # not divisible
+    assert L.msx_debug_lower_plan(6, 8, 2, 64, 256, None, 0, None, C.byref(w)) == 0 and w.value == 16 * 5
+    ops = (PlanOp * 4)()
+    start = (C.c_uint32 * 17)()
+    assert L.msx_debug_lower_plan(6, 8, 2, 64, 256, ops, 4, start, C.byref(w)) == -5       # buffer too small
+
+
+def test_automatic_choice_and_launch_shapes(L):
+    a, u, w = C.c_int(), C.c_int(), C.c_int()
+    ll = 4 << 20
+
+    def choose(nbytes, n=8):
+        assert L.msx_debug_choose(nbytes, n, ll, C.byref(a), C.byref(u), C.byref(w)) == 0
+        return a.value, u.value, w.value
+
+    assert choose(1024)[0] == 1 and choose(2048)[0] == 1          # tiny: one-phase LL
+    assert choose(2049)[0] == 3 and choose(1 << 30)[0] == 3       # everything else: fused HB
+    assert choose(1024, n=1)[0] == 3                              # a single rank is a copy
+    # launch shapes: one pass with two vectors per thread up to 4 MiB per rank, then 32, then 128 workgroups
+    assert choose(64 << 10) == (3, 2, 1)
+    assert choose(1 << 20) == (3, 2, 16)
+    assert choose(4 << 20) == (3, 2, 64)
+    assert choose(32 << 20) == (3, 1, 32)
+    assert choose(64 << 20) == (3, 1, 128)
+    assert choose(1 << 30) == (3, 1, 128)
+    # thresholds follow the options
+    import paper_2504_09014_amd as msx
+    old = msx.get_option("ll_2pa_max_bytes")
+    msx.set_option("ll_2pa_max_bytes", str(256 << 10))
+    try:
+        assert choose(128 << 10)[0] == 2 and choose(512 << 10)[0] == 3
+        assert choose(3 << 20)[0] == 3
+    finally:
+        msx.set_option("ll_2pa_max_bytes", old)
+    assert L.msx_debug_choose(1024, 0, ll, C.byref(a), C.byref(u), C.byref(w)) == -1
