@@ -402,6 +402,26 @@ def main():
         extras["config5_moe_dispatch_fp8"] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
                                               "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
         del rq, rsc
+        # primitives against the best achievable (the analogue of the paper's primitive table):
+        # a put -> signal || wait -> read hand-off of 4 KiB (latency) and 1 GiB (throughput) through the
+        # MemoryChannel (thread copy) and through the emulated PortChannel (FIFO + CPU proxy + runtime copy)
+        prim = {}
+        for label, nb, blocks in [("4KiB", 4096, 1), ("1GiB", 1 << 30, 128)]:
+            a_ = torch.empty(nb, dtype=torch.uint8, device="cuda").random_()
+            st_ = torch.empty_like(a_)
+            d_ = torch.empty_like(a_)
+            it = 50 if nb <= 4096 else 5
+            t_mem = median(time_calls(torch, lambda: msx.prim_put_signal_wait(a_, st_, d_, blocks), it, 3)[1])
+            t_port = median(time_calls(torch, lambda: msx.prim_port_put_signal_wait(a_, st_, d_), it, 3)[1])
+            t_copy = median(time_calls(torch, lambda: st_.copy_(a_), it, 3)[1])
+            prim[label] = {"memory_channel_us": round(t_mem, 1), "port_channel_us": round(t_port, 1),
+                           "one_runtime_copy_us": round(t_copy, 1)}
+            msx.check_status()
+            if not (torch.equal(d_, a_)):
+                print("bench.py: primitive hand-off delivered wrong bytes", file=sys.stderr)
+                sys.exit(1)
+            del a_, st_, d_
+        extras["handoff_put_signal_wait_read"] = prim
         extras["hop_ns"] = {"signal_wait_round_trip_cross_xcd": round(msx.prim_pingpong(2000, 16, 0, 1), 1),
                             "signal_wait_round_trip_same_xcd": round(msx.prim_pingpong(2000, 16, 0, 8), 1)}
         out["extras"] = extras

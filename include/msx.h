@@ -177,6 +177,13 @@ int msx_prim_barrier(int rounds, int nranks, int blocks_per_rank, uint32_t* sem_
 int msx_prim_put_signal_wait(const void* src, void* staging, void* dst, size_t nbytes,
                              int blocks_per_rank, void* stream);
 
+/* PortChannel hand-off (port-mapped I/O, emulated): rank 0 pushes put(src -> staging), signal and
+ * flush requests into a FIFO in host memory; a CPU proxy thread of the library carries them out
+ * (hipMemcpyAsync device to device on its own stream, semaphore increment after the copy, tail
+ * advance on flush); rank 1 waits on the semaphore, then copies staging -> dst with its threads.
+ * The first call starts the proxy thread and allocates the FIFO (blocks once). */
+int msx_prim_port_put_signal_wait(const void* src, void* staging, void* dst, size_t nbytes, void* stream);
+
 /* LL encode only: write ceil(nbytes/8) 16-byte packets {w0, flag, w1, flag} for src into
  * packets_out (device, 16-byte aligned, 16*ceil(nbytes/8) bytes). */
 int msx_prim_ll_encode(const void* src, size_t nbytes, uint32_t flag, void* packets_out,

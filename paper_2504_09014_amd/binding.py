@@ -14,7 +14,7 @@ __all__ = [
     "check_status", "last_launch", "version", "strerror",
     "allreduce", "reducescatter", "allgather", "alltoall",
     "allreduce_ex", "reducescatter_ex", "allgather_ex", "alltoall_ex", "moe_dispatch", "moe_dispatch_fp8", "moe_combine",
-    "prim_pingpong", "prim_barrier", "prim_put_signal_wait", "prim_ll_encode", "prim_ll_roundtrip",
+    "prim_pingpong", "prim_barrier", "prim_put_signal_wait", "prim_ll_encode", "prim_ll_roundtrip", "prim_port_put_signal_wait",
     "EXPORTS",
 ]
 
@@ -28,7 +28,7 @@ EXPORTS = [
     "msx_allreduce_ex", "msx_reducescatter_ex", "msx_allgather_ex", "msx_alltoall_ex",
     "msx_moe_dispatch", "msx_moe_dispatch_fp8", "msx_moe_combine",
     "msx_prim_pingpong", "msx_prim_barrier", "msx_prim_put_signal_wait", "msx_prim_ll_encode",
-    "msx_prim_ll_roundtrip",
+    "msx_prim_ll_roundtrip", "msx_prim_port_put_signal_wait",
     "msx_init", "msx_reset", "msx_finalize", "msx_set_option", "msx_get_option", "msx_status",
     "msx_last_launch", "msx_last_hip_error", "msx_strerror", "msx_version",
     "msx_debug_choose", "msx_debug_lower_plan",
@@ -74,6 +74,7 @@ def lib():
         L.msx_prim_pingpong.argtypes = [i, i, i, i, vp, vp]
         L.msx_prim_barrier.argtypes = [i, i, i, vp, vp]
         L.msx_prim_put_signal_wait.argtypes = [vp, vp, vp, sz, i, vp]
+        L.msx_prim_port_put_signal_wait.argtypes = [vp, vp, vp, sz, vp]
         L.msx_prim_ll_encode.argtypes = [vp, sz, u32, vp, vp]
         L.msx_prim_ll_roundtrip.argtypes = [vp, vp, sz, i, vp]
         L.msx_set_option.argtypes = [C.c_char_p, C.c_char_p]
@@ -314,6 +315,13 @@ def prim_put_signal_wait(src, staging, dst, blocks_per_rank=4, stream=None):
     _ck(lib().msx_prim_put_signal_wait(C.c_void_p(src.data_ptr()), C.c_void_p(staging.data_ptr()),
                                        C.c_void_p(dst.data_ptr()), nbytes, blocks_per_rank, _stream(stream)),
         "msx_prim_put_signal_wait")
+
+
+def prim_port_put_signal_wait(src, staging, dst, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _ck(lib().msx_prim_port_put_signal_wait(C.c_void_p(src.data_ptr()), C.c_void_p(staging.data_ptr()),
+                                            C.c_void_p(dst.data_ptr()), nbytes, _stream(stream)),
+        "msx_prim_port_put_signal_wait")
 
 
 def prim_ll_encode(src, flag, stream=None):

@@ -13,12 +13,17 @@
 #include <string>
 #include <utility>
 #include <vector>
+#include <atomic>
+#include <chrono>
+#include <condition_variable>
+#include <thread>
 
 #include "msx_device.hpp"
 #include "msx_kernels_hb.hpp"
 #include "msx_kernels_ll.hpp"
 #include "msx_kernels_moe.hpp"
 #include "msx_kernels_plan.hpp"
+#include "msx_port.hpp"
 #include "msx_kernels_prim.hpp"
 
 using namespace msx;
@@ -45,6 +50,20 @@ struct Options {
     unsigned chaos = 0;
 };
 
+// PortChannel emulation: the FIFO in pinned host memory and the CPU proxy thread that serves it.
+struct Port {
+    PortFifo* fifo = nullptr;
+    unsigned* expected = nullptr;      // device: what the next port wait of each (recv, send) pair needs
+    hipStream_t stream = nullptr;      // the proxy's own stream (default priority)
+    std::mutex mu;
+    std::condition_variable cv;
+    unsigned long long announced = 0;  // requests launched kernels will push in total
+    unsigned long long consumed = 0;   // requests served so far
+    bool stop = false;
+    std::atomic<bool> exited{false};
+    int device = 0;
+};
+
 struct Ctx {
     int device = -1;
     DevCtx d{};
@@ -58,6 +77,7 @@ struct Ctx {
     size_t ring_bytes = 0;
     struct Plan { int algo, n, chans; size_t nbytes; PlanOp* ops; unsigned* start; };
     std::vector<Plan> plans;       // lowered execution plans, kept on the device
+    Port* port = nullptr;          // created on the first port-channel call
     unsigned* snap = nullptr;  // small device scratch for snapshots
     size_t ll_limit = 0;       // ll_max_bytes this context was sized for
     std::map<std::pair<const void*, int>, int> occ;   // (kernel, threads) -> resident blocks per CU
@@ -83,10 +103,92 @@ int hip_fail(hipError_t e)
 size_t elem_size(int dtype) { return dtype == MSX_F32 ? 4 : 2; }
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+void port_proxy(Port* p)
+{
+    (void)hipSetDevice(p->device);
+    for (;;) {
+        {
+            std::unique_lock<std::mutex> lk(p->mu);
+            p->cv.wait(lk, [&] { return p->stop || p->consumed < p->announced; });
+            if (p->stop) break;
+        }
+        const auto deadline = std::chrono::steady_clock::now() + std::chrono::seconds(20);
+        for (;;) {
+            {
+                std::lock_guard<std::mutex> lk(p->mu);
+                if (p->stop || p->consumed >= p->announced) break;
+            }
+            const unsigned long long head = __atomic_load_n(&p->fifo->head, __ATOMIC_ACQUIRE);
+            if (head > p->consumed) {
+                const PortReq r = p->fifo->req[p->consumed % kPortSlots];
+                if (r.type == kPortPut) {
+                    (void)hipMemcpyAsync((void*)r.dst, (const void*)r.src, (size_t)r.bytes, hipMemcpyDeviceToDevice,
+                                         p->stream);
+                } else if (r.type == kPortSignal) {
+                    (void)hipStreamSynchronize(p->stream);      // the copies before the signal have landed
+                    if (r.arg < (unsigned)(kMaxRanks * kMaxRanks))
+                        __atomic_fetch_add(&p->fifo->sem[r.arg], 1u, __ATOMIC_RELEASE);
+                } else {
+                    (void)hipStreamSynchronize(p->stream);
+                }
+                std::lock_guard<std::mutex> lk(p->mu);
+                ++p->consumed;
+                __atomic_store_n(&p->fifo->tail, p->consumed, __ATOMIC_RELEASE);
+            } else if (std::chrono::steady_clock::now() > deadline) {
+                std::lock_guard<std::mutex> lk(p->mu);   // the kernel never pushed: forget the rest
+                p->announced = p->consumed;
+            } else {
+                std::this_thread::yield();
+            }
+        }
+    }
+    p->exited.store(true);
+}
+
+void destroy_port(Port* p)
+{
+    if (!p) return;
+    {
+        std::lock_guard<std::mutex> lk(p->mu);
+        p->stop = true;
+    }
+    p->cv.notify_all();
+    for (int i = 0; i < 5000 && !p->exited.load(); ++i) std::this_thread::sleep_for(std::chrono::milliseconds(1));
+    if (!p->exited.load()) return;      // never seen: leave everything in place rather than free under a live thread
+    if (p->stream) (void)hipStreamDestroy(p->stream);
+    if (p->fifo) (void)hipHostFree(p->fifo);
+    if (p->expected) (void)hipFree(p->expected);
+    delete p;
+}
+
+int get_port(Ctx* c, Port** out)
+{
+    if (c->port) { *out = c->port; return MSX_OK; }
+    Port* p = new Port();
+    p->device = c->device;
+    bool ok = hipHostMalloc((void**)&p->fifo, sizeof(PortFifo), hipHostMallocMapped) == hipSuccess;
+    if (ok) memset(p->fifo, 0, sizeof(PortFifo));
+    ok = ok && hipMalloc((void**)&p->expected, kMaxRanks * kMaxRanks * 4) == hipSuccess &&
+         hipMemset(p->expected, 0, kMaxRanks * kMaxRanks * 4) == hipSuccess &&
+         hipStreamCreateWithFlags(&p->stream, hipStreamNonBlocking) == hipSuccess &&
+         hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        if (p->fifo) (void)hipHostFree(p->fifo);
+        if (p->expected) (void)hipFree(p->expected);
+        delete p;
+        return MSX_ERR_NOMEM;
+    }
+    std::thread(port_proxy, p).detach();
+    c->port = p;
+    *out = p;
+    return MSX_OK;
+}
+
 int destroy_ctx(Ctx* c)
 {
     if (!c) return MSX_OK;
     (void)hipDeviceSynchronize();
+    destroy_port(c->port);
     if (c->d.sem) (void)hipFree(c->d.sem);
     if (c->d.expected) (void)hipFree(c->d.expected);
     if (c->d.status) (void)hipFree(c->d.status);
@@ -1026,6 +1128,33 @@ int msx_prim_ll_roundtrip(const void* src, void* dst, size_t nbytes, int blocks_
                   blocks_per_rank);
 }
 
+int msx_prim_port_put_signal_wait(const void* src, void* staging, void* dst, size_t nbytes, void* stream)
+{
+    if (!src || !staging || !dst || !aligned16(src) || !aligned16(staging) || !aligned16(dst)) return MSX_ERR_ARG;
+    if (nbytes == 0) return MSX_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = get_ctx(&c);
+    if (rc) return rc;
+    Port* p = nullptr;
+    if ((rc = get_port(c, &p))) return rc;
+    int resident = 0;
+    if ((rc = resident_blocks(c, (const void*)k_port_put_signal_wait, 256, &resident))) return rc;
+    if (resident < 2) return MSX_ERR_UNSUPPORTED;
+    size_t readers = (nbytes + (256 * 16 * 8) - 1) / (256 * 16 * 8);   // 32 KiB per reading workgroup and pass
+    if (readers < 1) readers = 1;
+    if (readers > 128) readers = 128;
+    if ((int)readers + 1 > resident) readers = (size_t)resident - 1;
+    {
+        std::lock_guard<std::mutex> pl(p->mu);
+        p->announced += g_opt.drop_rank == 0 ? 0 : 3;   // put, signal, flush (a dropped sender pushes nothing)
+    }
+    p->cv.notify_all();
+    note_launch(1 + (int)readers, 256, 0);
+    return launch(k_port_put_signal_wait, 1 + (int)readers, 256, (hipStream_t)stream, dev_ctx(c), p->fifo,
+                  p->expected, src, staging, dst, nbytes, (int)readers);
+}
+
 // ---- context, options, status ---------------------------------------------------------------
 
 int msx_init(void)
@@ -1048,6 +1177,10 @@ int msx_reset(void)
     HIPCHK(hipMemset(c->d.call_state, 0, 64));
     HIPCHK(hipMemset(c->d.ll, 0, c->d.ll_bytes));
     HIPCHK(hipDeviceSynchronize());
+    if (c->port) {                       // a port channel that timed out starts over with a fresh proxy
+        destroy_port(c->port);
+        c->port = nullptr;
+    }
     return MSX_OK;
 }
 

@@ -125,3 +125,37 @@ def test_a_missing_peer_times_out_instead_of_hanging(msx):
     # after a reset everything works again
     after = msx.prim_barrier(3, 8, 1)
     assert np.all(after[~np.eye(8, dtype=bool)] == 3)
+
+
+@pytest.mark.parametrize("nbytes", [16, 4096 + 3, (1 << 20) + 5, 64 << 20])
+def test_port_channel_put_signal_wait_flush(msx, nbytes):
+    src_h = _rand_bytes(nbytes, 5 + nbytes)
+    src = src_h.cuda()
+    staging = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    for _ in range(3):                                    # semaphore and FIFO positions carry over
+        dst.zero_()
+        torch.cuda.synchronize()
+        msx.prim_port_put_signal_wait(src, staging, dst)
+        msx.check_status()
+        assert torch.equal(dst.cpu(), src_h)
+    assert torch.equal(staging.cpu(), src_h)
+
+
+def test_port_channel_waiter_times_out_without_a_sender(msx):
+    src = _rand_bytes(4096, 3).cuda()
+    staging = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(4096, dtype=torch.uint8, device="cuda")
+    msx.set_option("spin_limit", "2000")
+    msx.set_option("drop_rank", "0")
+    try:
+        msx.prim_port_put_signal_wait(src, staging, dst)
+        rc, info = msx.status()
+        assert rc == -4 and info[2] == 502
+    finally:
+        msx.set_option("drop_rank", "-1")
+        msx.set_option("spin_limit", str(1 << 20))
+        msx.reset()
+    msx.prim_port_put_signal_wait(src, staging, dst)      # a fresh proxy serves the next call
+    msx.check_status()
+    assert torch.equal(dst, src)
