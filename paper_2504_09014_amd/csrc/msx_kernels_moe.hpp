@@ -71,13 +71,42 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
     const int t1 = min(T, t0 + per_thread);
     const int* topk = a.topk[rank];
 
-    // pass 1: my tokens' destination marks, counted per destination (16-bit fields)
-    unsigned long long cx = 0, cy = 0;
-    for (int t = t0; t < t1; ++t) {
+    // destination marks of a token: one bit per rank that owns one of its K experts
+    auto marks = [&](int t) -> unsigned {
         unsigned mask = 0;
-        for (int k = 0; k < K; ++k) {
-            const int e = topk[(size_t)t * K + k];
-            if (e >= 0 && e < a.n_experts) mask |= 1u << (e / a.per_rank);
+        if (K == 8) {                                    // the common case: two 16-byte loads per token
+            const u32x4 lo = *(const u32x4*)(topk + (size_t)t * 8), hi = *(const u32x4*)(topk + (size_t)t * 8 + 4);
+            const int e[8] = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
+#pragma unroll
+            for (int k = 0; k < 8; ++k)
+                if (e[k] >= 0 && e[k] < a.n_experts) mask |= 1u << (e[k] / a.per_rank);
+        } else {
+            for (int k = 0; k < K; ++k) {
+                const int e = topk[(size_t)t * K + k];
+                if (e >= 0 && e < a.n_experts) mask |= 1u << (e / a.per_rank);
+            }
+        }
+        return mask;
+    };
+
+    // pass 1: my tokens' destination marks, counted per destination (16-bit fields); the marks of the
+    // first few tokens stay in registers for pass 2
+    constexpr int kKeep = 8;
+    unsigned kept[kKeep];
+    unsigned long long cx = 0, cy = 0;
+#pragma unroll
+    for (int i = 0; i < kKeep; ++i) {
+        const int t = t0 + i;
+        kept[i] = t < t1 ? marks(t) : 0u;
+    }
+    for (int t = t0; t < t1; ++t) {
+        const int i = t - t0;
+        unsigned mask = 0;
+        if (i < kKeep) {
+#pragma unroll
+            for (int q = 0; q < kKeep; ++q) mask = q == i ? kept[q] : mask;
+        } else {
+            mask = marks(t);
         }
         for (int d = 0; d < 4; ++d) {
             cx += (unsigned long long)((mask >> d) & 1u) << (16 * d);
@@ -90,10 +119,13 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
     // pass 2: stable slots
     unsigned short* slots = a.slots + ((size_t)rank * T) * 8;
     for (int t = t0; t < t1; ++t) {
+        const int i = t - t0;
         unsigned mask = 0;
-        for (int k = 0; k < K; ++k) {
-            const int e = topk[(size_t)t * K + k];
-            if (e >= 0 && e < a.n_experts) mask |= 1u << (e / a.per_rank);
+        if (i < kKeep) {
+#pragma unroll
+            for (int q = 0; q < kKeep; ++q) mask = q == i ? kept[q] : mask;
+        } else {
+            mask = marks(t);
         }
         unsigned s[8];
         for (int d = 0; d < 4; ++d) {
