@@ -147,6 +147,88 @@ void orc_allreduce_residual_f32(const float *in, const float *res, float *out, i
     }
 }
 
+/* ---------- fp16 (IEEE binary16) and the other reduction operators ----------
+ * The paper's DSL carries a ReduceOp and the NCCL-style API more element types than the two the
+ * configurations use; these cover fp16 and max / min.  Sum is taken in fp32 in rank order and
+ * rounded once; max / min compare in fp32 in rank order and keep the earlier value unless the
+ * later one is strictly greater / smaller (so a NaN in a later rank never replaces a number, and
+ * a NaN in rank 0 stays). */
+
+float orc_f16_to_f32(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) << 31, e = (h >> 10) & 31u, m = h & 1023u, u;
+    if (e == 31)
+        u = sign | 0x7f800000u | (m << 13);
+    else if (e == 0) {
+        if (m == 0)
+            u = sign;
+        else {                                   /* subnormal: normalise */
+            int shift = 0;
+            while (!(m & 1024u)) { m <<= 1; ++shift; }
+            u = sign | ((uint32_t)(113 - shift) << 23) | ((m & 1023u) << 13);
+        }
+    } else
+        u = sign | ((e + 112u) << 23) | (m << 13);
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* round to nearest even; overflow to infinity; NaN stays NaN (quiet) */
+uint16_t orc_f32_to_f16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    uint32_t a = u & 0x7fffffffu;
+    if (a > 0x7f800000u)
+        return (uint16_t)(sign | 0x7e00u | ((a >> 13) & 0x3ffu));
+    if (a >= 0x477ff000u)                        /* rounds to 65536 or more: infinity */
+        return (uint16_t)(sign | 0x7c00u);
+    if (a < 0x38800000u) {                       /* below 2^-14: fp16 subnormal, multiples of 2^-24 */
+        if (a < 0x33000000u)                     /* below 2^-25: rounds to zero (2^-25 itself ties to even = 0) */
+            return (uint16_t)(sign | (a > 0x33000000u ? 1u : 0u));
+        uint32_t e = a >> 23, m = (a & 0x7fffffu) | 0x800000u;
+        uint32_t shift = 126u - e;               /* result = m >> shift, in units of 2^-24 */
+        uint32_t q = m >> shift, rem = m & ((1u << shift) - 1u), half = 1u << (shift - 1);
+        if (rem > half || (rem == half && (q & 1u)))
+            ++q;
+        return (uint16_t)(sign | q);
+    }
+    uint32_t r = a + 0xfffu + ((a >> 13) & 1u);
+    return (uint16_t)(sign | (uint16_t)((r - 0x38000000u) >> 13));
+}
+
+static float orc_load_elem(const void *p, size_t i, int dtype)
+{
+    if (dtype == 0) return ((const float *)p)[i];
+    if (dtype == 1) return orc_bf16_to_f32(((const uint16_t *)p)[i]);
+    return orc_f16_to_f32(((const uint16_t *)p)[i]);
+}
+
+static void orc_store_elem(void *p, size_t i, int dtype, float v)
+{
+    if (dtype == 0) ((float *)p)[i] = v;
+    else if (dtype == 1) ((uint16_t *)p)[i] = orc_f32_to_bf16(v);
+    else ((uint16_t *)p)[i] = orc_f32_to_f16(v);
+}
+
+/* dtype: 0 fp32, 1 bf16, 2 fp16.  op: 0 sum, 1 max, 2 min.  in: [n][count] -> out: [count] */
+void orc_allreduce_any(const void *in, void *out, int n, size_t count, int dtype, int op)
+{
+    size_t esz = dtype == 0 ? 4 : 2;
+    for (size_t i = 0; i < count; ++i) {
+        float acc = orc_load_elem(in, i, dtype);
+        for (int r = 1; r < n; ++r) {
+            float v = orc_load_elem((const char *)in + (size_t)r * count * esz, i, dtype);
+            if (op == 0) acc += v;
+            else if (op == 1) acc = v > acc ? v : acc;
+            else acc = v < acc ? v : acc;
+        }
+        orc_store_elem(out, i, dtype, acc);
+    }
+}
+
 /* ---------- ring order (two-phase ring AllReduce, Collectives Library section, 2PR) ----------
  * The buffer is cut into n equal chunks; chunk k starts at rank k and travels k -> k+1 -> ... ->
  * k-1 (mod n); every rank on the way adds its own values in fp32 and passes the partial sum on

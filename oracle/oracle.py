@@ -38,6 +38,12 @@ def lib():
         L.orc_allreduce_residual_bf16.restype = None
         L.orc_allreduce_residual_f32.argtypes = [vp, vp, vp, i32, sz]
         L.orc_allreduce_residual_f32.restype = None
+        L.orc_f16_to_f32.argtypes = [C.c_uint16]
+        L.orc_f16_to_f32.restype = C.c_float
+        L.orc_f32_to_f16.argtypes = [C.c_float]
+        L.orc_f32_to_f16.restype = C.c_uint16
+        L.orc_allreduce_any.argtypes = [vp, vp, i32, sz, i32, i32]
+        L.orc_allreduce_any.restype = None
         L.orc_allreduce_ring_bf16.argtypes = [vp, vp, i32, sz]
         L.orc_allreduce_ring_bf16.restype = None
         L.orc_allreduce_ring_f32.argtypes = [vp, vp, i32, sz]
@@ -149,6 +155,24 @@ def allreduce_residual_f32(x, res):
     assert res.shape == (count,)
     out = np.empty(count, np.float32)
     lib().orc_allreduce_residual_f32(_p(x), _p(res), _p(out), n, count)
+    return out
+
+
+def f16_to_f32(code):
+    return float(lib().orc_f16_to_f32(int(code) & 0xFFFF))
+
+
+def f32_to_f16(x):
+    return int(lib().orc_f32_to_f16(float(np.float32(x))))
+
+
+def allreduce_any(x, dtype, op):
+    """x: [n, count] float32 (dtype 0) or uint16 bit patterns (1 = bf16, 2 = fp16); op 0 sum, 1 max, 2 min."""
+    x = np.ascontiguousarray(x)
+    assert x.dtype == (np.float32 if dtype == 0 else np.uint16)
+    n, count = x.shape
+    out = np.empty(count, x.dtype)
+    lib().orc_allreduce_any(_p(x), _p(out), n, count, dtype, op)
     return out
 
 

@@ -214,6 +214,68 @@ def test_allreduce_bf16_bruteforce_fractions(orc, n, count):
         assert got == want, (i, got, want)
 
 
+# ---------------------------------------------------------------- fp16 and max / min
+
+def test_f16_conversions_against_numpy(orc):
+    codes = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    lib = codes.view(np.float16).astype(np.float32)                     # library decode, exact
+    got = np.array([orc.f16_to_f32(c) for c in codes], np.float32)
+    ok = ~np.isnan(lib)
+    assert np.array_equal(got[ok].view(np.uint32), lib[ok].view(np.uint32)) and np.all(np.isnan(got[~ok]))
+    for c in codes[ok][::7]:                                             # round trip
+        assert orc.f32_to_f16(orc.f16_to_f32(c)) == c
+    g = np.random.default_rng(4)
+    x = (g.standard_normal(200_000) * np.exp(g.standard_normal(200_000) * 6)).astype(np.float32)
+    x = np.concatenate([x, np.float32([65504, 65519.9, 65520, 65536, 1e9, 2.0 ** -24, 2.0 ** -25, 1.5 * 2.0 ** -25,
+                                       2.0 ** -25 * 1.0001, 3 * 2.0 ** -25, 2.0 ** -14, 2.0 ** -14 * 0.9999, 0.0, -0.0,
+                                       np.inf, -np.inf])])
+    with np.errstate(over="ignore"):
+        want = x.astype(np.float16).view(np.uint16)                     # library encode (round to nearest even)
+    got = np.array([orc.f32_to_f16(v) for v in x], np.uint16)
+    assert np.array_equal(got, want)
+    assert orc.f32_to_f16(float("nan")) & 0x7C00 == 0x7C00 and orc.f32_to_f16(float("nan")) & 0x3FF
+
+
+@pytest.mark.parametrize("dtype", [0, 1, 2])
+@pytest.mark.parametrize("n", [1, 2, 8])
+def test_allreduce_any_against_numpy(orc, dtype, n):
+    count = 5000
+    g = torch.Generator().manual_seed(dtype * 10 + n)
+    xf = torch.randn(n, count, generator=g) * 4
+    if dtype == 0:
+        x = xf.numpy()
+        as_f32 = x
+    elif dtype == 1:
+        x = synth.bf16_bits(xf.bfloat16())
+        as_f32 = xf.bfloat16().float().numpy()
+    else:
+        x = xf.numpy().astype(np.float16).view(np.uint16)
+        as_f32 = xf.numpy().astype(np.float16).astype(np.float32)
+
+    def back(bits):
+        if dtype == 0:
+            return bits
+        return orc.bf16_to_f32(bits) if dtype == 1 else bits.view(np.float16).astype(np.float32)
+
+    assert np.array_equal(back(orc.allreduce_any(x, dtype, 1)), as_f32.max(axis=0))       # exact: no rounding involved
+    assert np.array_equal(back(orc.allreduce_any(x, dtype, 2)), as_f32.min(axis=0))
+    acc = as_f32[0].copy()
+    for r in range(1, n):
+        acc = acc + as_f32[r]
+    want = acc if dtype == 0 else (synth.bf16_bits(torch.from_numpy(acc).bfloat16()) if dtype == 1
+                                   else acc.astype(np.float16).view(np.uint16))
+    assert np.array_equal(orc.allreduce_any(x, dtype, 0), want)
+    if dtype == 1:
+        assert np.array_equal(orc.allreduce_any(x, 1, 0), orc.allreduce_bf16(x))
+    # NaN rule: a later NaN never replaces a number, a NaN in rank 0 stays
+    if n > 1 and dtype == 0:
+        y = x.copy()
+        y[1, 0] = np.nan
+        y[0, 1] = np.nan
+        out = orc.allreduce_any(y, 0, 1)
+        assert out[0] == np.delete(y[:, 0], 1).max() and np.isnan(out[1])
+
+
 # ---------------------------------------------------------------- ring order
 
 @pytest.mark.parametrize("n", [1, 2, 3, 8])
