@@ -32,8 +32,13 @@
 extern "C" {
 #endif
 
-typedef enum { MSX_F32 = 0, MSX_BF16 = 1 } msx_dtype;
-typedef enum { MSX_SUM = 0 } msx_op;
+/* fp32 and bf16 sums run on the tuned kernels of every algorithm.  fp16, and max / min for any type,
+ * are served by AllReduce (automatic or MSX_ALGO_2PA_HB, no residual) and ReduceScatter through a
+ * generic kernel; the copy collectives and the token dispatch move any 2- or 4-byte type.
+ * Sum: fp32 accumulation in rank order, one rounding.  Max / min: fp32 comparison in rank order,
+ * the earlier value is kept unless the later one is strictly greater / smaller. */
+typedef enum { MSX_F32 = 0, MSX_BF16 = 1, MSX_F16 = 2 } msx_dtype;
+typedef enum { MSX_SUM = 0, MSX_MAX = 1, MSX_MIN = 2 } msx_op;
 
 typedef enum {
     MSX_OK = 0,

@@ -9,7 +9,7 @@ import os
 import torch
 
 __all__ = [
-    "F32", "BF16", "SUM", "ALGO_AUTO", "ALGO_1PA_LL", "ALGO_2PA_LL", "ALGO_2PA_HB", "ALGO_2PA_HB_2PHASE", "ALGO_2PR_HB", "ALGO_PLAN_2PA_HB", "ALGO_PLAN_2PR_HB",
+    "F32", "BF16", "F16", "SUM", "MAX", "MIN", "ALGO_AUTO", "ALGO_1PA_LL", "ALGO_2PA_LL", "ALGO_2PA_HB", "ALGO_2PA_HB_2PHASE", "ALGO_2PR_HB", "ALGO_PLAN_2PA_HB", "ALGO_PLAN_2PR_HB",
     "MsxError", "lib", "lib_path", "init", "reset", "finalize", "set_option", "get_option", "status",
     "check_status", "last_launch", "version", "strerror",
     "allreduce", "reducescatter", "allgather", "alltoall",
@@ -18,8 +18,8 @@ __all__ = [
     "EXPORTS",
 ]
 
-F32, BF16 = 0, 1
-SUM = 0
+F32, BF16, F16 = 0, 1, 2
+SUM, MAX, MIN = 0, 1, 2
 ALGO_AUTO, ALGO_1PA_LL, ALGO_2PA_LL, ALGO_2PA_HB, ALGO_2PA_HB_2PHASE, ALGO_2PR_HB = 0, 1, 2, 3, 4, 5
 ALGO_PLAN_2PA_HB, ALGO_PLAN_2PR_HB = 6, 7
 
@@ -109,6 +109,8 @@ def _dtype(t):
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
+    if t.dtype == torch.float16:
+        return F16
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
@@ -180,19 +182,19 @@ def last_launch():
 
 # ---- in-place forms: buf is a [nranks, ...] tensor -------------------------------------------
 
-def _inplace(fn, name, buf, count, nranks, stream):
+def _inplace(fn, name, buf, count, nranks, stream, op=SUM):
     _dev(buf, "buf")
-    _ck(fn(C.c_void_p(buf.data_ptr()), count, _dtype(buf), SUM, nranks, _stream(stream)), name)
+    _ck(fn(C.c_void_p(buf.data_ptr()), count, _dtype(buf), op, nranks, _stream(stream)), name)
 
 
-def allreduce(buf, stream=None):
-    """buf: [nranks, count]; every row becomes the sum of the rows."""
-    _inplace(lib().msx_allreduce, "msx_allreduce", buf, buf.shape[1], buf.shape[0], stream)
+def allreduce(buf, stream=None, op=SUM):
+    """buf: [nranks, count]; every row becomes the sum (max, min) of the rows."""
+    _inplace(lib().msx_allreduce, "msx_allreduce", buf, buf.shape[1], buf.shape[0], stream, op)
 
 
-def reducescatter(buf, stream=None):
-    """buf: [nranks, count]; row r's share r becomes the sum over rows of that share."""
-    _inplace(lib().msx_reducescatter, "msx_reducescatter", buf, buf.shape[1], buf.shape[0], stream)
+def reducescatter(buf, stream=None, op=SUM):
+    """buf: [nranks, count]; row r's share r becomes the sum (max, min) over rows of that share."""
+    _inplace(lib().msx_reducescatter, "msx_reducescatter", buf, buf.shape[1], buf.shape[0], stream, op)
 
 
 def allgather(buf, stream=None):
@@ -210,21 +212,21 @@ def alltoall(buf, stream=None):
 
 # ---- per-rank pointer forms ---------------------------------------------------------------------
 
-def allreduce_ex(send, recv, residual=None, algo=ALGO_AUTO, stream=None, count=None):
+def allreduce_ex(send, recv, residual=None, algo=ALGO_AUTO, stream=None, count=None, op=SUM):
     """send, recv (, residual): lists of nranks 1-D device tensors of equal length."""
     n = len(send)
     for t in list(send) + list(recv) + list(residual or []):
         _dev(t, "tensor")
     cnt = send[0].numel() if count is None else count
-    _ck(lib().msx_allreduce_ex(_table(send), _table(recv), _table(residual), cnt, _dtype(send[0]), SUM, n,
+    _ck(lib().msx_allreduce_ex(_table(send), _table(recv), _table(residual), cnt, _dtype(send[0]), op, n,
                                algo, _stream(stream)), "msx_allreduce_ex")
 
 
-def reducescatter_ex(send, recv, stream=None):
+def reducescatter_ex(send, recv, stream=None, op=SUM):
     n = len(send)
     for t in list(send) + list(recv):
         _dev(t, "tensor")
-    _ck(lib().msx_reducescatter_ex(_table(send), _table(recv), send[0].numel(), _dtype(send[0]), SUM, n,
+    _ck(lib().msx_reducescatter_ex(_table(send), _table(recv), send[0].numel(), _dtype(send[0]), op, n,
                                    _stream(stream)), "msx_reducescatter_ex")
 
 

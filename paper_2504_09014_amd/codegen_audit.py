@@ -1,0 +1,128 @@
+"""Build check: look for wave-uniform conditions that the compiler re-derived with a vector
+compare inside a loop and then reads outside that loop.
+
+hipcc keeps a wave-uniform boolean (rank == j, j < n) as a 64-bit lane mask.  Where it needs
+the negation it may emit `v_cndmask_b32 v, 0, 1, mask` + `v_cmp_ne_u32 s[a:b], 1, v`; a vector
+compare writes bits only for the lanes active at that point.  Inside a loop that lanes leave at
+different iterations this gives a mask that is wrong for every lane that has already left, and
+code after the loop (a later loop over the same data, say) that tests it can take the wrong side.
+The kernels avoid the pattern by forming such conditions from per-lane copies of the rank and the
+rank count (`per_lane` in csrc/msx_device.hpp); this module compiles the device code to assembly
+and reports any place where the pattern is back.
+
+    python -m paper_2504_09014_amd.codegen_audit          # prints findings, exit status 1 if any
+"""
+import os
+import re
+import subprocess
+import sys
+import tempfile
+
+from . import build as _build
+
+_RE_FN = re.compile(r'^(_Z\w+):')
+_RE_LABEL = re.compile(r'^(?:\.L(BB\d+_\d+):|; %bb\.(\d+):)')
+_RE_ROUNDTRIP = re.compile(r'v_cmp_ne_u32_e64 (s\[\d+:\d+\]), 1, v\d+')
+
+
+def device_assembly(out_path):
+    """Compile csrc/*.hip for gfx950, device side only, to assembly text."""
+    flags = [f for f in _build.FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [_build.HIPCC] + flags + ["--cuda-device-only", "-S", "-o", out_path] + _build.sources()
+    subprocess.run(cmd, check=True, stderr=subprocess.DEVNULL)
+    return out_path
+
+
+def _regs(tok):
+    m = re.match(r's\[(\d+):(\d+)\]', tok)
+    if m:
+        return set(range(int(m.group(1)), int(m.group(2)) + 1))
+    m = re.match(r's(\d+)$', tok)
+    if m:
+        return {int(m.group(1))}
+    return {106, 107} if tok == "vcc" else set()
+
+
+def parse(path):
+    """-> {function: [(block label, innermost loop header or None, instruction), ...]}, parents."""
+    funcs, parents = {}, {}
+    fn, cur = None, None
+    for raw in open(path):
+        line = raw.rstrip("\n")
+        m = _RE_FN.match(line)
+        if m:
+            fn = m.group(1)
+            cur = ["entry", None]
+            funcs[fn] = []
+            continue
+        if fn is None:
+            continue
+        if line.startswith("\t.end_amdhsa_kernel") or line.startswith(".Lfunc_end"):
+            fn = None
+            continue
+        m = _RE_LABEL.match(line)
+        if m:
+            label = m.group(1) or ("bb." + m.group(2))
+            loop = None
+            mm = re.search(r'in Loop: Header=(BB\d+_\d+) Depth=', line)
+            if mm:
+                loop = mm.group(1)
+            if "Loop Header" in line:
+                loop = label
+            cur = [label, loop]
+            continue
+        if re.match(r'^\s+;', line):            # further comment lines of a loop header block
+            if "Loop Header" in line:
+                cur[1] = cur[0]
+            mm = re.search(r'Parent Loop (BB\d+_\d+) Depth', line)
+            if mm:
+                parents.setdefault((fn, cur[0]), []).append(mm.group(1))
+            continue
+        if line.startswith("\t") and not line.startswith("\t."):
+            funcs[fn].append((cur[0], cur[1], line.strip()))
+    return funcs, parents
+
+
+def _chain(parents, fn, loop):
+    out = []
+    while loop and loop not in out:
+        out.append(loop)
+        ps = parents.get((fn, loop), [])
+        loop = ps[-1] if ps else None           # the innermost parent is listed last
+    return out
+
+
+def findings(path):
+    """[(function, (def block, loop, instruction), (use block, loop, instruction)), ...]"""
+    funcs, parents = parse(path)
+    found = []
+    for fn, flat in funcs.items():
+        for i, (lab, loop, ins) in enumerate(flat):
+            m = _RE_ROUNDTRIP.match(ins)
+            if not m or loop is None:
+                continue
+            d = _regs(m.group(1))
+            for lab2, loop2, ins2 in flat[i + 1:]:
+                ops = re.split(r'[ ,]+', ins2)
+                if ops[0].startswith(("s_cbranch", "s_branch")) or len(ops) < 2:
+                    continue
+                if any(_regs(t) & d for t in ops[2:]) and loop not in _chain(parents, fn, loop2):
+                    found.append((fn, (lab, loop, ins), (lab2, loop2, ins2)))
+                    break
+                if _regs(ops[1]) & d and not ops[0].startswith(("buffer_store", "global_store")):
+                    break                        # redefined
+    return found
+
+
+def main():
+    with tempfile.TemporaryDirectory() as tmp:
+        path = device_assembly(os.path.join(tmp, "msx_device.s"))
+        found = findings(path)
+    for fn, d, u in found:
+        print(f"{fn}\n   def  [{d[0]} in loop {d[1]}] {d[2]}\n   use  [{u[0]} in loop {u[1]}] {u[2]}")
+    print(f"{len(found)} finding(s)")
+    return 1 if found else 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

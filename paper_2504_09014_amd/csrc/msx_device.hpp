@@ -47,7 +47,7 @@ __device__ __forceinline__ unsigned sem_index(int recv, int send, int chan)
 }
 
 __device__ __forceinline__ void report(const DevCtx& c, unsigned code, unsigned rank, unsigned site,
-                                       unsigned expected, unsigned seen)
+                                       unsigned expected, unsigned seen, unsigned extra = 0u)
 {
     if (atomicCAS(c.status, 0u, code) == 0u) {
         c.status[1] = rank;
@@ -55,6 +55,7 @@ __device__ __forceinline__ void report(const DevCtx& c, unsigned code, unsigned 
         c.status[3] = expected;
         c.status[4] = seen;
         c.status[5] = blockIdx.x;
+        c.status[6] = extra;
     }
 }
 
@@ -66,6 +67,21 @@ __device__ __forceinline__ void chaos_delay(const DevCtx& c, unsigned site)
     h ^= h >> 15; h *= 2246822519u; h ^= h >> 13;
     unsigned n = h & 1023u;
     for (unsigned i = 0; i < n; ++i) __builtin_amdgcn_s_sleep(8);
+}
+
+// ---- wave-uniform values in conditions ----------------------------------------------------
+// A copy of a wave-uniform integer (the rank, the rank count) that the compiler must treat as a
+// per-lane value.  Conditions such as `j != rank` or `j < n` inside the unrolled per-peer loops
+// are formed from these copies, so they take the ordinary divergent-branch lowering.  Formed from
+// the uniform originals they are kept as 64-bit lane masks across loops, and this compiler
+// re-derives such a mask with vector compares wherever it needs the negation, also inside a
+// loop whose lanes leave at different iterations.  That mask has bits only for the lanes still
+// active there; a later loop running with other lanes reads it as false (seen as an LL poll loop
+// that, once lane 0 had left, started waiting on the rank's own, never written, packet slot).
+__device__ __forceinline__ int per_lane(int x)
+{
+    asm("" : "+v"(x));
+    return x;
 }
 
 // ---- semaphores ---------------------------------------------------------------------

@@ -23,6 +23,7 @@
 #include "msx_kernels_ll.hpp"
 #include "msx_kernels_moe.hpp"
 #include "msx_kernels_plan.hpp"
+#include "msx_kernels_generic.hpp"
 #include "msx_port.hpp"
 #include "msx_kernels_prim.hpp"
 
@@ -85,6 +86,7 @@ struct Ctx {
 
 std::mutex g_mu;
 Options g_opt;
+unsigned g_status_detail = 0;   // seventh status word of the last reported event (which peer was late)
 Ctx* g_ctx[64] = {};
 thread_local int t_hip_err = 0;
 thread_local int t_grid = 0, t_block = 0, t_algo = 0;
@@ -304,8 +306,8 @@ int pick_channels(Ctx* c, const void* k, int threads, int n, size_t work, size_t
 
 int check_common(int dtype, int op, int nranks)
 {
-    if (dtype != MSX_F32 && dtype != MSX_BF16) return MSX_ERR_ARG;
-    if (op != MSX_SUM) return MSX_ERR_UNSUPPORTED;
+    if (dtype != MSX_F32 && dtype != MSX_BF16 && dtype != MSX_F16) return MSX_ERR_ARG;
+    if (op != MSX_SUM && op != MSX_MAX && op != MSX_MIN) return MSX_ERR_UNSUPPORTED;
     if (nranks < 1 || nranks > kMaxRanks) return MSX_ERR_ARG;
     return MSX_OK;
 }
@@ -533,6 +535,38 @@ int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nb
     return launch((K)kp, n * chans, threads, stream, a, dev_ctx(c));
 }
 
+typedef void (*GenericKernel)(HbArgs, DevCtx, int, int);
+
+GenericKernel generic_kernel(int dtype, int op)
+{
+#define MSX_G(DT) (op == MSX_SUM ? (GenericKernel)k_reduce_generic<DT, 0> : op == MSX_MAX ? (GenericKernel)k_reduce_generic<DT, 1> : (GenericKernel)k_reduce_generic<DT, 2>)
+    return dtype == MSX_F32 ? MSX_G(0) : dtype == MSX_BF16 ? MSX_G(1) : MSX_G(2);
+#undef MSX_G
+}
+
+// fp16 and max / min: the generic HB kernel.  mode 0 AllReduce (count = elements per rank),
+// mode 1 ReduceScatter (count = elements per block).
+int reduce_generic(Ctx* c, const void* const* in, void* const* out, size_t count, int dtype, int op, int n,
+                   int mode, int vec, hipStream_t stream)
+{
+    GenericKernel k = generic_kernel(dtype, op);
+    const size_t vecs = count * elem_size(dtype) / 16;
+    const size_t per_rank = mode == 0 ? (vecs + (size_t)n - 1) / (size_t)n : (vec ? vecs : count);
+    int chans = 1, rc;
+    if ((rc = pick_channels(c, (const void*)k, 256, n, per_rank, 1, g_opt.hb_blocks, 128, &chans))) return rc;
+    HbArgs a{};
+    for (int i = 0; i < n; ++i) {
+        a.in[i] = in[i];
+        a.out[i] = out[i];
+    }
+    a.count = count;
+    a.n = n;
+    a.chans = chans;
+    a.barriers = g_opt.hb_barriers;
+    note_launch(n * chans, 256, MSX_ALGO_2PA_HB);
+    return launch(k, n * chans, 256, stream, a, dev_ctx(c), mode, vec);
+}
+
 int allreduce_impl(const void* const* send, void* const* recv, const void* const* residual, size_t count,
                    int dtype, int op, int nranks, int algo, hipStream_t stream)
 {
@@ -553,6 +587,14 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     bool res_shared = residual != nullptr;
     if (residual)
         for (int i = 1; i < n; ++i) res_shared = res_shared && residual[i] == residual[0];
+
+    if (dtype == MSX_F16 || op != MSX_SUM) {
+        // outside the tuned paths: only the fused all-pairs HB form exists
+        if (residual) return MSX_ERR_UNSUPPORTED;
+        if (algo == MSX_ALGO_AUTO) algo = g_opt.algo;
+        if (algo != MSX_ALGO_AUTO && algo != MSX_ALGO_2PA_HB) return MSX_ERR_UNSUPPORTED;
+        return reduce_generic(c, send, recv, count, dtype, op, n, 0, 1, stream);
+    }
 
     if (algo == MSX_ALGO_AUTO) algo = g_opt.algo;
     if (algo == MSX_ALGO_AUTO) algo = choose_algo(nbytes, n, c->ll_limit);
@@ -867,6 +909,12 @@ int msx_reducescatter_ex(const void* const* send, void* const* recv, size_t coun
         if (!recv[r]) return MSX_ERR_ARG;
         if (!aligned16(recv[r])) vec = 0;
         if ((uintptr_t)recv[r] % esz) return MSX_ERR_ARG;
+    }
+    if (dtype == MSX_F16 || op != MSX_SUM) {
+        std::lock_guard<std::mutex> lk(g_mu);
+        Ctx* ctx = nullptr;
+        if ((rc = get_ctx(&ctx))) return rc;
+        return reduce_generic(ctx, send, recv, c, dtype, op, nranks, 1, vec, (hipStream_t)stream);
     }
     if (nranks > 1) {
         bool al8 = true;
@@ -1321,6 +1369,7 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
     else if (k == "barrier_fences") u = (unsigned)g_opt.barrier_fences;
     else if (k == "spin_limit") u = g_opt.spin_limit;
     else if (k == "chaos") u = g_opt.chaos;
+    else if (k == "status_detail") u = g_status_detail;
     else if (k == "epoch") {
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64 && g_ctx[dev]) {
@@ -1349,6 +1398,7 @@ int msx_status(void* stream, uint32_t info[6])
     }
     if (info)
         for (int i = 0; i < 6; ++i) info[i] = h[i];
+    if (h[0] != 0) g_status_detail = h[6];
     if (h[0] == kStatusTimeout) return MSX_ERR_TIMEOUT;
     if (h[0] == kStatusCapacity) return MSX_ERR_CAPACITY;
     return MSX_OK;

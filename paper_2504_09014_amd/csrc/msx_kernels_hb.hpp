@@ -43,31 +43,31 @@ template <int DT> __device__ __forceinline__ void store_elem(void* p, size_t e, 
 // Elements past the last whole 16-byte vector: summed and written to every rank by the
 // first threads of rank 0, channel 0 (ordinary stores: that workgroup releases for real).
 template <int DT>
-__device__ __forceinline__ void allreduce_tail(const HbArgs& a, int n, size_t first, size_t count)
+__device__ __forceinline__ void allreduce_tail(const HbArgs& a, int n_l, size_t first, size_t count)
 {
     for (size_t e = first + threadIdx.x; e < count; e += blockDim.x) {
         float acc = load_elem<DT>(a.in[0], e);
 #pragma unroll
         for (int j = 1; j < kMaxRanks; ++j)
-            if (j < n) acc += load_elem<DT>(a.in[j], e);
+            if (j < n_l) acc += load_elem<DT>(a.in[j], e);
         float r[kMaxRanks];
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
-            r[p] = (p < n && a.has_res) ? load_elem<DT>(a.res[a.res_shared ? 0 : p], e) : 0.0f;
+            r[p] = (p < n_l && a.has_res) ? load_elem<DT>(a.res[a.res_shared ? 0 : p], e) : 0.0f;
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
-            if (p < n) store_elem<DT>(a.out[p], e, a.has_res ? acc + r[p] : acc);
+            if (p < n_l) store_elem<DT>(a.out[p], e, a.has_res ? acc + r[p] : acc);
     }
 }
 
 #define MSX_LOAD_ALL(v, ptrs, idx)                                   \
     _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)            \
-        if (j < n) v[j] = ld16(ptrs[j], idx);
+        if (j < n_l) v[j] = ld16(ptrs[j], idx);
 
 #define MSX_SUM_ALL(acc, v)                                          \
     acc.set(v[0]);                                                   \
     _Pragma("unroll") for (int j = 1; j < kMaxRanks; ++j)            \
-        if (j < n) acc.add(v[j]);
+        if (j < n_l) acc.add(v[j]);
 
 // ---- fused two-phase all-pairs: reduce chunk `rank` in registers and put it to everyone ----
 // (reduce-scatter chunk-sum feeding the all-gather copy with no memory round trip; the
@@ -81,6 +81,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
     const int n = NR ? NR : a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = NR ? NR : per_lane(n);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
     constexpr size_t epv = DT == 0 ? 4 : 8;
     const size_t V = a.count / epv;
@@ -110,11 +111,11 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
                     const u32x4 o = acc.pack();
 #pragma unroll
                     for (int p = 0; p < kMaxRanks; ++p)
-                        if (p < n) st16_wt(a.out[p], idx, o);
+                        if (p < n_l) st16_wt(a.out[p], idx, o);
                 } else {
 #pragma unroll
                     for (int p = 0; p < kMaxRanks; ++p)
-                        if (p < n) {
+                        if (p < n_l) {
                             VecAcc<DT> t = acc;
                             t.add(ld16(a.res[p], idx));
                             st16_wt(a.out[p], idx, t.pack());
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
         }
     }
     const bool tail = rank == 0 && chan == 0 && V * epv < a.count;
-    if (tail) allreduce_tail<DT>(a, n, V * epv, a.count);
+    if (tail) allreduce_tail<DT>(a, n_l, V * epv, a.count);
 
     put_drain();
     if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 11, tail, false);   // my puts have landed everywhere
@@ -137,6 +138,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_2phase(HbArgs a, DevCtx c)
     const int n = NR ? NR : a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = NR ? NR : per_lane(n), rank_l = per_lane(rank);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
     constexpr size_t epv = DT == 0 ? 4 : 8;
     const size_t V = a.count / epv;
@@ -184,10 +186,10 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_2phase(HbArgs a, DevCtx c)
             const u32x4 o = ld16(a.out[rank], idx);
 #pragma unroll
             for (int p = 0; p < kMaxRanks; ++p)
-                if (p < n && p != rank) st16_wt(a.out[p], idx, o);
+                if (p < n_l && p != rank_l) st16_wt(a.out[p], idx, o);
         }
     }
-    if (rank == 0 && chan == 0) allreduce_tail<DT>(a, n, V * epv, a.count);
+    if (rank == 0 && chan == 0) allreduce_tail<DT>(a, n_l, V * epv, a.count);
 
     // phase 1 and hb_put use ordinary streaming stores: this form releases for real
     put_drain();
@@ -204,6 +206,7 @@ __global__ __launch_bounds__(256) void k_reducescatter_hb(HbArgs a, DevCtx c, in
     const int n = a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = per_lane(n);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
     constexpr size_t epv = DT == 0 ? 4 : 8;
     constexpr size_t esz = DT == 0 ? 4 : 2;
@@ -253,6 +256,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int ve
     const int n = a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = per_lane(n);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
     const size_t RT = (size_t)a.chans * blockDim.x;
     const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
@@ -270,7 +274,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int ve
             if (i1 < nv) v1 = ld16(src, i1);
 #pragma unroll
             for (int p = 0; p < kMaxRanks; ++p)
-                if (p < n && dst[p] != src) {
+                if (p < n_l && dst[p] != src) {
                     st16_wt(dst[p], i, v0);
                     if (i1 < nv) st16_wt(dst[p], i1, v1);
                 }
@@ -292,6 +296,7 @@ __global__ __launch_bounds__(256) void k_alltoall_hb(HbArgs a, DevCtx c, int vec
     const int n = a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = per_lane(n);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
     const size_t RT = (size_t)a.chans * blockDim.x;
     const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
@@ -303,10 +308,10 @@ __global__ __launch_bounds__(256) void k_alltoall_hb(HbArgs a, DevCtx c, int vec
             u32x4 v[kMaxRanks];
 #pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)
-                if (d < n) v[d] = ld16(src + (size_t)d * nbytes, i);
+                if (d < n_l) v[d] = ld16(src + (size_t)d * nbytes, i);
 #pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)
-                if (d < n) st16_wt((char*)a.out[d] + (size_t)rank * nbytes, i, v[d]);
+                if (d < n_l) st16_wt((char*)a.out[d] + (size_t)rank * nbytes, i, v[d]);
         }
     } else {
         for (int d = 0; d < n; ++d) {

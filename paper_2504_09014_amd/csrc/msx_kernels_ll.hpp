@@ -44,19 +44,25 @@ __device__ __forceinline__ void store_words(void* base, size_t k, size_t nbytes,
         if (off + 2 * i + 2 <= nbytes) *(unsigned short*)((char*)base + off + 2 * i) = (unsigned short)h[i];
 }
 
-// Poll packet `pos` of slots j != me (j < n) of my scratch until all carry the flag.
+// Poll packet `pos` of slots j != me (j < n_l) of my scratch until all carry the flag.
 #define MSX_LL_POLL_ALL(v, base_off, slot_stride, pos)                                        \
     {                                                                                         \
         bool ready = false;                                                                   \
         for (unsigned spins = 0; !ready && spins <= c.spin_limit; ++spins) {                  \
             poll_fence();                                                                     \
-            ready = true;                                                                     \
             _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)                             \
-                if (j < n && j != rank) v[j] = ll_load(rs, (base_off) + (unsigned)j * (slot_stride) + (unsigned)(pos) * 16u); \
+                if (j < n_l && j != rank_l) v[j] = ll_load(rs, (base_off) + (unsigned)j * (slot_stride) + (unsigned)(pos) * 16u); \
+            unsigned miss = 0u;              /* any bit set: some packet lacks a flag */       \
             _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)                             \
-                if (j < n && j != rank) ready = ready && ll_ready(v[j], tag.flag);              \
+                if (j < n_l && j != rank_l) miss |= (v[j].y ^ tag.flag) | (v[j].w ^ tag.flag);    \
+            ready = miss == 0u;                                                               \
         }                                                                                     \
-        if (!ready) report(c, kStatusTimeout, (unsigned)rank, 100u, tag.flag, 0u);              \
+        if (!ready) {                                                                         \
+            unsigned late = 0u, seen = 0u;   /* the last slot still without the flag */         \
+            _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)                             \
+                if (j < n_l && j != rank_l && !ll_ready(v[j], tag.flag)) { late = (unsigned)j; seen = v[j].y; } \
+            report(c, kStatusTimeout, (unsigned)rank, 100u, tag.flag, seen, late);            \
+        }                                                                                     \
     }
 
 // ---- 1PA: every rank sends ALL its data to every peer, then reduces everything itself --------
@@ -66,6 +72,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
     const int n = NR ? NR : a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = NR ? NR : per_lane(n), rank_l = per_lane(rank);   // per-lane copies for conditions (see per_lane)
     const CallTag tag = call_begin(c);
     if (rank == c.drop_rank) { call_end(c, tag); return; }
     const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
@@ -81,7 +88,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
         const u32x2 w = load_words(a.in[rank], k, a.nbytes);
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
-            if (p < n && p != rank)
+            if (p < n_l && p != rank_l)
                 ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + k * 16u,
                          w.x, w.y, tag.flag);
     }
@@ -94,9 +101,9 @@ __global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
         WordAcc<DT> a0, a1;
 #pragma unroll
         for (int j = 0; j < kMaxRanks; ++j)
-            if (j < n) {
-                const unsigned w0 = j == rank ? own.x : v[j].x;
-                const unsigned w1 = j == rank ? own.y : v[j].z;
+            if (j < n_l) {
+                const unsigned w0 = j == rank_l ? own.x : v[j].x;
+                const unsigned w1 = j == rank_l ? own.y : v[j].z;
                 if (j == 0) { a0.set(w0); a1.set(w1); } else { a0.add(w0); a1.add(w1); }
             }
         if (a.has_res) {
@@ -118,6 +125,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
     const int n = NR ? NR : a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = NR ? NR : per_lane(n), rank_l = per_lane(rank);   // per-lane copies for conditions (see per_lane)
     const CallTag tag = call_begin(c);
     if (rank == c.drop_rank) { call_end(c, tag); return; }
     const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
@@ -137,10 +145,10 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
         u32x2 w[kMaxRanks];
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
-            if (p < n && p != rank && (unsigned)p * cp + q < P) w[p] = load_words(a.in[rank], (size_t)p * cp + q, a.nbytes);
+            if (p < n_l && p != rank_l && (unsigned)p * cp + q < P) w[p] = load_words(a.in[rank], (size_t)p * cp + q, a.nbytes);
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
-            if (p < n && p != rank && (unsigned)p * cp + q < P)
+            if (p < n_l && p != rank_l && (unsigned)p * cp + q < P)
                 ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + q * 16u,
                          w[p].x, w[p].y, tag.flag);
     }
@@ -154,9 +162,9 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
         WordAcc<DT> a0, a1;
 #pragma unroll
         for (int j = 0; j < kMaxRanks; ++j)
-            if (j < n) {
-                const unsigned w0 = j == rank ? own.x : v[j].x;
-                const unsigned w1 = j == rank ? own.y : v[j].z;
+            if (j < n_l) {
+                const unsigned w0 = j == rank_l ? own.x : v[j].x;
+                const unsigned w1 = j == rank_l ? own.y : v[j].z;
                 if (j == 0) { a0.set(w0); a1.set(w1); } else { a0.add(w0); a1.add(w1); }
             }
         if (!a.has_res || a.res_shared) {
@@ -167,7 +175,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
             const u32x2 o = {a0.pack(), a1.pack()};
 #pragma unroll
             for (int p = 0; p < kMaxRanks; ++p)
-                if (p < n && p != rank)
+                if (p < n_l && p != rank_l)
                     ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + ph2 + (unsigned)rank * slot_stride + q * 16u,
                              o.x, o.y, tag.flag);
             store_words(a.out[rank], k, a.nbytes, o);
@@ -175,12 +183,12 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
             // every destination adds its own residual before the single rounding
 #pragma unroll
             for (int p = 0; p < kMaxRanks; ++p)
-                if (p < n) {
+                if (p < n_l) {
                     const u32x2 r = load_words(a.res[p], k, a.nbytes);
                     WordAcc<DT> t0 = a0, t1 = a1;
                     t0.add(r.x); t1.add(r.y);
                     const u32x2 o = {t0.pack(), t1.pack()};
-                    if (p != rank)
+                    if (p != rank_l)
                         ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + ph2 + (unsigned)rank * slot_stride + q * 16u,
                                  o.x, o.y, tag.flag);
                     else
@@ -198,16 +206,16 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
             ready = true;
 #pragma unroll
             for (int j = 0; j < kMaxRanks; ++j)
-                if (j < n && j != rank && (unsigned)j * cp + q < P)
+                if (j < n_l && j != rank_l && (unsigned)j * cp + q < P)
                     v[j] = ll_load(rs, my_off + ph2 + (unsigned)j * slot_stride + q * 16u);
 #pragma unroll
             for (int j = 0; j < kMaxRanks; ++j)
-                if (j < n && j != rank && (unsigned)j * cp + q < P) ready = ready && ll_ready(v[j], tag.flag);
+                if (j < n_l && j != rank_l && (unsigned)j * cp + q < P) ready = ready && ll_ready(v[j], tag.flag);
         }
         if (!ready) report(c, kStatusTimeout, (unsigned)rank, 101u, tag.flag, 0u);
 #pragma unroll
         for (int j = 0; j < kMaxRanks; ++j)
-            if (j < n && j != rank && (unsigned)j * cp + q < P)
+            if (j < n_l && j != rank_l && (unsigned)j * cp + q < P)
                 store_words(a.out[rank], (size_t)j * cp + q, a.nbytes, u32x2{v[j].x, v[j].z});
     }
     call_end(c, tag);
@@ -233,6 +241,7 @@ __global__ __launch_bounds__(1024) void k_allgather_ll(LlCollArgs a, DevCtx c)
     const int n = NR ? NR : a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = NR ? NR : per_lane(n), rank_l = per_lane(rank);   // per-lane copies for conditions (see per_lane)
     const CallTag tag = call_begin(c);
     if (rank == c.drop_rank) { call_end(c, tag); return; }
     const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
@@ -248,7 +257,7 @@ __global__ __launch_bounds__(1024) void k_allgather_ll(LlCollArgs a, DevCtx c)
         const u32x2 w = load_words(a.in[rank], k, a.nbytes);
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
-            if (p < n && p != rank)
+            if (p < n_l && p != rank_l)
                 ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + k * 16u,
                          w.x, w.y, tag.flag);
         if ((const void*)mine != a.in[rank]) store_words(mine, k, a.nbytes, w);
@@ -258,7 +267,7 @@ __global__ __launch_bounds__(1024) void k_allgather_ll(LlCollArgs a, DevCtx c)
         MSX_LL_POLL_ALL(v, my_off, slot_stride, k)
 #pragma unroll
         for (int j = 0; j < kMaxRanks; ++j)
-            if (j < n && j != rank)
+            if (j < n_l && j != rank_l)
                 store_words((char*)a.out[rank] + (size_t)j * a.nbytes, k, a.nbytes, u32x2{v[j].x, v[j].z});
     }
     call_end(c, tag);
@@ -272,6 +281,7 @@ __global__ __launch_bounds__(1024) void k_reducescatter_ll(LlCollArgs a, DevCtx 
     const int n = NR ? NR : a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = NR ? NR : per_lane(n), rank_l = per_lane(rank);   // per-lane copies for conditions (see per_lane)
     const CallTag tag = call_begin(c);
     if (rank == c.drop_rank) { call_end(c, tag); return; }
     const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
@@ -286,10 +296,10 @@ __global__ __launch_bounds__(1024) void k_reducescatter_ll(LlCollArgs a, DevCtx 
         u32x2 w[kMaxRanks];
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
-            if (p < n && p != rank) w[p] = load_words((const char*)a.in[rank] + (size_t)p * a.nbytes, k, a.nbytes);
+            if (p < n_l && p != rank_l) w[p] = load_words((const char*)a.in[rank] + (size_t)p * a.nbytes, k, a.nbytes);
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
-            if (p < n && p != rank)
+            if (p < n_l && p != rank_l)
                 ll_store(rs, (unsigned)p * c.ll_rank_stride + rot_off + (unsigned)rank * slot_stride + k * 16u,
                          w[p].x, w[p].y, tag.flag);
     }
@@ -300,9 +310,9 @@ __global__ __launch_bounds__(1024) void k_reducescatter_ll(LlCollArgs a, DevCtx 
         WordAcc<DT> a0, a1;
 #pragma unroll
         for (int j = 0; j < kMaxRanks; ++j)
-            if (j < n) {
-                const unsigned w0 = j == rank ? own.x : v[j].x;
-                const unsigned w1 = j == rank ? own.y : v[j].z;
+            if (j < n_l) {
+                const unsigned w0 = j == rank_l ? own.x : v[j].x;
+                const unsigned w1 = j == rank_l ? own.y : v[j].z;
                 if (j == 0) { a0.set(w0); a1.set(w1); } else { a0.add(w0); a1.add(w1); }
             }
         store_words(a.out[rank], k, a.nbytes, u32x2{a0.pack(), a1.pack()});

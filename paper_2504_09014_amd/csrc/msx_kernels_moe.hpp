@@ -191,6 +191,7 @@ __global__ __launch_bounds__(256) void k_moe_pack(MoeArgs a, DevCtx c)
     const int n = a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = per_lane(n);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
     const int lane = (int)(threadIdx.x & 63u);
     const int waves = (int)(blockDim.x >> 6);
@@ -211,7 +212,7 @@ __global__ __launch_bounds__(256) void k_moe_pack(MoeArgs a, DevCtx c)
 #pragma unroll
         for (int d = 0; d < kMaxRanks; ++d) {
             const unsigned r = base[d] + row[d];
-            const bool go = d < n && row[d] != 0xffffu && r < a.cap;
+            const bool go = d < n_l && row[d] != 0xffffu && r < a.cap;
             dst[d] = go ? (char*)a.recv[d] + (size_t)r * row_bytes : nullptr;
             if (go && a.has_src && lane == 0) st32_wt(a.recv_src[d] + r, (unsigned)(rank * a.T + t));
         }
@@ -251,6 +252,7 @@ __global__ __launch_bounds__(256) void k_moe_pack_fp8(MoeArgs a, MoeFp8Args f, D
     const int n = a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = per_lane(n);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
     const int lane = (int)(threadIdx.x & 63u);
     const int waves = (int)(blockDim.x >> 6);
@@ -273,7 +275,7 @@ __global__ __launch_bounds__(256) void k_moe_pack_fp8(MoeArgs a, MoeFp8Args f, D
 #pragma unroll
         for (int d = 0; d < kMaxRanks; ++d) {
             const unsigned r = base[d] + row[d];
-            const bool go = d < n && row[d] != 0xffffu && r < a.cap;
+            const bool go = d < n_l && row[d] != 0xffffu && r < a.cap;
             dq[d] = go ? (char*)a.recv[d] + (size_t)r * q_row : nullptr;
             ds[d] = go ? f.recv_scales[d] + (size_t)r * f.groups : nullptr;
             if (go && a.has_src && lane == 0) st32_wt(a.recv_src[d] + r, (unsigned)(rank * a.T + t));
@@ -325,6 +327,7 @@ __global__ __launch_bounds__(256) void k_moe_combine(MoeArgs a, DevCtx c)
     const int n = a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = per_lane(n);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
     if (n > 1) rank_barrier(c, rank, n, chan, 220, false, false);   // every peer's rows are final
     const int lane = (int)(threadIdx.x & 63u);
@@ -346,7 +349,7 @@ __global__ __launch_bounds__(256) void k_moe_combine(MoeArgs a, DevCtx c)
 #pragma unroll
         for (int d = 0; d < kMaxRanks; ++d) {
             const unsigned r = base[d] + row[d];
-            const bool go = d < n && row[d] != 0xffffu && r < a.cap;
+            const bool go = d < n_l && row[d] != 0xffffu && r < a.cap;
             src[d] = go ? (const char*)a.recv[d] + (size_t)r * row_bytes : nullptr;
         }
         char* dst = out + (size_t)t * row_bytes;

@@ -43,7 +43,7 @@ def test_argument_errors_need_no_device(L):
     odd = C.c_void_p(0x1004)
     ARG, UNSUP = -1, -2
     assert L.msx_allreduce(fake, 16, 7, 0, 8, None) == ARG          # dtype
-    assert L.msx_allreduce(fake, 16, 0, 3, 8, None) == UNSUP        # op
+    assert L.msx_allreduce(fake, 16, 0, 3, 8, None) == UNSUP        # op (sum, max, min exist)
     assert L.msx_allreduce(fake, 16, 0, 0, 0, None) == ARG          # nranks
     assert L.msx_allreduce(fake, 16, 0, 0, 9, None) == ARG
     assert L.msx_allreduce(None, 16, 0, 0, 8, None) == ARG

@@ -370,3 +370,112 @@ def test_e4m3_encoder_on_gpu_covers_every_code_and_tie(msx, orc):
     assert np.all(scales == 1.0)
     for d in range(8):
         assert np.array_equal(rq[d].cpu().numpy(), q), d
+
+
+# ---------------------------------------------------------------- fp16 and max / min
+
+# fp32 / bf16 sums are the tuned paths, tested above: here every other (type, operator) pair
+@pytest.mark.parametrize("n", [1, 2, 3, 8])
+@pytest.mark.parametrize("dt,op", [(0, 1), (0, 2), (1, 1), (1, 2), (2, 0), (2, 1), (2, 2)])
+def test_fp16_and_max_min_allreduce_reducescatter(msx, orc, n, dt, op):
+    tdt = [torch.float32, torch.bfloat16, torch.float16][dt]
+    for count in [1, 7, 8 * n, 1000 * n, 70001 * n]:
+        g = torch.Generator().manual_seed(count + dt + 10 * op)
+        xf = torch.randn(n, count, generator=g) * 3
+        if count > 100:
+            xf[0, 5] = float("inf")
+            xf[n - 1, 6] = float("-inf")
+            xf[0, 7] = 6.0e-6                                   # fp16 subnormal territory
+        x = xf.to(tdt)
+        bits = x.view(torch.uint16).numpy() if dt else x.numpy()
+        want = orc.allreduce_any(bits, dt, op)
+        send = [x[r].clone().cuda() for r in range(n)]
+        recv = [torch.zeros_like(t) for t in send]
+        msx.set_option("chaos", "4")
+        msx.allreduce_ex(send, recv, None, op=op)
+        msx.check_status()
+        for r in range(n):
+            got = recv[r].cpu()
+            got = got.view(torch.uint16).numpy() if dt else got.numpy()
+            assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), (n, dt, op, count, r)
+        if count % n == 0:
+            c = count // n
+            part = [torch.zeros(c, dtype=tdt, device="cuda") for _ in range(n)]
+            msx.reducescatter_ex(send, part, op=op)
+            msx.check_status()
+            for r in range(n):
+                got = part[r].cpu()
+                got = got.view(torch.uint16).numpy() if dt else got.numpy()
+                assert np.array_equal(got.view(np.uint8), want[r * c:(r + 1) * c].view(np.uint8)), (n, dt, op, count, r)
+        msx.set_option("chaos", "0")
+
+
+def test_generic_reduce_refuses_what_it_does_not_cover(msx):
+    send = [torch.zeros(64, dtype=torch.float16, device="cuda") for _ in range(8)]
+    with pytest.raises(msx.MsxError) as e:
+        msx.allreduce_ex(send, send, send)                      # residual with fp16
+    assert e.value.code == -2
+    with pytest.raises(msx.MsxError) as e:
+        msx.allreduce_ex(send, send, None, algo=1)              # no LL form for fp16
+    assert e.value.code == -2
+    f = [torch.zeros(64, dtype=torch.float32, device="cuda") for _ in range(8)]
+    with pytest.raises(msx.MsxError) as e:
+        msx.allreduce_ex(f, f, None, algo=5, op=msx.MAX)        # no ring form for max
+    assert e.value.code == -2
+
+
+def test_copy_collectives_take_fp16(msx, orc):
+    n, c = 8, 1000
+    x = (torch.randn(n, n * c) * 3).half()
+    want = orc.alltoall(x.view(torch.uint16).numpy())
+    buf = x.clone().cuda()
+    msx.alltoall(buf)
+    msx.check_status()
+    assert np.array_equal(buf.cpu().view(torch.uint16).numpy(), want)
+
+
+# ---------------------------------------------------------------- packet kernels, ragged sizes, many calls
+
+def test_packet_kernels_with_a_one_lane_tail_never_stall(msx, orc):
+    """Packet counts that leave a single lane with one more packet than the rest of its wave, every
+    packet kernel, a few thousand calls each: a wave whose lanes leave the send loop at different
+    iterations must not change what the receive loop polls (a wave-uniform condition kept as a lane
+    mask once did, and a rank then waited on its own, never written, slot about once in 600 calls)."""
+    n, calls = 8, 2500
+
+    def hammer(name, fn):
+        for it in range(calls):
+            fn()
+            rc, info = msx.status()
+            assert rc == 0, (name, it, rc, info, msx.get_option("status_detail"))
+
+    for c in [65544, 100]:
+        msx.set_option("coll_algo", "ll")
+        try:
+            y = _tagged(n, c)
+            buf = torch.full((n, n * c), 7.0)
+            for r in range(n):
+                buf[r, r * c:(r + 1) * c] = y[r]
+            d = buf.cuda()
+            hammer(f"allgather c={c}", lambda: msx.allgather(d))
+            assert msx.last_launch()[2] == 1
+            assert np.array_equal(_bits(d).view(np.uint8), orc.allgather(_bits(y)).view(np.uint8))
+            x = _data(n, n * c, torch.float32, seed=c)
+            send = [x[r].clone().cuda() for r in range(n)]
+            recv = [torch.zeros(c, device="cuda") for _ in range(n)]
+            hammer(f"reducescatter c={c}", lambda: msx.reducescatter_ex(send, recv))
+            assert msx.last_launch()[2] == 2
+            want = orc.reducescatter(_bits(x))
+            for r in range(n):
+                assert np.array_equal(_bits(recv[r]), want[r]), (c, r)
+        finally:
+            msx.set_option("coll_algo", "auto")
+    for count in [2 * 32769, 14]:
+        x = _data(n, count, torch.float32, seed=count)
+        want = orc.allreduce_f32(x.numpy())
+        for algo in [msx.ALGO_1PA_LL, msx.ALGO_2PA_LL]:
+            send = [x[r].clone().cuda() for r in range(n)]
+            recv = [torch.zeros(count, device="cuda") for _ in range(n)]
+            hammer(f"allreduce algo={algo} count={count}", lambda: msx.allreduce_ex(send, recv, None, algo=algo))
+            for r in range(n):
+                assert np.array_equal(recv[r].cpu().numpy().view(np.uint8), want.view(np.uint8)), (algo, count, r)
