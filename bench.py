@@ -86,6 +86,11 @@ def median(v):
     return s[len(s) // 2]
 
 
+def pct(v, q):
+    s = sorted(v)
+    return s[min(len(s) - 1, max(0, int(round(q / 100.0 * (len(s) - 1)))))]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -185,6 +190,8 @@ def main():
             "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
             "kernel": "k_allreduce_hb_fused<bf16>", "algorithmic_bytes": alg_bytes,
             "kernel_ms_avg": round(kern_avg, 4), "kernel_ms_min": round(min(kern_ms), 4),
+            "kernel_ms_p10": round(pct(kern_ms, 10), 4), "kernel_ms_median": round(median(kern_ms), 4),
+            "kernel_ms_p90": round(pct(kern_ms, 90), 4),
         },
     }
 
@@ -200,7 +207,7 @@ def main():
     if not args.no_cpu:
         import numpy as np
         import oracle
-        sample = min(count, 256 << 20)                     # at most 512 MiB per rank
+        sample = min(count, 512 << 20)                     # the whole workload up to 1 GiB per rank (about 6 s)
         log(f"[bench] CPU oracle on the first {sample * 2 >> 20} MiB of every rank (single thread)")
         host = np.empty((n, sample), np.uint16)
         for r in range(n):
@@ -236,6 +243,9 @@ def main():
             for name, a in [("ll_us", ll_algo), ("hb_us", msx.ALGO_2PA_HB), ("auto_us", msx.ALGO_AUTO)]:
                 row[name] = round(graph_us(torch, lambda: msx.allreduce_ex(s_, r_, None, algo=a)), 2)
             g, b, a = msx.last_launch()
+            # the same call launched one by one (no graph): what a caller outside a graph pays
+            row["auto_plain_us"] = round(median([back_to_back_us(
+                torch, lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO), 100, 10) for _ in range(5)]), 2)
             row.update({"ll_algo": ll_algo, "auto_algo": a, "auto_grid": g, "auto_block": b})
             lat[f"{kib}KiB"] = row
         msx.check_status()
@@ -249,7 +259,15 @@ def main():
             fn = lambda: msx.allreduce_ex(s_, r_, rr, algo=msx.ALGO_AUTO)
             gus = graph_us(torch, fn)
             g, b, a = msx.last_launch()
-            dec[f"T{T}"] = {"us_in_graph": round(gus, 2), "algo": a, "grid": g}
+            # unfused: the same AllReduce without the residual, then one elementwise add over all ranks' outputs
+            flat = torch.stack(s_).contiguous()
+            rrow = res.cuda().reshape(1, -1)
+
+            def unfused():
+                msx.allreduce(flat)
+                flat.add_(rrow)
+            uus = graph_us(torch, unfused)
+            dec[f"T{T}"] = {"us_in_graph": round(gus, 2), "unfused_us_in_graph": round(uus, 2), "algo": a, "grid": g}
         msx.check_status()
         extras["config4_decode_residual"] = dec
         # config 1
@@ -424,6 +442,23 @@ def main():
         extras["handoff_put_signal_wait_read"] = prim
         extras["hop_ns"] = {"signal_wait_round_trip_cross_xcd": round(msx.prim_pingpong(2000, 16, 0, 1), 1),
                             "signal_wait_round_trip_same_xcd": round(msx.prim_pingpong(2000, 16, 0, 8), 1)}
+        # what a call costs on the host when it is not replayed from a graph: through the Python
+        # binding (tables built per call) and through the C ABI with its arguments built once
+        import ctypes
+        small = torch.zeros((n, 512), dtype=torch.bfloat16, device="cuda")
+        cargs = (ctypes.c_void_p(small.data_ptr()), ctypes.c_size_t(512), ctypes.c_int(msx.BF16), ctypes.c_int(msx.SUM),
+                 ctypes.c_int(n), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        cfn = msx.lib().msx_allreduce
+        extras["plain_launch_us_1KiB"] = {
+            "python_binding": round(median([back_to_back_us(torch, lambda: msx.allreduce(small), 100, 10) for _ in range(5)]), 2),
+            "c_abi_prebuilt_args": round(median([back_to_back_us(torch, lambda: cfn(*cargs), 100, 10) for _ in range(5)]), 2),
+        }
+        # floor of one graph node: a one-wave kernel that copies 64 semaphore words, replayed the same way
+        from paper_2504_09014_amd.binding import _stream
+        snap = torch.zeros(64, dtype=torch.int32, device="cuda")
+        extras["graph_node_floor_us"] = round(graph_us(
+            torch, lambda: msx.lib().msx_prim_barrier(0, n, 1, ctypes.c_void_p(snap.data_ptr()), _stream(None))), 2)
+        msx.check_status()
         out["extras"] = extras
 
     print(json.dumps(out), flush=True)

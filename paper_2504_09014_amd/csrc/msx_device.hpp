@@ -166,28 +166,32 @@ __device__ __forceinline__ void rank_barrier(const DevCtx& c, int me, int n, int
 // ---- per-call flag and scratch rotation for the LL protocol -----------------------------------
 // The flag of a call and the scratch half it uses come from device memory, not from kernel
 // arguments, so a captured launch can be replayed: every workgroup reads the state when it
-// starts, and the LAST workgroup to finish advances it (all others have read it by then).
-struct CallTag { unsigned flag; unsigned rot; };
+// starts and then counts itself in; the workgroup that finds all others counted advances the
+// state when it ends (every workgroup has read it by then).  Counting in at the start keeps the
+// counter's round trip off the end of the kernel, where nothing else is left to hide it.
+struct CallTag { unsigned flag; unsigned rot; unsigned arrivals; unsigned calls; };
 
+// Workgroup-collective; every workgroup of the launch calls it exactly once, first thing.
 __device__ __forceinline__ CallTag call_begin(const DevCtx& c)
 {
     const unsigned e = c.call_state[0], k = c.call_state[1];
+    asm volatile("" ::"s"(e), "s"(k));   // both values have arrived before the barrier below
+    __syncthreads();                     // ... in every wave of this workgroup
+    unsigned arrivals = 0u;
+    if (threadIdx.x == 0)
+        arrivals = __hip_atomic_fetch_add(c.call_state + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned f = e + 1u;
     if (f == 0u) f = 1u;            // 0 is what untouched scratch holds
-    return CallTag{f, k & 1u};
+    return CallTag{f, k & 1u, arrivals, k};
 }
 
-// Workgroup-collective; every workgroup of the launch must call it exactly once, at its end.
+// Every workgroup calls it exactly once, at its end (any path).
 __device__ __forceinline__ void call_end(const DevCtx& c, CallTag tag)
 {
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned done = __hip_atomic_fetch_add(c.call_state + 2, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (done == gridDim.x - 1u) {
-            __hip_atomic_store(c.call_state + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(c.call_state + 0, tag.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(c.call_state + 1, c.call_state[1] + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+    if (threadIdx.x == 0 && tag.arrivals == gridDim.x - 1u) {
+        __hip_atomic_store(c.call_state + 2, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(c.call_state + 0, tag.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(c.call_state + 1, tag.calls + 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 }
 

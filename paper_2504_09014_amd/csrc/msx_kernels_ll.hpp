@@ -73,19 +73,22 @@ __global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
     const int n_l = NR ? NR : per_lane(n), rank_l = per_lane(rank);   // per-lane copies for conditions (see per_lane)
-    const CallTag tag = call_begin(c);
-    if (rank == c.drop_rank) { call_end(c, tag); return; }
-    const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
     const unsigned P = (unsigned)((a.nbytes + 7) / 8);          // packets per rank
     const unsigned RT = (unsigned)a.chans * blockDim.x;
     const unsigned rt = (unsigned)chan * blockDim.x + threadIdx.x;
+    // the payload of my first packet is requested before the call state, so both arrive together
+    u32x2 first = {0u, 0u};
+    if (rt < P) first = load_words(a.in[rank], rt, a.nbytes);
+    const CallTag tag = call_begin(c);
+    if (rank == c.drop_rank) { call_end(c, tag); return; }
+    const __amdgpu_buffer_rsrc_t rs = ll_resource(c);
     const unsigned slot_stride = P * 16u;
     const unsigned rot_off = tag.rot * c.ll_rot_stride;
     chaos_delay(c, 70);
 
     // send: my packet k goes to slot `rank` of every peer, all peers before any wait
     for (unsigned k = rt; k < P; k += RT) {
-        const u32x2 w = load_words(a.in[rank], k, a.nbytes);
+        const u32x2 w = k == rt ? first : load_words(a.in[rank], k, a.nbytes);
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
             if (p < n_l && p != rank_l)
@@ -95,7 +98,9 @@ __global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
     // receive + reduce in rank order 0..n-1 (identical bits on every rank)
     const unsigned my_off = (unsigned)rank * c.ll_rank_stride + rot_off;
     for (unsigned k = rt; k < P; k += RT) {
-        const u32x2 own = load_words(a.in[rank], k, a.nbytes);
+        const u32x2 own = k == rt ? first : load_words(a.in[rank], k, a.nbytes);
+        u32x2 r = {0u, 0u};
+        if (a.has_res) r = load_words(a.res[rank], k, a.nbytes);     // in flight during the poll
         u32x4 v[kMaxRanks];
         MSX_LL_POLL_ALL(v, my_off, slot_stride, k)
         WordAcc<DT> a0, a1;
@@ -106,10 +111,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
                 const unsigned w1 = j == rank_l ? own.y : v[j].z;
                 if (j == 0) { a0.set(w0); a1.set(w1); } else { a0.add(w0); a1.add(w1); }
             }
-        if (a.has_res) {
-            const u32x2 r = load_words(a.res[rank], k, a.nbytes);
-            a0.add(r.x); a1.add(r.y);
-        }
+        if (a.has_res) { a0.add(r.x); a1.add(r.y); }
         store_words(a.out[rank], k, a.nbytes, u32x2{a0.pack(), a1.pack()});
     }
     call_end(c, tag);
