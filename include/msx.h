@@ -222,7 +222,7 @@ int msx_finalize(void);
  *   "coll_ll_max_bytes"   auto: LL up to this many bytes per block
  *   "ll_max_bytes"    largest per-rank message the LL scratch is sized for (set before init)
  *   "hb_blocks_per_rank", "ll_blocks_per_rank", "threads"   0 = automatic
- *   "hb_unroll"       1 | 2 | 4
+ *   "hb_unroll"       0 (by size) | 1 | 2 | 4 | 8 (8: AllGather only)   vectors in flight per thread
  *   "hb_barriers"     0 | 1   start/end rank barriers in the HB kernels
  *   "peer_outer"      0 | 1   two-phase HB all-gather: one put per peer instead of peer-inner
  *   "barrier_fences"  0..3    msx_prim_barrier only: bit 0 release fence, bit 1 acquire fence
@@ -231,6 +231,8 @@ int msx_finalize(void);
  *   "chaos"           0, or a seed: workgroups sleep pseudo-random times before they signal
  *   "epoch"           next LL flag value (tests of wrap-around; synchronises the device)
  *   "sem_base"        set every semaphore and expected value to this number (wrap tests; syncs)
+ * Read-only (msx_get_option): "status_detail" = for the last timeout msx_status() reported from a packet
+ * poll, the source rank whose packet was still missing.
  * Unknown key or bad value -> MSX_ERR_ARG. */
 int msx_set_option(const char* key, const char* value);
 int msx_get_option(const char* key, char* value_out, size_t value_len);

@@ -735,6 +735,20 @@ int use_ll_coll(size_t nbytes, bool aligned8)
 
 enum HbOther { kRS, kAG, kA2A, kA2AInplace };
 
+// AllGather kernel by vectors in flight per thread: a write-only stream to 8 destinations gains about 5 %
+// from 8 (measured), short blocks stay at 2
+const void* ag_kernel(size_t vectors_per_rank)
+{
+    int u = g_opt.hb_unroll;
+    if (u == 0) u = vectors_per_rank >= (size_t)8 * 128 * 256 ? 8 : 2;
+    switch (u) {
+        case 1: return (const void*)k_allgather_hb<1>;
+        case 4: return (const void*)k_allgather_hb<4>;
+        case 8: return (const void*)k_allgather_hb<8>;
+        default: return (const void*)k_allgather_hb<2>;
+    }
+}
+
 int hb_other(HbOther which, const void* const* in, void* const* out, size_t count_or_bytes, int dtype,
              int nranks, int vec, size_t work_units, hipStream_t stream)
 {
@@ -746,7 +760,7 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     const void* kp = nullptr;
     switch (which) {
         case kRS: kp = dtype == MSX_F32 ? (const void*)k_reducescatter_hb<0, 2> : (const void*)k_reducescatter_hb<1, 2>; break;
-        case kAG: kp = (const void*)k_allgather_hb; break;
+        case kAG: kp = ag_kernel(work_units); break;
         case kA2A: kp = (const void*)k_alltoall_hb; break;
         case kA2AInplace: kp = (const void*)k_alltoall_inplace; break;
     }
@@ -770,7 +784,10 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
         case kRS:
             if (dtype == MSX_F32) return launch(k_reducescatter_hb<0, 2>, n * chans, threads, stream, a, d, vec);
             return launch(k_reducescatter_hb<1, 2>, n * chans, threads, stream, a, d, vec);
-        case kAG: return launch(k_allgather_hb, n * chans, threads, stream, a, d, vec);
+        case kAG: {
+            typedef void (*K)(HbArgs, DevCtx, int);
+            return launch((K)kp, n * chans, threads, stream, a, d, vec);
+        }
         case kA2A: return launch(k_alltoall_hb, n * chans, threads, stream, a, d, vec);
         case kA2AInplace: return launch(k_alltoall_inplace, n * chans, threads, stream, a, d, vec);
     }
@@ -1291,7 +1308,7 @@ int msx_set_option(const char* key, const char* value)
         if (u > 1024) return MSX_ERR_ARG;
         g_opt.threads = (int)u;
     } else if (k == "hb_unroll") {
-        if (u != 0 && u != 1 && u != 2 && u != 4) return MSX_ERR_ARG;
+        if (u != 0 && u != 1 && u != 2 && u != 4 && u != 8) return MSX_ERR_ARG;
         g_opt.hb_unroll = (int)u;
     } else if (k == "hb_barriers") {
         if (u > 1) return MSX_ERR_ARG;

@@ -251,6 +251,7 @@ __global__ __launch_bounds__(256) void k_reducescatter_hb(HbArgs a, DevCtx c, in
 // ---- standalone AllGather: out[p] block r = in[r]; a.count = bytes per block ------------------
 // Put-based: rank r reads its block once and writes it into every rank's output (peer loop
 // inside the element loop).  A destination equal to the source (in-place) is skipped.
+template <int U>
 __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int vec)
 {
     const int n = a.n;
@@ -263,21 +264,31 @@ __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int ve
     const size_t nbytes = a.count;
     const char* src = (const char*)a.in[rank];
     char* dst[kMaxRanks];
+    int skip = -1;                       // the destination that is the source itself (in place)
 #pragma unroll
-    for (int p = 0; p < kMaxRanks; ++p) dst[p] = p < n ? (char*)a.out[p] + (size_t)rank * nbytes : nullptr;
+    for (int p = 0; p < kMaxRanks; ++p) {
+        dst[p] = p < n ? (char*)a.out[p] + (size_t)rank * nbytes : nullptr;
+        if (p < n && dst[p] == src) skip = p;
+    }
+    const int skip_l = per_lane(skip);
     if (vec) {
         const size_t nv = nbytes >> 4;
-        for (size_t i = rt; i < nv; i += RT * 2) {
-            const size_t i1 = i + RT;
-            const u32x4 v0 = ld16(src, i);
-            u32x4 v1 = v0;
-            if (i1 < nv) v1 = ld16(src, i1);
+        for (size_t i = rt; i < nv; i += RT * U) {
+            u32x4 v[U];
 #pragma unroll
-            for (int p = 0; p < kMaxRanks; ++p)
-                if (p < n_l && dst[p] != src) {
-                    st16_wt(dst[p], i, v0);
-                    if (i1 < nv) st16_wt(dst[p], i1, v1);
+            for (int u = 0; u < U; ++u) {
+                const size_t iu = i + (size_t)u * RT;
+                if (iu < nv) v[u] = ld16(src, iu);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const size_t iu = i + (size_t)u * RT;
+                if (iu < nv) {
+#pragma unroll
+                    for (int p = 0; p < kMaxRanks; ++p)
+                        if (p < n_l && p != skip_l) st16_wt(dst[p], iu, v[u]);
                 }
+            }
         }
     } else {
         for (size_t b = rt; b < nbytes; b += RT) {
