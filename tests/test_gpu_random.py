@@ -73,3 +73,129 @@ def test_random_allreduce_cases(msx, orc, seed):
             assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), \
                 dict(seed=seed, case=case, n=n, bf16=bf16, count=count, algo=algo, res=res_mode, inplace=inplace, rank=r)
     msx.set_option("chaos", "0")
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_random_reducescatter_allgather_alltoall_cases(msx, orc, seed):
+    """HB and packet forms, in place and out of place, every element type; reduce-scatter also with max / min."""
+    rng = np.random.default_rng(2000 + seed)
+    tdt = [torch.float32, torch.bfloat16, torch.float16]
+    for case in range(50):
+        n = int(rng.choice([1, 2, 3, 5, 8]))
+        dt = int(rng.integers(0, 3))
+        op = int(rng.choice([0, 0, 1, 2]))
+        c = int(rng.choice([rng.integers(1, 40), rng.integers(40, 3000), rng.integers(3000, 40000)]))
+        coll_algo = str(rng.choice(["auto", "hb", "ll"]))
+        inplace = bool(rng.integers(0, 2))
+        if inplace:
+            c = max(8, c // 8 * 8)                              # the rows of an in-place buffer are 16-byte aligned
+        if coll_algo == "ll" and ((c * (4 if dt == 0 else 2)) % 8 or dt == 2 or op):
+            coll_algo = "hb"                                    # packets carry whole 8-byte units of fp32 / bf16 sums
+        tag = dict(seed=seed, case=case, n=n, dt=dt, op=op, c=c, coll=coll_algo, inplace=inplace)
+        msx.set_option("coll_algo", coll_algo)
+        msx.set_option("chaos", str(int(rng.integers(0, 50))))
+        try:
+            x = (torch.randn(n, n * c, generator=torch.Generator().manual_seed(seed * 1000 + case)) * 3).to(tdt[dt])
+            xb = x.numpy() if dt == 0 else x.view(torch.uint16).numpy()
+            # reduce-scatter
+            want = orc.allreduce_any(xb, dt, op).reshape(n, c)
+            if inplace:
+                buf = x.clone().cuda()
+                msx.reducescatter(buf, op=op)
+                msx.check_status()
+                got = buf.cpu()
+                got = got.numpy() if dt == 0 else got.view(torch.uint16).numpy()
+                for r in range(n):
+                    assert np.array_equal(got[r, r * c:(r + 1) * c].view(np.uint8), want[r].view(np.uint8)), ("rs", tag, r)
+                    keep = np.ones(n * c, bool)
+                    keep[r * c:(r + 1) * c] = False
+                    assert np.array_equal(got[r][keep].view(np.uint8), xb[r][keep].view(np.uint8)), ("rs untouched", tag, r)
+            else:
+                send = [x[r].clone().cuda() for r in range(n)]
+                recv = [torch.zeros(c, dtype=tdt[dt], device="cuda") for _ in range(n)]
+                msx.reducescatter_ex(send, recv, op=op)
+                msx.check_status()
+                for r in range(n):
+                    got = recv[r].cpu()
+                    got = got.numpy() if dt == 0 else got.view(torch.uint16).numpy()
+                    assert np.array_equal(got.view(np.uint8), want[r].view(np.uint8)), ("rs", tag, r)
+            # all-gather of the first block of every row, all-to-all of the whole rows
+            y = x[:, :c].contiguous()
+            yb = y.numpy() if dt == 0 else y.view(torch.uint16).numpy()
+            want_ag = orc.allgather(yb)
+            want_a2a = orc.alltoall(xb)
+            if inplace:
+                buf = torch.zeros((n, n * c), dtype=tdt[dt])
+                for r in range(n):
+                    buf[r, r * c:(r + 1) * c] = y[r]
+                buf = buf.cuda()
+                msx.allgather(buf)
+                got = buf.cpu()
+                a2a = x.clone().cuda()
+                msx.alltoall(a2a)
+                got2 = a2a.cpu()
+            else:
+                send = [y[r].clone().cuda() for r in range(n)]
+                recv = [torch.zeros(n * c, dtype=tdt[dt], device="cuda") for _ in range(n)]
+                msx.allgather_ex(send, recv)
+                got = torch.stack([t.cpu() for t in recv])
+                send2 = [x[r].clone().cuda() for r in range(n)]
+                recv2 = [torch.zeros(n * c, dtype=tdt[dt], device="cuda") for _ in range(n)]
+                msx.alltoall_ex(send2, recv2)
+                got2 = torch.stack([t.cpu() for t in recv2])
+            msx.check_status()
+            got = got.numpy() if dt == 0 else got.view(torch.uint16).numpy()
+            got2 = got2.numpy() if dt == 0 else got2.view(torch.uint16).numpy()
+            assert np.array_equal(got.view(np.uint8), want_ag.view(np.uint8)), ("ag", tag)
+            assert np.array_equal(got2.view(np.uint8), want_a2a.view(np.uint8)), ("a2a", tag)
+        finally:
+            msx.set_option("coll_algo", "auto")
+            msx.set_option("chaos", "0")
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_random_dispatch_and_combine_cases(msx, orc, seed):
+    """Token counts, hidden sizes, top-k widths, expert counts and rank counts at random; receive buffers
+    sometimes too small (rows beyond the capacity are dropped and reported on both sides)."""
+    rng = np.random.default_rng(3000 + seed)
+    for case in range(12):
+        n = int(rng.choice([1, 2, 4, 8]))
+        T = int(rng.integers(1, 200))
+        H = int(rng.choice([8, 64, 128, 1000 // 8 * 8, 2048]))
+        per_rank = int(rng.choice([1, 2, 4]))
+        E = n * per_rank
+        K = int(rng.integers(1, min(E, 8) + 1))
+        tight = bool(rng.integers(0, 4) == 0)
+        tag = dict(seed=seed, case=case, n=n, T=T, H=H, E=E, K=K, tight=tight)
+        tokens = synth.moe_tokens(n, T, H, seed=seed * 100 + case)
+        topk = synth.moe_routing(n, T, K, E, seed=seed * 100 + case)
+        full = orc.moe_dispatch(_bits(tokens).reshape(n, T, H), topk.numpy(), E)
+        most = int(full[2].sum(axis=1).max())
+        cap = max(1, most // 2) if tight and most > 1 else max(1, most)
+        recv_w, src_w, counts_w, rc_w = orc.moe_dispatch(_bits(tokens).reshape(n, T, H), topk.numpy(), E, cap=cap)
+        tok = [tokens[r].clone().cuda() for r in range(n)]
+        idx = [topk[r].clone().cuda() for r in range(n)]
+        recv = [torch.zeros((cap, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        src = [torch.full((cap,), -1, dtype=torch.int32, device="cuda") for _ in range(n)]
+        counts = torch.zeros((n, n), dtype=torch.int32, device="cuda")
+        msx.moe_dispatch(tok, idx, E, recv, counts, src)
+        rc, info = msx.status()
+        assert (rc == -6) == (rc_w != 0), (tag, rc, info, rc_w)
+        assert rc in (0, -6), (tag, rc, info)
+        # the counts are what was routed (also when rows had to be dropped), the rows that fit are the first `cap`
+        assert np.array_equal(counts.cpu().numpy(), full[2]), tag
+        for d in range(n):
+            used = int(min(cap, full[2][d].sum()))
+            assert np.array_equal(src[d].cpu().numpy()[:used], src_w[d][:used]), (tag, d)
+            assert np.array_equal(_bits(recv[d])[:used], recv_w[d][:used]), (tag, d)
+        if rc == 0:
+            # the way back: the "experts" scale every row by a small integer that depends on the destination
+            y = [(recv[d].float() * float(d % 3 + 1)).to(torch.bfloat16) for d in range(n)]
+            out = [torch.zeros((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            msx.moe_combine(y, out)
+            msx.check_status()
+            yb = np.stack([_bits(t) for t in y])
+            want, rc2 = orc.moe_combine_bf16(yb, topk.numpy(), E)
+            assert rc2 == 0
+            for s in range(n):
+                assert np.array_equal(_bits(out[s]), want[s]), (tag, s)
