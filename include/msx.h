@@ -223,6 +223,8 @@ int msx_finalize(void);
  *   "ll_max_bytes"    largest per-rank message the LL scratch is sized for (set before init)
  *   "hb_blocks_per_rank", "ll_blocks_per_rank", "threads"   0 = automatic
  *   "hb_unroll"       0 (by size) | 1 | 2 | 4 | 8 (8: AllGather only)   vectors in flight per thread
+ *   "cache_mode"      auto | 0 | 1 | 2   fused HB AllReduce: 0 streaming loads and stores, 1 stores may stay in
+ *                     the memory-side cache, 2 loads too; auto picks by the footprint of the call
  *   "hb_barriers"     0 | 1   start/end rank barriers in the HB kernels
  *   "peer_outer"      0 | 1   two-phase HB all-gather: one put per peer instead of peer-inner
  *   "barrier_fences"  0..3    msx_prim_barrier only: bit 0 release fence, bit 1 acquire fence

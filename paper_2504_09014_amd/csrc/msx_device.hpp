@@ -313,6 +313,11 @@ __device__ __forceinline__ u32x4 ld16(const void* base, size_t vec_index)
 {
     return __builtin_nontemporal_load((const u32x4*)base + vec_index);
 }
+// the same load without the streaming hint: the line may stay in the caches
+__device__ __forceinline__ u32x4 ld16_keep(const void* base, size_t vec_index)
+{
+    return *((const u32x4*)base + vec_index);
+}
 __device__ __forceinline__ void st16(void* base, size_t vec_index, u32x4 v)
 {
     __builtin_nontemporal_store(v, (u32x4*)base + vec_index);
@@ -333,6 +338,13 @@ __device__ __forceinline__ void st16_wt(void* base, size_t vec_index, u32x4 v)
 {
     u32x4* p = (u32x4*)base + vec_index;
     asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+}
+// the same write-through store without the streaming hint: the memory-side cache may keep the line, which
+// pays while everything a call writes fits into it (measured: 6.7 instead of 5.6 TB/s at 32 MiB per rank)
+__device__ __forceinline__ void st16_wt_keep(void* base, size_t vec_index, u32x4 v)
+{
+    u32x4* p = (u32x4*)base + vec_index;
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
 __device__ __forceinline__ void st8_wt(void* addr, u32x2 v)
 {

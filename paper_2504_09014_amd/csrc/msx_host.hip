@@ -41,6 +41,7 @@ struct Options {
     size_t ll_max_bytes = 4u << 20;
     int hb_blocks = 0, ll_blocks = 0, threads = 0;
     int hb_unroll = 0;        // 0 = by size
+    int cache_mode = -1;      // -1 = by footprint, else 0 | 1 | 2 (see choose_cache_mode)
     int hb_barriers = 1;
     int peer_outer = 0;
     int barrier_fences = 3;   // msx_prim_barrier only: bit 0 release, bit 1 acquire
@@ -337,12 +338,21 @@ int launch(K k, int grid, int block, hipStream_t s, A... args)
 typedef void (*HbKernel)(HbArgs, DevCtx);
 typedef void (*LlKernel)(LlArgs, DevCtx);
 
-HbKernel hb_fused_kernel(int dt, int u, int n, int res)
+HbKernel hb_fused_kernel(int dt, int u, int n, int res, int cache)
 {
 #define MSX_N(DT, U, RES) (n == 8 ? (HbKernel)k_allreduce_hb_fused<DT, U, 8, RES> : (HbKernel)k_allreduce_hb_fused<DT, U, 0, RES>)
 #define MSX_R(DT, U) (res == 0 ? MSX_N(DT, U, 0) : res == 1 ? MSX_N(DT, U, 1) : MSX_N(DT, U, 2))
+    // cache-keeping forms: 8 ranks, the unrolls the automatic choice uses
+#define MSX_C(DT, U, RES) (cache == 1 ? (HbKernel)k_allreduce_hb_fused<DT, U, 8, RES, 1> : (HbKernel)k_allreduce_hb_fused<DT, U, 8, RES, 2>)
+#define MSX_CR(DT, U) (res == 0 ? MSX_C(DT, U, 0) : res == 1 ? MSX_C(DT, U, 1) : MSX_C(DT, U, 2))
+    if (cache != 0 && n == 8 && (u == 1 || u == 2)) {
+        if (dt == MSX_F32) return u == 2 ? MSX_CR(0, 2) : MSX_CR(0, 1);
+        return u == 2 ? MSX_CR(1, 2) : MSX_CR(1, 1);
+    }
     if (dt == MSX_F32) return u >= 4 ? MSX_R(0, 4) : u == 2 ? MSX_R(0, 2) : MSX_R(0, 1);
     return u >= 4 ? MSX_R(1, 4) : u == 2 ? MSX_R(1, 2) : MSX_R(1, 1);
+#undef MSX_CR
+#undef MSX_C
 #undef MSX_R
 #undef MSX_N
 }
@@ -404,6 +414,18 @@ void choose_hb_shape(size_t nbytes, int n, int threads, int* unroll, int* want)
     }
     *unroll = U;
     *want = w;
+}
+
+// Cache hints of the fused HB AllReduce by footprint (inputs + outputs of all ranks), from a sweep: up to
+// 64 MiB everything may stay cached, up to 512 MiB (the outputs then just fill the 256 MiB memory-side cache)
+// the stores may, beyond that both stream.
+int choose_cache_mode(size_t nbytes, int n)
+{
+    if (g_opt.cache_mode >= 0) return g_opt.cache_mode;
+    const size_t footprint = 2 * (size_t)n * nbytes;
+    if (footprint <= ((size_t)64 << 20)) return 2;
+    if (footprint <= ((size_t)512 << 20)) return 1;
+    return 0;
 }
 
 // ---- lowering of an AllReduce to an execution plan (the host half of the Executor analogue) ------------
@@ -668,7 +690,8 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     int U = 1, want = 1;
     choose_hb_shape(nbytes, n, threads, &U, &want);
     if (algo == MSX_ALGO_2PA_HB_2PHASE && U > 2) U = 2;
-    HbKernel k = algo == MSX_ALGO_2PA_HB ? hb_fused_kernel(dtype, U, n, !residual ? 0 : res_shared ? 1 : 2)
+    HbKernel k = algo == MSX_ALGO_2PA_HB ? hb_fused_kernel(dtype, U, n, !residual ? 0 : res_shared ? 1 : 2,
+                                                           choose_cache_mode(nbytes, n))
                                          : hb_2phase_kernel(dtype, U, n);
     int chans = 1;
     if ((rc = pick_channels(c, (const void*)k, threads, n, per_rank, (size_t)U, want, kMaxChannels, &chans)))
@@ -737,15 +760,15 @@ enum HbOther { kRS, kAG, kA2A, kA2AInplace };
 
 // AllGather kernel by vectors in flight per thread: a write-only stream to 8 destinations gains about 5 %
 // from 8 (measured), short blocks stay at 2
-const void* ag_kernel(size_t vectors_per_rank)
+const void* ag_kernel(size_t vectors_per_rank, int keep)
 {
     int u = g_opt.hb_unroll;
     if (u == 0) u = vectors_per_rank >= (size_t)8 * 128 * 256 ? 8 : 2;
     switch (u) {
         case 1: return (const void*)k_allgather_hb<1>;
         case 4: return (const void*)k_allgather_hb<4>;
-        case 8: return (const void*)k_allgather_hb<8>;
-        default: return (const void*)k_allgather_hb<2>;
+        case 8: return keep ? (const void*)k_allgather_hb<8, 1> : (const void*)k_allgather_hb<8>;
+        default: return keep ? (const void*)k_allgather_hb<2, 1> : (const void*)k_allgather_hb<2>;
     }
 }
 
@@ -758,10 +781,14 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     if (rc) return rc;
     const int n = nranks, threads = 256;
     const void* kp = nullptr;
+    // everything the call writes (n x n blocks) fits the memory-side cache: let the stores stay there
+    const size_t block_bytes = which == kRS ? 0 : count_or_bytes;
+    const int keep = g_opt.cache_mode >= 0 ? (g_opt.cache_mode != 0)
+                                           : (block_bytes * (size_t)n * (size_t)n <= ((size_t)256 << 20));
     switch (which) {
         case kRS: kp = dtype == MSX_F32 ? (const void*)k_reducescatter_hb<0, 2> : (const void*)k_reducescatter_hb<1, 2>; break;
-        case kAG: kp = ag_kernel(work_units); break;
-        case kA2A: kp = (const void*)k_alltoall_hb; break;
+        case kAG: kp = ag_kernel(work_units, keep); break;
+        case kA2A: kp = keep ? (const void*)k_alltoall_hb<1> : (const void*)k_alltoall_hb<0>; break;
         case kA2AInplace: kp = (const void*)k_alltoall_inplace; break;
     }
     // workgroups per rank for large inputs, from a sweep: the read-heavy reduce-scatter runs best
@@ -788,7 +815,10 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
             typedef void (*K)(HbArgs, DevCtx, int);
             return launch((K)kp, n * chans, threads, stream, a, d, vec);
         }
-        case kA2A: return launch(k_alltoall_hb, n * chans, threads, stream, a, d, vec);
+        case kA2A: {
+            typedef void (*K)(HbArgs, DevCtx, int);
+            return launch((K)kp, n * chans, threads, stream, a, d, vec);
+        }
         case kA2AInplace: return launch(k_alltoall_inplace, n * chans, threads, stream, a, d, vec);
     }
     return MSX_ERR_ARG;
@@ -1291,6 +1321,12 @@ int msx_set_option(const char* key, const char* value)
         g_opt.drop_rank = (int)u;
         return MSX_OK;
     }
+    if (k == "cache_mode") {
+        if (v == "auto") { g_opt.cache_mode = -1; return MSX_OK; }
+        if (!parse_u64(value, &u) || u > 2) return MSX_ERR_ARG;
+        g_opt.cache_mode = (int)u;
+        return MSX_OK;
+    }
     if (!parse_u64(value, &u)) return MSX_ERR_ARG;
     if (k == "ll_1pa_max_bytes") g_opt.ll_1pa_max = (size_t)u;
     else if (k == "ll_2pa_max_bytes") g_opt.ll_2pa_max = (size_t)u;
@@ -1381,6 +1417,10 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
     else if (k == "ll_blocks_per_rank") u = (unsigned)g_opt.ll_blocks;
     else if (k == "threads") u = (unsigned)g_opt.threads;
     else if (k == "hb_unroll") u = (unsigned)g_opt.hb_unroll;
+    else if (k == "cache_mode") {
+        snprintf(value_out, value_len, "%s", g_opt.cache_mode < 0 ? "auto" : g_opt.cache_mode == 0 ? "0" : g_opt.cache_mode == 1 ? "1" : "2");
+        return MSX_OK;
+    }
     else if (k == "hb_barriers") u = (unsigned)g_opt.hb_barriers;
     else if (k == "peer_outer") u = (unsigned)g_opt.peer_outer;
     else if (k == "barrier_fences") u = (unsigned)g_opt.barrier_fences;

@@ -75,7 +75,9 @@ __device__ __forceinline__ void allreduce_tail(const HbArgs& a, int n_l, size_t 
 // two local buffers to all N ranks.)  In place is safe: chunk r of every row is read and
 // written by rank r's threads only, and a thread loads all N values before it stores.
 // RES: 0 no residual, 1 one residual shared by all ranks, 2 one residual per destination.
-template <int DT, int U, int NR, int RES>
+// CACHE: 0 streaming loads and stores (large messages), 1 stores may stay in the memory-side cache,
+// 2 loads and stores may stay in the caches (the host picks by the call's footprint).
+template <int DT, int U, int NR, int RES, int CACHE = 0>
 __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
 {
     const int n = NR ? NR : a.n;
@@ -98,7 +100,11 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const size_t idx = i + (size_t)u * RT;
-            if (idx < hi) { MSX_LOAD_ALL(v[u], a.in, idx) }
+            if (idx < hi) {
+#pragma unroll
+                for (int j = 0; j < kMaxRanks; ++j)
+                    if (j < n_l) v[u][j] = CACHE == 2 ? ld16_keep(a.in[j], idx) : ld16(a.in[j], idx);
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -111,14 +117,14 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
                     const u32x4 o = acc.pack();
 #pragma unroll
                     for (int p = 0; p < kMaxRanks; ++p)
-                        if (p < n_l) st16_wt(a.out[p], idx, o);
+                        if (p < n_l) { if constexpr (CACHE == 0) st16_wt(a.out[p], idx, o); else st16_wt_keep(a.out[p], idx, o); }
                 } else {
 #pragma unroll
                     for (int p = 0; p < kMaxRanks; ++p)
                         if (p < n_l) {
                             VecAcc<DT> t = acc;
                             t.add(ld16(a.res[p], idx));
-                            st16_wt(a.out[p], idx, t.pack());
+                            if constexpr (CACHE == 0) st16_wt(a.out[p], idx, t.pack()); else st16_wt_keep(a.out[p], idx, t.pack());
                         }
                 }
             }
@@ -251,7 +257,8 @@ __global__ __launch_bounds__(256) void k_reducescatter_hb(HbArgs a, DevCtx c, in
 // ---- standalone AllGather: out[p] block r = in[r]; a.count = bytes per block ------------------
 // Put-based: rank r reads its block once and writes it into every rank's output (peer loop
 // inside the element loop).  A destination equal to the source (in-place) is skipped.
-template <int U>
+// KEEP: the stores may stay in the memory-side cache (blocks whose copies all fit into it)
+template <int U, int KEEP = 0>
 __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int vec)
 {
     const int n = a.n;
@@ -286,7 +293,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int ve
                 if (iu < nv) {
 #pragma unroll
                     for (int p = 0; p < kMaxRanks; ++p)
-                        if (p < n_l && p != skip_l) st16_wt(dst[p], iu, v[u]);
+                        if (p < n_l && p != skip_l) { if constexpr (KEEP) st16_wt_keep(dst[p], iu, v[u]); else st16_wt(dst[p], iu, v[u]); }
                 }
             }
         }
@@ -302,6 +309,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int ve
 }
 
 // ---- standalone AllToAll (out of place): out[d] block s = in[s] block d; a.count = bytes/block ---
+template <int KEEP>
 __global__ __launch_bounds__(256) void k_alltoall_hb(HbArgs a, DevCtx c, int vec)
 {
     const int n = a.n;
@@ -322,7 +330,10 @@ __global__ __launch_bounds__(256) void k_alltoall_hb(HbArgs a, DevCtx c, int vec
                 if (d < n_l) v[d] = ld16(src + (size_t)d * nbytes, i);
 #pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)
-                if (d < n_l) st16_wt((char*)a.out[d] + (size_t)rank * nbytes, i, v[d]);
+                if (d < n_l) {
+                    if constexpr (KEEP) st16_wt_keep((char*)a.out[d] + (size_t)rank * nbytes, i, v[d]);
+                    else st16_wt((char*)a.out[d] + (size_t)rank * nbytes, i, v[d]);
+                }
         }
     } else {
         for (int d = 0; d < n; ++d) {
