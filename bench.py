@@ -296,6 +296,21 @@ def main():
             torch.cuda.empty_cache()
         msx.check_status()
         extras["config3_other_sizes"] = c3
+        # the whole message-size axis of the paper's AllReduce figures, automatic choice, bf16
+        sw = {}
+        for kib in [1, 4, 16, 64, 256, 1024, 4096, 16384, 65536, 262144]:
+            c = kib * 1024 // 2
+            xs = synth.normal(n, c, seed=kib + 5, device="cuda")
+            s_ = [xs[r] for r in range(n)]
+            r_ = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            fn = lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO)
+            us = graph_us(torch, fn, calls=20, replays=5) if kib <= 16384 else median(time_calls(torch, fn, 10, 3)[1])
+            g, b, a = msx.last_launch()
+            sw[f"{kib}KiB"] = {"us": round(us, 2), "algbw_GBps": round(c * 2 / us / 1e3, 1), "algo": a, "grid": g}
+            del xs, s_, r_
+            torch.cuda.empty_cache()
+        msx.check_status()
+        extras["allreduce_auto_sweep"] = sw
         # two-phase ring over put/signal/wait hand-offs, next to the all-pairs form
         ring = {}
         for mib in [1, 64, 256]:
