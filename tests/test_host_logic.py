@@ -178,9 +178,11 @@ def test_automatic_choice_and_launch_shapes(L):
     assert choose(1024)[0] == 1 and choose(2048)[0] == 1          # tiny: one-phase LL
     assert choose(2049)[0] == 3 and choose(1 << 30)[0] == 3       # everything else: fused HB
     assert choose(1024, n=1)[0] == 3                              # a single rank is a copy
-    # launch shapes: one pass with two vectors per thread up to 4 MiB per rank, then 32, then 128 workgroups
-    assert choose(64 << 10) == (3, 2, 1)
-    assert choose(1 << 20) == (3, 2, 16)
+    # launch shapes: one pass with one vector per thread up to 2 MiB per rank, two up to 4 MiB, then 32, then
+    # 128 workgroups per rank
+    assert choose(64 << 10) == (3, 1, 2)
+    assert choose(1 << 20) == (3, 1, 32)
+    assert choose(2 << 20) == (3, 1, 64)
     assert choose(4 << 20) == (3, 2, 64)
     assert choose(32 << 20) == (3, 1, 32)
     assert choose(64 << 20) == (3, 1, 128)
