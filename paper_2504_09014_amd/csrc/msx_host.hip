@@ -793,11 +793,13 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
         case kA2A: kp = keep ? (const void*)k_alltoall_hb<1> : (const void*)k_alltoall_hb<0>; break;
         case kA2AInplace: kp = (const void*)k_alltoall_inplace; break;
     }
-    // workgroups per rank for large inputs, from a sweep: the read-heavy reduce-scatter runs best
-    // with few workgroups per rank, the write-heavy copies with many
-    const int cap = which == kRS ? 32 : 128;
+    // workgroups per rank, from sweeps: one vector per thread in a single pass while that fits (small and
+    // mid sizes are latency bound: 64 KiB rows 4.8 -> 4.2 us reduce-scatter, 7.9 -> 5.4 us all-gather); for
+    // large inputs the read-heavy reduce-scatter runs best with few workgroups per rank (32; 64 up to
+    // 64 MiB blocks), the write-heavy copies with many
+    const int cap = which == kRS ? (work_units <= ((size_t)4 << 20) ? 64 : 32) : 128;
     int chans = 1;
-    if ((rc = pick_channels(c, kp, threads, n, work_units, 2, g_opt.hb_blocks, cap, &chans))) return rc;
+    if ((rc = pick_channels(c, kp, threads, n, work_units, 1, g_opt.hb_blocks, cap, &chans))) return rc;
     HbArgs a{};
     for (int i = 0; i < n; ++i) {
         a.in[i] = in ? in[i] : nullptr;
