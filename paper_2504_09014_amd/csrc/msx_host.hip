@@ -421,10 +421,10 @@ void choose_hb_shape(size_t nbytes, int n, int threads, int* unroll, int* want)
 // Cache hints of the fused HB AllReduce by footprint (inputs + outputs of all ranks), from a sweep: up to
 // 64 MiB everything may stay cached, up to 512 MiB (the outputs then just fill the 256 MiB memory-side cache)
 // the stores may, beyond that both stream.
-int choose_cache_mode(size_t nbytes, int n)
+int choose_cache_mode(size_t nbytes, int n, int res_mode)
 {
     if (g_opt.cache_mode >= 0) return g_opt.cache_mode;
-    const size_t footprint = 2 * (size_t)n * nbytes;
+    const size_t footprint = (2 * (size_t)n + (res_mode == 0 ? 0 : res_mode == 1 ? 1 : (size_t)n)) * nbytes;
     if (footprint <= ((size_t)64 << 20)) return 2;
     if (footprint <= ((size_t)512 << 20)) return 1;
     return 0;
@@ -692,8 +692,8 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     int U = 1, want = 1;
     choose_hb_shape(nbytes, n, threads, &U, &want);
     if (algo == MSX_ALGO_2PA_HB_2PHASE && U > 2) U = 2;
-    HbKernel k = algo == MSX_ALGO_2PA_HB ? hb_fused_kernel(dtype, U, n, !residual ? 0 : res_shared ? 1 : 2,
-                                                           choose_cache_mode(nbytes, n))
+    const int res_mode = !residual ? 0 : res_shared ? 1 : 2;
+    HbKernel k = algo == MSX_ALGO_2PA_HB ? hb_fused_kernel(dtype, U, n, res_mode, choose_cache_mode(nbytes, n, res_mode))
                                          : hb_2phase_kernel(dtype, U, n);
     int chans = 1;
     if ((rc = pick_channels(c, (const void*)k, threads, n, per_rank, (size_t)U, want, kMaxChannels, &chans)))
