@@ -281,34 +281,47 @@ __global__ __launch_bounds__(256) void k_moe_pack_fp8(MoeArgs a, MoeFp8Args f, D
             if (go && a.has_src && lane == 0) st32_wt(a.recv_src[d] + r, (unsigned)(rank * a.T + t));
         }
         const char* src = tokens + (size_t)t * src_row;
-        for (unsigned i = (unsigned)lane; i < row_vecs; i += 64u) {
-            const u32x4 v = ld16(src, i);
-            float x[8] = {bf16_lo(v.x), bf16_hi(v.x), bf16_lo(v.y), bf16_hi(v.y),
-                          bf16_lo(v.z), bf16_hi(v.z), bf16_lo(v.w), bf16_hi(v.w)};
+        // a lane quantises 16 consecutive elements (two vectors in, one 16-byte vector out); the 8 lanes of a
+        // group share their maximum; the next pair of vectors is requested before this one is stored
+        const unsigned units = row_vecs >> 1;
+        unsigned i = (unsigned)lane;
+        u32x4 v0 = {0u, 0u, 0u, 0u}, v1 = v0;
+        if (i < units) { v0 = ld16(src, 2u * i); v1 = ld16(src, 2u * i + 1u); }
+        while (i < units) {
+            const unsigned nx = i + 64u;
+            u32x4 n0 = {0u, 0u, 0u, 0u}, n1 = n0;
+            if (nx < units) { n0 = ld16(src, 2u * nx); n1 = ld16(src, 2u * nx + 1u); }
+            const unsigned w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+            float x[16];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { x[2 * k] = bf16_lo(w[k]); x[2 * k + 1] = bf16_hi(w[k]); }
             float amax = 1e-4f;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
+            for (int k = 0; k < 16; ++k) {
                 const float m = fabsf(x[k]);
                 amax = m > amax ? m : amax;                  // a NaN never wins the comparison
             }
 #pragma unroll
-            for (int m = 8; m >= 1; m >>= 1) {
+            for (int m = 4; m >= 1; m >>= 1) {
                 const float o = __shfl_xor(amax, m, 64);
                 amax = o > amax ? o : amax;
             }
             const float inv = 448.0f / amax;
-            unsigned b[8];
+            unsigned b[16];
 #pragma unroll
-            for (int k = 0; k < 8; ++k) b[k] = e4m3_round(x[k] * inv);
-            const u32x2 q = {b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24),
-                             b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24)};
+            for (int k = 0; k < 16; ++k) b[k] = e4m3_round(x[k] * inv);
+            const u32x4 q = {b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24),
+                             b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24),
+                             b[8] | (b[9] << 8) | (b[10] << 16) | (b[11] << 24),
+                             b[12] | (b[13] << 8) | (b[14] << 16) | (b[15] << 24)};
             const float scale = amax / 448.0f;
 #pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)
                 if (dq[d]) {
-                    st8_wt(dq[d] + (size_t)i * 8, q);
-                    if ((lane & 15) == 0) st32_wt(ds[d] + (i >> 4), __float_as_uint(scale));
+                    st16_wt(dq[d], i, q);
+                    if ((lane & 7) == 0) st32_wt(ds[d] + (i >> 3), __float_as_uint(scale));
                 }
+            v0 = n0; v1 = n1; i = nx;
         }
     }
     put_drain();
