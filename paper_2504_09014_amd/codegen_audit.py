@@ -1,5 +1,8 @@
-"""Build check: look for wave-uniform conditions that the compiler re-derived with a vector
-compare inside a loop and then reads outside that loop.
+"""Build checks on the generated assembly: (1) wave-uniform conditions that the compiler re-derived with a
+vector compare inside a loop and then reads outside that loop; (2) per-peer write-through stores that each
+wait for all memory operations (see serialised_store_findings).
+
+(1):
 
 hipcc keeps a wave-uniform boolean (rank == j, j < n) as a 64-bit lane mask.  Where it needs
 the negation it may emit `v_cndmask_b32 v, 0, 1, mask` + `v_cmp_ne_u32 s[a:b], 1, v`; a vector
@@ -114,14 +117,51 @@ def findings(path):
     return found
 
 
+def serialised_store_findings(path, limit=3):
+    """Kernels in which more than `limit` write-through 16-byte stores each sit right behind a full
+    `s_waitcnt vmcnt(0)`.
+
+    The write-through stores are inline assembly, so the compiler does not know they are in flight.  When a
+    conditional store is the first use of a loaded register it waits for ALL memory operations there, which
+    also drains the stores already issued: a sequence of per-peer stores then runs one round trip at a time
+    (`settle()` in csrc/msx_device.hpp consumes the loaded vector once, before the stores).
+    -> [(function, stores behind a full wait, write-through stores)]"""
+    found = []
+    fn, prev, stores, waited = None, [], 0, 0
+    for raw in open(path):
+        m = _RE_FN.match(raw)
+        if m:
+            fn, prev, stores, waited = m.group(1), [], 0, 0
+            continue
+        if fn is None:
+            continue
+        t = raw.strip()
+        if t.startswith(".end_amdhsa_kernel") or t.startswith(".Lfunc_end"):
+            if waited > limit:
+                found.append((fn, waited, stores))
+            fn = None
+            continue
+        if not t or t.startswith(";") or t.startswith("."):
+            continue
+        if t.startswith("global_store_dwordx4") and " sc1" in t:
+            stores += 1
+            if any(p.startswith("s_waitcnt") and "vmcnt(0)" in p for p in prev[-3:]):
+                waited += 1
+        prev.append(t)
+    return found
+
+
 def main():
     with tempfile.TemporaryDirectory() as tmp:
         path = device_assembly(os.path.join(tmp, "msx_device.s"))
         found = findings(path)
+        slow = serialised_store_findings(path)
     for fn, d, u in found:
         print(f"{fn}\n   def  [{d[0]} in loop {d[1]}] {d[2]}\n   use  [{u[0]} in loop {u[1]}] {u[2]}")
-    print(f"{len(found)} finding(s)")
-    return 1 if found else 0
+    for fn, waited, stores in slow:
+        print(f"{fn}: {waited} of {stores} write-through stores wait for all memory operations first")
+    print(f"{len(found)} lane-mask finding(s), {len(slow)} kernel(s) with serialised stores")
+    return 1 if found or slow else 0
 
 
 if __name__ == "__main__":

@@ -323,6 +323,14 @@ __device__ __forceinline__ void st16(void* base, size_t vec_index, u32x4 v)
     __builtin_nontemporal_store(v, (u32x4*)base + vec_index);
 }
 
+// Marks a loaded vector as consumed.  The write-through stores below are inline assembly, whose memory
+// counter the compiler cannot see: when a conditional store is the first use of a loaded register, the
+// compiler waits for "all outstanding memory operations" in front of it, which also drains the stores issued
+// so far, and a sequence of conditional stores to N peers then runs one round trip at a time (measured: a
+// small AllGather 4.8 us instead of 3.3 us).  Settling the vector once, before the stores, leaves no load
+// pending at any of them.
+__device__ __forceinline__ void settle(u32x4& v) { asm volatile("" : "+v"(v)); }
+
 // ---- write-through put ---------------------------------------------------------------------------
 // A device-scope release fence writes the whole L2 of the XCD back, and those write-backs queue
 // up per XCD (measured: about 0.16 us per workgroup and barrier, 40 us for 256 workgroups per

@@ -97,6 +97,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
 
     for (size_t i = lo + rt; i < hi; i += RT * U) {
         u32x4 v[U][kMaxRanks];
+        u32x4 res[U][RES == 2 ? kMaxRanks : 1];     // residual vectors, requested together with the inputs
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const size_t idx = i + (size_t)u * RT;
@@ -104,6 +105,12 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
 #pragma unroll
                 for (int j = 0; j < kMaxRanks; ++j)
                     if (j < n_l) v[u][j] = CACHE == 2 ? ld16_keep(a.in[j], idx) : ld16(a.in[j], idx);
+                if constexpr (RES == 1) res[u][0] = ld16(a.res[0], idx);
+                if constexpr (RES == 2) {
+#pragma unroll
+                    for (int p = 0; p < kMaxRanks; ++p)
+                        if (p < n_l) res[u][p] = ld16(a.res[p], idx);
+                }
             }
         }
 #pragma unroll
@@ -113,19 +120,23 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
                 VecAcc<DT> acc;
                 MSX_SUM_ALL(acc, v[u])
                 if constexpr (RES != 2) {
-                    if constexpr (RES == 1) acc.add(ld16(a.res[0], idx));
+                    if constexpr (RES == 1) acc.add(res[u][0]);
                     const u32x4 o = acc.pack();
 #pragma unroll
                     for (int p = 0; p < kMaxRanks; ++p)
                         if (p < n_l) { if constexpr (CACHE == 0) st16_wt(a.out[p], idx, o); else st16_wt_keep(a.out[p], idx, o); }
                 } else {
+                    u32x4 o[kMaxRanks];
 #pragma unroll
                     for (int p = 0; p < kMaxRanks; ++p)
                         if (p < n_l) {
                             VecAcc<DT> t = acc;
-                            t.add(ld16(a.res[p], idx));
-                            if constexpr (CACHE == 0) st16_wt(a.out[p], idx, t.pack()); else st16_wt_keep(a.out[p], idx, t.pack());
+                            t.add(res[u][p]);
+                            o[p] = t.pack();
                         }
+#pragma unroll
+                    for (int p = 0; p < kMaxRanks; ++p)
+                        if (p < n_l) { if constexpr (CACHE == 0) st16_wt(a.out[p], idx, o[p]); else st16_wt_keep(a.out[p], idx, o[p]); }
                 }
             }
         }
@@ -189,7 +200,8 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_2phase(HbArgs a, DevCtx c)
         }
     } else {
         for (size_t idx = lo + rt; idx < hi; idx += RT) {
-            const u32x4 o = ld16(a.out[rank], idx);
+            u32x4 o = ld16(a.out[rank], idx);
+            settle(o);
 #pragma unroll
             for (int p = 0; p < kMaxRanks; ++p)
                 if (p < n_l && p != rank_l) st16_wt(a.out[p], idx, o);
@@ -288,6 +300,8 @@ __global__ __launch_bounds__(256) void k_allgather_hb(HbArgs a, DevCtx c, int ve
                 if (iu < nv) v[u] = ld16(src, iu);
             }
 #pragma unroll
+            for (int u = 0; u < U; ++u) settle(v[u]);
+#pragma unroll
             for (int u = 0; u < U; ++u) {
                 const size_t iu = i + (size_t)u * RT;
                 if (iu < nv) {
@@ -328,6 +342,8 @@ __global__ __launch_bounds__(256) void k_alltoall_hb(HbArgs a, DevCtx c, int vec
 #pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)
                 if (d < n_l) v[d] = ld16(src + (size_t)d * nbytes, i);
+#pragma unroll
+            for (int d = 0; d < kMaxRanks; ++d) settle(v[d]);
 #pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)
                 if (d < n_l) {

@@ -224,6 +224,8 @@ __global__ __launch_bounds__(256) void k_moe_pack(MoeArgs a, DevCtx c)
             for (int u = 0; u < 4; ++u)
                 if (i + 64u * u < a.row_vecs) v[u] = ld16(src, i + 64u * u);
 #pragma unroll
+            for (int u = 0; u < 4; ++u) settle(v[u]);
+#pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)
                 if (dst[d]) {
 #pragma unroll

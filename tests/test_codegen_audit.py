@@ -46,10 +46,22 @@ def test_audit_accepts_a_mask_formed_and_tested_in_the_same_loop(tmp_path):
     assert audit.findings(str(p)) == []
 
 
+def test_audit_reports_per_peer_stores_that_each_drain_the_memory_pipeline(tmp_path):
+    body = "".join("\ts_waitcnt vmcnt(0)\n\tglobal_store_dwordx4 v[50:51], v[6:9], off sc1 nt\n\ts_nop 1\n" for _ in range(8))
+    p = tmp_path / "slow.s"
+    p.write_text("_Z4slowv:\n" + body + "\ts_endpgm\n.Lfunc_end0:\n")
+    assert audit.serialised_store_findings(str(p)) == [("_Z4slowv", 8, 8)]
+    good = "\ts_waitcnt vmcnt(0)\n" + "".join("\tglobal_store_dwordx4 v[50:51], v[6:9], off sc1 nt\n\ts_nop 1\n" for _ in range(8))
+    p.write_text("_Z4fastv:\n" + good + "\ts_endpgm\n.Lfunc_end0:\n")
+    assert audit.serialised_store_findings(str(p)) == []
+
+
 def test_device_code_has_no_partial_exec_uniform_masks(tmp_path):
     t0 = time.time()
     path = audit.device_assembly(str(tmp_path / "msx_device.s"))
     assert os.path.getsize(path) > 100000
     found = audit.findings(path)
     assert found == [], found[:3]
+    slow = audit.serialised_store_findings(path)
+    assert slow == [], slow
     print(f"audit: {time.time() - t0:.0f} s")
