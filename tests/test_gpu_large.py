@@ -83,3 +83,59 @@ def test_large_in_place_allreduce_256mib(msx, orc):
         assert np.array_equal(_bits(x[3, lo:hi]), want), (lo, hi)
     del x
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("block_mib", [2, 32, 128])
+def test_large_reducescatter_allgather_alltoall(msx, orc, block_mib):
+    """The standalone collectives at the sizes the benchmark times (rows of 16 MiB, 256 MiB and 1 GiB: the
+    cache-keeping stores, the streaming forms and the deep-unrolled AllGather).  The oracle checks seeded
+    sample columns of every block; on the GPU every output is compared in full with what the copy collectives
+    must produce, and the reduce-scatter with the same columns summed by the AllReduce kernel."""
+    n = 8
+    c = block_mib * (1 << 20) // 2                           # bf16 elements per block
+    rng = np.random.default_rng(block_mib)
+    cols = np.unique(np.concatenate([rng.integers(0, c, 4096), np.arange(0, 4096), np.arange(c - 4096, c)]))
+    ti = torch.from_numpy(cols).cuda()
+
+    # AllGather: block r of every output is rank r's input
+    part = [synth.normal(1, c, seed=100 + r, device="cuda")[0] for r in range(n)]
+    full = [torch.empty(n * c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    msx.allgather_ex(part, full)
+    msx.check_status()
+    ref = torch.cat(part)
+    for r in range(n):
+        assert torch.equal(full[r].view(torch.int16), ref.view(torch.int16)), r
+    small = np.stack([_bits(p[ti]) for p in part])
+    want = orc.allgather(small)                                # [n, n * K]
+    for r in (0, 5):
+        got = _bits(full[r].view(n, c)[:, ti].reshape(-1))
+        assert np.array_equal(got, want[r]), r
+
+    # AllToAll of the gathered rows: out[d] block s = in[s] block d (all inputs are equal here, so also
+    # scramble them first: row s gets its blocks rotated by s)
+    rows = [torch.roll(full[s].view(n, c), shifts=s, dims=0).reshape(-1).contiguous() for s in range(n)]
+    out = [torch.empty(n * c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    msx.alltoall_ex(rows, out)
+    msx.check_status()
+    for d in range(n):
+        expect = torch.stack([rows[s].view(n, c)[d] for s in range(n)]).reshape(-1)
+        assert torch.equal(out[d].view(torch.int16), expect.view(torch.int16)), d
+    small = np.stack([_bits(rows[s].view(n, c)[:, ti].reshape(-1)) for s in range(n)])
+    want = orc.alltoall(small)
+    for d in (0, 3):
+        assert np.array_equal(_bits(out[d].view(n, c)[:, ti].reshape(-1)), want[d]), d
+    del full, out
+
+    # ReduceScatter of those rows
+    rs = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    msx.reducescatter_ex(rows, rs)
+    msx.check_status()
+    want = orc.reducescatter(small)                            # [n, K]
+    for r in range(n):
+        assert np.array_equal(_bits(rs[r][ti]), want[r]), r
+    # ... and in full against the AllReduce kernel's sums of the same rows (same order, same rounding)
+    ar = [torch.empty(n * c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    msx.allreduce_ex(rows, ar, None)
+    msx.check_status()
+    for r in range(n):
+        assert torch.equal(rs[r].view(torch.int16), ar[0].view(n, c)[r].view(torch.int16)), r
