@@ -42,7 +42,8 @@ def _windows(count, n, rng):
     return spans
 
 
-@pytest.mark.parametrize("mib,algo", [(64, 3), (64, 4), (256, 3), (1024, 3)])
+# 3, 8 and 24 MiB: the cache-keeping forms of the fused kernel (loads and stores / stores only)
+@pytest.mark.parametrize("mib,algo", [(3, 3), (8, 3), (24, 3), (64, 3), (64, 4), (256, 3), (1024, 3)])
 def test_config3_large_allreduce(msx, orc, mib, algo):
     n = 8
     count = mib * (1 << 20) // 2
