@@ -411,7 +411,10 @@ void choose_hb_shape(size_t nbytes, int n, int threads, int* unroll, int* want)
     if (w == 0) {
         if (per_rank <= 32768) w = (int)((per_rank + (size_t)threads * U - 1) / ((size_t)threads * U));
         else if (per_rank <= 262144) w = 32;   // up to 4 MiB of chunk per rank
-        else w = 128;
+        else {                                 // about 1024 workgroups in all, whatever the rank count
+            w = 1024 / n;
+            if (w > kMaxChannels) w = kMaxChannels;
+        }
         if (w < 1) w = 1;
     }
     *unroll = U;

@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void k_reduce_generic(HbArgs a, DevCtx c, int 
     bool plain_stores = false;
     if (mode == 0) {
         const size_t V = a.count / epv;
-        const size_t lo = V * (size_t)rank / (size_t)n, hi = V * (size_t)(rank + 1) / (size_t)n;
+        const size_t lo = chunk_begin(V, rank, n), hi = chunk_begin(V, rank + 1, n);
         for (size_t idx = lo + rt; idx < hi; idx += RT) {
             u32x4 v[kMaxRanks];
             MSX_LOAD_ALL(v, a.in, idx)

@@ -90,8 +90,8 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_fused(HbArgs a, DevCtx c)
 
     if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 10, false, false);   // every peer has entered the call
 
-    const size_t lo = V * (size_t)rank / (size_t)n;
-    const size_t hi = V * (size_t)(rank + 1) / (size_t)n;
+    const size_t lo = chunk_begin(V, rank, n);
+    const size_t hi = chunk_begin(V, rank + 1, n);
     const size_t RT = (size_t)a.chans * blockDim.x;
     const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
 
@@ -162,8 +162,8 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_2phase(HbArgs a, DevCtx c)
 
     if (n > 1) rank_barrier(c, rank, n, chan, 20, false, false);
 
-    const size_t lo = V * (size_t)rank / (size_t)n;
-    const size_t hi = V * (size_t)(rank + 1) / (size_t)n;
+    const size_t lo = chunk_begin(V, rank, n);
+    const size_t hi = chunk_begin(V, rank + 1, n);
     const size_t RT = (size_t)a.chans * blockDim.x;
     const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
 
