@@ -213,9 +213,25 @@ static void orc_store_elem(void *p, size_t i, int dtype, float v)
     else ((uint16_t *)p)[i] = orc_f32_to_f16(v);
 }
 
-/* dtype: 0 fp32, 1 bf16, 2 fp16.  op: 0 sum, 1 max, 2 min.  in: [n][count] -> out: [count] */
+/* dtype: 0 fp32, 1 bf16, 2 fp16, 3 int32.  op: 0 sum, 1 max, 2 min.  in: [n][count] -> out: [count].
+ * int32: the sum is taken modulo 2^32 (two's complement wrap-around, no trap), max / min are signed. */
 void orc_allreduce_any(const void *in, void *out, int n, size_t count, int dtype, int op)
 {
+    if (dtype == 3) {
+        const int32_t *x = (const int32_t *)in;
+        int32_t *o = (int32_t *)out;
+        for (size_t i = 0; i < count; ++i) {
+            int32_t acc = x[i];
+            for (int r = 1; r < n; ++r) {
+                int32_t v = x[(size_t)r * count + i];
+                if (op == 0) acc = (int32_t)((uint32_t)acc + (uint32_t)v);
+                else if (op == 1) acc = v > acc ? v : acc;
+                else acc = v < acc ? v : acc;
+            }
+            o[i] = acc;
+        }
+        return;
+    }
     size_t esz = dtype == 0 ? 4 : 2;
     for (size_t i = 0; i < count; ++i) {
         float acc = orc_load_elem(in, i, dtype);

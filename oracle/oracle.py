@@ -167,9 +167,10 @@ def f32_to_f16(x):
 
 
 def allreduce_any(x, dtype, op):
-    """x: [n, count] float32 (dtype 0) or uint16 bit patterns (1 = bf16, 2 = fp16); op 0 sum, 1 max, 2 min."""
+    """x: [n, count] float32 (dtype 0), uint16 bit patterns (1 = bf16, 2 = fp16) or int32 (3);
+    op 0 sum (int32: modulo 2^32), 1 max, 2 min."""
     x = np.ascontiguousarray(x)
-    assert x.dtype == (np.float32 if dtype == 0 else np.uint16)
+    assert x.dtype == (np.float32 if dtype == 0 else np.int32 if dtype == 3 else np.uint16)
     n, count = x.shape
     out = np.empty(count, x.dtype)
     lib().orc_allreduce_any(_p(x), _p(out), n, count, dtype, op)

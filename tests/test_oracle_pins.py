@@ -276,6 +276,25 @@ def test_allreduce_any_against_numpy(orc, dtype, n):
         assert out[0] == np.delete(y[:, 0], 1).max() and np.isnan(out[1])
 
 
+@pytest.mark.parametrize("n", [1, 2, 3, 8])
+def test_allreduce_any_int32_against_python_integers(orc, n):
+    rng = np.random.default_rng(n)
+    count = 3000
+    x = rng.integers(-2**31, 2**31, (n, count), dtype=np.int64).astype(np.int32)
+    x[0, :4] = [2**31 - 1, -2**31, 2**31 - 1, -1]                      # wrap-around on purpose
+    if n > 1:
+        x[1, :4] = [1, -1, 2**31 - 1, -2**31]
+    exact = x.astype(np.int64).sum(axis=0)                            # no overflow in int64
+    want = ((exact + 2**31) % 2**32 - 2**31).astype(np.int32)         # modulo 2^32, as a signed value
+    assert np.array_equal(orc.allreduce_any(x, 3, 0), want)
+    assert np.array_equal(orc.allreduce_any(x, 3, 1), x.max(axis=0))
+    assert np.array_equal(orc.allreduce_any(x, 3, 2), x.min(axis=0))
+    if n > 1:
+        assert orc.allreduce_any(x, 3, 0)[0] == (2**31 - 1 + 1 + int(x[2:, 0].astype(np.int64).sum()) + 2**31) % 2**32 - 2**31
+    small = rng.integers(-1000, 1001, (n, count)).astype(np.int32)    # the same numbers as floats: both paths agree
+    assert np.array_equal(orc.allreduce_any(small, 3, 0), orc.allreduce_f32(small.astype(np.float32)).astype(np.int32))
+
+
 # ---------------------------------------------------------------- ring order
 
 @pytest.mark.parametrize("n", [1, 2, 3, 8])
