@@ -32,12 +32,14 @@
 extern "C" {
 #endif
 
-/* fp32 and bf16 sums run on the tuned kernels of every algorithm.  fp16, and max / min for any type,
- * are served by AllReduce (automatic or MSX_ALGO_2PA_HB, no residual) and ReduceScatter through a
- * generic kernel; the copy collectives and the token dispatch move any 2- or 4-byte type.
- * Sum: fp32 accumulation in rank order, one rounding.  Max / min: fp32 comparison in rank order,
- * the earlier value is kept unless the later one is strictly greater / smaller. */
-typedef enum { MSX_F32 = 0, MSX_BF16 = 1, MSX_F16 = 2 } msx_dtype;
+/* fp32 and bf16 sums run on the tuned kernels of every algorithm.  fp16, int32, and max / min for any
+ * type, are served by AllReduce (automatic or MSX_ALGO_2PA_HB, no residual) and ReduceScatter through a
+ * generic kernel; the copy collectives and the token dispatch move any 2- or 4-byte type; the combine
+ * sums fp32 and bf16 only.
+ * Floating point: sum = fp32 accumulation in rank order, one rounding; max / min = fp32 comparison in
+ * rank order, the earlier value is kept unless the later one is strictly greater / smaller.
+ * int32: sum modulo 2^32 (two's complement wrap-around), max / min signed. */
+typedef enum { MSX_F32 = 0, MSX_BF16 = 1, MSX_F16 = 2, MSX_I32 = 3 } msx_dtype;
 typedef enum { MSX_SUM = 0, MSX_MAX = 1, MSX_MIN = 2 } msx_op;
 
 typedef enum {

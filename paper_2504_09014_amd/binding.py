@@ -9,7 +9,7 @@ import os
 import torch
 
 __all__ = [
-    "F32", "BF16", "F16", "SUM", "MAX", "MIN", "ALGO_AUTO", "ALGO_1PA_LL", "ALGO_2PA_LL", "ALGO_2PA_HB", "ALGO_2PA_HB_2PHASE", "ALGO_2PR_HB", "ALGO_PLAN_2PA_HB", "ALGO_PLAN_2PR_HB",
+    "F32", "BF16", "F16", "I32", "SUM", "MAX", "MIN", "ALGO_AUTO", "ALGO_1PA_LL", "ALGO_2PA_LL", "ALGO_2PA_HB", "ALGO_2PA_HB_2PHASE", "ALGO_2PR_HB", "ALGO_PLAN_2PA_HB", "ALGO_PLAN_2PR_HB",
     "MsxError", "lib", "lib_path", "init", "reset", "finalize", "set_option", "get_option", "status",
     "check_status", "last_launch", "version", "strerror",
     "allreduce", "reducescatter", "allgather", "alltoall",
@@ -18,7 +18,7 @@ __all__ = [
     "EXPORTS",
 ]
 
-F32, BF16, F16 = 0, 1, 2
+F32, BF16, F16, I32 = 0, 1, 2, 3
 SUM, MAX, MIN = 0, 1, 2
 ALGO_AUTO, ALGO_1PA_LL, ALGO_2PA_LL, ALGO_2PA_HB, ALGO_2PA_HB_2PHASE, ALGO_2PR_HB = 0, 1, 2, 3, 4, 5
 ALGO_PLAN_2PA_HB, ALGO_PLAN_2PR_HB = 6, 7
@@ -111,6 +111,8 @@ def _dtype(t):
         return BF16
     if t.dtype == torch.float16:
         return F16
+    if t.dtype == torch.int32:
+        return I32
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 

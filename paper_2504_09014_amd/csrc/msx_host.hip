@@ -103,7 +103,7 @@ int hip_fail(hipError_t e)
         if (e_ != hipSuccess) return hip_fail(e_);   \
     } while (0)
 
-size_t elem_size(int dtype) { return dtype == MSX_F32 ? 4 : 2; }
+size_t elem_size(int dtype) { return (dtype == MSX_F32 || dtype == MSX_I32) ? 4 : 2; }
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
 void port_proxy(Port* p)
@@ -307,7 +307,7 @@ int pick_channels(Ctx* c, const void* k, int threads, int n, size_t work, size_t
 
 int check_common(int dtype, int op, int nranks)
 {
-    if (dtype != MSX_F32 && dtype != MSX_BF16 && dtype != MSX_F16) return MSX_ERR_ARG;
+    if (dtype != MSX_F32 && dtype != MSX_BF16 && dtype != MSX_F16 && dtype != MSX_I32) return MSX_ERR_ARG;
     if (op != MSX_SUM && op != MSX_MAX && op != MSX_MIN) return MSX_ERR_UNSUPPORTED;
     if (nranks < 1 || nranks > kMaxRanks) return MSX_ERR_ARG;
     return MSX_OK;
@@ -567,7 +567,7 @@ typedef void (*GenericKernel)(HbArgs, DevCtx, int, int);
 GenericKernel generic_kernel(int dtype, int op)
 {
 #define MSX_G(DT) (op == MSX_SUM ? (GenericKernel)k_reduce_generic<DT, 0> : op == MSX_MAX ? (GenericKernel)k_reduce_generic<DT, 1> : (GenericKernel)k_reduce_generic<DT, 2>)
-    return dtype == MSX_F32 ? MSX_G(0) : dtype == MSX_BF16 ? MSX_G(1) : MSX_G(2);
+    return dtype == MSX_F32 ? MSX_G(0) : dtype == MSX_BF16 ? MSX_G(1) : dtype == MSX_F16 ? MSX_G(2) : MSX_G(3);
 #undef MSX_G
 }
 
@@ -615,7 +615,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     if (residual)
         for (int i = 1; i < n; ++i) res_shared = res_shared && residual[i] == residual[0];
 
-    if (dtype == MSX_F16 || op != MSX_SUM) {
+    if (dtype == MSX_F16 || dtype == MSX_I32 || op != MSX_SUM) {
         // outside the tuned paths: only the fused all-pairs HB form exists
         if (residual) return MSX_ERR_UNSUPPORTED;
         if (algo == MSX_ALGO_AUTO) algo = g_opt.algo;
@@ -964,7 +964,7 @@ int msx_reducescatter_ex(const void* const* send, void* const* recv, size_t coun
         if (!aligned16(recv[r])) vec = 0;
         if ((uintptr_t)recv[r] % esz) return MSX_ERR_ARG;
     }
-    if (dtype == MSX_F16 || op != MSX_SUM) {
+    if (dtype == MSX_F16 || dtype == MSX_I32 || op != MSX_SUM) {
         std::lock_guard<std::mutex> lk(g_mu);
         Ctx* ctx = nullptr;
         if ((rc = get_ctx(&ctx))) return rc;
@@ -1108,6 +1108,7 @@ int msx_moe_combine(const void* const* expert_out, void* const* out_tokens, int 
 {
     int rc = check_common(dtype, MSX_SUM, nranks);
     if (rc) return rc;
+    if (dtype != MSX_F32 && dtype != MSX_BF16) return MSX_ERR_UNSUPPORTED;   // the sums exist for these two
     if ((rc = check_table(expert_out, nranks))) return rc;
     if ((rc = check_table((const void* const*)out_tokens, nranks))) return rc;
     if (T < 0 || H <= 0) return MSX_ERR_ARG;

@@ -1,9 +1,10 @@
-// Element types and operators beyond the tuned paths: fp16, and max / min next to sum (the DSL
+// Element types and operators beyond the tuned paths: fp16, int32, and max / min next to sum (the DSL
 // carries a ReduceOp; the Collective API mirrors NCCL's).  One fused all-pairs HB kernel and one
 // reduce-scatter kernel, same structure as the tuned ones (every rank reads its chunk from all
 // ranks, combines in rank order in fp32, puts the result everywhere with write-through stores),
 // one vector per thread and pass, rank count at run time.  Sum rounds once at the end; max / min
-// keep the earlier value unless the later one is strictly greater / smaller.
+// keep the earlier value unless the later one is strictly greater / smaller.  int32 is combined as
+// integers: the sum modulo 2^32, max / min signed.
 #pragma once
 #include <hip/hip_fp16.h>
 #include "msx_device.hpp"
@@ -16,6 +17,13 @@ template <int OP> __device__ __forceinline__ float combine(float acc, float v)
     if constexpr (OP == 0) return acc + v;
     else if constexpr (OP == 1) return v > acc ? v : acc;
     else return v < acc ? v : acc;
+}
+
+template <int OP> __device__ __forceinline__ unsigned combine_i32(unsigned acc, unsigned v)
+{
+    if constexpr (OP == 0) return acc + v;                                  // wraps modulo 2^32
+    else if constexpr (OP == 1) return (int)v > (int)acc ? v : acc;
+    else return (int)v < (int)acc ? v : acc;
 }
 
 // fp16 <-> fp32 through the hardware converters (round to nearest even, subnormals kept)
@@ -39,39 +47,60 @@ template <int DT> __device__ __forceinline__ unsigned pack_word(float a, float b
 
 template <int DT, int OP> struct VecAccG {
     float a[4], b[4];
+    unsigned w[4];        // DT == 3 (int32): the words themselves
     __device__ __forceinline__ void set(u32x4 v)
     {
-        unpack_word<DT>(v.x, a[0], b[0]); unpack_word<DT>(v.y, a[1], b[1]);
-        unpack_word<DT>(v.z, a[2], b[2]); unpack_word<DT>(v.w, a[3], b[3]);
+        if constexpr (DT == 3) { w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w; }
+        else {
+            unpack_word<DT>(v.x, a[0], b[0]); unpack_word<DT>(v.y, a[1], b[1]);
+            unpack_word<DT>(v.z, a[2], b[2]); unpack_word<DT>(v.w, a[3], b[3]);
+        }
     }
     __device__ __forceinline__ void add(u32x4 v)
     {
-        float x[4], y[4];
-        unpack_word<DT>(v.x, x[0], y[0]); unpack_word<DT>(v.y, x[1], y[1]);
-        unpack_word<DT>(v.z, x[2], y[2]); unpack_word<DT>(v.w, x[3], y[3]);
+        if constexpr (DT == 3) {
+            w[0] = combine_i32<OP>(w[0], v.x); w[1] = combine_i32<OP>(w[1], v.y);
+            w[2] = combine_i32<OP>(w[2], v.z); w[3] = combine_i32<OP>(w[3], v.w);
+        } else {
+            float x[4], y[4];
+            unpack_word<DT>(v.x, x[0], y[0]); unpack_word<DT>(v.y, x[1], y[1]);
+            unpack_word<DT>(v.z, x[2], y[2]); unpack_word<DT>(v.w, x[3], y[3]);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            a[k] = combine<OP>(a[k], x[k]);
-            if constexpr (DT != 0) b[k] = combine<OP>(b[k], y[k]);
+            for (int k = 0; k < 4; ++k) {
+                a[k] = combine<OP>(a[k], x[k]);
+                if constexpr (DT != 0) b[k] = combine<OP>(b[k], y[k]);
+            }
         }
     }
     __device__ __forceinline__ u32x4 pack() const
     {
-        return u32x4{pack_word<DT>(a[0], b[0]), pack_word<DT>(a[1], b[1]), pack_word<DT>(a[2], b[2]), pack_word<DT>(a[3], b[3])};
+        if constexpr (DT == 3) return u32x4{w[0], w[1], w[2], w[3]};
+        else return u32x4{pack_word<DT>(a[0], b[0]), pack_word<DT>(a[1], b[1]), pack_word<DT>(a[2], b[2]), pack_word<DT>(a[3], b[3])};
     }
 };
 
-template <int DT> __device__ __forceinline__ float load_elem_g(const void* p, size_t e)
+// one element, as the accumulator type of the scalar paths: float, or the int32 bits in an unsigned
+template <int DT> struct ElemG { typedef float type; };
+template <> struct ElemG<3> { typedef unsigned type; };
+template <int DT, int OP> __device__ __forceinline__ typename ElemG<DT>::type combine_elem(typename ElemG<DT>::type acc, typename ElemG<DT>::type v)
+{
+    if constexpr (DT == 3) return combine_i32<OP>(acc, v);
+    else return combine<OP>(acc, v);
+}
+
+template <int DT> __device__ __forceinline__ typename ElemG<DT>::type load_elem_g(const void* p, size_t e)
 {
     if constexpr (DT == 0) return ((const float*)p)[e];
     else if constexpr (DT == 1) return __uint_as_float((unsigned)((const unsigned short*)p)[e] << 16);
-    else return __half2float(__ushort_as_half(((const unsigned short*)p)[e]));
+    else if constexpr (DT == 2) return __half2float(__ushort_as_half(((const unsigned short*)p)[e]));
+    else return ((const unsigned*)p)[e];
 }
-template <int DT> __device__ __forceinline__ void store_elem_g(void* p, size_t e, float v)
+template <int DT> __device__ __forceinline__ void store_elem_g(void* p, size_t e, typename ElemG<DT>::type v)
 {
     if constexpr (DT == 0) ((float*)p)[e] = v;
     else if constexpr (DT == 1) ((unsigned short*)p)[e] = (unsigned short)bf16_round(v);
-    else ((unsigned short*)p)[e] = (unsigned short)f16_round(v);
+    else if constexpr (DT == 2) ((unsigned short*)p)[e] = (unsigned short)f16_round(v);
+    else ((unsigned*)p)[e] = v;
 }
 
 // AllReduce (mode 0: result to every rank, a.count = elements per rank) or ReduceScatter
@@ -84,8 +113,8 @@ __global__ __launch_bounds__(256) void k_reduce_generic(HbArgs a, DevCtx c, int 
     const int chan = (int)(blockIdx.x / (unsigned)n);
     const int n_l = per_lane(n);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
-    constexpr size_t epv = DT == 0 ? 4 : 8;
-    constexpr size_t esz = DT == 0 ? 4 : 2;
+    constexpr size_t epv = (DT == 0 || DT == 3) ? 4 : 8;
+    constexpr size_t esz = (DT == 0 || DT == 3) ? 4 : 2;
     if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 600, false, false);
     const size_t RT = (size_t)a.chans * blockDim.x;
     const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
@@ -106,8 +135,8 @@ __global__ __launch_bounds__(256) void k_reduce_generic(HbArgs a, DevCtx c, int 
         if (rank == 0 && chan == 0 && V * epv < a.count) {
             plain_stores = true;
             for (size_t e = V * epv + threadIdx.x; e < a.count; e += blockDim.x) {
-                float acc = load_elem_g<DT>(a.in[0], e);
-                for (int j = 1; j < n; ++j) acc = combine<OP>(acc, load_elem_g<DT>(a.in[j], e));
+                auto acc = load_elem_g<DT>(a.in[0], e);
+                for (int j = 1; j < n; ++j) acc = combine_elem<DT, OP>(acc, load_elem_g<DT>(a.in[j], e));
                 for (int p = 0; p < n; ++p) store_elem_g<DT>(a.out[p], e, acc);
             }
         }
@@ -128,8 +157,8 @@ __global__ __launch_bounds__(256) void k_reduce_generic(HbArgs a, DevCtx c, int 
         } else {
             for (size_t k = rt; k < blk; k += RT) {
                 const size_t e = (size_t)rank * blk + k;
-                float acc = load_elem_g<DT>(a.in[0], e);
-                for (int j = 1; j < n; ++j) acc = combine<OP>(acc, load_elem_g<DT>(a.in[j], e));
+                auto acc = load_elem_g<DT>(a.in[0], e);
+                for (int j = 1; j < n; ++j) acc = combine_elem<DT, OP>(acc, load_elem_g<DT>(a.in[j], e));
                 store_elem_g<DT>(a.out[rank], k, acc);
             }
         }

@@ -376,18 +376,21 @@ def test_e4m3_encoder_on_gpu_covers_every_code_and_tie(msx, orc):
 
 # fp32 / bf16 sums are the tuned paths, tested above: here every other (type, operator) pair
 @pytest.mark.parametrize("n", [1, 2, 3, 8])
-@pytest.mark.parametrize("dt,op", [(0, 1), (0, 2), (1, 1), (1, 2), (2, 0), (2, 1), (2, 2)])
+@pytest.mark.parametrize("dt,op", [(0, 1), (0, 2), (1, 1), (1, 2), (2, 0), (2, 1), (2, 2), (3, 0), (3, 1), (3, 2)])
 def test_fp16_and_max_min_allreduce_reducescatter(msx, orc, n, dt, op):
-    tdt = [torch.float32, torch.bfloat16, torch.float16][dt]
+    tdt = [torch.float32, torch.bfloat16, torch.float16, torch.int32][dt]
     for count in [1, 7, 8 * n, 1000 * n, 70001 * n]:
         g = torch.Generator().manual_seed(count + dt + 10 * op)
-        xf = torch.randn(n, count, generator=g) * 3
-        if count > 100:
-            xf[0, 5] = float("inf")
-            xf[n - 1, 6] = float("-inf")
-            xf[0, 7] = 6.0e-6                                   # fp16 subnormal territory
-        x = xf.to(tdt)
-        bits = x.view(torch.uint16).numpy() if dt else x.numpy()
+        if dt == 3:
+            x = torch.randint(-2**31, 2**31, (n, count), generator=g, dtype=torch.int64).to(torch.int32)   # sums wrap
+        else:
+            xf = torch.randn(n, count, generator=g) * 3
+            if count > 100:
+                xf[0, 5] = float("inf")
+                xf[n - 1, 6] = float("-inf")
+                xf[0, 7] = 6.0e-6                               # fp16 subnormal territory
+            x = xf.to(tdt)
+        bits = x.view(torch.uint16).numpy() if dt in (1, 2) else x.numpy()
         want = orc.allreduce_any(bits, dt, op)
         send = [x[r].clone().cuda() for r in range(n)]
         recv = [torch.zeros_like(t) for t in send]
@@ -396,7 +399,7 @@ def test_fp16_and_max_min_allreduce_reducescatter(msx, orc, n, dt, op):
         msx.check_status()
         for r in range(n):
             got = recv[r].cpu()
-            got = got.view(torch.uint16).numpy() if dt else got.numpy()
+            got = got.view(torch.uint16).numpy() if dt in (1, 2) else got.numpy()
             assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), (n, dt, op, count, r)
         if count % n == 0:
             c = count // n
@@ -405,7 +408,7 @@ def test_fp16_and_max_min_allreduce_reducescatter(msx, orc, n, dt, op):
             msx.check_status()
             for r in range(n):
                 got = part[r].cpu()
-                got = got.view(torch.uint16).numpy() if dt else got.numpy()
+                got = got.view(torch.uint16).numpy() if dt in (1, 2) else got.numpy()
                 assert np.array_equal(got.view(np.uint8), want[r * c:(r + 1) * c].view(np.uint8)), (n, dt, op, count, r)
         msx.set_option("chaos", "0")
 
@@ -422,6 +425,42 @@ def test_generic_reduce_refuses_what_it_does_not_cover(msx):
     with pytest.raises(msx.MsxError) as e:
         msx.allreduce_ex(f, f, None, algo=5, op=msx.MAX)        # no ring form for max
     assert e.value.code == -2
+    i = [torch.zeros(64, dtype=torch.int32, device="cuda") for _ in range(8)]
+    with pytest.raises(msx.MsxError) as e:
+        msx.allreduce_ex(i, i, None, algo=2)                    # no LL form for int32
+    assert e.value.code == -2
+
+
+@pytest.mark.parametrize("dtype", [torch.float16, torch.int32])
+def test_combine_refuses_types_it_has_no_sum_for(msx, dtype):
+    n, T, H, K, E = 2, 4, 8, 1, 2
+    tok = [torch.zeros((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    idx = [torch.zeros((T, K), dtype=torch.int32, device="cuda") for _ in range(n)]
+    recv = [torch.zeros((n * T, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    src = [torch.zeros((n * T,), dtype=torch.int32, device="cuda") for _ in range(n)]
+    counts = torch.zeros((n, n), dtype=torch.int32, device="cuda")
+    msx.moe_dispatch(tok, idx, E, recv, counts, src)
+    msx.check_status()
+    y = [torch.zeros((n * T, H), dtype=dtype, device="cuda") for _ in range(n)]
+    out = [torch.zeros((T, H), dtype=dtype, device="cuda") for _ in range(n)]
+    with pytest.raises(msx.MsxError) as e:
+        msx.moe_combine(y, out)
+    assert e.value.code == -2
+
+
+def test_copy_collectives_take_int32(msx, orc):
+    n, c = 8, 999
+    x = torch.randint(-2**31, 2**31, (n, n * c), dtype=torch.int64).to(torch.int32)
+    want = orc.alltoall(x.numpy())
+    buf = x.clone().cuda()
+    msx.alltoall(buf)
+    msx.check_status()
+    assert np.array_equal(buf.cpu().numpy(), want)
+    y = x[:, :c].contiguous()
+    recv = [torch.zeros(n * c, dtype=torch.int32, device="cuda") for _ in range(n)]
+    msx.allgather_ex([y[r].cuda() for r in range(n)], recv)
+    msx.check_status()
+    assert np.array_equal(torch.stack([t.cpu() for t in recv]).numpy(), orc.allgather(y.numpy()))
 
 
 def test_copy_collectives_take_fp16(msx, orc):

@@ -79,24 +79,29 @@ def test_random_allreduce_cases(msx, orc, seed):
 def test_random_reducescatter_allgather_alltoall_cases(msx, orc, seed):
     """HB and packet forms, in place and out of place, every element type; reduce-scatter also with max / min."""
     rng = np.random.default_rng(2000 + seed)
-    tdt = [torch.float32, torch.bfloat16, torch.float16]
+    tdt = [torch.float32, torch.bfloat16, torch.float16, torch.int32]
+    view = lambda t, dt: t.view(torch.uint16).numpy() if dt in (1, 2) else t.numpy()
     for case in range(50):
         n = int(rng.choice([1, 2, 3, 5, 8]))
-        dt = int(rng.integers(0, 3))
+        dt = int(rng.integers(0, 4))
         op = int(rng.choice([0, 0, 1, 2]))
         c = int(rng.choice([rng.integers(1, 40), rng.integers(40, 3000), rng.integers(3000, 40000)]))
         coll_algo = str(rng.choice(["auto", "hb", "ll"]))
         inplace = bool(rng.integers(0, 2))
         if inplace:
             c = max(8, c // 8 * 8)                              # the rows of an in-place buffer are 16-byte aligned
-        if coll_algo == "ll" and ((c * (4 if dt == 0 else 2)) % 8 or dt == 2 or op):
+        if coll_algo == "ll" and ((c * (2 if dt in (1, 2) else 4)) % 8 or dt >= 2 or op):
             coll_algo = "hb"                                    # packets carry whole 8-byte units of fp32 / bf16 sums
         tag = dict(seed=seed, case=case, n=n, dt=dt, op=op, c=c, coll=coll_algo, inplace=inplace)
         msx.set_option("coll_algo", coll_algo)
         msx.set_option("chaos", str(int(rng.integers(0, 50))))
         try:
-            x = (torch.randn(n, n * c, generator=torch.Generator().manual_seed(seed * 1000 + case)) * 3).to(tdt[dt])
-            xb = x.numpy() if dt == 0 else x.view(torch.uint16).numpy()
+            g = torch.Generator().manual_seed(seed * 1000 + case)
+            if dt == 3:
+                x = torch.randint(-2**31, 2**31, (n, n * c), generator=g, dtype=torch.int64).to(torch.int32)
+            else:
+                x = (torch.randn(n, n * c, generator=g) * 3).to(tdt[dt])
+            xb = view(x, dt)
             # reduce-scatter
             want = orc.allreduce_any(xb, dt, op).reshape(n, c)
             if inplace:
@@ -104,7 +109,7 @@ def test_random_reducescatter_allgather_alltoall_cases(msx, orc, seed):
                 msx.reducescatter(buf, op=op)
                 msx.check_status()
                 got = buf.cpu()
-                got = got.numpy() if dt == 0 else got.view(torch.uint16).numpy()
+                got = view(got, dt)
                 for r in range(n):
                     assert np.array_equal(got[r, r * c:(r + 1) * c].view(np.uint8), want[r].view(np.uint8)), ("rs", tag, r)
                     keep = np.ones(n * c, bool)
@@ -117,11 +122,11 @@ def test_random_reducescatter_allgather_alltoall_cases(msx, orc, seed):
                 msx.check_status()
                 for r in range(n):
                     got = recv[r].cpu()
-                    got = got.numpy() if dt == 0 else got.view(torch.uint16).numpy()
+                    got = view(got, dt)
                     assert np.array_equal(got.view(np.uint8), want[r].view(np.uint8)), ("rs", tag, r)
             # all-gather of the first block of every row, all-to-all of the whole rows
             y = x[:, :c].contiguous()
-            yb = y.numpy() if dt == 0 else y.view(torch.uint16).numpy()
+            yb = view(y, dt)
             want_ag = orc.allgather(yb)
             want_a2a = orc.alltoall(xb)
             if inplace:
@@ -144,8 +149,7 @@ def test_random_reducescatter_allgather_alltoall_cases(msx, orc, seed):
                 msx.alltoall_ex(send2, recv2)
                 got2 = torch.stack([t.cpu() for t in recv2])
             msx.check_status()
-            got = got.numpy() if dt == 0 else got.view(torch.uint16).numpy()
-            got2 = got2.numpy() if dt == 0 else got2.view(torch.uint16).numpy()
+            got, got2 = view(got, dt), view(got2, dt)
             assert np.array_equal(got.view(np.uint8), want_ag.view(np.uint8)), ("ag", tag)
             assert np.array_equal(got2.view(np.uint8), want_a2a.view(np.uint8)), ("a2a", tag)
         finally:
