@@ -153,6 +153,9 @@ def main():
     log(f"[bench] AllReduce {args.mib} MiB/rank: {ms_per_step:.3f} ms/step wall, {kern_avg:.3f} ms kernel, "
         f"{achieved:.0f} GB/s, algBW {S / (kern_avg * 1e-3) / 1e9:.0f} GB/s, grid {grid}x{block}")
 
+    # which form of the fused kernel the library picked for this size (same sums, same bytes)
+    phased = msx.get_option("hb_phased_min_bytes") == "auto" and n == 8 and S >= (64 << 20)
+    kernel_name = "k_allreduce_hb_phased<bf16, 8 ranks, 64 sums held>" if phased else "k_allreduce_hb_fused<bf16>"
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
@@ -188,7 +191,7 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
-            "kernel": "k_allreduce_hb_fused<bf16>", "algorithmic_bytes": alg_bytes,
+            "kernel": kernel_name, "algorithmic_bytes": alg_bytes,
             "kernel_ms_avg": round(kern_avg, 4), "kernel_ms_min": round(min(kern_ms), 4),
             "kernel_ms_p10": round(pct(kern_ms, 10), 4), "kernel_ms_median": round(median(kern_ms), 4),
             "kernel_ms_p90": round(pct(kern_ms, 90), 4),

@@ -227,6 +227,9 @@ int msx_finalize(void);
  *   "hb_unroll"       0 (by size) | 1 | 2 | 4 | 8 (8: AllGather only)   vectors in flight per thread
  *   "cache_mode"      auto | 0 | 1 | 2   fused HB AllReduce: 0 streaming loads and stores, 1 stores may stay in
  *                     the memory-side cache, 2 loads too; auto picks by the footprint of the call
+ *   "hb_phased_min_bytes"   auto | bytes per rank from which the fused HB AllReduce (no residual, or one
+ *                     shared by all ranks) runs in chip-wide read and write phases, one workgroup per CU; auto:
+ *                     8 ranks from 64 MiB, never otherwise; an explicit value applies to every rank count
  *   "hb_barriers"     0 | 1   start/end rank barriers in the HB kernels
  *   "peer_outer"      0 | 1   two-phase HB all-gather: one put per peer instead of peer-inner
  *   "barrier_fences"  0..3    msx_prim_barrier only: bit 0 release fence, bit 1 acquire fence
@@ -252,7 +255,8 @@ int msx_last_launch(int* grid, int* block, int* algo);
 
 /* Host logic on its own (no device is touched; usable on a machine without a GPU).
  * msx_debug_choose: what the automatic choice would run for `nbytes` per rank given an LL scratch
- * sized for ll_limit bytes, and the HB launch shape (unroll, wanted workgroups per rank).
+ * sized for ll_limit bytes, and the HB launch shape (unroll, wanted workgroups per rank; for the phased form
+ * the sums a thread holds per phase, and 256 = as many workgroups as are resident).
  * msx_debug_lower_plan: the execution plan the interpreter algorithms run.  ops_out receives
  * 128-byte records {int code, peer, flags, nsrc, ndst; {int16 kind, rank} src[9], dst[8]; int dst_wt;
  * uint64 first, end, step} (see csrc/msx_kernels_plan.hpp), start_out the nranks*blocks_per_rank+1

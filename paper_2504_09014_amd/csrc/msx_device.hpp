@@ -11,6 +11,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
+#include <utility>
 
 namespace msx {
 
@@ -32,6 +34,7 @@ struct DevCtx {
     unsigned* expected;   // [kMaxRanks recv][kMaxRanks send][kMaxChannels] value the next wait needs
     unsigned* status;     // 8 words: code, rank, site, expected, seen, block
     unsigned* call_state; // {last LL flag handed out, LL calls so far, workgroups finished this call}
+    unsigned* gbar;       // chip-wide barrier: 8 counters, one per 128-byte line, then the 8 values they held when the last call ended
     void* ll;             // LL scratch, ll_bytes long: [rank][rotation][...]
     unsigned ll_bytes;
     unsigned ll_rank_stride;
@@ -161,6 +164,68 @@ __device__ __forceinline__ void rank_barrier(const DevCtx& c, int me, int n, int
         sem_spin(c, c.sem + (size_t)idx * kSemStrideWords, want, (unsigned)me, site, acquire);
     }
     __syncthreads();
+}
+
+// ---- barrier over every workgroup of a co-resident launch -----------------------------------------
+// Eight counters (workgroup b adds to counter b % 8, so the arrivals of one barrier queue up on eight
+// lines instead of one); the first wave of every workgroup polls all eight with one 8-lane load.  The
+// counters only grow: a call reads, when it starts, the values they had when the last call ended (kept
+// beside them), and workgroup 0 leaves the new values behind when it has passed its last barrier (every
+// workgroup has read the old ones by then).  Signed distances, so the counters may wrap.
+// Measured on MI355X with 256 workgroups: about 2 us from the last arrival to the release (one counter
+// and one polling thread: 5 us).
+struct GridBar { unsigned base, per_gen; bool ok; };   // lanes 0..7 of the first wave hold counter x's values
+
+constexpr int kGridBarBaseWord = 8 * kSemStrideWords;
+constexpr size_t kGridBarBytes = (size_t)(kGridBarBaseWord + 8) * 4;
+
+// Workgroup-collective; first thing (before any arrival of this call can have happened: an arrival
+// needs this workgroup's own).
+__device__ __forceinline__ GridBar grid_barrier_begin(const DevCtx& c)
+{
+    GridBar g{0u, 0u, true};
+    if (threadIdx.x < 8) {
+        g.base = c.gbar[kGridBarBaseWord + threadIdx.x];
+        g.per_gen = (gridDim.x + 7u - threadIdx.x) / 8u;      // workgroups b with b % 8 == x
+    }
+    return g;
+}
+
+// gen = 1, 2, ... counts this call's barriers; every workgroup of the launch takes part in each.
+// No fence: data the workgroups exchange is written through and drained before the call.
+__device__ __forceinline__ void grid_barrier(const DevCtx& c, GridBar& g, unsigned gen, unsigned rank, unsigned site)
+{
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        if (threadIdx.x == 0) {
+            chaos_delay(c, site + gen);
+            __hip_atomic_fetch_add(c.gbar + (blockIdx.x & 7u) * kSemStrideWords, 1u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const unsigned want = g.base + gen * g.per_gen;
+        unsigned seen = want;
+        if (g.ok) {                                              // after one timeout the call no longer waits
+            bool done = false;
+            for (unsigned spins = 0; spins <= c.spin_limit; ++spins) {
+                if (threadIdx.x < 8)
+                    seen = __hip_atomic_load(c.gbar + threadIdx.x * kSemStrideWords, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+                if (__all((int)(seen - want) >= 0)) { done = true; break; }
+                __builtin_amdgcn_s_sleep(1);
+            }
+            if (!done) {
+                g.ok = false;
+                if ((int)(seen - want) < 0) report(c, kStatusTimeout, rank, site, want, seen, threadIdx.x);
+            }
+        }
+    }
+    __syncthreads();
+}
+
+// Workgroup-collective; after the call's last barrier (gens = how many there were).
+__device__ __forceinline__ void grid_barrier_end(const DevCtx& c, const GridBar& g, unsigned gens)
+{
+    if (blockIdx.x == 0 && threadIdx.x < 8) c.gbar[kGridBarBaseWord + threadIdx.x] = g.base + gens * g.per_gen;
 }
 
 // ---- per-call flag and scratch rotation for the LL protocol -----------------------------------
@@ -323,6 +388,18 @@ __device__ __forceinline__ void st16(void* base, size_t vec_index, u32x4 v)
     __builtin_nontemporal_store(v, (u32x4*)base + vec_index);
 }
 
+// f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order: a loop whose index is a constant
+// in every iteration whatever the optimiser's unrolling limits are
+template <int... I, class F>
+__device__ __forceinline__ void static_for_each(std::integer_sequence<int, I...>, F&& f)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_each(std::make_integer_sequence<int, N>{}, f);
+}
+
 // Marks a loaded vector as consumed.  The write-through stores below are inline assembly, whose memory
 // counter the compiler cannot see: when a conditional store is the first use of a loaded register, the
 // compiler waits for "all outstanding memory operations" in front of it, which also drains the stores issued
@@ -334,7 +411,7 @@ __device__ __forceinline__ void settle(u32x4& v) { asm volatile("" : "+v"(v)); }
 // First 16-byte vector of rank r's chunk when V vectors are split over n ranks: the even split rounded down
 // to a whole 128-byte line (8 vectors), so that no two ranks write into the same line and every wave's accesses
 // start on a line (with 7 ranks the unaligned split cost 20 % of the bandwidth).  chunk_begin(V, n, n) = V.
-__device__ __forceinline__ size_t chunk_begin(size_t V, int r, int n)
+__host__ __device__ __forceinline__ size_t chunk_begin(size_t V, int r, int n)
 {
     if (r >= n) return V;
     const size_t b = V * (size_t)r / (size_t)n;

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <climits>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -42,6 +43,11 @@ struct Options {
     int hb_blocks = 0, ll_blocks = 0, threads = 0;
     int hb_unroll = 0;        // 0 = by size
     int cache_mode = -1;      // -1 = by footprint, else 0 | 1 | 2 (see choose_cache_mode)
+    // fused HB AllReduce: from this many bytes per rank on, the launch alternates between chip-wide read and
+    // write phases (k_allreduce_hb_phased).  -1 = automatic: 8 ranks from 64 MiB (measured against the
+    // free-running kernel: 1.03x at 64-128 MiB, 1.07x at 256 MiB, 1.10x at 1 GiB; below 64 MiB, and with
+    // fewer ranks, whose phases are smaller, it loses), never otherwise
+    long long hb_phased_min = -1;
     int hb_barriers = 1;
     int peer_outer = 0;
     int barrier_fences = 3;   // msx_prim_barrier only: bit 0 release, bit 1 acquire
@@ -196,6 +202,7 @@ int destroy_ctx(Ctx* c)
     if (c->d.expected) (void)hipFree(c->d.expected);
     if (c->d.status) (void)hipFree(c->d.status);
     if (c->d.call_state) (void)hipFree(c->d.call_state);
+    if (c->d.gbar) (void)hipFree(c->d.gbar);
     if (c->d.ll) (void)hipFree(c->d.ll);
     if (c->moe_slots) (void)hipFree(c->moe_slots);
     if (c->ring) (void)hipFree(c->ring);
@@ -239,6 +246,7 @@ int get_ctx(Ctx** out)
               hipMalloc((void**)&c->d.expected, exp_bytes) == hipSuccess &&
               hipMalloc((void**)&c->d.status, 64) == hipSuccess &&
               hipMalloc((void**)&c->d.call_state, 64) == hipSuccess &&
+              hipMalloc((void**)&c->d.gbar, kGridBarBytes) == hipSuccess &&
               hipMalloc((void**)&c->d.ll, ll_bytes) == hipSuccess &&
               hipMalloc((void**)&c->moe_base, 64 * 4) == hipSuccess &&
               hipMalloc((void**)&c->snap, 4096) == hipSuccess;
@@ -246,6 +254,7 @@ int get_ctx(Ctx** out)
          hipMemset(c->d.expected, 0, exp_bytes) == hipSuccess &&
          hipMemset(c->d.status, 0, 64) == hipSuccess &&
          hipMemset(c->d.call_state, 0, 64) == hipSuccess &&
+         hipMemset(c->d.gbar, 0, kGridBarBytes) == hipSuccess &&
          hipMemset(c->d.ll, 0, ll_bytes) == hipSuccess &&
          hipMemset(c->moe_base, 0, 64 * 4) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
     if (!ok) { destroy_ctx(c); t_hip_err = (int)hipErrorOutOfMemory; return MSX_ERR_NOMEM; }
@@ -355,6 +364,22 @@ HbKernel hb_fused_kernel(int dt, int u, int n, int res, int cache)
 #undef MSX_C
 #undef MSX_R
 #undef MSX_N
+}
+// sums held per thread and phase: 64 vectors fill the register file of a CU that runs one workgroup
+constexpr int kPhasedHeld = 64;
+// does a fused HB AllReduce of nbytes per rank run in chip-wide phases?  (res_mode 2, one residual per
+// destination, would need loads in the write phase)
+bool use_phased(size_t nbytes, int n, int res_mode)
+{
+    if (n < 2 || res_mode == 2 || g_opt.hb_unroll != 0) return false;
+    return g_opt.hb_phased_min < 0 ? n == 8 && nbytes >= ((size_t)64 << 20) : nbytes >= (size_t)g_opt.hb_phased_min;
+}
+HbKernel hb_phased_kernel(int dt, int n, int res)
+{
+#define MSX_P(DT, RES) (n == 8 ? (HbKernel)k_allreduce_hb_phased<DT, 8, RES, kPhasedHeld> : (HbKernel)k_allreduce_hb_phased<DT, 0, RES, kPhasedHeld>)
+    if (dt == MSX_F32) return res ? MSX_P(0, 1) : MSX_P(0, 0);
+    return res ? MSX_P(1, 1) : MSX_P(1, 0);
+#undef MSX_P
 }
 HbKernel hb_2phase_kernel(int dt, int u, int n)
 {
@@ -698,6 +723,13 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     const int res_mode = !residual ? 0 : res_shared ? 1 : 2;
     HbKernel k = algo == MSX_ALGO_2PA_HB ? hb_fused_kernel(dtype, U, n, res_mode, choose_cache_mode(nbytes, n, res_mode))
                                          : hb_2phase_kernel(dtype, U, n);
+    // very large messages: the same sums in chip-wide read and write phases, one workgroup per CU (as many
+    // as are resident; an explicit hb_blocks_per_rank still counts)
+    if (algo == MSX_ALGO_2PA_HB && use_phased(nbytes, n, res_mode)) {
+        k = hb_phased_kernel(dtype, n, res_mode);
+        U = kPhasedHeld;
+        want = g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels;
+    }
     int chans = 1;
     if ((rc = pick_channels(c, (const void*)k, threads, n, per_rank, (size_t)U, want, kMaxChannels, &chans)))
         return rc;
@@ -1278,6 +1310,7 @@ int msx_reset(void)
     HIPCHK(hipMemset(c->d.expected, 0, (size_t)kMaxRanks * kMaxRanks * kMaxChannels * 4));
     HIPCHK(hipMemset(c->d.status, 0, 64));
     HIPCHK(hipMemset(c->d.call_state, 0, 64));
+    HIPCHK(hipMemset(c->d.gbar, 0, kGridBarBytes));
     HIPCHK(hipMemset(c->d.ll, 0, c->d.ll_bytes));
     HIPCHK(hipDeviceSynchronize());
     if (c->port) {                       // a port channel that timed out starts over with a fresh proxy
@@ -1329,6 +1362,7 @@ int msx_set_option(const char* key, const char* value)
         g_opt.drop_rank = (int)u;
         return MSX_OK;
     }
+    if (k == "hb_phased_min_bytes" && v == "auto") { g_opt.hb_phased_min = -1; return MSX_OK; }
     if (k == "cache_mode") {
         if (v == "auto") { g_opt.cache_mode = -1; return MSX_OK; }
         if (!parse_u64(value, &u) || u > 2) return MSX_ERR_ARG;
@@ -1339,6 +1373,7 @@ int msx_set_option(const char* key, const char* value)
     if (k == "ll_1pa_max_bytes") g_opt.ll_1pa_max = (size_t)u;
     else if (k == "ll_2pa_max_bytes") g_opt.ll_2pa_max = (size_t)u;
     else if (k == "coll_ll_max_bytes") g_opt.coll_ll_max = (size_t)u;
+    else if (k == "hb_phased_min_bytes") g_opt.hb_phased_min = u > (unsigned long long)LLONG_MAX ? LLONG_MAX : (long long)u;
     else if (k == "ll_max_bytes") {
         if (u < 4096 || u > (16u << 20)) return MSX_ERR_ARG;
         g_opt.ll_max_bytes = (size_t)u;
@@ -1417,6 +1452,10 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
     if (k == "ll_1pa_max_bytes") u = g_opt.ll_1pa_max;
     else if (k == "ll_2pa_max_bytes") u = g_opt.ll_2pa_max;
     else if (k == "coll_ll_max_bytes") u = g_opt.coll_ll_max;
+    else if (k == "hb_phased_min_bytes") {
+        if (g_opt.hb_phased_min < 0) { snprintf(value_out, value_len, "auto"); return MSX_OK; }
+        u = (unsigned long long)g_opt.hb_phased_min;
+    }
     else if (k == "ll_max_bytes") {
         int dev = 0;
         u = g_opt.ll_max_bytes;
@@ -1475,6 +1514,10 @@ int msx_debug_choose(size_t nbytes, int nranks, size_t ll_limit, int* algo, int*
     std::lock_guard<std::mutex> lk(g_mu);
     *algo = g_opt.algo != MSX_ALGO_AUTO ? g_opt.algo : choose_algo(nbytes, nranks, ll_limit);
     choose_hb_shape(nbytes, nranks, 256, unroll, want_blocks);
+    if (*algo == MSX_ALGO_2PA_HB && use_phased(nbytes, nranks, 0)) {
+        *unroll = kPhasedHeld;
+        *want_blocks = g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels;
+    }
     return MSX_OK;
 }
 

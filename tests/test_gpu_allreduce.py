@@ -371,3 +371,112 @@ def test_plan_interpreter_argument_checks_and_dead_rank(msx, orc):
         msx.set_option("spin_limit", str(1 << 20))
         msx.reset()
     assert np.array_equal(_run_ex(msx, x, 6)[0], _oracle(orc, x))
+
+
+# ---------------------------------------------------------------- fused HB in chip-wide read / write phases
+
+@pytest.fixture
+def phased(msx):
+    """Forces the phased form of the fused HB kernel at any size (by default it starts at 128 MiB per rank)."""
+    old = msx.get_option("hb_phased_min_bytes")
+    msx.set_option("hb_phased_min_bytes", "0")
+    yield msx
+    msx.set_option("hb_phased_min_bytes", old)
+    msx.set_option("hb_blocks_per_rank", "0")
+    msx.set_option("chaos", "0")
+
+
+@pytest.mark.parametrize("n", [2, 3, 7, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_phased_fused_hb_matches_oracle_over_rounds_and_ragged_ends(phased, orc, n, dtype):
+    msx = phased
+    epv = 4 if dtype == torch.float32 else 8
+    # workgroups per rank 1 / 2 / all: a round is (workgroups x 64) tiles of 256 vectors per chunk, so the small
+    # launches run several rounds (the last one partial, some workgroups idle in it) at sizes the oracle likes
+    for blocks, vecs_per_chunk in [(1, 256 * 64 * 3 + 256 * 5 + 77), (2, 256 * 64 * 2 * 2 + 256 * 64 + 1),
+                                   (1, 255), (1, 256), (2, 256 * 64 * 2), (0, 256 * 70 + 9), (0, 3)]:
+        count = vecs_per_chunk * n * epv + (3 if vecs_per_chunk % 2 else 0)        # sometimes a few odd elements
+        msx.set_option("hb_blocks_per_rank", str(blocks))
+        msx.set_option("chaos", str(blocks * 7 + n))
+        x = synth.normal(n, count, seed=300 + n + blocks, dtype=dtype)
+        want = _oracle(orc, x)
+        for inplace in (False, True):
+            got = _run_ex(msx, x, 3, inplace=inplace)
+            grid = msx.last_launch()[0]                          # the phased launch: what was asked for, else one workgroup per CU
+            assert grid == n * blocks if blocks else (grid % n == 0 and 200 <= grid <= 256), (grid, n, blocks)
+            for r in range(n):
+                assert np.array_equal(got[r], want), (n, dtype, blocks, vecs_per_chunk, inplace, r)
+
+
+def test_phased_fused_hb_with_shared_residual_and_back_to_back_calls(phased, orc):
+    msx = phased
+    n, count = 8, 8 * (256 * 64 * 2 + 300) * 8
+    msx.set_option("hb_blocks_per_rank", "1")
+    x = synth.normal(n, count, seed=310)
+    res = synth.normal(1, count, seed=311)[0]
+    want = orc.allreduce_residual_bf16(_bits(x), _bits(res))
+    got = _run_ex(msx, x, 3, residual=res)
+    for r in range(n):
+        assert np.array_equal(got[r], want), r
+    # the barrier counters carry over from call to call, also across other kernels and launch shapes
+    plain = _oracle(orc, x)
+    for i, blocks in enumerate([1, 3, 0, 2, 0, 1]):
+        msx.set_option("hb_blocks_per_rank", str(blocks))
+        msx.set_option("chaos", str(i))
+        assert np.array_equal(_run_ex(msx, x, 3)[i % n], plain), (i, blocks)
+        small = synth.normal(n, 512, seed=320 + i)
+        assert np.array_equal(_run_ex(msx, small, 1)[0], _oracle(orc, small))        # a packet call in between
+    # per-rank residuals are not phased: the ordinary fused kernel serves them
+    per_rank = synth.normal(n, count, seed=312)
+    got = _run_ex(msx, x, 3, residual=per_rank)
+    for r in (0, 5):
+        assert np.array_equal(got[r], orc.allreduce_residual_bf16(_bits(x), _bits(per_rank[r]))), r
+
+
+def test_phased_fused_hb_replays_in_a_hip_graph(phased, orc):
+    msx = phased
+    n, count = 8, 8 * (256 * 64 + 40) * 8
+    msx.set_option("hb_blocks_per_rank", "2")
+    xs = [synth.normal(n, count, seed=330 + i) for i in range(3)]
+    send = [xs[0][r].clone().cuda() for r in range(n)]
+    out = [torch.zeros(count, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    msx.allreduce_ex(send, out, None, algo=3)
+    msx.check_status()
+    st = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(g, stream=st):
+            for _ in range(3):
+                msx.allreduce_ex(send, out, None, algo=3)
+    torch.cuda.synchronize()
+    for i, x in enumerate(xs):
+        for r in range(n):
+            send[r].copy_(x[r])
+            out[r].zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        msx.check_status()
+        want = _oracle(orc, x)
+        for r in (0, 3, 7):
+            assert np.array_equal(_bits(out[r]), want), (i, r)
+        assert np.array_equal(_run_ex(msx, x, 3)[2], want)        # an eager call between the replays
+
+
+def test_phased_fused_hb_dead_rank_times_out_and_context_recovers(phased, orc):
+    msx = phased
+    x = synth.normal(8, 8 * (256 * 64 + 5) * 8, seed=340)
+    msx.set_option("hb_blocks_per_rank", "1")
+    msx.set_option("spin_limit", "2000")
+    msx.set_option("drop_rank", "5")
+    try:
+        send = [x[r].clone().cuda() for r in range(8)]
+        recv = [torch.empty_like(s) for s in send]
+        msx.allreduce_ex(send, recv, None, algo=3)
+        rc, info = msx.status()
+        assert rc == -4, info
+    finally:
+        msx.set_option("drop_rank", "-1")
+        msx.set_option("spin_limit", str(1 << 20))
+        msx.reset()
+    assert np.array_equal(_run_ex(msx, x, 3)[0], _oracle(orc, x))

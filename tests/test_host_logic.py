@@ -179,14 +179,17 @@ def test_automatic_choice_and_launch_shapes(L):
     assert choose(2049)[0] == 3 and choose(1 << 30)[0] == 3       # everything else: fused HB
     assert choose(1024, n=1)[0] == 3                              # a single rank is a copy
     # launch shapes: one pass with one vector per thread up to 2 MiB per rank, two up to 4 MiB, then 32, then
-    # 128 workgroups per rank
+    # 128 workgroups per rank (1024 in all)
     assert choose(64 << 10) == (3, 1, 2)
     assert choose(1 << 20) == (3, 1, 32)
     assert choose(2 << 20) == (3, 1, 64)
     assert choose(4 << 20) == (3, 2, 64)
     assert choose(32 << 20) == (3, 1, 32)
-    assert choose(64 << 20) == (3, 1, 128)
-    assert choose(1 << 30) == (3, 1, 128)
+    assert choose((64 << 20) - 16) == (3, 1, 128)
+    # 8 ranks from 64 MiB: chip-wide read / write phases, 64 sums held per thread, every resident workgroup
+    assert choose(64 << 20) == (3, 64, 256)
+    assert choose(1 << 30) == (3, 64, 256)
+    assert choose(1 << 30, n=7) == (3, 1, 146)
     # thresholds follow the options
     import paper_2504_09014_amd as msx
     old = msx.get_option("ll_2pa_max_bytes")
