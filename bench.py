@@ -160,7 +160,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            t = json.load(open(tpath)).get(f"allreduce_hb_fused_{args.mib}MiB")
+            t = json.load(open(tpath)).get(f"allreduce_hb_{'phased' if phased else 'fused'}_{args.mib}MiB")
             if t:
                 traffic = t["fetch_bytes"] + t["write_bytes"]
         except Exception:
