@@ -828,6 +828,31 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
         case kA2A: kp = keep ? (const void*)k_alltoall_hb<1> : (const void*)k_alltoall_hb<0>; break;
         case kA2AInplace: kp = (const void*)k_alltoall_inplace; break;
     }
+    // large blocks, 8 ranks: chip-wide read and write phases, one workgroup per CU (see k_allreduce_hb_phased)
+    const size_t row_bytes = (which == kRS ? count_or_bytes * elem_size(dtype) : count_or_bytes) * (size_t)n;
+    if ((which == kRS || which == kAG) && vec && use_phased(row_bytes, n, 0)) {
+        HbKernel pk;
+        if (which == kRS)
+            pk = dtype == MSX_F32 ? (n == 8 ? (HbKernel)k_allreduce_hb_phased<0, 8, 0, kPhasedHeld, 1> : (HbKernel)k_allreduce_hb_phased<0, 0, 0, kPhasedHeld, 1>)
+                                  : (n == 8 ? (HbKernel)k_allreduce_hb_phased<1, 8, 0, kPhasedHeld, 1> : (HbKernel)k_allreduce_hb_phased<1, 0, 0, kPhasedHeld, 1>);
+        else
+            pk = n == 8 ? (HbKernel)k_allgather_hb_phased<8, kPhasedHeld> : (HbKernel)k_allgather_hb_phased<0, kPhasedHeld>;
+        int pch = 1;
+        if ((rc = pick_channels(c, (const void*)pk, threads, n, work_units, kPhasedHeld,
+                                g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels, kMaxChannels, &pch)))
+            return rc;
+        HbArgs pa{};
+        for (int i = 0; i < n; ++i) {
+            pa.in[i] = in[i];
+            pa.out[i] = out[i];
+        }
+        pa.count = count_or_bytes;
+        pa.n = n;
+        pa.chans = pch;
+        pa.barriers = g_opt.hb_barriers;
+        note_launch(n * pch, threads, MSX_ALGO_2PA_HB);
+        return launch(pk, n * pch, threads, stream, pa, dev_ctx(c));
+    }
     // workgroups per rank, from sweeps: one vector per thread in a single pass while that fits (small and
     // mid sizes are latency bound: 64 KiB rows 4.8 -> 4.2 us reduce-scatter, 7.9 -> 5.4 us all-gather); for
     // large inputs the read-heavy reduce-scatter runs best with few workgroups per rank (32; 64 up to

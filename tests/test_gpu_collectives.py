@@ -473,6 +473,63 @@ def test_copy_collectives_take_fp16(msx, orc):
     assert np.array_equal(buf.cpu().view(torch.uint16).numpy(), want)
 
 
+# ---------------------------------------------------------------- ReduceScatter / AllGather in chip-wide phases
+
+@pytest.mark.parametrize("n", [2, 3, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_phased_reducescatter_and_allgather_match_oracle(msx, orc, n, dtype):
+    """The forms that alternate between chip-wide read and write phases (by default: 8 ranks, rows from 64 MiB),
+    forced at sizes the oracle likes: 1 or 2 workgroups per rank make several rounds of 64 tiles of 256 vectors
+    (the last round partial), blocks end in a partial tile; in place and out of place."""
+    epv = 4 if dtype == torch.float32 else 8
+    old = msx.get_option("hb_phased_min_bytes")
+    msx.set_option("hb_phased_min_bytes", "0")
+    try:
+        for blocks, vecs in [(1, 256 * 64 * 2 + 256 * 3 + 5), (2, 256 * 64 * 2 * 2 + 256), (1, 200), (0, 256 * 9 + 1)]:
+            c = vecs * epv
+            msx.set_option("hb_blocks_per_rank", str(blocks))
+            msx.set_option("chaos", str(3 + blocks))
+            x = _data(n, n * c, dtype, seed=vecs % 1000)
+            want = orc.reducescatter(_bits(x))
+            send = [x[r].clone().cuda() for r in range(n)]
+            recv = [torch.zeros(c, dtype=dtype, device="cuda") for _ in range(n)]
+            msx.reducescatter_ex(send, recv)
+            msx.check_status()
+            grid = msx.last_launch()[0]
+            assert grid == n * blocks if blocks else (grid % n == 0 and 200 <= grid <= 256), (grid, n, blocks)
+            for r in range(n):
+                assert np.array_equal(_bits(recv[r]), want[r]), ("rs", n, blocks, vecs, r)
+            buf = x.clone().cuda()
+            msx.reducescatter(buf)
+            msx.check_status()
+            got, orig = _bits(buf), _bits(x)
+            for r in range(n):
+                assert np.array_equal(got[r, r * c:(r + 1) * c], want[r]), ("rs in place", n, blocks, vecs, r)
+                mask = np.ones(n * c, bool)
+                mask[r * c:(r + 1) * c] = False
+                assert np.array_equal(got[r, mask], orig[r, mask])
+            y = x[:, :c].contiguous()
+            want_ag = orc.allgather(_bits(y))
+            out = [torch.zeros(n * c, dtype=dtype, device="cuda") for _ in range(n)]
+            msx.allgather_ex([y[r].clone().cuda() for r in range(n)], out)
+            msx.check_status()
+            grid = msx.last_launch()[0]
+            assert grid == n * blocks if blocks else (grid % n == 0 and 200 <= grid <= 256), (grid, n, blocks)
+            for r in range(n):
+                assert np.array_equal(_bits(out[r]), want_ag[r]), ("ag", n, blocks, vecs, r)
+            buf = torch.zeros((n, n * c), dtype=dtype)
+            for r in range(n):
+                buf[r, r * c:(r + 1) * c] = y[r]
+            buf = buf.cuda()
+            msx.allgather(buf)
+            msx.check_status()
+            assert np.array_equal(_bits(buf), want_ag), ("ag in place", n, blocks, vecs)
+    finally:
+        msx.set_option("hb_phased_min_bytes", old)
+        msx.set_option("hb_blocks_per_rank", "0")
+        msx.set_option("chaos", "0")
+
+
 # ---------------------------------------------------------------- packet kernels, ragged sizes, many calls
 
 def test_packet_kernels_with_a_one_lane_tail_never_stall(msx, orc):
