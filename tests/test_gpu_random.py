@@ -50,6 +50,11 @@ def test_random_allreduce_cases(msx, orc, seed):
         if res_mode:
             res = synth.normal(n if res_mode == 2 else 1, count, seed=seed * 100 + case + 50, dtype=dtype)
         msx.set_option("chaos", str(int(rng.integers(0, 50))))
+        # a third of the cases: the fused HB kernel in its phased form (by default only for very large messages),
+        # with few workgroups per rank so that small inputs still take several rounds
+        force_phased = bool(rng.integers(0, 3) == 0)
+        msx.set_option("hb_phased_min_bytes", "0" if force_phased else "auto")
+        msx.set_option("hb_blocks_per_rank", str(int(rng.choice([0, 1, 2, 3]))) if force_phased else "0")
         send = [x[r].clone().cuda() for r in range(n)]
         recv = send if inplace else [torch.full_like(s, float("nan")) for s in send]
         rtab = None
@@ -71,8 +76,11 @@ def test_random_allreduce_cases(msx, orc, seed):
                 want = orc.allreduce_residual_bf16(xb, rr) if bf16 else orc.allreduce_residual_f32(xb, rr)
             got = _bits(recv[r])
             assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), \
-                dict(seed=seed, case=case, n=n, bf16=bf16, count=count, algo=algo, res=res_mode, inplace=inplace, rank=r)
+                dict(seed=seed, case=case, n=n, bf16=bf16, count=count, algo=algo, res=res_mode, inplace=inplace,
+                     phased=force_phased, rank=r)
     msx.set_option("chaos", "0")
+    msx.set_option("hb_phased_min_bytes", "auto")
+    msx.set_option("hb_blocks_per_rank", "0")
 
 
 @pytest.mark.parametrize("seed", range(4))
@@ -95,6 +103,10 @@ def test_random_reducescatter_allgather_alltoall_cases(msx, orc, seed):
         tag = dict(seed=seed, case=case, n=n, dt=dt, op=op, c=c, coll=coll_algo, inplace=inplace)
         msx.set_option("coll_algo", coll_algo)
         msx.set_option("chaos", str(int(rng.integers(0, 50))))
+        force_phased = bool(rng.integers(0, 3) == 0)             # reduce-scatter / all-gather in chip-wide phases
+        msx.set_option("hb_phased_min_bytes", "0" if force_phased else "auto")
+        msx.set_option("hb_blocks_per_rank", str(int(rng.choice([0, 1, 2]))) if force_phased else "0")
+        tag["phased"] = force_phased
         try:
             g = torch.Generator().manual_seed(seed * 1000 + case)
             if dt == 3:
@@ -155,6 +167,8 @@ def test_random_reducescatter_allgather_alltoall_cases(msx, orc, seed):
         finally:
             msx.set_option("coll_algo", "auto")
             msx.set_option("chaos", "0")
+            msx.set_option("hb_phased_min_bytes", "auto")
+            msx.set_option("hb_blocks_per_rank", "0")
 
 
 @pytest.mark.parametrize("seed", range(3))
