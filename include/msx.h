@@ -237,7 +237,8 @@ int msx_finalize(void);
  *   "drop_rank"       -1, or a rank whose workgroups return at once (failure-path tests)
  *   "chaos"           0, or a seed: workgroups sleep pseudo-random times before they signal
  *   "epoch"           next LL flag value (tests of wrap-around; synchronises the device)
- *   "sem_base"        set every semaphore and expected value to this number (wrap tests; syncs)
+ *   "sem_base"        set every semaphore and expected value, and the counters of the chip-wide barrier, to
+ *                     this number (wrap tests; syncs)
  * Read-only (msx_get_option): "status_detail" = for the last timeout msx_status() reported from a packet
  * poll, the source rank whose packet was still missing.
  * Unknown key or bad value -> MSX_ERR_ARG. */

@@ -1446,9 +1446,11 @@ int msx_set_option(const char* key, const char* value)
         for (size_t i = 0; i < ns * kSemStrideWords; ++i) host[i] = (unsigned)u;
         hipError_t e1 = hipMemcpy(c->d.sem, host, ns * kSemStrideWords * 4, hipMemcpyHostToDevice);
         hipError_t e2 = hipMemcpy(c->d.expected, host, ns * 4, hipMemcpyHostToDevice);
+        hipError_t e3 = hipMemcpy(c->d.gbar, host, kGridBarBytes, hipMemcpyHostToDevice);   // counters and their bases
         free(host);
         HIPCHK(e1);
         HIPCHK(e2);
+        HIPCHK(e3);
         HIPCHK(hipDeviceSynchronize());
     } else {
         return MSX_ERR_ARG;

@@ -480,3 +480,19 @@ def test_phased_fused_hb_dead_rank_times_out_and_context_recovers(phased, orc):
         msx.set_option("spin_limit", str(1 << 20))
         msx.reset()
     assert np.array_equal(_run_ex(msx, x, 3)[0], _oracle(orc, x))
+
+
+def test_phased_fused_hb_survives_barrier_counter_wraparound(phased, orc):
+    """The chip-wide barrier's counters only grow; here they start three short of 2^32, so the very first
+    barrier of the first call wraps them (signed distances decide), and later calls continue from there."""
+    msx = phased
+    n, count = 8, 8 * (256 * 64 * 3 + 40) * 8
+    msx.set_option("hb_blocks_per_rank", "1")
+    msx.set_option("sem_base", str(2 ** 32 - 3))
+    try:
+        for i in range(3):
+            x = synth.normal(n, count, seed=350 + i)
+            got = _run_ex(msx, x, 3)
+            assert np.array_equal(got[i], _oracle(orc, x)), i
+    finally:
+        msx.reset()
