@@ -31,8 +31,18 @@ _RE_ROUNDTRIP = re.compile(r'v_cmp_ne_u32_e64 (s\[\d+:\d+\]), 1, v\d+')
 def device_assembly(out_path):
     """Compile csrc/*.hip for gfx950, device side only, to assembly text."""
     flags = [f for f in _build.FLAGS if f not in ("-shared", "-fPIC")]
-    cmd = [_build.HIPCC] + flags + ["--cuda-device-only", "-S", "-o", out_path] + _build.sources()
-    subprocess.run(cmd, check=True, stderr=subprocess.DEVNULL)
+    jobs = []
+    for k, src in enumerate(_build.sources()):              # one translation unit each, all at once
+        part = f"{out_path}.{k}"
+        cmd = [_build.HIPCC] + flags + ["--cuda-device-only", "-S", "-o", part, src]
+        jobs.append((cmd, part, subprocess.Popen(cmd, stderr=subprocess.DEVNULL)))
+    with open(out_path, "w") as out:
+        for cmd, part, proc in jobs:
+            if proc.wait() != 0:
+                raise subprocess.CalledProcessError(proc.returncode, cmd)
+            with open(part) as f:
+                out.write(f.read())
+            os.remove(part)
     return out_path
 
 

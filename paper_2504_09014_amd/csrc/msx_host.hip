@@ -21,6 +21,7 @@
 
 #include "msx_device.hpp"
 #include "msx_kernels_hb.hpp"
+#include "msx_phased.hpp"
 #include "msx_kernels_ll.hpp"
 #include "msx_kernels_moe.hpp"
 #include "msx_kernels_plan.hpp"
@@ -365,21 +366,12 @@ HbKernel hb_fused_kernel(int dt, int u, int n, int res, int cache)
 #undef MSX_R
 #undef MSX_N
 }
-// sums held per thread and phase: 64 vectors fill the register file of a CU that runs one workgroup
-constexpr int kPhasedHeld = 64;
 // does a fused HB AllReduce of nbytes per rank run in chip-wide phases?  (res_mode 2, one residual per
 // destination, would need loads in the write phase)
 bool use_phased(size_t nbytes, int n, int res_mode)
 {
     if (n < 2 || res_mode == 2 || g_opt.hb_unroll != 0) return false;
     return g_opt.hb_phased_min < 0 ? n == 8 && nbytes >= ((size_t)64 << 20) : nbytes >= (size_t)g_opt.hb_phased_min;
-}
-HbKernel hb_phased_kernel(int dt, int n, int res)
-{
-#define MSX_P(DT, RES) (n == 8 ? (HbKernel)k_allreduce_hb_phased<DT, 8, RES, kPhasedHeld> : (HbKernel)k_allreduce_hb_phased<DT, 0, RES, kPhasedHeld>)
-    if (dt == MSX_F32) return res ? MSX_P(0, 1) : MSX_P(0, 0);
-    return res ? MSX_P(1, 1) : MSX_P(1, 0);
-#undef MSX_P
 }
 HbKernel hb_2phase_kernel(int dt, int u, int n)
 {
@@ -726,7 +718,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     // very large messages: the same sums in chip-wide read and write phases, one workgroup per CU (as many
     // as are resident; an explicit hb_blocks_per_rank still counts)
     if (algo == MSX_ALGO_2PA_HB && use_phased(nbytes, n, res_mode)) {
-        k = hb_phased_kernel(dtype, n, res_mode);
+        k = phased_reduce_kernel(dtype == MSX_F32, n, res_mode, 0);
         U = kPhasedHeld;
         want = g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels;
     }
@@ -831,12 +823,7 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     // large blocks, 8 ranks: chip-wide read and write phases, one workgroup per CU (see k_allreduce_hb_phased)
     const size_t row_bytes = (which == kRS ? count_or_bytes * elem_size(dtype) : count_or_bytes) * (size_t)n;
     if ((which == kRS || which == kAG) && vec && use_phased(row_bytes, n, 0)) {
-        HbKernel pk;
-        if (which == kRS)
-            pk = dtype == MSX_F32 ? (n == 8 ? (HbKernel)k_allreduce_hb_phased<0, 8, 0, kPhasedHeld, 1> : (HbKernel)k_allreduce_hb_phased<0, 0, 0, kPhasedHeld, 1>)
-                                  : (n == 8 ? (HbKernel)k_allreduce_hb_phased<1, 8, 0, kPhasedHeld, 1> : (HbKernel)k_allreduce_hb_phased<1, 0, 0, kPhasedHeld, 1>);
-        else
-            pk = n == 8 ? (HbKernel)k_allgather_hb_phased<8, kPhasedHeld> : (HbKernel)k_allgather_hb_phased<0, kPhasedHeld>;
+        HbKernel pk = which == kRS ? phased_reduce_kernel(dtype == MSX_F32, n, 0, 1) : phased_allgather_kernel(n);
         int pch = 1;
         if ((rc = pick_channels(c, (const void*)pk, threads, n, work_units, kPhasedHeld,
                                 g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels, kMaxChannels, &pch)))

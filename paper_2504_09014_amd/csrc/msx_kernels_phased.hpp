@@ -1,0 +1,222 @@
+// HB-protocol kernels that alternate, over the whole chip, between a read phase and a write phase: the fused
+// two-phase all-pairs AllReduce (Collectives Library section, 2PA with the DSL's fused reduce-then-put), its
+// reduce-scatter half on its own, and the all-gather copy.  Compiled in a translation unit of their own
+// (msx_phased.hip): each instantiation is tens of thousands of instructions long.
+#pragma once
+#include "msx_device.hpp"
+#include "msx_hb_common.hpp"
+
+namespace msx {
+
+// ---- the fused form with the whole chip alternating between reading and writing ---------------
+// Same result, same bytes and the same owner-computes layout as k_allreduce_hb_fused, for messages far
+// larger than the caches.  HBM runs a pure read stream or a pure write stream faster than any mix of the
+// two (measured on MI355X: 8 input streams alone 6.4-7.0 TB/s, stores alone 5.6-6.4 TB/s, every mix from
+// 8:1 to 1:1 5.2-5.4 TB/s), so the launch works in rounds: every thread sums H vectors of its rank's chunk
+// into registers (read phase), all workgroups meet at a barrier, every thread puts its H sums to all ranks
+// (write phase), barrier.  A phase moves H x 16 B x 8 ranks x (threads of the launch) bytes, about 0.5 GB
+// at H = 64: more than the memory-side cache holds, so DRAM itself sees the alternation (phases of a few
+// tens of MB, tried with a plain copy, gave nothing).  One workgroup per CU (the sums take most of the
+// register file); loads run two groups of G vectors x N ranks ahead.
+// RES: 0 no residual, 1 one residual shared by all ranks (one more input stream).
+// KIND: 0 AllReduce (a.count = elements per rank), 1 ReduceScatter on its own (a.count = elements per
+// block, whole vectors; the sums go to the rank's own output only: the write phase is an eighth of the read
+// phase, and keeping even that out of the reads pays).
+template <int DT, int NR, int RES, int H, int KIND = 0>
+__global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
+{
+    constexpr int G = 2, HG = H / G, NS = kMaxRanks + (RES ? 1 : 0);
+    static_assert(H % (2 * G) == 0, "the read phase is unrolled in pairs of groups");
+    static_assert(KIND == 0 || RES == 0, "the reduce-scatter takes no residual");
+    const int n = NR ? NR : a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = NR ? NR : per_lane(n);   // per-lane copies for conditions (see per_lane)
+    if (rank == c.drop_rank) return;
+    constexpr size_t epv = DT == 0 ? 4 : 8;
+    constexpr size_t esz = DT == 0 ? 4 : 2;
+    const size_t V = a.count / epv;
+
+    GridBar gb = grid_barrier_begin(c);
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, KIND ? 32 : 12, false, false);   // every peer has entered the call
+
+    // the vectors [lo, hi) of every source belong to this rank
+    const void* src[kMaxRanks];
+#pragma unroll
+    for (int j = 0; j < kMaxRanks; ++j)
+        src[j] = j >= n ? nullptr : KIND ? (const void*)((const char*)a.in[j] + (size_t)rank * a.count * esz) : a.in[j];
+    const size_t lo = KIND ? 0 : chunk_begin(V, rank, n);
+    const size_t hi = KIND ? V : chunk_begin(V, rank + 1, n);
+    const size_t tiles = (hi - lo) / 256;                // whole tiles; a tile: one vector per thread of the workgroup
+    size_t most = tiles;                                 // every workgroup runs as many rounds as the longest chunk needs
+    if constexpr (KIND == 0) {
+        most = 0;
+        for (int r = 0; r < n; ++r) {
+            const size_t t = (chunk_begin(V, r + 1, n) - chunk_begin(V, r, n)) / 256;
+            most = t > most ? t : most;
+        }
+    }
+    const size_t per_round = (size_t)a.chans * H;
+    const unsigned rounds = (unsigned)((most + per_round - 1) / per_round);
+    unsigned gen = 0;
+    auto put = [&](size_t idx, u32x4 o) {
+        if constexpr (KIND == 1) {
+            st16(a.out[rank], idx, o);                   // my own output: nothing to publish
+        } else {
+#pragma unroll
+            for (int p = 0; p < kMaxRanks; ++p)
+                if (p < n_l) st16_wt(a.out[p], idx, o);
+        }
+    };
+
+    for (unsigned round = 0; round < rounds; ++round) {
+        const size_t first = ((size_t)round * a.chans + (size_t)chan) * H;       // my H consecutive tiles of this round
+        const unsigned mine = first >= tiles ? 0u : (unsigned)(tiles - first < (size_t)H ? tiles - first : (size_t)H);
+        const int nq = (int)((mine + G - 1) / G);
+        const size_t i0 = lo + first * 256 + threadIdx.x;
+        u32x4 held[H];
+        u32x4 va[G][NS], vb[G][NS];
+        // all: the workgroup has all H tiles this round (every round but a chunk's last): no conditions at all,
+        // so that the loads of the next groups stay in flight while a group is summed
+        auto issue = [&](auto all, int g, u32x4 (&v)[G][NS]) {
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                const size_t idx = i0 + (size_t)(g * G + i) * 256;
+                if (decltype(all)::value || (unsigned)(g * G + i) < mine) {     // uniform: whole tiles only
+                    MSX_LOAD_ALL(v[i], src, idx)
+                    if constexpr (RES == 1) v[i][kMaxRanks] = ld16(a.res[0], idx);
+                }
+            }
+        };
+        auto reduce = [&](int g, u32x4 (&v)[G][NS]) {
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                VecAcc<DT> acc;
+                MSX_SUM_ALL(acc, v[i])
+                if constexpr (RES == 1) acc.add(v[i][kMaxRanks]);
+                held[g * G + i] = acc.pack();
+            }
+        };
+        // read phase (static_for: the sums must stay in registers, so every index into `held` is a constant;
+        // a loop this long is beyond what the unrolling pragma is honoured for)
+        auto read_phase = [&](auto all) {
+            constexpr bool A = decltype(all)::value;
+            if (A || 0 < nq) issue(all, 0, va);
+            static_for<HG / 2>([&](auto k) {
+                constexpr int g = 2 * decltype(k)::value;
+                if (A || g + 1 < nq) issue(all, g + 1, vb);
+                if (A || g < nq) reduce(g, va);
+                if (g + 2 < HG && (A || g + 2 < nq)) issue(all, g + 2, va);
+                if (A || g + 1 < nq) reduce(g + 1, vb);
+            });
+        };
+        if constexpr (NR != 0) {
+            if (mine == (unsigned)H) read_phase(std::true_type{});
+            else read_phase(std::false_type{});
+        } else {
+            read_phase(std::false_type{});     // rank count at run time: the second copy would not fit the registers
+        }
+        grid_barrier(c, gb, ++gen, (unsigned)rank, 13);
+        // write phase
+        auto write_phase = [&](auto all) {
+            static_for<H>([&](auto k) {
+                constexpr int h = decltype(k)::value;
+                if (decltype(all)::value || (unsigned)h < mine) put(i0 + (size_t)h * 256, held[h]);
+            });
+        };
+        if constexpr (NR != 0) {
+            if (mine == (unsigned)H) write_phase(std::true_type{});
+            else write_phase(std::false_type{});
+        } else {
+            write_phase(std::false_type{});
+        }
+        put_drain();
+        if (round + 1 < rounds) grid_barrier(c, gb, ++gen, (unsigned)rank, 14);
+    }
+    grid_barrier_end(c, gb, gen);
+    // what is left of the chunk behind its last whole tile (less than one vector per thread): the rank's first workgroup
+    if (chan == 0) {
+        const size_t idx = lo + tiles * 256 + threadIdx.x;
+        if (idx < hi) {
+            u32x4 v[NS];
+            MSX_LOAD_ALL(v, src, idx)
+            if constexpr (RES == 1) v[kMaxRanks] = ld16(a.res[0], idx);
+            VecAcc<DT> acc;
+            MSX_SUM_ALL(acc, v)
+            if constexpr (RES == 1) acc.add(v[kMaxRanks]);
+            put(idx, acc.pack());
+        }
+    }
+    bool tail = false;
+    if constexpr (KIND == 0) {
+        tail = rank == 0 && chan == 0 && V * epv < a.count;
+        if (tail) allreduce_tail<DT>(a, n_l, V * epv, a.count);
+    }
+    put_drain();
+    // AllReduce: my puts have landed everywhere; ReduceScatter: the peers are done reading my input
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, KIND ? 33 : 11, tail, false);
+}
+
+// ---- standalone AllGather in chip-wide read and write phases ------------------------------------
+// out[p] block r = in[r] as k_allgather_hb does (a.count = bytes per block, whole vectors).  The write phase
+// is eight times the read phase; what the phases buy is that the stores run without loads between them.
+template <int NR, int H>
+__global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
+{
+    const int n = NR ? NR : a.n;
+    const int rank = (int)(blockIdx.x % (unsigned)n);
+    const int chan = (int)(blockIdx.x / (unsigned)n);
+    const int n_l = NR ? NR : per_lane(n);   // per-lane copies for conditions (see per_lane)
+    if (rank == c.drop_rank) return;
+    GridBar gb = grid_barrier_begin(c);
+    const size_t nbytes = a.count;
+    const char* src = (const char*)a.in[rank];
+    char* dst[kMaxRanks];
+    int skip = -1;                       // the destination that is the source itself (in place)
+#pragma unroll
+    for (int p = 0; p < kMaxRanks; ++p) {
+        dst[p] = p < n ? (char*)a.out[p] + (size_t)rank * nbytes : nullptr;
+        if (p < n && dst[p] == src) skip = p;
+    }
+    const int skip_l = per_lane(skip);
+    const size_t nv = nbytes >> 4, tiles = nv / 256;
+    const size_t per_round = (size_t)a.chans * H;
+    const unsigned rounds = (unsigned)((tiles + per_round - 1) / per_round);
+    unsigned gen = 0;
+    auto put = [&](size_t idx, u32x4 o) {
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p)
+            if (p < n_l && p != skip_l) st16_wt(dst[p], idx, o);
+    };
+    for (unsigned round = 0; round < rounds; ++round) {
+        const size_t first = ((size_t)round * a.chans + (size_t)chan) * H;
+        const unsigned mine = first >= tiles ? 0u : (unsigned)(tiles - first < (size_t)H ? tiles - first : (size_t)H);
+        const size_t i0 = first * 256 + threadIdx.x;
+        u32x4 held[H];
+        static_for<H>([&](auto k) {
+            constexpr int h = decltype(k)::value;
+            if ((unsigned)h < mine) held[h] = ld16(src, i0 + (size_t)h * 256);
+        });
+        static_for<H>([&](auto k) { settle(held[decltype(k)::value]); });
+        grid_barrier(c, gb, ++gen, (unsigned)rank, 43);
+        static_for<H>([&](auto k) {
+            constexpr int h = decltype(k)::value;
+            if ((unsigned)h < mine) put(i0 + (size_t)h * 256, held[h]);
+        });
+        put_drain();
+        if (round + 1 < rounds) grid_barrier(c, gb, ++gen, (unsigned)rank, 44);
+    }
+    grid_barrier_end(c, gb, gen);
+    if (chan == 0) {
+        const size_t idx = tiles * 256 + threadIdx.x;
+        if (idx < nv) {
+            u32x4 v = ld16(src, idx);
+            settle(v);
+            put(idx, v);
+        }
+    }
+    put_drain();
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 40, false, false);   // my block has landed everywhere
+}
+
+}  // namespace msx

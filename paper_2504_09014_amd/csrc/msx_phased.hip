@@ -1,0 +1,20 @@
+// Selectors of the phased HB kernels, and the all-gather's instantiations (see msx_kernels_phased.hpp).
+#include <hip/hip_runtime.h>
+
+#include "msx_kernels_phased.hpp"
+#include "msx_phased.hpp"
+
+namespace msx {
+
+PhasedKernel phased_reduce_kernel(bool f32, int nranks, int res, int kind)
+{
+    if (kind == 1) return phased_reducescatter(f32, nranks);
+    return f32 ? phased_allreduce_f32(nranks, res) : phased_allreduce_bf16(nranks, res);
+}
+
+PhasedKernel phased_allgather_kernel(int nranks)
+{
+    return nranks == 8 ? (PhasedKernel)k_allgather_hb_phased<8, kPhasedHeld> : (PhasedKernel)k_allgather_hb_phased<0, kPhasedHeld>;
+}
+
+}  // namespace msx
