@@ -228,6 +228,31 @@ __device__ __forceinline__ void grid_barrier_end(const DevCtx& c, const GridBar&
     if (blockIdx.x == 0 && threadIdx.x < 8) c.gbar[kGridBarBaseWord + threadIdx.x] = g.base + gens * g.per_gen;
 }
 
+// ---- pacing against the wall clock ------------------------------------------------------------------
+// Holds the wave until the 100 MHz wall clock has reached `target`.  Written as one assembly block: a C++
+// loop (or even a branch around this call) between the loads and sums of a long unrolled sequence made
+// the register allocator spill a thousand registers.  The clock always advances, so the loop ends; callers
+// keep targets within a millisecond of the present.
+__device__ __forceinline__ void wait_until(unsigned long long target)
+{
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)target);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(target >> 32));
+    asm volatile(
+        "1:\n\t"
+        "s_memrealtime s[90:91]\n\t"
+        "s_waitcnt lgkmcnt(0)\n\t"
+        "s_sub_u32 s90, s90, %0\n\t"
+        "s_subb_u32 s91, s91, %1\n\t"
+        "s_cmp_lt_i32 s91, 0\n\t"        // now - target < 0: not yet
+        "s_cbranch_scc0 2f\n\t"
+        "s_sleep 1\n\t"
+        "s_branch 1b\n"
+        "2:\n\t"
+        :
+        : "s"(lo), "s"(hi)
+        : "s90", "s91", "scc");
+}
+
 // ---- per-call flag and scratch rotation for the LL protocol -----------------------------------
 // The flag of a call and the scratch half it uses come from device memory, not from kernel
 // arguments, so a captured launch can be replayed: every workgroup reads the state when it

@@ -16,6 +16,7 @@ struct HbArgs {
     int res_shared;     // all residual pointers are the same buffer
     int barriers;       // run the start / end rank barriers
     int peer_outer;     // two-phase all-gather: one hb_put per peer instead of peer-inner
+    int pace;           // phased kernels: hold the write phase to a common schedule
 };
 
 template <int DT> __device__ __forceinline__ float load_elem(const void* p, size_t e)

@@ -50,6 +50,7 @@ struct Options {
     // fewer ranks, whose phases are smaller, it loses), never otherwise
     long long hb_phased_min = -1;
     int hb_barriers = 1;
+    int hb_pace = 1;          // phased kernels: pace the write phase (see k_allreduce_hb_phased)
     int peer_outer = 0;
     int barrier_fences = 3;   // msx_prim_barrier only: bit 0 release, bit 1 acquire
     int coll_algo = 0;        // allgather / reducescatter: 0 auto, 1 LL packets, 2 HB
@@ -738,6 +739,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     a.res_shared = res_shared ? 1 : 0;
     a.barriers = g_opt.hb_barriers;
     a.peer_outer = g_opt.peer_outer;
+    a.pace = g_opt.hb_pace;
     note_launch(n * chans, threads, algo);
     return launch(k, n * chans, threads, stream, a, dev_ctx(c));
 }
@@ -837,6 +839,7 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
         pa.n = n;
         pa.chans = pch;
         pa.barriers = g_opt.hb_barriers;
+        pa.pace = g_opt.hb_pace;
         note_launch(n * pch, threads, MSX_ALGO_2PA_HB);
         return launch(pk, n * pch, threads, stream, pa, dev_ctx(c));
     }
@@ -1401,6 +1404,9 @@ int msx_set_option(const char* key, const char* value)
     } else if (k == "hb_unroll") {
         if (u != 0 && u != 1 && u != 2 && u != 4 && u != 8) return MSX_ERR_ARG;
         g_opt.hb_unroll = (int)u;
+    } else if (k == "hb_pace") {
+        if (u > 1) return MSX_ERR_ARG;
+        g_opt.hb_pace = (int)u;
     } else if (k == "hb_barriers") {
         if (u > 1) return MSX_ERR_ARG;
         g_opt.hb_barriers = (int)u;
@@ -1483,6 +1489,7 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
         return MSX_OK;
     }
     else if (k == "hb_barriers") u = (unsigned)g_opt.hb_barriers;
+    else if (k == "hb_pace") u = (unsigned)g_opt.hb_pace;
     else if (k == "peer_outer") u = (unsigned)g_opt.peer_outer;
     else if (k == "barrier_fences") u = (unsigned)g_opt.barrier_fences;
     else if (k == "spin_limit") u = g_opt.spin_limit;

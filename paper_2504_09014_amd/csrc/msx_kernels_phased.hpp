@@ -8,6 +8,9 @@
 
 namespace msx {
 
+// launches with fewer rounds than this do not pace their write phases (see k_allreduce_hb_phased)
+constexpr unsigned kPacedRounds = 12;
+
 // ---- the fused form with the whole chip alternating between reading and writing ---------------
 // Same result, same bytes and the same owner-computes layout as k_allreduce_hb_fused, for messages far
 // larger than the caches.  HBM runs a pure read stream or a pure write stream faster than any mix of the
@@ -58,7 +61,10 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
     }
     const size_t per_round = (size_t)a.chans * H;
     const unsigned rounds = (unsigned)((most + per_round - 1) / per_round);
+    const bool pacing = a.pace && rounds >= kPacedRounds;
     unsigned gen = 0;
+    unsigned pace = 0;        // wall-clock ticks between the puts of two tiles in a full write phase (0: none yet)
+    unsigned long long best = 100000ull;   // shortest full write phase seen, in ticks (a millisecond: none yet)
     auto put = [&](size_t idx, u32x4 o) {
         if constexpr (KIND == 1) {
             st16(a.out[rank], idx, o);                   // my own output: nothing to publish
@@ -117,10 +123,21 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
             read_phase(std::false_type{});     // rank count at run time: the second copy would not fit the registers
         }
         grid_barrier(c, gb, ++gen, (unsigned)rank, 13);
-        // write phase
+        // write phase.  The dies do not get equal shares of the store bandwidth (in one phase the fastest is done
+        // after 45 us, the slowest after 70 us, and which is which changes from phase to phase), and the last
+        // dies alone cannot fill the memory system.  So a full write phase is paced: tile h goes out no earlier
+        // than h x pace after the phase began, with pace = 61/64 of what the shortest full write phase so far took
+        // per tile (the shortest: a phase that was slow for another reason must not loosen the schedule).  Fast dies are held to the common schedule, the slow ones get the bandwidth that frees, and all
+        // finish together (measured: arrival spread 23 -> 3 us, write phase 70 -> 65 us).  A schedule that is
+        // too tight paces nobody.  Only for launches of kPacedRounds rounds or more: the read phase that
+        // follows a paced write phase is a little slower (every die has only just stopped writing when it
+        // begins), and the schedule needs some rounds to tighten; measured over several machines, 8 ranks:
+        // -1 to -5 % at 128-512 MiB per rank (4-8 rounds), +4 to +6 % at 1 GiB (16 rounds).
+        const unsigned long long w0 = wall_clock64();
         auto write_phase = [&](auto all) {
             static_for<H>([&](auto k) {
                 constexpr int h = decltype(k)::value;
+                if constexpr (decltype(all)::value && KIND == 0) wait_until(w0 + (unsigned long long)((unsigned)h * pace));
                 if (decltype(all)::value || (unsigned)h < mine) put(i0 + (size_t)h * 256, held[h]);
             });
         };
@@ -131,7 +148,18 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
             write_phase(std::false_type{});
         }
         put_drain();
-        if (round + 1 < rounds) grid_barrier(c, gb, ++gen, (unsigned)rank, 14);
+        if (round + 1 < rounds) {
+            grid_barrier(c, gb, ++gen, (unsigned)rank, 14);
+            if constexpr (NR != 0 && KIND == 0) {
+                // every workgroup of a round but the last few of a chunk is full, so all of them see (nearly) the
+                // same duration and pace alike
+                const unsigned long long took = wall_clock64() - w0;
+                if (pacing && mine == (unsigned)H && took < best) {     // the shortest full write phase so far sets the schedule
+                    best = took;
+                    pace = (unsigned)(took * 61ull / (64ull * H));
+                }
+            }
+        }
     }
     grid_barrier_end(c, gb, gen);
     // what is left of the chunk behind its last whole tile (less than one vector per thread): the rank's first workgroup
@@ -184,7 +212,10 @@ __global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
     const size_t nv = nbytes >> 4, tiles = nv / 256;
     const size_t per_round = (size_t)a.chans * H;
     const unsigned rounds = (unsigned)((tiles + per_round - 1) / per_round);
+    const bool pacing = a.pace && rounds >= kPacedRounds;
     unsigned gen = 0;
+    unsigned pace = 0;        // wall-clock ticks between the puts of two tiles (0: none yet)
+    unsigned long long best = 100000ull;
     auto put = [&](size_t idx, u32x4 o) {
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
@@ -201,12 +232,23 @@ __global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
         });
         static_for<H>([&](auto k) { settle(held[decltype(k)::value]); });
         grid_barrier(c, gb, ++gen, (unsigned)rank, 43);
+        const unsigned long long w0 = wall_clock64();          // paced like the AllReduce's write phase
         static_for<H>([&](auto k) {
             constexpr int h = decltype(k)::value;
-            if ((unsigned)h < mine) put(i0 + (size_t)h * 256, held[h]);
+            if ((unsigned)h < mine) {
+                wait_until(w0 + (unsigned long long)((unsigned)h * pace));
+                put(i0 + (size_t)h * 256, held[h]);
+            }
         });
         put_drain();
-        if (round + 1 < rounds) grid_barrier(c, gb, ++gen, (unsigned)rank, 44);
+        if (round + 1 < rounds) {
+            grid_barrier(c, gb, ++gen, (unsigned)rank, 44);
+            const unsigned long long took = wall_clock64() - w0;
+            if (pacing && mine == (unsigned)H && took < best) {     // the shortest full write phase so far sets the schedule
+                    best = took;
+                    pace = (unsigned)(took * 61ull / (64ull * H));
+                }
+        }
     }
     grid_barrier_end(c, gb, gen);
     if (chan == 0) {

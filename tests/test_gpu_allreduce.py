@@ -496,3 +496,30 @@ def test_phased_fused_hb_survives_barrier_counter_wraparound(phased, orc):
             assert np.array_equal(got[i], _oracle(orc, x)), i
     finally:
         msx.reset()
+
+
+def test_phased_fused_hb_with_paced_write_phases(phased, orc):
+    """Launches of 12 rounds or more hold their write phases to a wall-clock schedule derived from the rounds
+    before; one workgroup per rank makes 13 rounds out of 27 MiB per rank.  Pacing must not change a bit."""
+    msx = phased
+    n, count = 8, 8 * (256 * 64 * 13 + 77) * 8
+    msx.set_option("hb_blocks_per_rank", "1")
+    x = synth.normal(n, count, seed=360)
+    want = _oracle(orc, x)
+    for pace in ("1", "0"):
+        msx.set_option("hb_pace", pace)
+        try:
+            got = _run_ex(msx, x, 3)
+        finally:
+            msx.set_option("hb_pace", "1")
+        for r in (0, 7):
+            assert np.array_equal(got[r], want), (pace, r)
+    # the all-gather paces the same way
+    blk = (256 * 64 * 13 + 5) * 8
+    y = synth.normal(n, blk, seed=361)
+    out = [torch.zeros(n * blk, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    msx.allgather_ex([y[r].clone().cuda() for r in range(n)], out)
+    msx.check_status()
+    want_ag = orc.allgather(_bits(y))
+    for r in (0, 5):
+        assert np.array_equal(_bits(out[r]), want_ag[r]), r
