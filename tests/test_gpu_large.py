@@ -42,8 +42,9 @@ def _windows(count, n, rng):
     return spans
 
 
-# 3, 8 and 24 MiB: the cache-keeping forms of the fused kernel (loads and stores / stores only)
-@pytest.mark.parametrize("mib,algo", [(3, 3), (8, 3), (24, 3), (64, 3), (64, 4), (256, 3), (1024, 3)])
+# 3, 8 and 24 MiB: the cache-keeping forms of the fused kernel (loads and stores / stores only); 4 GiB: 2^31
+# elements per rank (64-bit indexing everywhere), 64 rounds of the phased kernel with paced write phases
+@pytest.mark.parametrize("mib,algo", [(3, 3), (8, 3), (24, 3), (64, 3), (64, 4), (256, 3), (1024, 3), (4096, 3)])
 def test_config3_large_allreduce(msx, orc, mib, algo):
     n = 8
     count = mib * (1 << 20) // 2
