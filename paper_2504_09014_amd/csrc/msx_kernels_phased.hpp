@@ -1,7 +1,7 @@
 // HB-protocol kernels that alternate, over the whole chip, between a read phase and a write phase: the fused
 // two-phase all-pairs AllReduce (Collectives Library section, 2PA with the DSL's fused reduce-then-put), its
 // reduce-scatter half on its own, and the all-gather copy.  Compiled in a translation unit of their own
-// (msx_phased.hip): each instantiation is tens of thousands of instructions long.
+// (msx_phased*.hip): each instantiation is tens of thousands of instructions long.
 #pragma once
 #include "msx_device.hpp"
 #include "msx_hb_common.hpp"
@@ -126,13 +126,14 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
         // write phase.  The dies do not get equal shares of the store bandwidth (in one phase the fastest is done
         // after 45 us, the slowest after 70 us, and which is which changes from phase to phase), and the last
         // dies alone cannot fill the memory system.  So a full write phase is paced: tile h goes out no earlier
-        // than h x pace after the phase began, with pace = 61/64 of what the shortest full write phase so far took
-        // per tile (the shortest: a phase that was slow for another reason must not loosen the schedule).  Fast dies are held to the common schedule, the slow ones get the bandwidth that frees, and all
-        // finish together (measured: arrival spread 23 -> 3 us, write phase 70 -> 65 us).  A schedule that is
-        // too tight paces nobody.  Only for launches of kPacedRounds rounds or more: the read phase that
-        // follows a paced write phase is a little slower (every die has only just stopped writing when it
-        // begins), and the schedule needs some rounds to tighten; measured over several machines, 8 ranks:
-        // -1 to -5 % at 128-512 MiB per rank (4-8 rounds), +4 to +6 % at 1 GiB (16 rounds).
+        // than h x pace after the phase began, with pace = 61/64 of what the shortest full write phase so far
+        // took per tile (the shortest: a phase that was slow for another reason must not loosen the schedule).
+        // Fast dies are held to the common schedule, the slow ones get the bandwidth that frees, and all finish
+        // together (measured: arrival spread 23 -> 3 us, write phase 70 -> 65 us).  A schedule that is too
+        // tight paces nobody.  Only for launches of kPacedRounds rounds or more: the read phase that follows a
+        // paced write phase is a little slower (every die has only just stopped writing when it begins), and
+        // the schedule needs some rounds to tighten; measured over several machines, 8 ranks: -1 to -5 % at
+        // 128-512 MiB per rank (4-8 rounds), +4 to +6 % at 1 GiB (16 rounds).
         const unsigned long long w0 = wall_clock64();
         auto write_phase = [&](auto all) {
             static_for<H>([&](auto k) {
