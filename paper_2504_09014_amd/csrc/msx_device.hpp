@@ -177,7 +177,8 @@ __device__ __forceinline__ void rank_barrier(const DevCtx& c, int me, int n, int
 struct GridBar { unsigned base, per_gen; bool ok; };   // lanes 0..7 of the first wave hold counter x's values
 
 constexpr int kGridBarBaseWord = 8 * kSemStrideWords;
-constexpr size_t kGridBarBytes = (size_t)(kGridBarBaseWord + 8) * 4;
+constexpr int kGridBarPaceWord = kGridBarBaseWord + kSemStrideWords;     // a word of its own line: the write-phase schedule
+constexpr size_t kGridBarBytes = (size_t)(kGridBarPaceWord + kSemStrideWords) * 4;
 
 // Workgroup-collective; first thing (before any arrival of this call can have happened: an arrival
 // needs this workgroup's own).
@@ -251,6 +252,37 @@ __device__ __forceinline__ void wait_until(unsigned long long target)
         :
         : "s"(lo), "s"(hi)
         : "s90", "s91", "scc");
+}
+
+// ---- the schedule of paced write phases (phased kernels) -----------------------------------------
+// A write phase of H tiles is held to `pace` wall-clock ticks per tile (wait_until), so that all dies finish
+// it together; the controller looks for the tightest schedule the memory system still meets.  Workgroup 0
+// decides after every full write phase, from how long the phase took, and leaves the new pace in the barrier's
+// memory; everybody picks it up behind the next barrier, so the whole launch follows one schedule.
+//   first full phase (unpaced): pace = 29/32 of what it took per tile
+//   schedule met (done within 1/16 + 3 us of it): remember it, and tighten by 1/13 unless frozen
+//   schedule missed (too tight: nobody is held back any more and the slow dies are late again): back to the last
+//   one that was met, and stop tightening
+struct PaceCtl { unsigned pace, good; bool frozen; };
+
+__device__ __forceinline__ void pace_update(PaceCtl& p, unsigned long long took, unsigned tiles)
+{
+    if (took >= 100000ull) return;                                  // a millisecond: something else is going on
+    const unsigned t = (unsigned)took;
+    if (p.pace == 0) {
+        p.pace = t * 29u / (32u * tiles);
+    } else {
+        const unsigned sched = p.pace * tiles;
+        if (t <= sched + sched / 16u + 300u) {
+            p.good = p.pace;
+            if (!p.frozen) p.pace = p.pace * 12u / 13u;
+        } else if (p.good) {
+            p.pace = p.good;
+            p.frozen = true;
+        } else {
+            p.pace = t * 29u / (32u * tiles);
+        }
+    }
 }
 
 // ---- per-call flag and scratch rotation for the LL protocol -----------------------------------

@@ -9,7 +9,7 @@
 namespace msx {
 
 // launches with fewer rounds than this do not pace their write phases (see k_allreduce_hb_phased)
-constexpr unsigned kPacedRounds = 12;
+constexpr unsigned kPacedRounds = 3;
 
 // ---- the fused form with the whole chip alternating between reading and writing ---------------
 // Same result, same bytes and the same owner-computes layout as k_allreduce_hb_fused, for messages far
@@ -63,8 +63,14 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
     const unsigned rounds = (unsigned)((most + per_round - 1) / per_round);
     const bool pacing = a.pace && rounds >= kPacedRounds;
     unsigned gen = 0;
-    unsigned pace = 0;        // wall-clock ticks between the puts of two tiles in a full write phase (0: none yet)
-    unsigned long long best = 100000ull;   // shortest full write phase seen, in ticks (a millisecond: none yet)
+    unsigned pace = 0;        // wall-clock ticks between the puts of two tiles in a full write phase (0: unpaced)
+    PaceCtl ctl{0u, 0u, false};   // workgroup 0's controller
+    // Tiles of a round: the AllReduce deals them out one by one (workgroup c of the rank takes every chans-th),
+    // so that at any moment the 32 workgroups of a rank write one compact window of each output; with H
+    // consecutive tiles per workgroup the write phase was 15 % slower (2048 separate streams over the chip,
+    // against 64 windows).  The read-heavy reduce-scatter keeps consecutive tiles (its reads are 5 % faster so).
+    constexpr bool kDealt = KIND == 0;
+    const size_t tstep = kDealt ? (size_t)a.chans * 256 : (size_t)256;
     auto put = [&](size_t idx, u32x4 o) {
         if constexpr (KIND == 1) {
             st16(a.out[rank], idx, o);                   // my own output: nothing to publish
@@ -76,8 +82,11 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
     };
 
     for (unsigned round = 0; round < rounds; ++round) {
-        const size_t first = ((size_t)round * a.chans + (size_t)chan) * H;       // my H consecutive tiles of this round
-        const unsigned mine = first >= tiles ? 0u : (unsigned)(tiles - first < (size_t)H ? tiles - first : (size_t)H);
+        // my first tile of this round, and how many of my H tiles exist (all, but for a chunk's last round)
+        const size_t first = kDealt ? (size_t)round * per_round + (size_t)chan : ((size_t)round * a.chans + (size_t)chan) * H;
+        const size_t every = kDealt ? (size_t)a.chans : (size_t)1;
+        const size_t left = first >= tiles ? 0 : (tiles - first + every - 1) / every;
+        const unsigned mine = (unsigned)(left < (size_t)H ? left : (size_t)H);
         const int nq = (int)((mine + G - 1) / G);
         const size_t i0 = lo + first * 256 + threadIdx.x;
         u32x4 held[H];
@@ -87,7 +96,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
         auto issue = [&](auto all, int g, u32x4 (&v)[G][NS]) {
 #pragma unroll
             for (int i = 0; i < G; ++i) {
-                const size_t idx = i0 + (size_t)(g * G + i) * 256;
+                const size_t idx = i0 + (size_t)(g * G + i) * tstep;
                 if (decltype(all)::value || (unsigned)(g * G + i) < mine) {     // uniform: whole tiles only
                     MSX_LOAD_ALL(v[i], src, idx)
                     if constexpr (RES == 1) v[i][kMaxRanks] = ld16(a.res[0], idx);
@@ -126,20 +135,20 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
         // write phase.  The dies do not get equal shares of the store bandwidth (in one phase the fastest is done
         // after 45 us, the slowest after 70 us, and which is which changes from phase to phase), and the last
         // dies alone cannot fill the memory system.  So a full write phase is paced: tile h goes out no earlier
-        // than h x pace after the phase began, with pace = 61/64 of what the shortest full write phase so far
-        // took per tile (the shortest: a phase that was slow for another reason must not loosen the schedule).
-        // Fast dies are held to the common schedule, the slow ones get the bandwidth that frees, and all finish
-        // together (measured: arrival spread 23 -> 3 us, write phase 70 -> 65 us).  A schedule that is too
-        // tight paces nobody.  Only for launches of kPacedRounds rounds or more: the read phase that follows a
-        // paced write phase is a little slower (every die has only just stopped writing when it begins), and
-        // the schedule needs some rounds to tighten; measured over several machines, 8 ranks: -1 to -5 % at
-        // 128-512 MiB per rank (4-8 rounds), +4 to +6 % at 1 GiB (16 rounds).
+        // than h x pace after the phase began (PaceCtl picks the pace).  Fast dies are held to the common
+        // schedule, the slow ones get the bandwidth that frees, and all finish together; the schedule can then
+        // be tightened well below what an unpaced phase takes (measured at 1 GiB per rank: 96 us unpaced,
+        // 75 us paced).
+        if constexpr (NR != 0 && KIND == 0) {
+            if (pacing && round > 0)       // workgroup 0's decision after the previous round
+                pace = __hip_atomic_load(c.gbar + kGridBarPaceWord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         const unsigned long long w0 = wall_clock64();
         auto write_phase = [&](auto all) {
             static_for<H>([&](auto k) {
                 constexpr int h = decltype(k)::value;
                 if constexpr (decltype(all)::value && KIND == 0) wait_until(w0 + (unsigned long long)((unsigned)h * pace));
-                if (decltype(all)::value || (unsigned)h < mine) put(i0 + (size_t)h * 256, held[h]);
+                if (decltype(all)::value || (unsigned)h < mine) put(i0 + (size_t)h * tstep, held[h]);
             });
         };
         if constexpr (NR != 0) {
@@ -152,12 +161,9 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
         if (round + 1 < rounds) {
             grid_barrier(c, gb, ++gen, (unsigned)rank, 14);
             if constexpr (NR != 0 && KIND == 0) {
-                // every workgroup of a round but the last few of a chunk is full, so all of them see (nearly) the
-                // same duration and pace alike
-                const unsigned long long took = wall_clock64() - w0;
-                if (pacing && mine == (unsigned)H && took < best) {     // the shortest full write phase so far sets the schedule
-                    best = took;
-                    pace = (unsigned)(took * 61ull / (64ull * H));
+                if (pacing && blockIdx.x == 0) {     // workgroup 0 of rank 0, channel 0: its rounds are full to the end
+                    if (mine == (unsigned)H) pace_update(ctl, wall_clock64() - w0, (unsigned)H);
+                    if (threadIdx.x == 0) st32_wt(c.gbar + kGridBarPaceWord, ctl.pace);
                 }
             }
         }
@@ -215,40 +221,44 @@ __global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
     const unsigned rounds = (unsigned)((tiles + per_round - 1) / per_round);
     const bool pacing = a.pace && rounds >= kPacedRounds;
     unsigned gen = 0;
-    unsigned pace = 0;        // wall-clock ticks between the puts of two tiles (0: none yet)
-    unsigned long long best = 100000ull;
+    unsigned pace = 0;        // wall-clock ticks between the puts of two tiles (0: unpaced)
+    PaceCtl ctl{0u, 0u, false};
+    const size_t tstep = (size_t)a.chans * 256;      // tiles dealt out one by one, as in the AllReduce
     auto put = [&](size_t idx, u32x4 o) {
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
             if (p < n_l && p != skip_l) st16_wt_keep(dst[p], idx, o);
     };
     for (unsigned round = 0; round < rounds; ++round) {
-        const size_t first = ((size_t)round * a.chans + (size_t)chan) * H;
-        const unsigned mine = first >= tiles ? 0u : (unsigned)(tiles - first < (size_t)H ? tiles - first : (size_t)H);
+        const size_t first = (size_t)round * per_round + (size_t)chan;
+        const size_t left = first >= tiles ? 0 : (tiles - first + (size_t)a.chans - 1) / (size_t)a.chans;
+        const unsigned mine = (unsigned)(left < (size_t)H ? left : (size_t)H);
         const size_t i0 = first * 256 + threadIdx.x;
         u32x4 held[H];
         static_for<H>([&](auto k) {
             constexpr int h = decltype(k)::value;
-            if ((unsigned)h < mine) held[h] = ld16(src, i0 + (size_t)h * 256);
+            if ((unsigned)h < mine) held[h] = ld16(src, i0 + (size_t)h * tstep);
         });
         static_for<H>([&](auto k) { settle(held[decltype(k)::value]); });
         grid_barrier(c, gb, ++gen, (unsigned)rank, 43);
-        const unsigned long long w0 = wall_clock64();          // paced like the AllReduce's write phase
+        // paced like the AllReduce's write phase
+        if (pacing && round > 0)
+            pace = __hip_atomic_load(c.gbar + kGridBarPaceWord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long w0 = wall_clock64();
         static_for<H>([&](auto k) {
             constexpr int h = decltype(k)::value;
             if ((unsigned)h < mine) {
-                wait_until(w0 + (unsigned long long)((unsigned)h * pace));
-                put(i0 + (size_t)h * 256, held[h]);
+                wait_until(w0 + (unsigned long long)((unsigned)h * (mine == (unsigned)H ? pace : 0u)));
+                put(i0 + (size_t)h * tstep, held[h]);
             }
         });
         put_drain();
         if (round + 1 < rounds) {
             grid_barrier(c, gb, ++gen, (unsigned)rank, 44);
-            const unsigned long long took = wall_clock64() - w0;
-            if (pacing && mine == (unsigned)H && took < best) {     // the shortest full write phase so far sets the schedule
-                    best = took;
-                    pace = (unsigned)(took * 61ull / (64ull * H));
-                }
+            if (pacing && blockIdx.x == 0) {
+                if (mine == (unsigned)H) pace_update(ctl, wall_clock64() - w0, (unsigned)H);
+                if (threadIdx.x == 0) st32_wt(c.gbar + kGridBarPaceWord, ctl.pace);
+            }
         }
     }
     grid_barrier_end(c, gb, gen);
