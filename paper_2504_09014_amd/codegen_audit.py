@@ -128,8 +128,10 @@ def findings(path):
 
 
 def serialised_store_findings(path, limit=3):
-    """Kernels in which more than `limit` write-through 16-byte stores each sit right behind a full
-    `s_waitcnt vmcnt(0)`.
+    """Kernels in which more than `limit` write-through 16-byte stores (or, in kernels with hundreds of
+    them, more than one in 64) each sit right behind a full `s_waitcnt vmcnt(0)`.  A serialised per-peer
+    sequence shows as one store in eight or more; the first store behind a barrier's own drain, once per
+    code path, is not it.
 
     The write-through stores are inline assembly, so the compiler does not know they are in flight.  When a
     conditional store is the first use of a loaded register it waits for ALL memory operations there, which
@@ -147,7 +149,7 @@ def serialised_store_findings(path, limit=3):
             continue
         t = raw.strip()
         if t.startswith(".end_amdhsa_kernel") or t.startswith(".Lfunc_end"):
-            if waited > limit:
+            if waited > max(limit, stores // 64):
                 found.append((fn, waited, stores))
             fn = None
             continue

@@ -261,26 +261,50 @@ __device__ __forceinline__ void wait_until(unsigned long long target)
 // memory; everybody picks it up behind the next barrier, so the whole launch follows one schedule.
 //   first full phase (unpaced): pace = 29/32 of what it took per tile
 //   schedule met (done within 1/16 + 3 us of it): remember it, and tighten by 1/13 unless frozen
-//   schedule missed (too tight: nobody is held back any more and the slow dies are late again): back to the last
-//   one that was met, and stop tightening
-struct PaceCtl { unsigned pace, good; bool frozen; };
+//   schedule missed (too tight: nobody is held back any more and the slow dies are late again): back to the
+//   last one that was met, and stop tightening; missed three times in a row: learn again from scratch
+// The state outlives the call (four words beside the barrier counters, tagged with the call's shape), so a
+// call of the same shape as the one before starts from the schedule that one ended with.
+struct PaceCtl { unsigned pace, good, frozen, misses; };
+
+// no schedule is slower than this many ticks per tile (15 us; a phase of 64 tiles then lasts a millisecond):
+// whatever the words in memory say, a wave never waits longer
+constexpr unsigned kMaxPace = 1500;
+__device__ __forceinline__ unsigned pace_clamp(unsigned pace) { return pace > kMaxPace ? 0u : pace; }
+
+__device__ __forceinline__ PaceCtl pace_load(const DevCtx& c, unsigned key)
+{
+    const unsigned* w = c.gbar + kGridBarPaceWord;
+    PaceCtl p{0u, 0u, 0u, 0u};
+    if (w[1] == key) { p.pace = pace_clamp(w[0]); p.good = pace_clamp(w[2]); p.frozen = w[3] & 1u; p.misses = (w[3] >> 8) & 3u; }
+    return p;
+}
+
+// workgroup 0, one thread, after the call's last barrier
+__device__ __forceinline__ void pace_save(const DevCtx& c, const PaceCtl& p, unsigned key)
+{
+    unsigned* w = c.gbar + kGridBarPaceWord;
+    w[0] = p.pace; w[1] = key; w[2] = p.good; w[3] = (p.frozen & 1u) | (p.misses << 8);
+}
 
 __device__ __forceinline__ void pace_update(PaceCtl& p, unsigned long long took, unsigned tiles)
 {
     if (took >= 100000ull) return;                                  // a millisecond: something else is going on
     const unsigned t = (unsigned)took;
+    const unsigned fresh = pace_clamp(t * 29u / (32u * tiles));
     if (p.pace == 0) {
-        p.pace = t * 29u / (32u * tiles);
+        p.pace = fresh;
     } else {
         const unsigned sched = p.pace * tiles;
         if (t <= sched + sched / 16u + 300u) {
             p.good = p.pace;
+            p.misses = 0;
             if (!p.frozen) p.pace = p.pace * 12u / 13u;
-        } else if (p.good) {
-            p.pace = p.good;
-            p.frozen = true;
+        } else if (++p.misses >= 3u || !p.good) {
+            p = PaceCtl{fresh, 0u, 0u, 0u};
         } else {
-            p.pace = t * 29u / (32u * tiles);
+            p.pace = p.good;
+            p.frozen = 1u;
         }
     }
 }

@@ -9,7 +9,7 @@
 namespace msx {
 
 // launches with fewer rounds than this do not pace their write phases (see k_allreduce_hb_phased)
-constexpr unsigned kPacedRounds = 3;
+constexpr unsigned kPacedRounds = 2;
 
 // ---- the fused form with the whole chip alternating between reading and writing ---------------
 // Same result, same bytes and the same owner-computes layout as k_allreduce_hb_fused, for messages far
@@ -63,8 +63,10 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
     const unsigned rounds = (unsigned)((most + per_round - 1) / per_round);
     const bool pacing = a.pace && rounds >= kPacedRounds;
     unsigned gen = 0;
-    unsigned pace = 0;        // wall-clock ticks between the puts of two tiles in a full write phase (0: unpaced)
-    PaceCtl ctl{0u, 0u, false};   // workgroup 0's controller
+    // what the schedule is remembered under from call to call: the shape of the launch
+    const unsigned key = ((unsigned)a.count ^ (unsigned)(a.count >> 32)) * 2654435761u + gridDim.x * 64u + (unsigned)(DT * 8 + RES * 2 + KIND) + 1u;
+    PaceCtl ctl = pace_load(c, key);   // every workgroup reads it; workgroup 0 keeps it up to date
+    unsigned pace = pacing ? ctl.pace : 0u;   // wall-clock ticks between the puts of two tiles in a full write phase (0: unpaced)
     // Tiles of a round: the AllReduce deals them out one by one (workgroup c of the rank takes every chans-th),
     // so that at any moment the 32 workgroups of a rank write one compact window of each output; with H
     // consecutive tiles per workgroup the write phase was 15 % slower (2048 separate streams over the chip,
@@ -141,7 +143,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
         // 75 us paced).
         if constexpr (NR != 0 && KIND == 0) {
             if (pacing && round > 0)       // workgroup 0's decision after the previous round
-                pace = __hip_atomic_load(c.gbar + kGridBarPaceWord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pace = pace_clamp(__hip_atomic_load(c.gbar + kGridBarPaceWord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         }
         const unsigned long long w0 = wall_clock64();
         auto write_phase = [&](auto all) {
@@ -169,6 +171,9 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
         }
     }
     grid_barrier_end(c, gb, gen);
+    if constexpr (NR != 0 && KIND == 0) {
+        if (pacing && blockIdx.x == 0 && threadIdx.x == 0) pace_save(c, ctl, key);
+    }
     // what is left of the chunk behind its last whole tile (less than one vector per thread): the rank's first workgroup
     if (chan == 0) {
         const size_t idx = lo + tiles * 256 + threadIdx.x;
@@ -221,8 +226,9 @@ __global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
     const unsigned rounds = (unsigned)((tiles + per_round - 1) / per_round);
     const bool pacing = a.pace && rounds >= kPacedRounds;
     unsigned gen = 0;
-    unsigned pace = 0;        // wall-clock ticks between the puts of two tiles (0: unpaced)
-    PaceCtl ctl{0u, 0u, false};
+    const unsigned key = ((unsigned)a.count ^ (unsigned)(a.count >> 32)) * 2654435761u + gridDim.x * 64u + 32u + 1u;
+    PaceCtl ctl = pace_load(c, key);
+    unsigned pace = pacing ? ctl.pace : 0u;   // wall-clock ticks between the puts of two tiles (0: unpaced)
     const size_t tstep = (size_t)a.chans * 256;      // tiles dealt out one by one, as in the AllReduce
     auto put = [&](size_t idx, u32x4 o) {
 #pragma unroll
@@ -243,7 +249,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
         grid_barrier(c, gb, ++gen, (unsigned)rank, 43);
         // paced like the AllReduce's write phase
         if (pacing && round > 0)
-            pace = __hip_atomic_load(c.gbar + kGridBarPaceWord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            pace = pace_clamp(__hip_atomic_load(c.gbar + kGridBarPaceWord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
         const unsigned long long w0 = wall_clock64();
         static_for<H>([&](auto k) {
             constexpr int h = decltype(k)::value;
@@ -261,6 +267,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
             }
         }
     }
+    if (pacing && blockIdx.x == 0 && threadIdx.x == 0) pace_save(c, ctl, key);
     grid_barrier_end(c, gb, gen);
     if (chan == 0) {
         const size_t idx = tiles * 256 + threadIdx.x;
