@@ -230,8 +230,9 @@ int msx_finalize(void);
  *   "hb_phased_min_bytes"   auto | bytes per rank from which the fused HB AllReduce (no residual, or one
  *                     shared by all ranks) runs in chip-wide read and write phases, one workgroup per CU; auto:
  *                     8 ranks from 64 MiB, never otherwise; an explicit value applies to every rank count
- *   "hb_pace"         0 | 1   phased kernels: hold the write phases of long launches (12 rounds or more) to a
- *                     common schedule, so that all dies finish them together
+ *   "hb_pace"         0 | 1   phased kernels: hold the write phases to a common wall-clock schedule, so that all
+ *                     dies finish them together (the schedule is found by the kernels themselves and kept, per
+ *                     launch shape, in the context)
  *   "hb_barriers"     0 | 1   start/end rank barriers in the HB kernels
  *   "peer_outer"      0 | 1   two-phase HB all-gather: one put per peer instead of peer-inner
  *   "barrier_fences"  0..3    msx_prim_barrier only: bit 0 release fence, bit 1 acquire fence

@@ -263,8 +263,8 @@ __device__ __forceinline__ void wait_until(unsigned long long target)
 //   schedule met (done within 1/16 + 3 us of it): remember it, and tighten by 1/13 unless frozen
 //   schedule missed (too tight: nobody is held back any more and the slow dies are late again): back to the
 //   last one that was met, and stop tightening; missed three times in a row: learn again from scratch
-// The state outlives the call (four words beside the barrier counters, tagged with the call's shape), so a
-// call of the same shape as the one before starts from the schedule that one ended with.
+// The state outlives the call (beside the barrier counters, four slots tagged with the shape of the launch), so
+// a call of a shape seen before starts from the schedule that one ended with.
 struct PaceCtl { unsigned pace, good, frozen, misses; };
 
 // no schedule is slower than this many ticks per tile (15 us; a phase of 64 tiles then lasts a millisecond):
@@ -272,9 +272,10 @@ struct PaceCtl { unsigned pace, good, frozen, misses; };
 constexpr unsigned kMaxPace = 1500;
 __device__ __forceinline__ unsigned pace_clamp(unsigned pace) { return pace > kMaxPace ? 0u : pace; }
 
+// word 0 of the line: the pace of the launch that is running; words 4.. : four remembered shapes, direct-mapped
 __device__ __forceinline__ PaceCtl pace_load(const DevCtx& c, unsigned key)
 {
-    const unsigned* w = c.gbar + kGridBarPaceWord;
+    const unsigned* w = c.gbar + kGridBarPaceWord + 4u + (key & 3u) * 4u;
     PaceCtl p{0u, 0u, 0u, 0u};
     if (w[1] == key) { p.pace = pace_clamp(w[0]); p.good = pace_clamp(w[2]); p.frozen = w[3] & 1u; p.misses = (w[3] >> 8) & 3u; }
     return p;
@@ -283,7 +284,7 @@ __device__ __forceinline__ PaceCtl pace_load(const DevCtx& c, unsigned key)
 // workgroup 0, one thread, after the call's last barrier
 __device__ __forceinline__ void pace_save(const DevCtx& c, const PaceCtl& p, unsigned key)
 {
-    unsigned* w = c.gbar + kGridBarPaceWord;
+    unsigned* w = c.gbar + kGridBarPaceWord + 4u + (key & 3u) * 4u;
     w[0] = p.pace; w[1] = key; w[2] = p.good; w[3] = (p.frozen & 1u) | (p.misses << 8);
 }
 
