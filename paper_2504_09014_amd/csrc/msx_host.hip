@@ -945,6 +945,21 @@ int moe_dispatch_impl(const void* const* tokens, const int32_t* const* topk_idx,
     a.chans = chans;
     c->plan_T = T;
     c->plan_n = n;
+    // many long rows (bf16 / fp32 pack only): chip-wide read and write phases, one workgroup per CU.  Automatic
+    // for 8 ranks from 32 MiB of tokens per rank in rows of 512 to 1024 vectors; an explicit
+    // hb_phased_min_bytes counts for every shape the kernel can hold (rows of at most 1024 vectors).
+    const size_t token_bytes = (size_t)T * row_bytes;
+    if (!recv_scales && a.row_vecs <= (unsigned)(64 * kPackVecsPerLane) &&
+        (g_opt.hb_phased_min < 0 ? n == 8 && a.row_vecs >= 512u && token_bytes >= ((size_t)32 << 20)
+                                 : token_bytes >= (size_t)g_opt.hb_phased_min)) {
+        int pch = 1;
+        if ((rc = pick_channels(c, (const void*)k_moe_pack_phased, 256, n, (size_t)T * 64, 4 * kPackRows,
+                                g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels, kMaxChannels, &pch)))
+            return rc;
+        a.chans = pch;
+        note_launch(n * pch, 256, MSX_ALGO_2PA_HB);
+        return launch(k_moe_pack_phased, n * pch, 256, s, a, d, g_opt.hb_pace);
+    }
     note_launch(n * chans, 256, MSX_ALGO_2PA_HB);
     if (recv_scales) {
         MoeFp8Args f{};

@@ -211,6 +211,37 @@ def test_moe_dispatch_small_shapes(msx, orc, n, T, H, K, E):
         assert np.array_equal(_bits(recv[d]), want_recv[d]), d
 
 
+@pytest.mark.parametrize("n,T,H,K,E,blocks", [(8, 1000, 64, 8, 256, 1), (8, 300, 7168, 8, 256, 2), (4, 333, 8192, 2, 16, 0),
+                                              (2, 77, 520, 1, 4, 1)])
+def test_moe_dispatch_in_read_and_write_phases(msx, orc, n, T, H, K, E, blocks):
+    """The pack kernel that alternates between chip-wide read and write phases (by default: 8 ranks, many long
+    rows), forced here; one or two workgroups per rank make dozens of rounds, the last one partial, with the
+    write phases paced.  Twice in a row: the second call starts from the schedule the first one left."""
+    tokens = synth.moe_tokens(n, T, H, seed=21)
+    topk = synth.moe_routing(n, T, K, E, seed=21)
+    cap = n * T
+    want_recv, want_src, want_counts, orc_rc = orc.moe_dispatch(_bits(tokens), topk.numpy(), E, cap)
+    assert orc_rc == 0
+    old = msx.get_option("hb_phased_min_bytes")
+    msx.set_option("hb_phased_min_bytes", "0")
+    msx.set_option("hb_blocks_per_rank", str(blocks))
+    msx.set_option("chaos", "9")
+    try:
+        for rep in range(2):
+            recv, src, counts, rc, info = _dispatch(msx, tokens, topk, E, cap)
+            grid = msx.last_launch()[0]
+            assert grid == n * blocks if blocks else (grid % n == 0 and 200 <= grid <= 256), (grid, n, blocks)
+            assert rc == 0, info
+            assert np.array_equal(counts.cpu().numpy(), want_counts)
+            for d in range(n):
+                assert np.array_equal(src[d].cpu().numpy(), want_src[d]), (rep, d)
+                assert np.array_equal(_bits(recv[d]), want_recv[d]), (rep, d)
+    finally:
+        msx.set_option("hb_phased_min_bytes", old)
+        msx.set_option("hb_blocks_per_rank", "0")
+        msx.set_option("chaos", "0")
+
+
 def test_moe_dispatch_special_routings(msx, orc):
     n, T, H, E = 8, 200, 32, 256
     tokens = synth.moe_tokens(n, T, H, seed=5)

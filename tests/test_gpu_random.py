@@ -191,6 +191,12 @@ def test_random_dispatch_and_combine_cases(msx, orc, seed):
         most = int(full[2].sum(axis=1).max())
         cap = max(1, most // 2) if tight and most > 1 else max(1, most)
         recv_w, src_w, counts_w, rc_w = orc.moe_dispatch(_bits(tokens).reshape(n, T, H), topk.numpy(), E, cap=cap)
+        # half of the cases: the pack in chip-wide read / write phases (by default only for many long rows), with
+        # few workgroups per rank so that it takes several rounds
+        force_phased = bool(rng.integers(0, 2))
+        msx.set_option("hb_phased_min_bytes", "0" if force_phased else "auto")
+        msx.set_option("hb_blocks_per_rank", str(int(rng.choice([0, 1, 2]))) if force_phased else "0")
+        tag["phased"] = force_phased
         tok = [tokens[r].clone().cuda() for r in range(n)]
         idx = [topk[r].clone().cuda() for r in range(n)]
         recv = [torch.zeros((cap, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
@@ -217,3 +223,5 @@ def test_random_dispatch_and_combine_cases(msx, orc, seed):
             assert rc2 == 0
             for s in range(n):
                 assert np.array_equal(_bits(out[s]), want[s]), (tag, s)
+    msx.set_option("hb_phased_min_bytes", "auto")
+    msx.set_option("hb_blocks_per_rank", "0")
