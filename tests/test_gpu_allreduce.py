@@ -435,8 +435,8 @@ def test_phased_fused_hb_with_shared_residual_and_back_to_back_calls(phased, orc
 
 def test_phased_fused_hb_replays_in_a_hip_graph(phased, orc):
     msx = phased
-    n, count = 8, 8 * (256 * 64 + 40) * 8
-    msx.set_option("hb_blocks_per_rank", "2")
+    n, count = 8, 8 * (256 * 64 * 3 + 40) * 8                     # three rounds with one workgroup per rank: paced
+    msx.set_option("hb_blocks_per_rank", "1")
     xs = [synth.normal(n, count, seed=330 + i) for i in range(3)]
     send = [xs[0][r].clone().cuda() for r in range(n)]
     out = [torch.zeros(count, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
