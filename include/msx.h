@@ -266,6 +266,10 @@ int msx_last_launch(int* grid, int* block, int* algo);
  * uint64 first, end, step} (see csrc/msx_kernels_plan.hpp), start_out the nranks*blocks_per_rank+1
  * list offsets.  With ops_out == NULL only *ops_written is set. */
 int msx_debug_choose(size_t nbytes, int nranks, size_t ll_limit, int* algo, int* unroll, int* want_blocks);
+/* One step of the controller that paces the write phases of the phased kernels: state = {pace, last pace that
+ * was met, frozen, misses in a row} (pace in 10 ns ticks per tile, 0 = unpaced); took_ticks = how long the
+ * full write phase of `tiles` tiles just took.  The same function the kernels call. */
+int msx_debug_pace_update(uint32_t state[4], uint64_t took_ticks, uint32_t tiles);
 int msx_debug_lower_plan(int algo, int nranks, int blocks_per_rank, size_t vectors_per_rank, int threads,
                          void* ops_out, size_t ops_capacity, uint32_t* start_out, size_t* ops_written);
 

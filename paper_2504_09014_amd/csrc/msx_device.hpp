@@ -262,7 +262,8 @@ __device__ __forceinline__ void wait_until(unsigned long long target)
 //   first full phase (unpaced): pace = 29/32 of what it took per tile
 //   schedule met (done within 1/16 + 3 us of it): remember it, and tighten by 1/13 unless frozen
 //   schedule missed (too tight: nobody is held back any more and the slow dies are late again): back to the
-//   last one that was met, and stop tightening; missed three times in a row: learn again from scratch
+//   last one that was met, and stop tightening; missed three times in a row: learn again from scratch; missed
+//   before any was met: loosen by 1/16
 // The state outlives the call (beside the barrier counters, four slots tagged with the shape of the launch), so
 // a call of a shape seen before starts from the schedule that one ended with.
 struct PaceCtl { unsigned pace, good, frozen, misses; };
@@ -270,7 +271,7 @@ struct PaceCtl { unsigned pace, good, frozen, misses; };
 // no schedule is slower than this many ticks per tile (15 us; a phase of 64 tiles then lasts a millisecond):
 // whatever the words in memory say, a wave never waits longer
 constexpr unsigned kMaxPace = 1500;
-__device__ __forceinline__ unsigned pace_clamp(unsigned pace) { return pace > kMaxPace ? 0u : pace; }
+__host__ __device__ __forceinline__ unsigned pace_clamp(unsigned pace) { return pace > kMaxPace ? 0u : pace; }
 
 // word 0 of the line: the pace of the launch that is running; words 4.. : four remembered shapes, direct-mapped
 __device__ __forceinline__ PaceCtl pace_load(const DevCtx& c, unsigned key)
@@ -288,7 +289,7 @@ __device__ __forceinline__ void pace_save(const DevCtx& c, const PaceCtl& p, uns
     w[0] = p.pace; w[1] = key; w[2] = p.good; w[3] = (p.frozen & 1u) | (p.misses << 8);
 }
 
-__device__ __forceinline__ void pace_update(PaceCtl& p, unsigned long long took, unsigned tiles)
+__host__ __device__ __forceinline__ void pace_update(PaceCtl& p, unsigned long long took, unsigned tiles)
 {
     if (took >= 100000ull) return;                                  // a millisecond: something else is going on
     const unsigned t = (unsigned)took;
@@ -301,7 +302,12 @@ __device__ __forceinline__ void pace_update(PaceCtl& p, unsigned long long took,
             p.good = p.pace;
             p.misses = 0;
             if (!p.frozen) p.pace = p.pace * 12u / 13u;
-        } else if (++p.misses >= 3u || !p.good) {
+        } else if (!p.good) {
+            // no schedule has been met yet: this one is too tight, try a looser one (never looser than what the
+            // unpaced phase just took, which is met by definition and ends the search)
+            const unsigned looser = p.pace + p.pace / 16u + 1u, unpaced = t / tiles + 1u;
+            p.pace = pace_clamp(looser < unpaced ? looser : unpaced);
+        } else if (++p.misses >= 3u) {
             p = PaceCtl{fresh, 0u, 0u, 0u};
         } else {
             p.pace = p.good;

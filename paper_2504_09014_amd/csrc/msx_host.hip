@@ -1557,6 +1557,15 @@ int msx_debug_choose(size_t nbytes, int nranks, size_t ll_limit, int* algo, int*
     return MSX_OK;
 }
 
+int msx_debug_pace_update(uint32_t state[4], uint64_t took_ticks, uint32_t tiles)
+{
+    if (!state || tiles == 0) return MSX_ERR_ARG;
+    PaceCtl p{state[0], state[1], state[2], state[3]};
+    pace_update(p, took_ticks, tiles);
+    state[0] = p.pace; state[1] = p.good; state[2] = p.frozen; state[3] = p.misses;
+    return MSX_OK;
+}
+
 int msx_debug_lower_plan(int algo, int nranks, int blocks_per_rank, size_t vectors_per_rank, int threads,
                          void* ops_out, size_t ops_capacity, uint32_t* start_out, size_t* ops_written)
 {

@@ -200,3 +200,44 @@ def test_automatic_choice_and_launch_shapes(L):
     finally:
         msx.set_option("ll_2pa_max_bytes", old)
     assert L.msx_debug_choose(1024, 0, ll, C.byref(a), C.byref(u), C.byref(w)) == -1
+
+
+def test_write_phase_pacing_controller_finds_and_keeps_the_tightest_schedule(L):
+    """The controller of the paced write phases, run against a model of the memory system: a phase held to a
+    schedule s (ticks per tile) takes s * tiles + tail when the schedule can be met, and the unpaced time when
+    it is too tight (nobody is held back then).  It must settle just above the cliff, hold there, recover when
+    the cliff moves, and never leave [0, 1500] ticks per tile."""
+    L.msx_debug_pace_update.argtypes = [C.POINTER(C.c_uint32), C.c_uint64, C.c_uint32]
+    tiles, tail, unpaced = 64, 250, 9600                        # 10 ns ticks: 96 us unpaced
+
+    def run(state, cliff, rounds):
+        took_log = []
+        for _ in range(rounds):
+            s = state[0]
+            took = unpaced if s == 0 or s * tiles < cliff else s * tiles + tail
+            took_log.append(took)
+            assert L.msx_debug_pace_update(state, took, tiles) == 0
+            assert 0 <= state[0] <= 1500
+        return took_log
+
+    state = (C.c_uint32 * 4)(0, 0, 0, 0)
+    log = run(state, cliff=7000, rounds=16)                     # the system can do 70 us, not less
+    assert log[0] == unpaced and state[2] == 1                  # learnt from an unpaced phase, frozen by the end
+    assert 7000 <= state[0] * tiles <= 7000 * 13 // 12 + tiles  # within one tightening step above the cliff
+    assert sum(t == unpaced for t in log) <= 2                  # the first phase and the one miss that found the cliff
+    assert all(t <= 7000 * 13 // 12 + tail + tiles for t in log[-8:])
+    held = state[0]
+    run(state, cliff=7000, rounds=8)
+    assert state[0] == held                                     # frozen: stays
+    log = run(state, cliff=9000, rounds=12)                     # conditions change: the old schedule is too tight now
+    assert sum(t == unpaced for t in log) <= 6 and 9000 <= state[0] * tiles <= 9000 * 13 // 12 + tiles
+    # a system on which pacing gains nothing (no schedule below the unpaced time can be met): the search ends
+    # within the tolerance of the unpaced time and does no harm (no phase ever takes longer than unpaced)
+    state = (C.c_uint32 * 4)(0, 0, 0, 0)
+    log = run(state, cliff=unpaced, rounds=20)
+    assert unpaced * 15 // 16 <= state[0] * tiles <= unpaced + 2 * tiles and max(log) <= unpaced + tail + 2 * tiles
+    # nonsense input leaves the state alone or clamps it
+    junk = (C.c_uint32 * 4)(0, 0, 0, 0)
+    assert L.msx_debug_pace_update(junk, 10 ** 9, tiles) == 0 and junk[0] == 0      # over a millisecond: ignored
+    assert L.msx_debug_pace_update(junk, 99999, 1) == 0 and junk[0] == 0            # would exceed the clamp
+    assert L.msx_debug_pace_update(None, 100, tiles) == -1
