@@ -264,7 +264,7 @@ __device__ __forceinline__ void wait_until(unsigned long long target)
 //   schedule missed (too tight: nobody is held back any more and the slow dies are late again): back to the
 //   last one that was met, and stop tightening; missed three times in a row: learn again from scratch; missed
 //   before any was met: loosen by 1/16
-// The state outlives the call (beside the barrier counters, four slots tagged with the shape of the launch), so
+// The state outlives the call (beside the barrier counters, seven slots tagged with the shape of the launch), so
 // a call of a shape seen before starts from the schedule that one ended with.
 struct PaceCtl { unsigned pace, good, frozen, misses; };
 
@@ -273,10 +273,10 @@ struct PaceCtl { unsigned pace, good, frozen, misses; };
 constexpr unsigned kMaxPace = 1500;
 __host__ __device__ __forceinline__ unsigned pace_clamp(unsigned pace) { return pace > kMaxPace ? 0u : pace; }
 
-// word 0 of the line: the pace of the launch that is running; words 4.. : four remembered shapes, direct-mapped
+// word 0 of the line: the pace of the launch that is running; words 4..31: seven remembered shapes, direct-mapped
 __device__ __forceinline__ PaceCtl pace_load(const DevCtx& c, unsigned key)
 {
-    const unsigned* w = c.gbar + kGridBarPaceWord + 4u + (key & 3u) * 4u;
+    const unsigned* w = c.gbar + kGridBarPaceWord + 4u + ((key >> 7) % 7u) * 4u;
     PaceCtl p{0u, 0u, 0u, 0u};
     if (w[1] == key) { p.pace = pace_clamp(w[0]); p.good = pace_clamp(w[2]); p.frozen = w[3] & 1u; p.misses = (w[3] >> 8) & 3u; }
     return p;
@@ -285,7 +285,7 @@ __device__ __forceinline__ PaceCtl pace_load(const DevCtx& c, unsigned key)
 // workgroup 0, one thread, after the call's last barrier
 __device__ __forceinline__ void pace_save(const DevCtx& c, const PaceCtl& p, unsigned key)
 {
-    unsigned* w = c.gbar + kGridBarPaceWord + 4u + (key & 3u) * 4u;
+    unsigned* w = c.gbar + kGridBarPaceWord + 4u + ((key >> 7) % 7u) * 4u;
     w[0] = p.pace; w[1] = key; w[2] = p.good; w[3] = (p.frozen & 1u) | (p.misses << 8);
 }
 

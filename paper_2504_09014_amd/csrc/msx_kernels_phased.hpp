@@ -8,8 +8,10 @@
 
 namespace msx {
 
-// launches with fewer rounds than this do not pace their write phases (see k_allreduce_hb_phased)
-constexpr unsigned kPacedRounds = 2;
+// Launches with fewer rounds than this do not pace their write phases (see k_allreduce_hb_phased).  One round is
+// enough: a paced launch ends with a barrier behind its last write phase, so that this phase is measured too,
+// and the schedule a launch finds is kept for the next launch of its shape.
+constexpr unsigned kPacedRounds = 1;
 
 // ---- the fused form with the whole chip alternating between reading and writing ---------------
 // Same result, same bytes and the same owner-computes layout as k_allreduce_hb_fused, for messages far
@@ -160,7 +162,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
             write_phase(std::false_type{});
         }
         put_drain();
-        if (round + 1 < rounds) {
+        if (round + 1 < rounds || (NR != 0 && KIND == 0 && pacing)) {
             grid_barrier(c, gb, ++gen, (unsigned)rank, 14);
             if constexpr (NR != 0 && KIND == 0) {
                 if (pacing && blockIdx.x == 0) {     // workgroup 0 of rank 0, channel 0: its rounds are full to the end
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
             }
         });
         put_drain();
-        if (round + 1 < rounds) {
+        if (round + 1 < rounds || pacing) {
             grid_barrier(c, gb, ++gen, (unsigned)rank, 44);
             if (pacing && blockIdx.x == 0) {
                 if (mine == (unsigned)H) pace_update(ctl, wall_clock64() - w0, (unsigned)H);
