@@ -154,7 +154,7 @@ def main():
         f"{achieved:.0f} GB/s, algBW {S / (kern_avg * 1e-3) / 1e9:.0f} GB/s, grid {grid}x{block}")
 
     # which form of the fused kernel the library picked for this size (same sums, same bytes)
-    phased = msx.get_option("hb_phased_min_bytes") == "auto" and n == 8 and S >= (64 << 20)
+    phased = msx.get_option("hb_phased_min_bytes") == "auto" and n == 8 and S >= (40 << 20)
     kernel_name = "k_allreduce_hb_phased<bf16, 8 ranks, 64 sums held>" if phased else "k_allreduce_hb_fused<bf16>"
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")

@@ -45,9 +45,8 @@ struct Options {
     int hb_unroll = 0;        // 0 = by size
     int cache_mode = -1;      // -1 = by footprint, else 0 | 1 | 2 (see choose_cache_mode)
     // fused HB AllReduce: from this many bytes per rank on, the launch alternates between chip-wide read and
-    // write phases (k_allreduce_hb_phased).  -1 = automatic: 8 ranks from 64 MiB (measured against the
-    // free-running kernel: 1.03x at 64-128 MiB, 1.07x at 256 MiB, 1.10x at 1 GiB; below 64 MiB, and with
-    // fewer ranks, whose phases are smaller, it loses), never otherwise
+    // write phases (k_allreduce_hb_phased).  -1 = automatic: 8 ranks from 40 MiB (see use_phased; with fewer
+    // ranks, whose phases are smaller, it loses), never otherwise
     long long hb_phased_min = -1;
     int hb_barriers = 1;
     int hb_pace = 1;          // phased kernels: pace the write phase (see k_allreduce_hb_phased)
@@ -369,10 +368,13 @@ HbKernel hb_fused_kernel(int dt, int u, int n, int res, int cache)
 }
 // does a fused HB AllReduce of nbytes per rank run in chip-wide phases?  (res_mode 2, one residual per
 // destination, would need loads in the write phase)
-bool use_phased(size_t nbytes, int n, int res_mode)
+// auto_min: where the automatic choice starts for 8 ranks: 40 MiB per rank for the AllReduce (measured
+// against the free-running kernel, TB/s: 32 MiB 4.9 / 5.8, 40 MiB 5.0 / 4.8, 48 MiB 5.2 / 4.8, 64 MiB 6.2 / 5.1),
+// 64 MiB rows for the reduce-scatter and the all-gather
+bool use_phased(size_t nbytes, int n, int res_mode, size_t auto_min = (size_t)40 << 20)
 {
     if (n < 2 || res_mode == 2 || g_opt.hb_unroll != 0) return false;
-    return g_opt.hb_phased_min < 0 ? n == 8 && nbytes >= ((size_t)64 << 20) : nbytes >= (size_t)g_opt.hb_phased_min;
+    return g_opt.hb_phased_min < 0 ? n == 8 && nbytes >= auto_min : nbytes >= (size_t)g_opt.hb_phased_min;
 }
 HbKernel hb_2phase_kernel(int dt, int u, int n)
 {
@@ -824,7 +826,7 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     }
     // large blocks, 8 ranks: chip-wide read and write phases, one workgroup per CU (see k_allreduce_hb_phased)
     const size_t row_bytes = (which == kRS ? count_or_bytes * elem_size(dtype) : count_or_bytes) * (size_t)n;
-    if ((which == kRS || which == kAG) && vec && use_phased(row_bytes, n, 0)) {
+    if ((which == kRS || which == kAG) && vec && use_phased(row_bytes, n, 0, (size_t)64 << 20)) {
         HbKernel pk = which == kRS ? phased_reduce_kernel(dtype == MSX_F32, n, 0, 1) : phased_allgather_kernel(n);
         int pch = 1;
         if ((rc = pick_channels(c, (const void*)pk, threads, n, work_units, kPhasedHeld,

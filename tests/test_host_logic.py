@@ -185,8 +185,9 @@ def test_automatic_choice_and_launch_shapes(L):
     assert choose(2 << 20) == (3, 1, 64)
     assert choose(4 << 20) == (3, 2, 64)
     assert choose(32 << 20) == (3, 1, 32)
-    assert choose((64 << 20) - 16) == (3, 1, 128)
-    # 8 ranks from 64 MiB: chip-wide read / write phases, 64 sums held per thread, every resident workgroup
+    assert choose((40 << 20) - 16) == (3, 1, 128)
+    # 8 ranks from 40 MiB: chip-wide read / write phases, 64 sums held per thread, every resident workgroup
+    assert choose(40 << 20) == (3, 64, 256)
     assert choose(64 << 20) == (3, 64, 256)
     assert choose(1 << 30) == (3, 64, 256)
     assert choose(1 << 30, n=7) == (3, 1, 146)
