@@ -369,7 +369,7 @@ HbKernel hb_fused_kernel(int dt, int u, int n, int res, int cache)
 // does a fused HB AllReduce of nbytes per rank run in chip-wide phases?  (res_mode 2, one residual per
 // destination, would need loads in the write phase)
 // auto_min: where the automatic choice starts for 8 ranks: 40 MiB per rank for the AllReduce (measured
-// against the free-running kernel, TB/s: 32 MiB 4.9 / 5.8, 40 MiB 5.0 / 4.8, 48 MiB 5.2 / 4.8, 64 MiB 6.2 / 5.1),
+// against the free-running kernel, TB/s: 32 MiB 5.3 / 5.6-5.9, 40 MiB 5.6 / 4.9, 48 MiB 5.9 / 5.0, 64 MiB 6.0-6.2 / 5.2),
 // 64 MiB rows for the reduce-scatter and the all-gather
 bool use_phased(size_t nbytes, int n, int res_mode, size_t auto_min = (size_t)40 << 20)
 {

@@ -151,8 +151,15 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
         auto write_phase = [&](auto all) {
             static_for<H>([&](auto k) {
                 constexpr int h = decltype(k)::value;
-                if constexpr (decltype(all)::value && KIND == 0) wait_until(w0 + (unsigned long long)((unsigned)h * pace));
-                if (decltype(all)::value || (unsigned)h < mine) put(i0 + (size_t)h * tstep, held[h]);
+                if constexpr (decltype(all)::value) {
+                    if constexpr (KIND == 0) wait_until(w0 + (unsigned long long)((unsigned)h * pace));
+                    put(i0 + (size_t)h * tstep, held[h]);
+                } else if ((unsigned)h < mine) {
+                    // a chunk's last round: the tiles are dealt out, so every workgroup has (nearly) as many,
+                    // and the schedule per tile holds for it too
+                    if constexpr (KIND == 0 && NR != 0) wait_until(w0 + (unsigned long long)((unsigned)h * pace));
+                    put(i0 + (size_t)h * tstep, held[h]);
+                }
             });
         };
         if constexpr (NR != 0) {
@@ -166,7 +173,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
             grid_barrier(c, gb, ++gen, (unsigned)rank, 14);
             if constexpr (NR != 0 && KIND == 0) {
                 if (pacing && blockIdx.x == 0) {     // workgroup 0 of rank 0, channel 0: its rounds are full to the end
-                    if (mine == (unsigned)H) pace_update(ctl, wall_clock64() - w0, (unsigned)H);
+                    if (mine >= (unsigned)H / 4) pace_update(ctl, wall_clock64() - w0, mine);   // also from a partial round
                     if (threadIdx.x == 0) st32_wt(c.gbar + kGridBarPaceWord, ctl.pace);
                 }
             }
