@@ -229,7 +229,7 @@ int msx_finalize(void);
  *                     the memory-side cache, 2 loads too; auto picks by the footprint of the call
  *   "hb_phased_min_bytes"   auto | bytes per rank from which the fused HB AllReduce (no residual, or one
  *                     shared by all ranks) runs in chip-wide read and write phases, one workgroup per CU; auto:
- *                     8 ranks from 40 MiB (64 MiB rows for ReduceScatter / AllGather), never otherwise; an
+ *                     8 ranks from 40 MiB (per rank; rows, for ReduceScatter / AllGather), never otherwise; an
  *                     explicit value applies to every rank count
  *   "hb_pace"         0 | 1   phased kernels: hold the write phases to a common wall-clock schedule, so that all
  *                     dies finish them together (the schedule is found by the kernels themselves and kept, per

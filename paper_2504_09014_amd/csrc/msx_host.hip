@@ -368,13 +368,14 @@ HbKernel hb_fused_kernel(int dt, int u, int n, int res, int cache)
 }
 // does a fused HB AllReduce of nbytes per rank run in chip-wide phases?  (res_mode 2, one residual per
 // destination, would need loads in the write phase)
-// auto_min: where the automatic choice starts for 8 ranks: 40 MiB per rank for the AllReduce (measured
-// against the free-running kernel, TB/s: 32 MiB 5.3 / 5.6-5.9, 40 MiB 5.6 / 4.9, 48 MiB 5.9 / 5.0, 64 MiB 6.0-6.2 / 5.2),
-// 64 MiB rows for the reduce-scatter and the all-gather
-bool use_phased(size_t nbytes, int n, int res_mode, size_t auto_min = (size_t)40 << 20)
+// The automatic choice starts at 40 MiB per rank (rows, for the reduce-scatter and the all-gather) with 8 ranks;
+// measured against the free-running kernels, TB/s: AllReduce 32 MiB 5.3 / 5.6-5.9, 40 MiB 5.6 / 4.9, 48 MiB
+// 5.9 / 5.0, 64 MiB 6.0-6.2 / 5.2; AllGather 32 MiB 5.2 / 5.5, 40 MiB 5.3 / 4.75, 64 MiB 6.0 / 4.5;
+// ReduceScatter 32 MiB 4.3 / 4.35, 40 MiB 4.7 / 4.6, 64 MiB 5.55 / 4.9.
+bool use_phased(size_t nbytes, int n, int res_mode)
 {
     if (n < 2 || res_mode == 2 || g_opt.hb_unroll != 0) return false;
-    return g_opt.hb_phased_min < 0 ? n == 8 && nbytes >= auto_min : nbytes >= (size_t)g_opt.hb_phased_min;
+    return g_opt.hb_phased_min < 0 ? n == 8 && nbytes >= ((size_t)40 << 20) : nbytes >= (size_t)g_opt.hb_phased_min;
 }
 HbKernel hb_2phase_kernel(int dt, int u, int n)
 {
@@ -826,7 +827,7 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     }
     // large blocks, 8 ranks: chip-wide read and write phases, one workgroup per CU (see k_allreduce_hb_phased)
     const size_t row_bytes = (which == kRS ? count_or_bytes * elem_size(dtype) : count_or_bytes) * (size_t)n;
-    if ((which == kRS || which == kAG) && vec && use_phased(row_bytes, n, 0, (size_t)64 << 20)) {
+    if ((which == kRS || which == kAG) && vec && use_phased(row_bytes, n, 0)) {
         HbKernel pk = which == kRS ? phased_reduce_kernel(dtype == MSX_F32, n, 0, 1) : phased_allgather_kernel(n);
         int pch = 1;
         if ((rc = pick_channels(c, (const void*)pk, threads, n, work_units, kPhasedHeld,

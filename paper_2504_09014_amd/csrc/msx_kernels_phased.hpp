@@ -263,7 +263,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
         static_for<H>([&](auto k) {
             constexpr int h = decltype(k)::value;
             if ((unsigned)h < mine) {
-                wait_until(w0 + (unsigned long long)((unsigned)h * (mine == (unsigned)H ? pace : 0u)));
+                wait_until(w0 + (unsigned long long)((unsigned)h * pace));     // partial last rounds too: dealt tiles
                 put(i0 + (size_t)h * tstep, held[h]);
             }
         });
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
         if (round + 1 < rounds || pacing) {
             grid_barrier(c, gb, ++gen, (unsigned)rank, 44);
             if (pacing && blockIdx.x == 0) {
-                if (mine == (unsigned)H) pace_update(ctl, wall_clock64() - w0, (unsigned)H);
+                if (mine >= (unsigned)H / 4) pace_update(ctl, wall_clock64() - w0, mine);
                 if (threadIdx.x == 0) st32_wt(c.gbar + kGridBarPaceWord, ctl.pace);
             }
         }
