@@ -948,20 +948,21 @@ int moe_dispatch_impl(const void* const* tokens, const int32_t* const* topk_idx,
     a.chans = chans;
     c->plan_T = T;
     c->plan_n = n;
-    // many long rows (bf16 / fp32 pack only): chip-wide read and write phases, one workgroup per CU.  Automatic
-    // for 8 ranks from 32 MiB of tokens per rank in rows of 512 to 1024 vectors; an explicit
-    // hb_phased_min_bytes counts for every shape the kernel can hold (rows of at most 1024 vectors).
+    // many rows of whole multiples of 64 vectors (bf16 / fp32 pack only): chip-wide read and write phases, one
+    // workgroup per CU.  Automatic for 8 ranks from 32 MiB of tokens per rank; an explicit hb_phased_min_bytes
+    // counts for every rank count.
     const size_t token_bytes = (size_t)T * row_bytes;
-    if (!recv_scales && a.row_vecs <= (unsigned)(64 * kPackVecsPerLane) &&
-        (g_opt.hb_phased_min < 0 ? n == 8 && a.row_vecs >= 512u && token_bytes >= ((size_t)32 << 20)
+    if (!recv_scales && a.row_vecs % 64u == 0 && (unsigned long long)T * a.row_vecs < (1ull << 32) &&
+        (g_opt.hb_phased_min < 0 ? n == 8 && token_bytes >= ((size_t)32 << 20)
                                  : token_bytes >= (size_t)g_opt.hb_phased_min)) {
-        int pch = 1;
-        if ((rc = pick_channels(c, (const void*)k_moe_pack_phased, 256, n, (size_t)T * 64, 4 * kPackRows,
-                                g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels, kMaxChannels, &pch)))
+        auto kd = k_moe_pack_dealt<kPhasedHeld>;
+        int dch = 1;
+        if ((rc = pick_channels(c, (const void*)kd, 256, n, (size_t)T * a.row_vecs, (size_t)kPhasedHeld,
+                                g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels, kMaxChannels, &dch)))
             return rc;
-        a.chans = pch;
-        note_launch(n * pch, 256, MSX_ALGO_2PA_HB);
-        return launch(k_moe_pack_phased, n * pch, 256, s, a, d, g_opt.hb_pace);
+        a.chans = dch;
+        note_launch(n * dch, 256, MSX_ALGO_2PA_HB);
+        return launch(kd, n * dch, 256, s, a, d, g_opt.hb_pace);
     }
     note_launch(n * chans, 256, MSX_ALGO_2PA_HB);
     if (recv_scales) {

@@ -238,108 +238,118 @@ __global__ __launch_bounds__(256) void k_moe_pack(MoeArgs a, DevCtx c)
     if (n > 1) rank_barrier(c, rank, n, chan, 210, false, false);   // write-through puts: all rows destined to me have landed
 }
 
-// ---- pack in chip-wide read and write phases -----------------------------------------------------------
-// Same rows to the same places as k_moe_pack, for many long rows: a round reads kPackRows rows per wave into
-// registers (up to 16 vectors per lane and row, so rows of at most 1024 vectors), all workgroups meet at the
-// chip-wide barrier, and the rows go out to their destinations with nothing but stores on the memory system
-// (the pack writes about five times what it reads), held to the common wall-clock schedule of the other
-// phased kernels (PaceCtl; one step of the schedule = one vector per lane to all the destinations of its row)
-// and without the streaming hint.  One workgroup per CU.  Measured at 8 x 4096 rows of 7168 bf16, top-8 of
-// 256 experts, plan and pack together: 0.590 ms against 0.640 ms free-running (a form in which a whole
-// workgroup shares a row, 4 KiB per destination and step, was no better: 0.600 ms).
-constexpr int kPackRows = 4, kPackVecsPerLane = 16;
+// ---- pack in chip-wide read and write phases: a dealt copy of the rank's whole token array ------------
+// Same rows to the same places as k_moe_pack, for many rows that are whole multiples of 64 vectors.  The T rows
+// of a rank are one linear array, and this form walks it exactly as k_allgather_hb_phased walks its block: tiles
+// of 256 vectors dealt out one by one over the rank's workgroups, H of them held per thread and round, all
+// workgroups meeting at the chip-wide barrier between reading and writing (the pack writes about five times
+// what it reads), stores without the streaming hint, write phases on the shared paced schedule (PaceCtl).
+// The 64 vectors of a wave always lie in one row, so the row's slots are wave-uniform: lane h fetches those of
+// held tile h in the read phase, the write phase takes them out of that lane into scalar registers, and they
+// decide, without any per-lane condition or load, which destinations the wave's vector goes to.  At any
+// moment the 32 workgroups of a rank write 128 KiB of consecutive source, about nine rows of 14 KiB, and the rows one
+// source sends to one destination are consecutive there: every (source, destination) pair writes one compact
+// window.  Measured at 8 x 4096 rows of 7168 bf16, top-8 of 256 experts, plan and pack together: 0.548 ms
+// against 0.625 ms with the schedule off and 0.61-0.64 ms for the free-running k_moe_pack.  A form that held
+// 4 whole rows per wave (each wave writing 1 KiB pieces 14 KiB apart) reached 0.59-0.61 ms, one in which a
+// workgroup shared a row (4 KiB pieces) 0.60 ms.  One workgroup per CU.
+typedef const __attribute__((address_space(4))) u32x4* UniformVecPtr;
 
-__global__ __launch_bounds__(256) void k_moe_pack_phased(MoeArgs a, DevCtx c, int pace_on)
+template <int H>
+__global__ __launch_bounds__(256) void k_moe_pack_dealt(MoeArgs a, DevCtx c, int pace_on)
 {
     const int n = a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
-    const int n_l = per_lane(n);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
     GridBar gb = grid_barrier_begin(c);
     const unsigned lane = threadIdx.x & 63u;
-    const int waves = (int)(blockDim.x >> 6);
-    const int wave = chan * waves + (int)(threadIdx.x >> 6);
-    const int per_round = a.chans * waves * kPackRows;            // rows of this rank per round
-    const unsigned rounds = (unsigned)((a.T + per_round - 1) / per_round);
-    const unsigned vpl = (a.row_vecs + 63u) / 64u;                // vectors per lane and row
-    const unsigned steps = (unsigned)kPackRows * vpl;             // steps of a full write phase
-    const bool pacing = pace_on && rounds >= 2u;
-    const unsigned key = ((unsigned)a.T * 40503u + a.row_vecs) * 2654435761u + gridDim.x * 64u + 48u + 1u;
+    const unsigned wave_first = __builtin_amdgcn_readfirstlane(threadIdx.x & ~63u);   // of the wave, in the tile
+    const unsigned rv = a.row_vecs;
+    const unsigned nv = (unsigned)a.T * rv;                       // the host keeps this below 2^32
+    const unsigned tiles = nv / 256u;
+    const unsigned per_round = (unsigned)a.chans * (unsigned)H;
+    const unsigned rounds = (tiles + per_round - 1u) / per_round;
+    const bool pacing = pace_on && rounds >= 1u;
+    const unsigned key = ((unsigned)a.T * 40503u + rv) * 2654435761u + gridDim.x * 64u + 56u + 1u;
     PaceCtl ctl = pace_load(c, key);
     unsigned pace = pacing ? ctl.pace : 0u;
     unsigned base[kMaxRanks];
 #pragma unroll
     for (int d = 0; d < kMaxRanks; ++d) base[d] = a.base[rank * 8 + d];
-    const char* tokens = (const char*)a.tokens[rank];
-    const size_t row_bytes = (size_t)a.row_vecs * 16;
+    const char* src = (const char*)a.tokens[rank];
+    const unsigned short* slots = a.slots + (size_t)rank * a.T * 8;
+    const unsigned tstep = (unsigned)a.chans * 256u;              // vectors between two of my tiles
+    const unsigned step_rows = tstep / rv, step_cols = tstep % rv;
     unsigned gen = 0;
 
-    for (unsigned round = 0; round < rounds; ++round) {
-        const int t0 = (int)round * per_round + wave * kPackRows;   // my kPackRows consecutive rows
-        const bool full = t0 + kPackRows <= a.T;
-        u32x4 held[kPackRows][kPackVecsPerLane];
-        u32x4 pk[kPackRows];
-        static_for<kPackRows>([&](auto rr) {
-            constexpr int r = decltype(rr)::value;
-            const int t = t0 + r;
-            if (t < a.T) {
-                pk[r] = *(const u32x4*)(a.slots + ((size_t)rank * a.T + t) * 8);
-                const char* src = tokens + (size_t)t * row_bytes;
-                static_for<kPackVecsPerLane>([&](auto kk) {
-                    constexpr unsigned k = (unsigned)decltype(kk)::value;
-                    if (k * 64u + lane < a.row_vecs) held[r][k] = ld16(src, k * 64u + lane);
-                });
+    // the vector `held`, the wave's share [v, v + 64) of the array starting at column `col` of row t
+    auto put = [&](unsigned t, unsigned col, u32x4 pk, u32x4 held) {
+        unsigned row[kMaxRanks];
+        row[0] = pk.x & 0xffffu; row[1] = pk.x >> 16; row[2] = pk.y & 0xffffu; row[3] = pk.y >> 16;
+        row[4] = pk.z & 0xffffu; row[5] = pk.z >> 16; row[6] = pk.w & 0xffffu; row[7] = pk.w >> 16;
+#pragma unroll
+        for (int d = 0; d < kMaxRanks; ++d) {
+            const unsigned slot = base[d] + row[d];
+            if (d < n && row[d] != 0xffffu && slot < a.cap) {     // wave-uniform
+                st16_wt_keep(a.recv[d], (size_t)slot * rv + col + lane, held);
+                if (a.has_src && col == 0u && lane == 0u) st32_wt(a.recv_src[d] + slot, (unsigned)(rank * a.T) + t);
             }
+        }
+    };
+
+    for (unsigned round = 0; round < rounds; ++round) {
+        const unsigned first = round * per_round + (unsigned)chan;
+        const unsigned left = first >= tiles ? 0u : (tiles - first + (unsigned)a.chans - 1u) / (unsigned)a.chans;
+        const unsigned mine = left < (unsigned)H ? left : (unsigned)H;
+        const unsigned v0 = first * 256u + wave_first;            // the wave's first vector in my first tile
+        u32x4 held[H];
+        static_for<H>([&](auto k) {
+            constexpr unsigned h = (unsigned)decltype(k)::value;
+            if (h < mine) held[h] = ld16(src, (size_t)v0 + (size_t)h * tstep + lane);
         });
-        static_for<kPackRows>([&](auto rr) {
-            static_for<kPackVecsPerLane>([&](auto kk) { settle(held[decltype(rr)::value][decltype(kk)::value]); });
-            settle(pk[decltype(rr)::value]);
-        });
-        grid_barrier(c, gb, ++gen, (unsigned)rank, 213);
+        // the slots of the rows my tiles lie in: lane h fetches those of tile h, the write phase reads them lane by lane
+        u32x4 pks = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
+        static_assert(H <= 64, "one lane per held tile");
+        if (lane < mine) pks = *(const u32x4*)(slots + (size_t)((v0 + lane * tstep) / rv) * 8);
+        static_for<H>([&](auto k) { settle(held[decltype(k)::value]); });
+        settle(pks);
+        grid_barrier(c, gb, ++gen, (unsigned)rank, 215);
         if (pacing && round > 0)
             pace = pace_clamp(__hip_atomic_load(c.gbar + kGridBarPaceWord, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-        const unsigned step_ticks = full ? pace : 0u;
+        unsigned t = v0 / rv, col = v0 % rv;
         const unsigned long long w0 = wall_clock64();
-        static_for<kPackRows>([&](auto rr) {
-            constexpr int r = decltype(rr)::value;
-            const int t = t0 + r;
-            if (t < a.T) {
-                unsigned row[kMaxRanks];
-                row[0] = pk[r].x & 0xffffu; row[1] = pk[r].x >> 16; row[2] = pk[r].y & 0xffffu; row[3] = pk[r].y >> 16;
-                row[4] = pk[r].z & 0xffffu; row[5] = pk[r].z >> 16; row[6] = pk[r].w & 0xffffu; row[7] = pk[r].w >> 16;
-                char* dst[kMaxRanks];
-#pragma unroll
-                for (int d = 0; d < kMaxRanks; ++d) {
-                    const unsigned slot = base[d] + row[d];
-                    const bool go = d < n_l && row[d] != 0xffffu && slot < a.cap;
-                    dst[d] = go ? (char*)a.recv[d] + (size_t)slot * row_bytes : nullptr;
-                    if (go && a.has_src && lane == 0) st32_wt(a.recv_src[d] + slot, (unsigned)(rank * a.T + t));
-                }
-                static_for<kPackVecsPerLane>([&](auto kk) {
-                    constexpr unsigned k = (unsigned)decltype(kk)::value;
-                    if (k < vpl) {
-                        wait_until(w0 + (unsigned long long)(((unsigned)r * vpl + k) * step_ticks));
-                        if (k * 64u + lane < a.row_vecs) {
-#pragma unroll
-                            for (int d = 0; d < kMaxRanks; ++d)
-                                if (dst[d]) st16_wt_keep(dst[d], k * 64u + lane, held[r][k]);
-                        }
-                    }
-                });
+        static_for<H>([&](auto k) {
+            constexpr unsigned h = (unsigned)decltype(k)::value;
+            if (h < mine) {
+                wait_until(w0 + (unsigned long long)(h * pace));
+                const u32x4 pk = {(unsigned)__builtin_amdgcn_readlane((int)pks.x, (int)h), (unsigned)__builtin_amdgcn_readlane((int)pks.y, (int)h),
+                                  (unsigned)__builtin_amdgcn_readlane((int)pks.z, (int)h), (unsigned)__builtin_amdgcn_readlane((int)pks.w, (int)h)};
+                put(t, col, pk, held[h]);
+                t += step_rows; col += step_cols;
+                if (col >= rv) { col -= rv; ++t; }
             }
         });
         put_drain();
-        if (round + 1 < rounds) {
-            grid_barrier(c, gb, ++gen, (unsigned)rank, 214);
-            if (pacing && blockIdx.x == 0) {          // rank 0's first workgroup: its rounds are full to the end
-                if (full) pace_update(ctl, wall_clock64() - w0, steps);
+        if (round + 1 < rounds || pacing) {
+            grid_barrier(c, gb, ++gen, (unsigned)rank, 216);
+            if (pacing && blockIdx.x == 0) {
+                if (mine >= (unsigned)H / 4) pace_update(ctl, wall_clock64() - w0, mine);
                 if (threadIdx.x == 0) st32_wt(c.gbar + kGridBarPaceWord, ctl.pace);
             }
         }
     }
     if (pacing && blockIdx.x == 0 && threadIdx.x == 0) pace_save(c, ctl, key);
     grid_barrier_end(c, gb, gen);
+    if (chan == 0) {                                              // what is left behind the last whole tile
+        const unsigned v = tiles * 256u + wave_first;
+        if (v < nv) {
+            const u32x4 x = ld16(src, (size_t)v + lane);
+            const u32x4 pk = *(UniformVecPtr)(slots + (size_t)(v / rv) * 8);   // a scalar load: wave-uniform address
+            put(v / rv, v % rv, pk, x);
+        }
+    }
+    put_drain();
     if (n > 1) rank_barrier(c, rank, n, chan, 210, false, false);   // write-through puts: all rows destined to me have landed
 }
 

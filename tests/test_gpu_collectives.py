@@ -211,12 +211,13 @@ def test_moe_dispatch_small_shapes(msx, orc, n, T, H, K, E):
         assert np.array_equal(_bits(recv[d]), want_recv[d]), d
 
 
-@pytest.mark.parametrize("n,T,H,K,E,blocks", [(8, 1000, 64, 8, 256, 1), (8, 300, 7168, 8, 256, 2), (4, 333, 8192, 2, 16, 0),
-                                              (2, 77, 520, 1, 4, 1)])
+@pytest.mark.parametrize("n,T,H,K,E,blocks", [(8, 1000, 512, 8, 256, 1), (8, 301, 7168, 8, 256, 2), (4, 333, 8192, 2, 16, 0),
+                                              (2, 77, 1536, 1, 4, 1), (8, 3, 512, 8, 64, 1)])
 def test_moe_dispatch_in_read_and_write_phases(msx, orc, n, T, H, K, E, blocks):
-    """The pack kernel that alternates between chip-wide read and write phases (by default: 8 ranks, many long
-    rows), forced here; one or two workgroups per rank make dozens of rounds, the last one partial, with the
-    write phases paced.  Twice in a row: the second call starts from the schedule the first one left."""
+    """The pack kernel that alternates between chip-wide read and write phases (by default: 8 ranks, 32 MiB of
+    tokens per rank; rows of whole multiples of 64 vectors), forced here; one or two workgroups per rank make
+    dozens of rounds, the last one partial, with the write phases paced; token arrays that end inside a tile, and one
+    smaller than a tile.  Twice in a row: the second call starts from the schedule the first one left."""
     tokens = synth.moe_tokens(n, T, H, seed=21)
     topk = synth.moe_routing(n, T, K, E, seed=21)
     cap = n * T

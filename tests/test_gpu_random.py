@@ -179,7 +179,7 @@ def test_random_dispatch_and_combine_cases(msx, orc, seed):
     for case in range(12):
         n = int(rng.choice([1, 2, 4, 8]))
         T = int(rng.integers(1, 200))
-        H = int(rng.choice([8, 64, 128, 1000 // 8 * 8, 2048]))
+        H = int(rng.choice([8, 64, 512, 1000 // 8 * 8, 1536, 2048]))   # rows of 64, 192, 256 vectors can take the phased pack
         per_rank = int(rng.choice([1, 2, 4]))
         E = n * per_rank
         K = int(rng.integers(1, min(E, 8) + 1))
