@@ -421,23 +421,23 @@ __device__ __forceinline__ unsigned bf16_round(float f)
     return ((u & 0x7fffffffu) > 0x7f800000u) ? q : r;
 }
 
-// fp32 -> OCP E4M3 code (1-4-3, bias 7, largest finite 448 = 0x7E, no infinity): round to nearest
-// even, magnitudes from 448 up (and infinities) saturate to 0x7E, NaN -> 0x7F.
-__device__ __forceinline__ unsigned e4m3_round(float f)
+// Four fp32 -> four OCP E4M3 codes in one word (a in bits 0-7).  E4M3: 1-4-3, bias 7, largest finite 448 =
+// 0x7E, no infinity; round to nearest even, magnitudes from 448 up (and infinities) saturate to 0x7E, NaN ->
+// 0x7F.  Done by the conversion instruction of the matrix-core data types (denormals kept).  It is fed
+// values clamped to +-448, so that what it does on overflow never matters (infinities saturate like the rest);
+// the clamp does not keep NaNs, so those are patched in afterwards as 0x7F.
+__device__ __forceinline__ unsigned e4m3_quad(float a, float b, float c, float d)
 {
-    const unsigned u = __float_as_uint(f);
-    const unsigned sign = (u >> 24) & 0x80u;
-    const unsigned a = u & 0x7fffffffu;
-    unsigned code;
-    if (a > 0x7f800000u) return 0x7fu;
-    if (a >= 0x43e00000u) code = 0x7eu;                       // |f| >= 448
-    else if (a >= 0x3c800000u) {                              // normal E4M3 range, |f| >= 2^-6
-        const unsigned r = a + 0x7ffffu + ((a >> 20) & 1u);   // round the mantissa to 3 bits
-        code = (((r >> 23) - 120u) << 3) | ((r >> 20) & 7u);
-    } else {
-        code = (unsigned)__float2int_rn(__uint_as_float(a) * 512.0f);   // multiples of 2^-9; 8 -> 0x08
-    }
-    return sign | code;
+    const float ca = __builtin_amdgcn_fmed3f(a, 448.0f, -448.0f), cb = __builtin_amdgcn_fmed3f(b, 448.0f, -448.0f);
+    const float cc = __builtin_amdgcn_fmed3f(c, 448.0f, -448.0f), cd = __builtin_amdgcn_fmed3f(d, 448.0f, -448.0f);
+    int w = __builtin_amdgcn_cvt_pk_fp8_f32(ca, cb, 0, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(cc, cd, w, true);
+    unsigned u = (unsigned)w;
+    if (a != a) u = (u & 0xffffff00u) | 0x0000007fu;
+    if (b != b) u = (u & 0xffff00ffu) | 0x00007f00u;
+    if (c != c) u = (u & 0xff00ffffu) | 0x007f0000u;
+    if (d != d) u = (u & 0x00ffffffu) | 0x7f000000u;
+    return u;
 }
 
 // Accumulator for the elements held in one 32-bit word: 1 x fp32 or 2 x bf16.

@@ -424,13 +424,11 @@ __global__ __launch_bounds__(256) void k_moe_pack_fp8(MoeArgs a, MoeFp8Args f, D
                 amax = o > amax ? o : amax;
             }
             const float inv = 448.0f / amax;
-            unsigned b[16];
+            float y[16];
 #pragma unroll
-            for (int k = 0; k < 16; ++k) b[k] = e4m3_round(x[k] * inv);
-            const u32x4 q = {b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24),
-                             b[4] | (b[5] << 8) | (b[6] << 16) | (b[7] << 24),
-                             b[8] | (b[9] << 8) | (b[10] << 16) | (b[11] << 24),
-                             b[12] | (b[13] << 8) | (b[14] << 16) | (b[15] << 24)};
+            for (int k = 0; k < 16; ++k) y[k] = x[k] * inv;
+            const u32x4 q = {e4m3_quad(y[0], y[1], y[2], y[3]), e4m3_quad(y[4], y[5], y[6], y[7]),
+                             e4m3_quad(y[8], y[9], y[10], y[11]), e4m3_quad(y[12], y[13], y[14], y[15])};
             const float scale = amax / 448.0f;
 #pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)

@@ -404,6 +404,41 @@ def test_e4m3_encoder_on_gpu_covers_every_code_and_tie(msx, orc):
         assert np.array_equal(rq[d].cpu().numpy(), q), d
 
 
+def test_fp8_pack_special_values(msx, orc):
+    """NaN, infinities, signed zeros, values under the 1e-4 floor of the group maximum and the largest bf16
+    magnitudes: groups of their own, every code and every scale bit for bit against the oracle."""
+    H = 128 * 8
+    row = torch.zeros(H)
+    rng = np.random.default_rng(5)
+    g = lambda k: slice(128 * k, 128 * k + 128)
+    row[g(0)] = torch.tensor(rng.standard_normal(128), dtype=torch.float32)
+    row[3] = float("nan"); row[77] = float("nan")
+    row[g(1)] = torch.tensor(rng.standard_normal(128), dtype=torch.float32)
+    row[128 + 9] = float("inf")
+    row[g(2)] = torch.tensor(rng.standard_normal(128), dtype=torch.float32)
+    row[256 + 100] = float("-inf"); row[256 + 5] = float("nan")
+    row[g(3)] = torch.tensor(rng.standard_normal(128) * 1e-6, dtype=torch.float32)       # all under the floor
+    row[g(4)] = torch.tensor(rng.standard_normal(128), dtype=torch.float32) * 3e38       # overflows bf16 in places
+    row[g(5)] = 0.0
+    row[640 + 1] = -0.0; row[640 + 2] = 1.0; row[640 + 3] = -1e-6; row[640 + 4] = 1e-6
+    row[g(6)] = torch.tensor(rng.standard_normal(128), dtype=torch.float32) * 1e-30
+    row[g(7)] = torch.tensor(rng.integers(-448, 449, 128), dtype=torch.float32)
+    tokens = row.bfloat16().view(1, 1, H).repeat(8, 1, 1)
+    topk = torch.arange(0, 256, 32, dtype=torch.int32).repeat(8, 1, 1)
+    q, scales = orc.fp8_quantize_rows(_bits(tokens).reshape(8, H))
+    assert 0x7F in q[0] and 0x80 in q[0] and np.isinf(scales[0]).any()
+    tok = [tokens[r].clone().cuda() for r in range(8)]
+    idx = [topk[r].clone().cuda() for r in range(8)]
+    rq = [torch.zeros((8, H), dtype=torch.uint8, device="cuda") for _ in range(8)]
+    rs = [torch.zeros((8, H // 128), dtype=torch.float32, device="cuda") for _ in range(8)]
+    counts = torch.zeros((8, 8), dtype=torch.int32, device="cuda")
+    msx.moe_dispatch_fp8(tok, idx, 256, rq, rs, counts)
+    msx.check_status()
+    for d in range(8):
+        assert np.array_equal(rq[d].cpu().numpy(), q), (d, np.nonzero(rq[d].cpu().numpy() != q))
+        assert np.array_equal(rs[d].cpu().numpy().view(np.uint32), scales.view(np.uint32)), d
+
+
 # ---------------------------------------------------------------- fp16 and max / min
 
 # fp32 / bf16 sums are the tuned paths, tested above: here every other (type, operator) pair
