@@ -243,6 +243,67 @@ def test_moe_dispatch_in_read_and_write_phases(msx, orc, n, T, H, K, E, blocks):
         msx.set_option("chaos", "0")
 
 
+def test_phased_dispatch_and_combine_replay_in_a_hip_graph(msx, orc):
+    """Dispatch (plan + pack in read and write phases, paced) and combine captured once and replayed with other
+    tokens and routings of the same shape; an eager dispatch of another shape between the replays."""
+    n, T, H, K, E = 8, 301, 1536, 4, 64
+    cap = n * T
+    cases = [(synth.moe_tokens(n, T, H, seed=60 + i), synth.moe_routing(n, T, K, E, seed=60 + i)) for i in range(3)]
+    tok = [cases[0][0][r].clone().cuda() for r in range(n)]
+    idx = [cases[0][1][r].clone().cuda() for r in range(n)]
+    recv = [torch.zeros((cap, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    src = [torch.full((cap,), -1, dtype=torch.int32, device="cuda") for _ in range(n)]
+    counts = torch.zeros((n, n), dtype=torch.int32, device="cuda")
+    out = [torch.zeros((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    old = msx.get_option("hb_phased_min_bytes")
+    msx.set_option("hb_phased_min_bytes", "0")
+    msx.set_option("hb_blocks_per_rank", "2")
+    try:
+        msx.moe_dispatch(tok, idx, E, recv, counts, src)          # warm-up outside the capture (plan scratch)
+        msx.moe_combine(recv, out)
+        msx.check_status()
+        st = torch.cuda.Stream()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(st):
+            with torch.cuda.graph(g, stream=st):
+                msx.moe_dispatch(tok, idx, E, recv, counts, src)
+                msx.moe_combine(recv, out)
+        torch.cuda.synchronize()
+        for i, (tokens, topk) in enumerate(cases):
+            for r in range(n):
+                tok[r].copy_(tokens[r])
+                idx[r].copy_(topk[r])
+                recv[r].zero_()
+                src[r].fill_(-1)
+                out[r].zero_()
+            counts.zero_()
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            msx.check_status()
+            want_recv, want_src, want_counts, rc = orc.moe_dispatch(_bits(tokens), topk.numpy(), E, cap)
+            assert rc == 0
+            assert np.array_equal(counts.cpu().numpy(), want_counts), i
+            for d in range(n):
+                used = int(want_counts[d].sum())
+                assert np.array_equal(src[d].cpu().numpy()[:used], want_src[d][:used]), (i, d)
+                assert np.array_equal(_bits(recv[d])[:used], want_recv[d][:used]), (i, d)
+            want_out, rc2 = orc.moe_combine_bf16(np.stack([_bits(t) for t in recv]), topk.numpy(), E)
+            assert rc2 == 0
+            for s_ in range(n):
+                assert np.array_equal(_bits(out[s_]), want_out[s_]), (i, s_)
+            # an eager dispatch of another shape in between: the plan scratch and the pacing slots are shared
+            t2 = synth.moe_tokens(n, 40, 512, seed=90 + i)
+            k2 = synth.moe_routing(n, 40, 2, E, seed=90 + i)
+            r2, s2, c2, rc3, info = _dispatch(msx, t2, k2, E, n * 40)
+            assert rc3 == 0, info
+            w2 = orc.moe_dispatch(_bits(t2), k2.numpy(), E, n * 40)
+            assert np.array_equal(c2.cpu().numpy(), w2[2])
+    finally:
+        msx.set_option("hb_phased_min_bytes", old)
+        msx.set_option("hb_blocks_per_rank", "0")
+
+
 def test_moe_dispatch_special_routings(msx, orc):
     n, T, H, E = 8, 200, 32, 256
     tokens = synth.moe_tokens(n, T, H, seed=5)
