@@ -107,6 +107,23 @@ int msx_alltoall(void* buf, size_t count, int dtype, int op, int nranks, void* s
 int msx_allreduce_ex(const void* const* send, void* const* recv, const void* const* residual,
                      size_t count, int dtype, int op, int nranks, int algo, void* stream);
 
+/* msx_allreduce_ex for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same results, same kernels; but the
+ * semaphores, the call state and the LL scratch it works on are a fixed array inside the library's code
+ * object (about 6.2 MiB, which every GPU the library runs on holds until the process ends), and the call
+ * itself makes no hipMalloc / hipFree and uses no allocating routine.
+ *   Limits: count*elemsize <= 16 MiB per rank (else MSX_ERR_NOMEM); the LL algorithms <= 64 KiB per rank
+ *   (1PA-LL <= 16 KiB), else MSX_ERR_NOMEM; MSX_ALGO_2PR_HB and the MSX_ALGO_PLAN_* forms, whose scratch
+ *   grows on demand, are refused with MSX_ERR_UNSUPPORTED; the "algo" option does not apply (pass algo).
+ *   The array is set up (address looked up, cleared once) by msx_init or by the first such call on a
+ *   device; that first call waits for the device and therefore must not happen during stream capture
+ *   (then MSX_ERR_UNSUPPORTED: run msx_init before capturing).
+ *   Every call on a GPU shares that GPU's array and its flag epoch: issue these calls on one stream or
+ *   order them yourself; calls that overlap on one GPU race.  They are independent of the calls that
+ *   use the allocated context, and msx_status / msx_reset cover both. */
+int msx_allreduce_ex_static(const void* const* send, void* const* recv, const void* const* residual,
+                            size_t count, int dtype, int op, int nranks, int algo, void* stream);
+
 /* ReduceScatter: send[r] is [count]; recv[r] is [count/nranks] = sum_j send[j][r*c + k]. */
 int msx_reducescatter_ex(const void* const* send, void* const* recv, size_t count, int dtype,
                          int op, int nranks, void* stream);

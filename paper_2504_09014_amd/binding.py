@@ -13,7 +13,7 @@ __all__ = [
     "MsxError", "lib", "lib_path", "init", "reset", "finalize", "set_option", "get_option", "status",
     "check_status", "last_launch", "version", "strerror",
     "allreduce", "reducescatter", "allgather", "alltoall",
-    "allreduce_ex", "reducescatter_ex", "allgather_ex", "alltoall_ex", "moe_dispatch", "moe_dispatch_fp8", "moe_combine",
+    "allreduce_ex", "allreduce_ex_static", "reducescatter_ex", "allgather_ex", "alltoall_ex", "moe_dispatch", "moe_dispatch_fp8", "moe_combine",
     "prim_pingpong", "prim_barrier", "prim_put_signal_wait", "prim_ll_encode", "prim_ll_roundtrip", "prim_port_put_signal_wait",
     "EXPORTS",
 ]
@@ -25,7 +25,7 @@ ALGO_PLAN_2PA_HB, ALGO_PLAN_2PR_HB = 6, 7
 
 EXPORTS = [
     "msx_allreduce", "msx_reducescatter", "msx_allgather", "msx_alltoall",
-    "msx_allreduce_ex", "msx_reducescatter_ex", "msx_allgather_ex", "msx_alltoall_ex",
+    "msx_allreduce_ex", "msx_allreduce_ex_static", "msx_reducescatter_ex", "msx_allgather_ex", "msx_alltoall_ex",
     "msx_moe_dispatch", "msx_moe_dispatch_fp8", "msx_moe_combine",
     "msx_prim_pingpong", "msx_prim_barrier", "msx_prim_put_signal_wait", "msx_prim_ll_encode",
     "msx_prim_ll_roundtrip", "msx_prim_port_put_signal_wait",
@@ -65,6 +65,7 @@ def lib():
         for name in ("msx_allreduce", "msx_reducescatter", "msx_allgather", "msx_alltoall"):
             getattr(L, name).argtypes = [vp, sz, i, i, i, vp]
         L.msx_allreduce_ex.argtypes = [pp, pp, pp, sz, i, i, i, i, vp]
+        L.msx_allreduce_ex_static.argtypes = [pp, pp, pp, sz, i, i, i, i, vp]
         L.msx_reducescatter_ex.argtypes = [pp, pp, sz, i, i, i, vp]
         L.msx_allgather_ex.argtypes = [pp, pp, sz, i, i, vp]
         L.msx_alltoall_ex.argtypes = [pp, pp, sz, i, i, vp]
@@ -223,6 +224,16 @@ def allreduce_ex(send, recv, residual=None, algo=ALGO_AUTO, stream=None, count=N
     cnt = send[0].numel() if count is None else count
     _ck(lib().msx_allreduce_ex(_table(send), _table(recv), _table(residual), cnt, _dtype(send[0]), op, n,
                                algo, _stream(stream)), "msx_allreduce_ex")
+
+
+def allreduce_ex_static(send, recv, residual=None, algo=ALGO_AUTO, stream=None, count=None, op=SUM):
+    """allreduce_ex on the library's fixed scratch array: the call allocates nothing."""
+    n = len(send)
+    for t in list(send) + list(recv) + list(residual or []):
+        _dev(t, "tensor")
+    cnt = send[0].numel() if count is None else count
+    _ck(lib().msx_allreduce_ex_static(_table(send), _table(recv), _table(residual), cnt, _dtype(send[0]), op, n,
+                                      algo, _stream(stream)), "msx_allreduce_ex_static")
 
 
 def reducescatter_ex(send, recv, stream=None, op=SUM):

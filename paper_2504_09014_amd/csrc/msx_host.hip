@@ -89,6 +89,7 @@ struct Ctx {
     Port* port = nullptr;          // created on the first port-channel call
     unsigned* snap = nullptr;  // small device scratch for snapshots
     size_t ll_limit = 0;       // ll_max_bytes this context was sized for
+    bool fixed = false;        // its device memory is the file-scope array below: nothing to free, nothing may grow
     std::map<std::pair<const void*, int>, int> occ;   // (kernel, threads) -> resident blocks per CU
 };
 
@@ -263,6 +264,74 @@ int get_ctx(Ctx** out)
     c->d.ll_rank_stride = (unsigned)rank_stride;
     c->d.ll_rot_stride = (unsigned)rot;
     g_ctx[dev] = c;
+    *out = c;
+    return MSX_OK;
+}
+
+// ---- the context that lives in a file-scope device array ---------------------------------------
+// For callers that must not allocate (msx_allreduce_ex_static): semaphores, expected values, status,
+// call state, the chip-wide barrier's counters and a small LL scratch, carved out of one array that
+// every GPU the library runs on holds until the process ends.  In host code the array's name only
+// stands for the symbol; its address on a device comes from hipGetSymbolAddress, once per device.
+constexpr size_t kStaticLlMax = (size_t)64 << 10;                       // LL algorithms: bytes per rank
+constexpr size_t kStaticMaxBytes = (size_t)16 << 20;                    // any algorithm: bytes per rank
+constexpr size_t kStaticSemBytes = (size_t)kMaxRanks * kMaxRanks * kMaxChannels * kSemStrideWords * 4;
+constexpr size_t kStaticExpBytes = (size_t)kMaxRanks * kMaxRanks * kMaxChannels * 4;
+constexpr size_t kStaticRot = 4 * kStaticLlMax + 4096;
+constexpr size_t kStaticLlBytes = 2 * kStaticRot * kMaxRanks;
+constexpr size_t kStaticOffExp = kStaticSemBytes;
+constexpr size_t kStaticOffStatus = kStaticOffExp + kStaticExpBytes;
+constexpr size_t kStaticOffCall = kStaticOffStatus + 256;
+constexpr size_t kStaticOffGbar = kStaticOffCall + 256;
+constexpr size_t kStaticOffLl = kStaticOffGbar + ((kGridBarBytes + 255) / 256) * 256;
+constexpr size_t kStaticBytes = kStaticOffLl + kStaticLlBytes;          // about 6.2 MiB
+static_assert(kStaticBytes % 16 == 0, "cleared in 16-byte vectors");
+
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+__global__ __launch_bounds__(256) void k_clear(u32x4* p, size_t nvec)
+{
+    const u32x4 z = {0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < nvec; i += (size_t)gridDim.x * blockDim.x) p[i] = z;
+}
+
+Ctx* g_static[64] = {};
+
+// The current device's fixed context; set up on first use (msx_init does it).  Caller holds g_mu.  Set-up
+// clears the array with a kernel on the null stream and waits for it, so it cannot happen while `stream` is
+// being captured: such a caller has to run msx_init first.
+int get_static_ctx(hipStream_t stream, Ctx** out)
+{
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return MSX_ERR_ARG;
+    if (g_static[dev]) { *out = g_static[dev]; return MSX_OK; }
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (stream && hipStreamIsCapturing(stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+        return MSX_ERR_UNSUPPORTED;
+    unsigned char* ptr = nullptr;
+    HIPCHK(hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return MSX_ERR_HIP;
+    hipDeviceProp_t prop;
+    HIPCHK(hipGetDeviceProperties(&prop, dev));
+    hipLaunchKernelGGL(k_clear, dim3(256), dim3(256), 0, nullptr, (u32x4*)ptr, kStaticBytes / 16);
+    HIPCHK(hipGetLastError());
+    HIPCHK(hipDeviceSynchronize());
+    Ctx* c = new Ctx();
+    c->device = dev;
+    c->fixed = true;
+    c->cus = prop.multiProcessorCount;
+    c->d.sem = (unsigned*)ptr;
+    c->d.expected = (unsigned*)(ptr + kStaticOffExp);
+    c->d.status = (unsigned*)(ptr + kStaticOffStatus);
+    c->d.call_state = (unsigned*)(ptr + kStaticOffCall);
+    c->d.gbar = (unsigned*)(ptr + kStaticOffGbar);
+    c->d.ll = ptr + kStaticOffLl;
+    c->d.ll_bytes = (unsigned)kStaticLlBytes;
+    c->d.ll_rank_stride = (unsigned)(2 * kStaticRot);
+    c->d.ll_rot_stride = (unsigned)kStaticRot;
+    c->ll_limit = kStaticLlMax;
+    g_static[dev] = c;
     *out = c;
     return MSX_OK;
 }
@@ -616,7 +685,7 @@ int reduce_generic(Ctx* c, const void* const* in, void* const* out, size_t count
 }
 
 int allreduce_impl(const void* const* send, void* const* recv, const void* const* residual, size_t count,
-                   int dtype, int op, int nranks, int algo, hipStream_t stream)
+                   int dtype, int op, int nranks, int algo, hipStream_t stream, bool fixed_ctx = false)
 {
     int rc = check_common(dtype, op, nranks);
     if (rc) return rc;
@@ -629,7 +698,13 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
 
     std::lock_guard<std::mutex> lk(g_mu);
     Ctx* c = nullptr;
-    if ((rc = get_ctx(&c))) return rc;
+    if (fixed_ctx) {
+        // nothing below may allocate: the ring's and the interpreter's scratch grow on demand, so they are out
+        if (nbytes > kStaticMaxBytes) return MSX_ERR_NOMEM;
+        if (algo == MSX_ALGO_2PR_HB || algo == MSX_ALGO_PLAN_2PA_HB || algo == MSX_ALGO_PLAN_2PR_HB)
+            return MSX_ERR_UNSUPPORTED;
+        if ((rc = get_static_ctx(stream, &c))) return rc;
+    } else if ((rc = get_ctx(&c))) return rc;
     const int n = nranks;
 
     bool res_shared = residual != nullptr;
@@ -639,12 +714,12 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     if (dtype == MSX_F16 || dtype == MSX_I32 || op != MSX_SUM) {
         // outside the tuned paths: only the fused all-pairs HB form exists
         if (residual) return MSX_ERR_UNSUPPORTED;
-        if (algo == MSX_ALGO_AUTO) algo = g_opt.algo;
+        if (algo == MSX_ALGO_AUTO && !fixed_ctx) algo = g_opt.algo;
         if (algo != MSX_ALGO_AUTO && algo != MSX_ALGO_2PA_HB) return MSX_ERR_UNSUPPORTED;
         return reduce_generic(c, send, recv, count, dtype, op, n, 0, 1, stream);
     }
 
-    if (algo == MSX_ALGO_AUTO) algo = g_opt.algo;
+    if (algo == MSX_ALGO_AUTO && !fixed_ctx) algo = g_opt.algo;
     if (algo == MSX_ALGO_AUTO) algo = choose_algo(nbytes, n, c->ll_limit);
 
     if (algo == MSX_ALGO_1PA_LL || algo == MSX_ALGO_2PA_LL) {
@@ -1000,6 +1075,12 @@ int msx_allreduce_ex(const void* const* send, void* const* recv, const void* con
     return allreduce_impl(send, recv, residual, count, dtype, op, nranks, algo, (hipStream_t)stream);
 }
 
+int msx_allreduce_ex_static(const void* const* send, void* const* recv, const void* const* residual, size_t count,
+                            int dtype, int op, int nranks, int algo, void* stream)
+{
+    return allreduce_impl(send, recv, residual, count, dtype, op, nranks, algo, (hipStream_t)stream, true);
+}
+
 int msx_allreduce(void* buf, size_t count, int dtype, int op, int nranks, void* stream)
 {
     int rc = check_common(dtype, op, nranks);
@@ -1330,7 +1411,9 @@ int msx_init(void)
 {
     std::lock_guard<std::mutex> lk(g_mu);
     Ctx* c = nullptr;
-    return get_ctx(&c);
+    int rc = get_ctx(&c);
+    if (rc) return rc;
+    return get_static_ctx(nullptr, &c);
 }
 
 int msx_reset(void)
@@ -1346,6 +1429,9 @@ int msx_reset(void)
     HIPCHK(hipMemset(c->d.call_state, 0, 64));
     HIPCHK(hipMemset(c->d.gbar, 0, kGridBarBytes));
     HIPCHK(hipMemset(c->d.ll, 0, c->d.ll_bytes));
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev >= 0 && dev < 64 && g_static[dev]) HIPCHK(hipMemset(g_static[dev]->d.sem, 0, kStaticBytes));
     HIPCHK(hipDeviceSynchronize());
     if (c->port) {                       // a port channel that timed out starts over with a fresh proxy
         destroy_port(c->port);
@@ -1539,6 +1625,10 @@ int msx_status(void* stream, uint32_t info[6])
     if (c) {
         HIPCHK(hipMemcpy(h, c->d.status, 32, hipMemcpyDeviceToHost));
         if (h[0] != 0) HIPCHK(hipMemset(c->d.status, 0, 32));
+    }
+    if (h[0] == 0 && g_static[dev]) {        // the fixed context of msx_allreduce_ex_static has a status block of its own
+        HIPCHK(hipMemcpy(h, g_static[dev]->d.status, 32, hipMemcpyDeviceToHost));
+        if (h[0] != 0) HIPCHK(hipMemset(g_static[dev]->d.status, 0, 32));
     }
     if (info)
         for (int i = 0; i < 6; ++i) info[i] = h[i];
