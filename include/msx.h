@@ -14,13 +14,36 @@
  *     alive until the stream has run the call.  Pointer TABLES (`const void* const*`)
  *     are HOST arrays of `nranks` device pointers; they are read during the call only.
  *   - nranks is 1..8.  count == 0 is a successful no-op.
- *   - All calls share one per-device context (flag epoch, semaphore counters): issue
- *     them on one stream, or order them yourself.  That state lives in device memory and
- *     is advanced by the kernels, so calls may be captured into a HIP graph and replayed
- *     (create the context with msx_init or a first call before capturing).
+ *   - Every call runs on a CONTEXT: the flag epoch, the semaphores and their expected values,
+ *     the LL scratch.  Without further ado that is the device's default context, created by
+ *     msx_init or the first call; msx_ctx_create makes more (the communicator objects of the
+ *     paper's NCCL-shaped Collective API, Overview section) and msx_ctx_use selects the one
+ *     the calling thread's calls run on.  All calls on ONE context must be issued on one
+ *     stream or be ordered by the caller; calls on different contexts are independent and may
+ *     run concurrently on different streams (see the co-residency rule below).  The state
+ *     lives in device memory and is advanced by the kernels, so calls may be captured into a
+ *     HIP graph and replayed (create the context before capturing).
+ *   - Warm-up: the first call on a device creates the default context, and the first call of a
+ *     new shape may grow scratch (ring scratch, a lowered plan, the built-in routing plan of
+ *     the token dispatch): those calls allocate and wait for the device, so they must not
+ *     happen during stream capture.  msx_prepare_* does all of that ahead of time; msx_run
+ *     never allocates and never waits.
+ *   - CO-RESIDENCY (a hard precondition).  The ranks of a call wait for each other inside ONE
+ *     launch, so all its workgroups must be on the GPU at the same time.  Every launch is
+ *     sized to what the otherwise idle GPU can hold, or to the context's budget
+ *     (msx_ctx_set_max_blocks).  Work that occupies compute units next to a call (another
+ *     stream's kernels, a second context) may keep some of its workgroups from starting; the
+ *     call then times out instead of completing.  Callers that overlap contexts give each a
+ *     budget such that the budgets add up to no more than the GPU holds (256 workgroups of the
+ *     large-message kernels, one per compute unit).
  *   - A device-side wait that does not finish within the spin budget makes its workgroup
- *     record {rank, site, expected, seen} and carry on; nothing hangs.  msx_status()
- *     reports it.  After a timeout call msx_reset().
+ *     record {rank, site, expected, seen}; a workgroup whose wait guards data it was about
+ *     to consume (packets, a partial sum, a peer's rows) stops there, so no output element is
+ *     ever built from data that did not arrive.  After a timeout the outputs of that call are
+ *     incomplete (partly written).  Nothing hangs.  The timeout is latched in the context: every later
+ *     call on it returns MSX_ERR_TIMEOUT without launching anything, until the status has been
+ *     read (msx_status, msx_last_status) or the context reset (msx_reset, msx_ctx_reset; do
+ *     reset: semaphore counts are out of step after a timeout).
  */
 #ifndef MSX_H
 #define MSX_H
@@ -49,7 +72,8 @@ typedef enum {
     MSX_ERR_HIP = -3,          /* a HIP runtime call failed (msx_last_hip_error has the code) */
     MSX_ERR_TIMEOUT = -4,      /* a device-side wait ran out of its spin budget */
     MSX_ERR_NOMEM = -5,        /* scratch too small for the request / allocation failed */
-    MSX_ERR_CAPACITY = -6      /* token dispatch: a destination buffer overflowed */
+    MSX_ERR_CAPACITY = -6,     /* token dispatch: a destination buffer overflowed */
+    MSX_ERR_INDEX = -7         /* token dispatch: an expert id outside [0, n_experts) */
 } msx_error;
 
 /* AllReduce algorithms (Collectives Library section: one-phase and two-phase all-pairs). */
@@ -75,10 +99,10 @@ typedef enum {
  * These four take ONE rank-major contiguous device buffer and work IN PLACE.
  * ---------------------------------------------------------------------------------- */
 
-/* AllReduce: buf is [nranks][count]; afterwards every row holds the elementwise sum of
- * the rows.  count*elemsize must be a multiple of 16 when nranks > 1 (rows stay aligned);
- * msx_allreduce_ex takes any count.  Sum is taken in fp32 in rank order 0..nranks-1 and
- * rounded once. */
+/* AllReduce: buf is [nranks][count], any count; afterwards every row holds the elementwise sum
+ * of the rows.  Sum is taken in fp32 in rank order 0..nranks-1 and rounded once.  Rows whose
+ * size is not a multiple of 16 bytes do not start on 16-byte boundaries and go through an
+ * element-by-element kernel (correct, not fast). */
 int msx_allreduce(void* buf, size_t count, int dtype, int op, int nranks, void* stream);
 
 /* ReduceScatter: buf is [nranks][count], count % nranks == 0, c = count / nranks.
@@ -149,13 +173,27 @@ int msx_alltoall_ex(const void* const* send, void* const* recv, size_t count, in
  *   recv_src_token[d] device [recv_capacity_tokens] int32 = s*T + t of each row, or the
  *                    whole table may be NULL
  *   recv_counts      device [nranks dst][nranks src] int32 (rows received per source)
+ *   plan             a routing plan (msx_moe_plan_create) in which the call leaves where every
+ *                    token went, for the msx_moe_combine that follows; NULL = the context's
+ *                    built-in plan, which a later dispatch overwrites (and regrows, blocking,
+ *                    when T grows)
  * Rows that would exceed recv_capacity_tokens are dropped and msx_status() then reports
- * MSX_ERR_CAPACITY; recv_counts still holds the true counts.  T <= 65534, K <= 32.
+ * MSX_ERR_CAPACITY; recv_counts still holds the true counts.  An expert id outside
+ * [0, n_experts) sends its token nowhere on that id's account (the other ids of the token
+ * count as usual) and msx_status() reports MSX_ERR_INDEX with info[4] = the id.
+ * T <= 65534, K <= 32.
  * ---------------------------------------------------------------------------------- */
 int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, int T, int H,
                      int K, int n_experts, int dtype, int nranks, void* const* recv_tokens,
                      int32_t* const* recv_src_token, int32_t* recv_counts,
-                     size_t recv_capacity_tokens, void* stream);
+                     size_t recv_capacity_tokens, void* plan, void* stream);
+
+/* Routing plans: device memory for the slots of up to max_tokens_per_rank tokens of each of 8
+ * ranks (16 bytes per token), owned by `ctx` (NULL = the calling thread's current context) and
+ * freed with it or by msx_moe_plan_destroy.  A dispatch with more tokens than the plan was made
+ * for returns MSX_ERR_NOMEM.  Both calls allocate / free and wait for the device. */
+int msx_moe_plan_create(void* ctx, int max_tokens_per_rank, void** plan);
+int msx_moe_plan_destroy(void* plan);
 
 /* The same dispatch with FP8 quantisation fused into the packing (the paper's setting is "FP8
  * dispatch and BF16 combine"): tokens are bf16 [T][H], H % 128 == 0.  Each row is quantised in
@@ -167,18 +205,47 @@ int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, 
 int msx_moe_dispatch_fp8(const void* const* tokens, const int32_t* const* topk_idx, int T, int H,
                          int K, int n_experts, int nranks, void* const* recv_q,
                          float* const* recv_scales, int32_t* const* recv_src_token,
-                         int32_t* recv_counts, size_t recv_capacity_tokens, void* stream);
+                         int32_t* recv_counts, size_t recv_capacity_tokens, void* plan, void* stream);
 
 /* Combine, the way back of msx_moe_dispatch (the paper's expert-parallel experiment runs
- * "dispatch and combine").  Uses the routing of the LAST msx_moe_dispatch on this device, which
- * must have had the same T and nranks (else MSX_ERR_ARG).
+ * "dispatch and combine").  Uses the routing the last dispatch through `plan` left there (NULL: the
+ * context's built-in plan, i.e. the last dispatch without a plan), which must have had the same T
+ * and nranks (else MSX_ERR_ARG).
  *   expert_out[d]  device [capacity_tokens][H]: one processed row per row destination d received,
  *                  in the order the dispatch delivered them
  *   out_tokens[s]  device [T][H]: out[s][t] = round( sum over the destination ranks of token (s,t),
  *                  ascending, in fp32 starting from the first, of its row in expert_out[d] )
  * Rows the dispatch dropped for lack of capacity are left out of the sum. */
 int msx_moe_combine(const void* const* expert_out, void* const* out_tokens, int T, int H, int dtype,
-                    int nranks, size_t capacity_tokens, void* stream);
+                    int nranks, size_t capacity_tokens, void* plan, void* stream);
+
+/* ------------------------------------------------------------------------------------
+ * Prepared calls (Overview and Primitive API sections: channels are set up once, on the host, at
+ * initialisation; the kernels only run the data path).  msx_prepare_* does everything the matching
+ * call does on the host - argument checks, algorithm and launch shape, argument blocks, scratch
+ * (ring scratch and lowered plans belong to the handle) - and launches nothing; msx_run(handle,
+ * stream) enqueues the kernels and nothing else: no allocation, no lock, no wait.  The handle is
+ * bound to the context current at prepare time, to the pointers given (the tables are read during
+ * prepare only) and to the options and test hooks in force then; it dies with its context.
+ * msx_run returns MSX_ERR_TIMEOUT while a timeout is latched in that context.  Token dispatch and
+ * combine need an explicit plan here.  msx_release waits for the device if the handle owns scratch.
+ * ---------------------------------------------------------------------------------- */
+int msx_prepare_allreduce(const void* const* send, void* const* recv, const void* const* residual,
+                          size_t count, int dtype, int op, int nranks, int algo, void** handle);
+int msx_prepare_reducescatter(const void* const* send, void* const* recv, size_t count, int dtype,
+                              int op, int nranks, void** handle);
+int msx_prepare_allgather(const void* const* send, void* const* recv, size_t count, int dtype,
+                          int nranks, void** handle);
+int msx_prepare_alltoall(const void* const* send, void* const* recv, size_t count, int dtype,
+                         int nranks, void** handle);
+int msx_prepare_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, int T, int H,
+                             int K, int n_experts, int dtype, int nranks, void* const* recv_tokens,
+                             int32_t* const* recv_src_token, int32_t* recv_counts,
+                             size_t recv_capacity_tokens, void* plan, void** handle);
+int msx_prepare_moe_combine(const void* const* expert_out, void* const* out_tokens, int T, int H,
+                            int dtype, int nranks, size_t capacity_tokens, void* plan, void** handle);
+int msx_run(void* handle, void* stream);
+int msx_release(void* handle);
 
 /* ------------------------------------------------------------------------------------
  * MemoryChannel primitives on their own (Primitive API figure and MemoryChannel section:
@@ -222,15 +289,35 @@ int msx_prim_ll_roundtrip(const void* src, void* dst, size_t nbytes, int blocks_
  * Context, options, status
  * ---------------------------------------------------------------------------------- */
 
-/* Create the current device's context now (otherwise the first call does). */
+/* Create the current device's default context now (otherwise the first call does), and set up the
+ * fixed array msx_allreduce_ex_static works on. */
 int msx_init(void);
 
-/* Re-zero scratch, semaphores and the flag epoch of the current device's context.
- * Synchronises the device. */
+/* Re-zero scratch, semaphores and the flag epoch of the calling thread's current context (and, when
+ * that is the default one, of the fixed array too); clears a latched timeout.  Synchronises the device. */
 int msx_reset(void);
 
-/* Free the current device's context.  Synchronises the device. */
+/* Free the current device's default context.  Synchronises the device. */
 int msx_finalize(void);
+
+/* Context handles (the Collective API is NCCL-shaped: collectives run on communicator objects).
+ * msx_ctx_create: a new context on the current device; nranks (1..8) = the most ranks a call on it
+ * will have; max_ll_bytes = largest per-rank message of the LL algorithms (4 KiB .. 16 MiB; 0 = the
+ * "ll_max_bytes" option).  Allocates about 4 MiB + 64 x max_ll_bytes and waits for the device.
+ * msx_ctx_use: the calling thread's calls run on ctx from now on (NULL: back to the default context).
+ * msx_ctx_set_max_blocks: no launch of this context takes more workgroups than that (0 = what the idle
+ * GPU holds); see the co-residency rule at the top.
+ * msx_ctx_reset / msx_ctx_destroy: as msx_reset / msx_finalize, for one context (NULL = the current
+ * one, for reset).  Destroying a context invalidates its prepared calls and routing plans.
+ * msx_last_status: the device-side status of ctx (NULL = current), read and cleared WITHOUT waiting:
+ * call it after the stream in question has been synchronised.  Returns MSX_OK, MSX_ERR_TIMEOUT,
+ * MSX_ERR_CAPACITY or MSX_ERR_INDEX; the out pointers may be NULL. */
+int msx_ctx_create(int nranks, size_t max_ll_bytes, void** ctx);
+int msx_ctx_destroy(void* ctx);
+int msx_ctx_reset(void* ctx);
+int msx_ctx_use(void* ctx);
+int msx_ctx_set_max_blocks(void* ctx, int max_blocks);
+int msx_last_status(void* ctx, int* rank, int* site, unsigned* expected, unsigned* seen);
 
 /* Options (strings; numbers in decimal):
  *   "algo"            auto | 1pa_ll | 2pa_ll | 2pa_hb | 2pa_hb_2phase | 2pr_hb | plan_2pa_hb | plan_2pr_hb
@@ -267,9 +354,9 @@ int msx_finalize(void);
 int msx_set_option(const char* key, const char* value);
 int msx_get_option(const char* key, char* value_out, size_t value_len);
 
-/* Wait for `stream`, then report and clear the device-side status.  info (nullable) gets
- * {code, rank, site, expected, seen, block}.  Returns MSX_OK, MSX_ERR_TIMEOUT or
- * MSX_ERR_CAPACITY. */
+/* Wait for `stream`, then report and clear the device-side status of the calling thread's current
+ * context (a latched timeout included).  info (nullable) gets {code, rank, site, expected, seen,
+ * block}.  Returns MSX_OK, MSX_ERR_TIMEOUT, MSX_ERR_CAPACITY or MSX_ERR_INDEX. */
 int msx_status(void* stream, uint32_t info[6]);
 
 /* Name and launch shape of the kernel the last call on this thread launched

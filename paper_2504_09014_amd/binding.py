@@ -14,6 +14,10 @@ __all__ = [
     "check_status", "last_launch", "version", "strerror",
     "allreduce", "reducescatter", "allgather", "alltoall",
     "allreduce_ex", "allreduce_ex_static", "reducescatter_ex", "allgather_ex", "alltoall_ex", "moe_dispatch", "moe_dispatch_fp8", "moe_combine",
+    "ctx_create", "ctx_destroy", "ctx_reset", "ctx_use", "ctx_set_max_blocks", "last_status",
+    "moe_plan_create", "moe_plan_destroy",
+    "prepare_allreduce", "prepare_reducescatter", "prepare_allgather", "prepare_alltoall",
+    "prepare_moe_dispatch", "prepare_moe_combine", "run", "release", "Prepared",
     "prim_pingpong", "prim_barrier", "prim_put_signal_wait", "prim_ll_encode", "prim_ll_roundtrip", "prim_port_put_signal_wait",
     "EXPORTS",
 ]
@@ -26,7 +30,10 @@ ALGO_PLAN_2PA_HB, ALGO_PLAN_2PR_HB = 6, 7
 EXPORTS = [
     "msx_allreduce", "msx_reducescatter", "msx_allgather", "msx_alltoall",
     "msx_allreduce_ex", "msx_allreduce_ex_static", "msx_reducescatter_ex", "msx_allgather_ex", "msx_alltoall_ex",
-    "msx_moe_dispatch", "msx_moe_dispatch_fp8", "msx_moe_combine",
+    "msx_moe_dispatch", "msx_moe_dispatch_fp8", "msx_moe_combine", "msx_moe_plan_create", "msx_moe_plan_destroy",
+    "msx_prepare_allreduce", "msx_prepare_reducescatter", "msx_prepare_allgather", "msx_prepare_alltoall",
+    "msx_prepare_moe_dispatch", "msx_prepare_moe_combine", "msx_run", "msx_release",
+    "msx_ctx_create", "msx_ctx_destroy", "msx_ctx_reset", "msx_ctx_use", "msx_ctx_set_max_blocks", "msx_last_status",
     "msx_prim_pingpong", "msx_prim_barrier", "msx_prim_put_signal_wait", "msx_prim_ll_encode",
     "msx_prim_ll_roundtrip", "msx_prim_port_put_signal_wait",
     "msx_init", "msx_reset", "msx_finalize", "msx_set_option", "msx_get_option", "msx_status",
@@ -69,9 +76,25 @@ def lib():
         L.msx_reducescatter_ex.argtypes = [pp, pp, sz, i, i, i, vp]
         L.msx_allgather_ex.argtypes = [pp, pp, sz, i, i, vp]
         L.msx_alltoall_ex.argtypes = [pp, pp, sz, i, i, vp]
-        L.msx_moe_dispatch.argtypes = [pp, pp, i, i, i, i, i, i, pp, pp, vp, sz, vp]
-        L.msx_moe_dispatch_fp8.argtypes = [pp, pp, i, i, i, i, i, pp, pp, pp, vp, sz, vp]
-        L.msx_moe_combine.argtypes = [pp, pp, i, i, i, i, sz, vp]
+        L.msx_moe_dispatch.argtypes = [pp, pp, i, i, i, i, i, i, pp, pp, vp, sz, vp, vp]
+        L.msx_moe_dispatch_fp8.argtypes = [pp, pp, i, i, i, i, i, pp, pp, pp, vp, sz, vp, vp]
+        L.msx_moe_combine.argtypes = [pp, pp, i, i, i, i, sz, vp, vp]
+        L.msx_moe_plan_create.argtypes = [vp, i, pp]
+        L.msx_moe_plan_destroy.argtypes = [vp]
+        L.msx_prepare_allreduce.argtypes = [pp, pp, pp, sz, i, i, i, i, pp]
+        L.msx_prepare_reducescatter.argtypes = [pp, pp, sz, i, i, i, pp]
+        L.msx_prepare_allgather.argtypes = [pp, pp, sz, i, i, pp]
+        L.msx_prepare_alltoall.argtypes = [pp, pp, sz, i, i, pp]
+        L.msx_prepare_moe_dispatch.argtypes = [pp, pp, i, i, i, i, i, i, pp, pp, vp, sz, vp, pp]
+        L.msx_prepare_moe_combine.argtypes = [pp, pp, i, i, i, i, sz, vp, pp]
+        L.msx_run.argtypes = [vp, vp]
+        L.msx_release.argtypes = [vp]
+        L.msx_ctx_create.argtypes = [i, sz, pp]
+        L.msx_ctx_destroy.argtypes = [vp]
+        L.msx_ctx_reset.argtypes = [vp]
+        L.msx_ctx_use.argtypes = [vp]
+        L.msx_ctx_set_max_blocks.argtypes = [vp, i]
+        L.msx_last_status.argtypes = [vp, C.POINTER(i), C.POINTER(i), C.POINTER(u32), C.POINTER(u32)]
         L.msx_prim_pingpong.argtypes = [i, i, i, i, vp, vp]
         L.msx_prim_barrier.argtypes = [i, i, i, vp, vp]
         L.msx_prim_put_signal_wait.argtypes = [vp, vp, vp, sz, i, vp]
@@ -260,7 +283,7 @@ def alltoall_ex(send, recv, stream=None):
                               _stream(stream)), "msx_alltoall_ex")
 
 
-def moe_dispatch(tokens, topk_idx, n_experts, recv_tokens, recv_counts, recv_src_token=None, stream=None):
+def moe_dispatch(tokens, topk_idx, n_experts, recv_tokens, recv_counts, recv_src_token=None, stream=None, plan=None):
     """tokens[s]: [T, H]; topk_idx[s]: [T, K] int32; recv_tokens[d]: [cap, H];
     recv_counts: [nranks, nranks] int32; recv_src_token[d]: [cap] int32 (optional)."""
     n = len(tokens)
@@ -273,11 +296,11 @@ def moe_dispatch(tokens, topk_idx, n_experts, recv_tokens, recv_counts, recv_src
         raise TypeError("topk_idx and recv_counts must be int32")
     _ck(lib().msx_moe_dispatch(_table(tokens), _table(topk_idx), T, H, K, n_experts, _dtype(tokens[0]), n,
                                _table(recv_tokens), _table(recv_src_token), C.c_void_p(recv_counts.data_ptr()),
-                               cap, _stream(stream)), "msx_moe_dispatch")
+                               cap, plan, _stream(stream)), "msx_moe_dispatch")
 
 
 def moe_dispatch_fp8(tokens, topk_idx, n_experts, recv_q, recv_scales, recv_counts, recv_src_token=None,
-                     stream=None):
+                     stream=None, plan=None):
     """tokens[s]: [T, H] bf16; recv_q[d]: [cap, H] uint8; recv_scales[d]: [cap, H/128] float32."""
     n = len(tokens)
     T, H = tokens[0].shape
@@ -290,20 +313,156 @@ def moe_dispatch_fp8(tokens, topk_idx, n_experts, recv_q, recv_scales, recv_coun
         raise TypeError("tokens bf16, recv_q uint8, recv_scales float32")
     _ck(lib().msx_moe_dispatch_fp8(_table(tokens), _table(topk_idx), T, H, K, n_experts, n, _table(recv_q),
                                    _table(recv_scales), _table(recv_src_token),
-                                   C.c_void_p(recv_counts.data_ptr()), cap, _stream(stream)),
+                                   C.c_void_p(recv_counts.data_ptr()), cap, plan, _stream(stream)),
         "msx_moe_dispatch_fp8")
 
 
-def moe_combine(expert_out, out_tokens, stream=None):
+def moe_combine(expert_out, out_tokens, stream=None, plan=None):
     """expert_out[d]: [cap, H] processed rows in dispatch order; out_tokens[s]: [T, H].
-    Uses the routing of the last moe_dispatch."""
+    Uses the routing the last moe_dispatch through `plan` left there (None: the built-in plan)."""
     n = len(expert_out)
     cap, H = expert_out[0].shape
     T = out_tokens[0].shape[0]
     for t in list(expert_out) + list(out_tokens):
         _dev(t, "tensor")
     _ck(lib().msx_moe_combine(_table(expert_out), _table(out_tokens), T, H, _dtype(expert_out[0]), n, cap,
-                              _stream(stream)), "msx_moe_combine")
+                              plan, _stream(stream)), "msx_moe_combine")
+
+
+# ---- contexts, routing plans, prepared calls --------------------------------------------------------
+
+def ctx_create(nranks=8, max_ll_bytes=0):
+    h = C.c_void_p()
+    _ck(lib().msx_ctx_create(nranks, max_ll_bytes, C.byref(h)), "msx_ctx_create")
+    return h
+
+
+def ctx_destroy(ctx):
+    _ck(lib().msx_ctx_destroy(ctx), "msx_ctx_destroy")
+
+
+def ctx_reset(ctx=None):
+    _ck(lib().msx_ctx_reset(ctx), "msx_ctx_reset")
+
+
+def ctx_use(ctx=None):
+    _ck(lib().msx_ctx_use(ctx), "msx_ctx_use")
+
+
+def ctx_set_max_blocks(ctx, max_blocks):
+    _ck(lib().msx_ctx_set_max_blocks(ctx, max_blocks), "msx_ctx_set_max_blocks")
+
+
+def last_status(ctx=None):
+    """(code, rank, site, expected, seen) of ctx, read and cleared without waiting for the device."""
+    r, s_, e, v = C.c_int(0), C.c_int(0), C.c_uint32(0), C.c_uint32(0)
+    rc = lib().msx_last_status(ctx, C.byref(r), C.byref(s_), C.byref(e), C.byref(v))
+    return rc, r.value, s_.value, e.value, v.value
+
+
+def moe_plan_create(max_tokens_per_rank, ctx=None):
+    h = C.c_void_p()
+    _ck(lib().msx_moe_plan_create(ctx, max_tokens_per_rank, C.byref(h)), "msx_moe_plan_create")
+    return h
+
+
+def moe_plan_destroy(plan):
+    _ck(lib().msx_moe_plan_destroy(plan), "msx_moe_plan_destroy")
+
+
+class Prepared:
+    """A prepared call: `run()` only enqueues its kernels.  Keeps the tensors alive."""
+
+    def __init__(self, handle, keep):
+        self.handle = handle
+        self._keep = keep
+        self._run = lib().msx_run
+
+    def run(self, stream=None):
+        rc = self._run(self.handle, _stream(stream) if stream is None or hasattr(stream, "cuda_stream") else stream)
+        if rc != 0:
+            raise MsxError(rc, "msx_run")
+
+    def release(self):
+        if self.handle is not None:
+            _ck(lib().msx_release(self.handle), "msx_release")
+            self.handle = None
+
+
+def run(prepared, stream=None):
+    prepared.run(stream)
+
+
+def release(prepared):
+    prepared.release()
+
+
+def prepare_allreduce(send, recv, residual=None, algo=ALGO_AUTO, count=None, op=SUM):
+    n = len(send)
+    for t in list(send) + list(recv) + list(residual or []):
+        _dev(t, "tensor")
+    cnt = send[0].numel() if count is None else count
+    h = C.c_void_p()
+    _ck(lib().msx_prepare_allreduce(_table(send), _table(recv), _table(residual), cnt, _dtype(send[0]), op, n,
+                                    algo, C.byref(h)), "msx_prepare_allreduce")
+    return Prepared(h, (list(send), list(recv), list(residual or [])))
+
+
+def prepare_reducescatter(send, recv, op=SUM):
+    n = len(send)
+    for t in list(send) + list(recv):
+        _dev(t, "tensor")
+    h = C.c_void_p()
+    _ck(lib().msx_prepare_reducescatter(_table(send), _table(recv), send[0].numel(), _dtype(send[0]), op, n,
+                                        C.byref(h)), "msx_prepare_reducescatter")
+    return Prepared(h, (list(send), list(recv)))
+
+
+def prepare_allgather(send, recv):
+    n = len(send)
+    for t in list(send) + list(recv):
+        _dev(t, "tensor")
+    h = C.c_void_p()
+    _ck(lib().msx_prepare_allgather(_table(send), _table(recv), send[0].numel(), _dtype(send[0]), n, C.byref(h)),
+        "msx_prepare_allgather")
+    return Prepared(h, (list(send), list(recv)))
+
+
+def prepare_alltoall(send, recv):
+    n = len(send)
+    for t in list(send) + list(recv):
+        _dev(t, "tensor")
+    h = C.c_void_p()
+    _ck(lib().msx_prepare_alltoall(_table(send), _table(recv), send[0].numel(), _dtype(send[0]), n, C.byref(h)),
+        "msx_prepare_alltoall")
+    return Prepared(h, (list(send), list(recv)))
+
+
+def prepare_moe_dispatch(tokens, topk_idx, n_experts, recv_tokens, recv_counts, plan, recv_src_token=None):
+    n = len(tokens)
+    T, H = tokens[0].shape
+    K = topk_idx[0].shape[1]
+    cap = recv_tokens[0].shape[0]
+    for t in list(tokens) + list(topk_idx) + list(recv_tokens) + list(recv_src_token or []) + [recv_counts]:
+        _dev(t, "tensor")
+    h = C.c_void_p()
+    _ck(lib().msx_prepare_moe_dispatch(_table(tokens), _table(topk_idx), T, H, K, n_experts, _dtype(tokens[0]), n,
+                                       _table(recv_tokens), _table(recv_src_token),
+                                       C.c_void_p(recv_counts.data_ptr()), cap, plan, C.byref(h)),
+        "msx_prepare_moe_dispatch")
+    return Prepared(h, (list(tokens), list(topk_idx), list(recv_tokens), list(recv_src_token or []), recv_counts))
+
+
+def prepare_moe_combine(expert_out, out_tokens, plan):
+    n = len(expert_out)
+    cap, H = expert_out[0].shape
+    T = out_tokens[0].shape[0]
+    for t in list(expert_out) + list(out_tokens):
+        _dev(t, "tensor")
+    h = C.c_void_p()
+    _ck(lib().msx_prepare_moe_combine(_table(expert_out), _table(out_tokens), T, H, _dtype(expert_out[0]), n, cap,
+                                      plan, C.byref(h)), "msx_prepare_moe_combine")
+    return Prepared(h, (list(expert_out), list(out_tokens)))
 
 
 # ---- primitives ------------------------------------------------------------------------------------

@@ -27,12 +27,15 @@ constexpr int kSemStrideWords = 32;  // one semaphore per 128-byte line
 constexpr unsigned kStatusOk = 0;
 constexpr unsigned kStatusTimeout = 1;
 constexpr unsigned kStatusCapacity = 2;
+constexpr unsigned kStatusBadIndex = 3;
 
 // Everything a kernel needs from the per-device context; passed by value.
 struct DevCtx {
     unsigned* sem;        // [kMaxRanks recv][kMaxRanks send][kMaxChannels] x kSemStrideWords
     unsigned* expected;   // [kMaxRanks recv][kMaxRanks send][kMaxChannels] value the next wait needs
     unsigned* status;     // 8 words: code, rank, site, expected, seen, block
+    unsigned* latch;      // host memory the device can write (or null): set to the code of a timeout, so that the
+                          // host sees it at its next call without waiting for the device
     unsigned* call_state; // {last LL flag handed out, LL calls so far, workgroups finished this call}
     unsigned* gbar;       // chip-wide barrier: 8 counters, one per 128-byte line, then the 8 values they held when the last call ended
     void* ll;             // LL scratch, ll_bytes long: [rank][rotation][...]
@@ -59,6 +62,8 @@ __device__ __forceinline__ void report(const DevCtx& c, unsigned code, unsigned 
         c.status[4] = seen;
         c.status[5] = blockIdx.x;
         c.status[6] = extra;
+        if (code == kStatusTimeout && c.latch)
+            __hip_atomic_store(c.latch, code, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
@@ -131,15 +136,21 @@ __device__ __forceinline__ void channel_signal(const DevCtx& c, int me, int peer
     }
 }
 
-__device__ __forceinline__ void channel_wait(const DevCtx& c, int me, int peer, int chan, unsigned site)
+// Returns false (in every thread) when the wait ran out of its spin budget: what the peer was to deliver is
+// not there, and the caller must not go on to consume it (nor wait again in this launch: the result word in
+// LDS is rewritten by the next wait without a barrier in between).
+__device__ __forceinline__ bool channel_wait(const DevCtx& c, int me, int peer, int chan, unsigned site,
+                                             bool acquire = true)
 {
+    __shared__ unsigned wait_failed;
     if (threadIdx.x == 0) {
         unsigned idx = sem_index(me, peer, chan);
         unsigned want = c.expected[idx] + 1u;
         c.expected[idx] = want;
-        sem_spin(c, c.sem + (size_t)idx * kSemStrideWords, want, (unsigned)me, site);
+        wait_failed = sem_spin(c, c.sem + (size_t)idx * kSemStrideWords, want, (unsigned)me, site, acquire) ? 0u : 1u;
     }
     __syncthreads();   // the first thread waited for everybody
+    return wait_failed == 0u;
 }
 
 // Barrier among all ranks on one channel: signal every peer, then wait for every peer.
@@ -148,9 +159,14 @@ __device__ __forceinline__ void channel_wait(const DevCtx& c, int me, int peer, 
 //   acquire: this workgroup is about to read data the peers wrote
 // A device-scope release writes the whole L2 of this XCD back and an acquire invalidates it,
 // and those operations queue up per XCD, so each barrier asks only for what it needs.
-__device__ __forceinline__ void rank_barrier(const DevCtx& c, int me, int n, int chan, unsigned site,
+// CHECKED: the result tells every thread whether all peers arrived in time (through a word in LDS: one store
+// and one load more); the unchecked form is for barriers with nothing behind them that depends on the peers.
+template <bool CHECKED = false>
+__device__ __forceinline__ bool rank_barrier(const DevCtx& c, int me, int n, int chan, unsigned site,
                                              bool release = true, bool acquire = true)
 {
+    __shared__ unsigned barrier_failed;
+    if (CHECKED && threadIdx.x == 0) barrier_failed = 0u;   // only ever re-armed by a thread that saw it clear
     __syncthreads();
     const int t = (int)threadIdx.x;
     if (t < n - 1) {
@@ -161,9 +177,11 @@ __device__ __forceinline__ void rank_barrier(const DevCtx& c, int me, int n, int
         unsigned idx = sem_index(me, peer, chan);
         unsigned want = c.expected[idx] + 1u;
         c.expected[idx] = want;
-        sem_spin(c, c.sem + (size_t)idx * kSemStrideWords, want, (unsigned)me, site, acquire);
+        const bool ok = sem_spin(c, c.sem + (size_t)idx * kSemStrideWords, want, (unsigned)me, site, acquire);
+        if (CHECKED && !ok) barrier_failed = 1u;
     }
     __syncthreads();
+    return CHECKED ? barrier_failed == 0u : true;
 }
 
 // ---- barrier over every workgroup of a co-resident launch -----------------------------------------

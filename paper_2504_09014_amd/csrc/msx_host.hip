@@ -9,6 +9,8 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <functional>
+#include <memory>
 #include <map>
 #include <mutex>
 #include <string>
@@ -73,15 +75,25 @@ struct Port {
     int device = 0;
 };
 
+// Where a token dispatch leaves the slots of its tokens for the combine that follows.
+struct Ctx;
+struct MoePlan {
+    Ctx* owner = nullptr;
+    void* slots = nullptr;         // u16 [kMaxRanks][T][8]
+    size_t slots_bytes = 0;
+    unsigned* base = nullptr;      // u32 [kMaxRanks][8]
+    int T = -1, n = 0;             // shape of the routing the last dispatch through this plan left behind
+    bool fixed_size = false;       // created by msx_moe_plan_create: never regrown inside a dispatch
+};
+
 struct Ctx {
     int device = -1;
     DevCtx d{};
     int cus = 0;
     double ns_per_tick = 10.0;
-    void* moe_slots = nullptr;
-    size_t moe_slots_bytes = 0;
-    unsigned* moe_base = nullptr;
-    int plan_T = -1, plan_n = 0;   // shape of the routing plan the last dispatch left behind
+    MoePlan moe;                   // the built-in routing plan (grown on demand)
+    unsigned* latch = nullptr;     // pinned host word the kernels set on a timeout (d.latch is its device address)
+    int max_blocks = 0;            // workgroups one launch of this context may take (0: all the GPU can hold)
     void* ring = nullptr;          // ring AllReduce: per-rank receive scratch, grown on demand
     size_t ring_bytes = 0;
     struct Plan { int algo, n, chans; size_t nbytes; PlanOp* ops; unsigned* start; };
@@ -195,34 +207,46 @@ int get_port(Ctx* c, Port** out)
     return MSX_OK;
 }
 
+std::vector<Ctx*> g_made;         // contexts made by msx_ctx_create, any device
+std::vector<MoePlan*> g_plans;    // routing plans made by msx_moe_plan_create
+
 int destroy_ctx(Ctx* c)
 {
     if (!c) return MSX_OK;
     (void)hipDeviceSynchronize();
     destroy_port(c->port);
+    for (size_t i = 0; i < g_plans.size();) {        // plans die with their context
+        if (g_plans[i]->owner != c) { ++i; continue; }
+        if (g_plans[i]->slots) (void)hipFree(g_plans[i]->slots);
+        if (g_plans[i]->base) (void)hipFree(g_plans[i]->base);
+        delete g_plans[i];
+        g_plans.erase(g_plans.begin() + (long)i);
+    }
+    if (c->latch) (void)hipHostFree(c->latch);
     if (c->d.sem) (void)hipFree(c->d.sem);
     if (c->d.expected) (void)hipFree(c->d.expected);
     if (c->d.status) (void)hipFree(c->d.status);
     if (c->d.call_state) (void)hipFree(c->d.call_state);
     if (c->d.gbar) (void)hipFree(c->d.gbar);
     if (c->d.ll) (void)hipFree(c->d.ll);
-    if (c->moe_slots) (void)hipFree(c->moe_slots);
+    if (c->moe.slots) (void)hipFree(c->moe.slots);
     if (c->ring) (void)hipFree(c->ring);
     for (auto& p : c->plans) { (void)hipFree(p.ops); (void)hipFree(p.start); }
-    if (c->moe_base) (void)hipFree(c->moe_base);
+    if (c->moe.base) (void)hipFree(c->moe.base);
     if (c->snap) (void)hipFree(c->snap);
     delete c;
     return MSX_OK;
 }
 
-// Context of the current device, created on first use.  Caller holds g_mu.
-int get_ctx(Ctx** out)
+// A new context on the current device (blocks: allocates and clears its device memory).  ll_max = largest
+// per-rank message its LL scratch is sized for.  Caller holds g_mu.
+int make_ctx(size_t ll_max, Ctx** out)
 {
     int dev = 0;
     HIPCHK(hipGetDevice(&dev));
     if (dev < 0 || dev >= 64) return MSX_ERR_ARG;
-    if (g_ctx[dev]) { *out = g_ctx[dev]; return MSX_OK; }
     Ctx* c = new Ctx();
+    c->moe.owner = c;
     c->device = dev;
     hipDeviceProp_t prop;
     hipError_t e = hipGetDeviceProperties(&prop, dev);
@@ -236,7 +260,6 @@ int get_ctx(Ctx** out)
     const size_t exp_bytes = (size_t)kMaxRanks * kMaxRanks * kMaxChannels * 4;
     // one rotation half holds either 1PA's n slots of P packets (P <= ll_max/4/8) or 2PA's
     // 2 phases x n slots of ceil(P/n) packets (P <= ll_max/8): both at most 4*ll_max (+ slack)
-    size_t ll_max = g_opt.ll_max_bytes;
     if (ll_max < 4096) ll_max = 4096;
     if (ll_max > (16u << 20)) ll_max = 16u << 20;
     const size_t rot = 4 * ll_max + 4096;
@@ -250,20 +273,75 @@ int get_ctx(Ctx** out)
               hipMalloc((void**)&c->d.call_state, 64) == hipSuccess &&
               hipMalloc((void**)&c->d.gbar, kGridBarBytes) == hipSuccess &&
               hipMalloc((void**)&c->d.ll, ll_bytes) == hipSuccess &&
-              hipMalloc((void**)&c->moe_base, 64 * 4) == hipSuccess &&
-              hipMalloc((void**)&c->snap, 4096) == hipSuccess;
+              hipMalloc((void**)&c->moe.base, 64 * 4) == hipSuccess &&
+              hipMalloc((void**)&c->snap, 4096) == hipSuccess &&
+              hipHostMalloc((void**)&c->latch, 64, hipHostMallocMapped) == hipSuccess;
+    if (ok) {
+        *c->latch = 0u;
+        ok = hipHostGetDevicePointer((void**)&c->d.latch, c->latch, 0) == hipSuccess;
+    }
     ok = ok && hipMemset(c->d.sem, 0, sem_bytes) == hipSuccess &&
          hipMemset(c->d.expected, 0, exp_bytes) == hipSuccess &&
          hipMemset(c->d.status, 0, 64) == hipSuccess &&
          hipMemset(c->d.call_state, 0, 64) == hipSuccess &&
          hipMemset(c->d.gbar, 0, kGridBarBytes) == hipSuccess &&
          hipMemset(c->d.ll, 0, ll_bytes) == hipSuccess &&
-         hipMemset(c->moe_base, 0, 64 * 4) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+         hipMemset(c->moe.base, 0, 64 * 4) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
     if (!ok) { destroy_ctx(c); t_hip_err = (int)hipErrorOutOfMemory; return MSX_ERR_NOMEM; }
     c->d.ll_bytes = (unsigned)ll_bytes;
     c->d.ll_rank_stride = (unsigned)rank_stride;
     c->d.ll_rot_stride = (unsigned)rot;
-    g_ctx[dev] = c;
+    *out = c;
+    return MSX_OK;
+}
+
+thread_local Ctx* t_use = nullptr;      // msx_ctx_use: the context this thread's calls run on (null: the default one)
+
+bool known_ctx(const Ctx* c)
+{
+    for (const Ctx* k : g_made)
+        if (k == c) return true;
+    return false;
+}
+
+// The default context of the current device, created on first use.  Caller holds g_mu.
+int default_ctx(Ctx** out)
+{
+    int dev = 0;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= 64) return MSX_ERR_ARG;
+    if (!g_ctx[dev]) {
+        int rc = make_ctx(g_opt.ll_max_bytes, &g_ctx[dev]);
+        if (rc) return rc;
+    }
+    *out = g_ctx[dev];
+    return MSX_OK;
+}
+
+// A timeout a kernel of this context has run into and nobody has read yet (msx_status / msx_last_status read
+// and clear it, a reset clears it): until then the context launches nothing more.
+int latched(const Ctx* c)
+{
+    return c->latch && __atomic_load_n(c->latch, __ATOMIC_RELAXED) != 0u ? MSX_ERR_TIMEOUT : MSX_OK;
+}
+
+// The context this thread's next call runs on: the one chosen with msx_ctx_use, else the device's default.
+// launching = the caller is about to enqueue kernels (refused while a timeout is latched).  Caller holds g_mu.
+int get_ctx(Ctx** out, bool launching = true)
+{
+    Ctx* c = t_use;
+    if (c) {
+        int dev = -1;
+        HIPCHK(hipGetDevice(&dev));
+        if (!known_ctx(c) || c->device != dev) return MSX_ERR_ARG;
+    } else {
+        int rc = default_ctx(&c);
+        if (rc) return rc;
+    }
+    if (launching) {
+        int rc = latched(c);
+        if (rc) return rc;
+    }
     *out = c;
     return MSX_OK;
 }
@@ -359,6 +437,7 @@ int resident_blocks(Ctx* c, const void* k, int threads, int* out)
         per_cu = it->second;
     }
     *out = per_cu * c->cus;
+    if (c->max_blocks > 0 && *out > c->max_blocks) *out = c->max_blocks;
     return MSX_OK;
 }
 
@@ -402,10 +481,31 @@ int check_table(const void* const* t, int n)
 
 void note_launch(int grid, int block, int algo) { t_grid = grid; t_block = block; t_algo = algo; }
 
+// A prepared call: everything a collective does on the host (checks, algorithm and launch shape, argument
+// blocks, scratch) done once; running it only enqueues the kernels.  Scratch a prepared call needs beyond the
+// context's fixed parts (ring scratch, a lowered plan) belongs to it and is freed with it.
+constexpr unsigned kPreparedMagic = 0x6d737850u;
+struct Prepared {
+    unsigned magic = kPreparedMagic;
+    Ctx* ctx = nullptr;
+    std::vector<std::function<hipError_t(hipStream_t)>> steps;
+    std::vector<void*> owned;      // device allocations of this call
+    int grid = 0, block = 0, algo = 0;
+};
+std::vector<Prepared*> g_prepared;
+thread_local Prepared* t_record = nullptr;   // set while a msx_prepare_* call runs the ordinary host path
+
 template <typename K, typename... A>
 int launch(K k, int grid, int block, hipStream_t s, A... args)
 {
     if (grid <= 0 || block <= 0) return MSX_ERR_ARG;
+    if (t_record) {
+        t_record->steps.push_back([=](hipStream_t st) {
+            hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3((unsigned)block), 0, st, args...);
+            return hipGetLastError();
+        });
+        return MSX_OK;
+    }
     hipLaunchKernelGGL(k, dim3((unsigned)grid), dim3((unsigned)block), 0, s, args...);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e);
@@ -601,6 +701,29 @@ void lower_allreduce(int algo, int n, int chans, size_t nvec, int threads, std::
     start->push_back((unsigned)ops->size());
 }
 
+// Ring scratch of `need` bytes: the context's own (grown on demand, which waits for the device), or, for a
+// prepared call, an allocation that call owns.
+int ring_scratch(Ctx* c, size_t need, void** out)
+{
+    if (t_record) {
+        void* p = nullptr;
+        if (hipMalloc(&p, need) != hipSuccess) return MSX_ERR_NOMEM;
+        t_record->owned.push_back(p);
+        *out = p;
+        return MSX_OK;
+    }
+    if (need > c->ring_bytes) {
+        HIPCHK(hipDeviceSynchronize());
+        if (c->ring) { HIPCHK(hipFree(c->ring)); c->ring = nullptr; c->ring_bytes = 0; }
+        if (hipMalloc(&c->ring, need) != hipSuccess) return MSX_ERR_NOMEM;
+        c->ring_bytes = need;
+    }
+    *out = c->ring;
+    return MSX_OK;
+}
+
+constexpr size_t kPlanCacheMax = 16;     // lowered plans a context keeps; the oldest goes first
+
 int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nbytes, int dtype, int n, int algo,
                    hipStream_t stream)
 {
@@ -614,38 +737,41 @@ int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nb
     const size_t per_rank = nvec / (size_t)n;
     if (!ring) choose_hb_shape(nbytes, n, threads, &unroll_unused, &want);   // same shape as the hand kernel
     if ((rc = pick_channels(c, kp, threads, n, per_rank, 4, want, ring ? 64 : kMaxChannels, &chans))) return rc;
-    if (ring) {
-        const size_t need = nbytes * (size_t)n;
-        if (need > c->ring_bytes) {
-            HIPCHK(hipDeviceSynchronize());
-            if (c->ring) { HIPCHK(hipFree(c->ring)); c->ring = nullptr; c->ring_bytes = 0; }
-            if (hipMalloc(&c->ring, need) != hipSuccess) return MSX_ERR_NOMEM;
-            c->ring_bytes = need;
-        }
-    }
-    const Ctx::Plan* plan = nullptr;
-    for (const auto& p : c->plans)
-        if (p.algo == algo && p.n == n && p.chans == chans && p.nbytes == nbytes) plan = &p;
-    if (!plan) {
+    void* ring_mem = nullptr;
+    if (ring && (rc = ring_scratch(c, nbytes * (size_t)n, &ring_mem))) return rc;
+    Ctx::Plan found{algo, n, chans, nbytes, nullptr, nullptr};
+    if (!t_record)
+        for (const auto& p : c->plans)
+            if (p.algo == algo && p.n == n && p.chans == chans && p.nbytes == nbytes) found = p;
+    if (!found.ops) {
         std::vector<PlanOp> ops;
         std::vector<unsigned> start;
         lower_allreduce(algo, n, chans, nvec, threads, &ops, &start);
-        Ctx::Plan p{algo, n, chans, nbytes, nullptr, nullptr};
-        if (hipMalloc((void**)&p.ops, ops.size() * sizeof(PlanOp)) != hipSuccess) return MSX_ERR_NOMEM;
-        if (hipMalloc((void**)&p.start, start.size() * sizeof(unsigned)) != hipSuccess) { (void)hipFree(p.ops); return MSX_ERR_NOMEM; }
-        HIPCHK(hipMemcpy(p.ops, ops.data(), ops.size() * sizeof(PlanOp), hipMemcpyHostToDevice));
-        HIPCHK(hipMemcpy(p.start, start.data(), start.size() * sizeof(unsigned), hipMemcpyHostToDevice));
-        c->plans.push_back(p);
-        plan = &c->plans.back();
+        if (hipMalloc((void**)&found.ops, ops.size() * sizeof(PlanOp)) != hipSuccess) return MSX_ERR_NOMEM;
+        if (hipMalloc((void**)&found.start, start.size() * sizeof(unsigned)) != hipSuccess) { (void)hipFree(found.ops); return MSX_ERR_NOMEM; }
+        if (t_record) {                                  // a prepared call keeps its plan for itself
+            t_record->owned.push_back(found.ops);
+            t_record->owned.push_back(found.start);
+        } else {
+            if (c->plans.size() >= kPlanCacheMax) {      // a launch in flight may still be reading the oldest one
+                HIPCHK(hipDeviceSynchronize());
+                (void)hipFree(c->plans.front().ops);
+                (void)hipFree(c->plans.front().start);
+                c->plans.erase(c->plans.begin());
+            }
+            c->plans.push_back(found);
+        }
+        HIPCHK(hipMemcpy(found.ops, ops.data(), ops.size() * sizeof(PlanOp), hipMemcpyHostToDevice));
+        HIPCHK(hipMemcpy(found.start, start.data(), start.size() * sizeof(unsigned), hipMemcpyHostToDevice));
     }
     PlanArgs a{};
     for (int i = 0; i < n; ++i) {
         a.in[i] = send[i];
         a.out[i] = recv[i];
-        a.scratch[i] = ring ? (void*)((char*)c->ring + (size_t)i * nbytes) : nullptr;
+        a.scratch[i] = ring ? (void*)((char*)ring_mem + (size_t)i * nbytes) : nullptr;
     }
-    a.ops = plan->ops;
-    a.start = plan->start;
+    a.ops = found.ops;
+    a.start = found.start;
     a.n = n;
     note_launch(n * chans, threads, algo);
     typedef void (*K)(PlanArgs, DevCtx);
@@ -668,7 +794,8 @@ int reduce_generic(Ctx* c, const void* const* in, void* const* out, size_t count
 {
     GenericKernel k = generic_kernel(dtype, op);
     const size_t vecs = count * elem_size(dtype) / 16;
-    const size_t per_rank = mode == 0 ? (vecs + (size_t)n - 1) / (size_t)n : (vec ? vecs : count);
+    const size_t per_rank = mode == 0 ? (vecs + (size_t)n - 1) / (size_t)n
+                            : mode == 2 ? (count + (size_t)n - 1) / (size_t)n : (vec ? vecs : count);
     int chans = 1, rc;
     if ((rc = pick_channels(c, (const void*)k, 256, n, per_rank, 1, g_opt.hb_blocks, 128, &chans))) return rc;
     HbArgs a{};
@@ -757,19 +884,14 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
         // two-phase ring: n equal chunks of whole 16-byte vectors, no residual
         if (residual) return MSX_ERR_UNSUPPORTED;
         if (nbytes % (16 * (size_t)n)) return MSX_ERR_UNSUPPORTED;
-        const size_t need = nbytes * (size_t)n;
-        if (need > c->ring_bytes) {
-            HIPCHK(hipDeviceSynchronize());
-            if (c->ring) { HIPCHK(hipFree(c->ring)); c->ring = nullptr; c->ring_bytes = 0; }
-            if (hipMalloc(&c->ring, need) != hipSuccess) return MSX_ERR_NOMEM;
-            c->ring_bytes = need;
-        }
+        void* ring_mem = nullptr;
+        if ((rc = ring_scratch(c, nbytes * (size_t)n, &ring_mem))) return rc;
         const void* kp = dtype == MSX_F32 ? (const void*)k_allreduce_ring<0> : (const void*)k_allreduce_ring<1>;
         RingArgs a{};
         for (int i = 0; i < n; ++i) {
             a.in[i] = send[i];
             a.out[i] = recv[i];
-            a.scratch[i] = (char*)c->ring + (size_t)i * nbytes;
+            a.scratch[i] = (char*)ring_mem + (size_t)i * nbytes;
         }
         a.chunk_vecs = nbytes / 16 / (size_t)n;
         a.n = n;
@@ -956,11 +1078,29 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     return MSX_ERR_ARG;
 }
 
+// The routing plan a dispatch / combine works on: the handle's, or the context's built-in one.  A prepared
+// call needs a plan of fixed size (the built-in one may be regrown, and moved, by a later dispatch).
+int moe_plan_of(Ctx* c, void* handle, MoePlan** out)
+{
+    if (!handle) {
+        if (t_record) return MSX_ERR_ARG;
+        *out = &c->moe;
+        return MSX_OK;
+    }
+    for (MoePlan* p : g_plans)
+        if (p == handle) {
+            if (p->owner != c) return MSX_ERR_ARG;
+            *out = p;
+            return MSX_OK;
+        }
+    return MSX_ERR_ARG;
+}
+
 // Token dispatch; recv_scales != nullptr selects the fused FP8 quantisation (tokens are bf16 then).
 int moe_dispatch_impl(const void* const* tokens, const int32_t* const* topk_idx, int T, int H, int K, int n_experts,
                       int dtype, int nranks, void* const* recv_tokens, float* const* recv_scales,
                       int32_t* const* recv_src_token, int32_t* recv_counts, size_t recv_capacity_tokens,
-                      hipStream_t s)
+                      void* plan_handle, hipStream_t s)
 {
     int rc = check_common(dtype, MSX_SUM, nranks);
     if (rc) return rc;
@@ -984,11 +1124,14 @@ int moe_dispatch_impl(const void* const* tokens, const int32_t* const* topk_idx,
     Ctx* c = nullptr;
     if ((rc = get_ctx(&c))) return rc;
     const int n = nranks;
+    MoePlan* plan = nullptr;
+    if ((rc = moe_plan_of(c, plan_handle, &plan))) return rc;
     const size_t need = (size_t)kMaxRanks * (size_t)(T > 0 ? T : 1) * 16;
-    if (need > c->moe_slots_bytes) {
-        if (c->moe_slots) { HIPCHK(hipDeviceSynchronize()); HIPCHK(hipFree(c->moe_slots)); c->moe_slots = nullptr; c->moe_slots_bytes = 0; }
-        HIPCHK(hipMalloc(&c->moe_slots, need));
-        c->moe_slots_bytes = need;
+    if (need > plan->slots_bytes) {
+        if (plan->fixed_size) return MSX_ERR_NOMEM;      // made for fewer tokens per rank
+        if (plan->slots) { HIPCHK(hipDeviceSynchronize()); HIPCHK(hipFree(plan->slots)); plan->slots = nullptr; plan->slots_bytes = 0; }
+        HIPCHK(hipMalloc(&plan->slots, need));
+        plan->slots_bytes = need;
     }
     MoeArgs a{};
     for (int i = 0; i < n; ++i) {
@@ -998,8 +1141,8 @@ int moe_dispatch_impl(const void* const* tokens, const int32_t* const* topk_idx,
         a.recv_src[i] = recv_src_token ? recv_src_token[i] : nullptr;
     }
     a.recv_counts = recv_counts;
-    a.slots = (unsigned short*)c->moe_slots;
-    a.base = c->moe_base;
+    a.slots = (unsigned short*)plan->slots;
+    a.base = plan->base;
     a.T = T;
     a.K = K;
     a.n = n;
@@ -1021,8 +1164,8 @@ int moe_dispatch_impl(const void* const* tokens, const int32_t* const* topk_idx,
     if ((rc = pick_channels(c, (const void*)k_moe_pack, 256, n, (size_t)T * 64, 4, g_opt.hb_blocks, 128, &chans)))
         return rc;
     a.chans = chans;
-    c->plan_T = T;
-    c->plan_n = n;
+    plan->T = T;
+    plan->n = n;
     // many rows of whole multiples of 64 vectors (bf16 / fp32 pack only): chip-wide read and write phases, one
     // workgroup per CU.  Automatic for 8 ranks from 32 MiB of tokens per rank; an explicit hb_phased_min_bytes
     // counts for every rank count.
@@ -1088,10 +1231,16 @@ int msx_allreduce(void* buf, size_t count, int dtype, int op, int nranks, void* 
     if (count == 0) return MSX_OK;
     if (!buf || !aligned16(buf)) return MSX_ERR_ARG;
     const size_t row = count * elem_size(dtype);
-    if (nranks > 1 && (row & 15u)) return MSX_ERR_ARG;   // every row must start 16-byte aligned
     const void* in[kMaxRanks];
     void* out[kMaxRanks];
     for (int r = 0; r < nranks; ++r) in[r] = out[r] = (char*)buf + (size_t)r * row;
+    if (nranks > 1 && (row & 15u)) {
+        // rows that do not start on 16-byte boundaries: the element-by-element kernel
+        std::lock_guard<std::mutex> lk(g_mu);
+        Ctx* c = nullptr;
+        if ((rc = get_ctx(&c))) return rc;
+        return reduce_generic(c, in, out, count, dtype, op, nranks, 2, 0, (hipStream_t)stream);
+    }
     return allreduce_impl(in, out, nullptr, count, dtype, op, nranks, MSX_ALGO_AUTO, (hipStream_t)stream);
 }
 
@@ -1233,25 +1382,25 @@ int msx_alltoall(void* buf, size_t count, int dtype, int op, int nranks, void* s
 
 int msx_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, int T, int H, int K, int n_experts,
                      int dtype, int nranks, void* const* recv_tokens, int32_t* const* recv_src_token,
-                     int32_t* recv_counts, size_t recv_capacity_tokens, void* stream)
+                     int32_t* recv_counts, size_t recv_capacity_tokens, void* plan, void* stream)
 {
     return moe_dispatch_impl(tokens, topk_idx, T, H, K, n_experts, dtype, nranks, recv_tokens, nullptr,
-                             recv_src_token, recv_counts, recv_capacity_tokens, (hipStream_t)stream);
+                             recv_src_token, recv_counts, recv_capacity_tokens, plan, (hipStream_t)stream);
 }
 
 int msx_moe_dispatch_fp8(const void* const* tokens, const int32_t* const* topk_idx, int T, int H, int K,
                          int n_experts, int nranks, void* const* recv_q, float* const* recv_scales,
                          int32_t* const* recv_src_token, int32_t* recv_counts, size_t recv_capacity_tokens,
-                         void* stream)
+                         void* plan, void* stream)
 {
     if (!recv_scales) return MSX_ERR_ARG;
     if (H <= 0 || H % 128) return MSX_ERR_ARG;
     return moe_dispatch_impl(tokens, topk_idx, T, H, K, n_experts, MSX_BF16, nranks, recv_q, recv_scales,
-                             recv_src_token, recv_counts, recv_capacity_tokens, (hipStream_t)stream);
+                             recv_src_token, recv_counts, recv_capacity_tokens, plan, (hipStream_t)stream);
 }
 
 int msx_moe_combine(const void* const* expert_out, void* const* out_tokens, int T, int H, int dtype, int nranks,
-                    size_t capacity_tokens, void* stream)
+                    size_t capacity_tokens, void* plan_handle, void* stream)
 {
     int rc = check_common(dtype, MSX_SUM, nranks);
     if (rc) return rc;
@@ -1266,7 +1415,9 @@ int msx_moe_combine(const void* const* expert_out, void* const* out_tokens, int 
     std::lock_guard<std::mutex> lk(g_mu);
     Ctx* c = nullptr;
     if ((rc = get_ctx(&c))) return rc;
-    if (c->plan_T != T || c->plan_n != nranks || !c->moe_slots) return MSX_ERR_ARG;   // no matching dispatch before
+    MoePlan* plan = nullptr;
+    if ((rc = moe_plan_of(c, plan_handle, &plan))) return rc;
+    if (plan->T != T || plan->n != nranks || !plan->slots) return MSX_ERR_ARG;   // no matching dispatch through this plan
     if (T == 0) return MSX_OK;
     const int n = nranks;
     MoeArgs a{};
@@ -1274,8 +1425,8 @@ int msx_moe_combine(const void* const* expert_out, void* const* out_tokens, int 
         a.recv[i] = const_cast<void*>(expert_out[i]);
         a.tokens[i] = out_tokens[i];
     }
-    a.slots = (unsigned short*)c->moe_slots;
-    a.base = c->moe_base;
+    a.slots = (unsigned short*)plan->slots;
+    a.base = plan->base;
     a.T = T;
     a.n = n;
     a.row_vecs = (unsigned)(row_bytes / 16);
@@ -1382,6 +1533,7 @@ int msx_prim_port_put_signal_wait(const void* src, void* staging, void* dst, siz
 {
     if (!src || !staging || !dst || !aligned16(src) || !aligned16(staging) || !aligned16(dst)) return MSX_ERR_ARG;
     if (nbytes == 0) return MSX_OK;
+    if (t_record) return MSX_ERR_UNSUPPORTED;      // the proxy is told of every launch: not a call to prepare
     std::lock_guard<std::mutex> lk(g_mu);
     Ctx* c = nullptr;
     int rc = get_ctx(&c);
@@ -1411,32 +1563,47 @@ int msx_init(void)
 {
     std::lock_guard<std::mutex> lk(g_mu);
     Ctx* c = nullptr;
-    int rc = get_ctx(&c);
+    int rc = default_ctx(&c);
     if (rc) return rc;
     return get_static_ctx(nullptr, &c);
 }
+
+}  // extern "C"
+namespace {
+// Re-zero everything a context's kernels synchronise through.  Waits for the device.
+int reset_ctx(Ctx* c)
+{
+    HIPCHK(hipDeviceSynchronize());
+    if (c->fixed) {
+        HIPCHK(hipMemset(c->d.sem, 0, kStaticBytes));
+    } else {
+        HIPCHK(hipMemset(c->d.sem, 0, (size_t)kMaxRanks * kMaxRanks * kMaxChannels * kSemStrideWords * 4));
+        HIPCHK(hipMemset(c->d.expected, 0, (size_t)kMaxRanks * kMaxRanks * kMaxChannels * 4));
+        HIPCHK(hipMemset(c->d.status, 0, 64));
+        HIPCHK(hipMemset(c->d.call_state, 0, 64));
+        HIPCHK(hipMemset(c->d.gbar, 0, kGridBarBytes));
+        HIPCHK(hipMemset(c->d.ll, 0, c->d.ll_bytes));
+    }
+    HIPCHK(hipDeviceSynchronize());
+    if (c->latch) __atomic_store_n(c->latch, 0u, __ATOMIC_RELAXED);
+    if (c->port) {                       // a port channel that timed out starts over with a fresh proxy
+        destroy_port(c->port);
+        c->port = nullptr;
+    }
+    return MSX_OK;
+}
+
+}  // namespace
+extern "C" {
 
 int msx_reset(void)
 {
     std::lock_guard<std::mutex> lk(g_mu);
     Ctx* c = nullptr;
-    int rc = get_ctx(&c);
+    int rc = get_ctx(&c, false);
     if (rc) return rc;
-    HIPCHK(hipDeviceSynchronize());
-    HIPCHK(hipMemset(c->d.sem, 0, (size_t)kMaxRanks * kMaxRanks * kMaxChannels * kSemStrideWords * 4));
-    HIPCHK(hipMemset(c->d.expected, 0, (size_t)kMaxRanks * kMaxRanks * kMaxChannels * 4));
-    HIPCHK(hipMemset(c->d.status, 0, 64));
-    HIPCHK(hipMemset(c->d.call_state, 0, 64));
-    HIPCHK(hipMemset(c->d.gbar, 0, kGridBarBytes));
-    HIPCHK(hipMemset(c->d.ll, 0, c->d.ll_bytes));
-    int dev = 0;
-    HIPCHK(hipGetDevice(&dev));
-    if (dev >= 0 && dev < 64 && g_static[dev]) HIPCHK(hipMemset(g_static[dev]->d.sem, 0, kStaticBytes));
-    HIPCHK(hipDeviceSynchronize());
-    if (c->port) {                       // a port channel that timed out starts over with a fresh proxy
-        destroy_port(c->port);
-        c->port = nullptr;
-    }
+    if ((rc = reset_ctx(c))) return rc;
+    if (!t_use && g_static[c->device]) return reset_ctx(g_static[c->device]);
     return MSX_OK;
 }
 
@@ -1448,7 +1615,269 @@ int msx_finalize(void)
     if (dev < 0 || dev >= 64) return MSX_ERR_ARG;
     Ctx* c = g_ctx[dev];
     g_ctx[dev] = nullptr;
+    for (Prepared* p : g_prepared)
+        if (p->ctx == c) p->ctx = nullptr;          // its handles can no longer run
     return destroy_ctx(c);
+}
+
+// ---- context handles ----------------------------------------------------------------------------
+
+int msx_ctx_create(int nranks, size_t max_ll_bytes, void** ctx)
+{
+    if (!ctx || nranks < 1 || nranks > kMaxRanks) return MSX_ERR_ARG;
+    if (max_ll_bytes != 0 && (max_ll_bytes < 4096 || max_ll_bytes > (16u << 20))) return MSX_ERR_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = make_ctx(max_ll_bytes ? max_ll_bytes : g_opt.ll_max_bytes, &c);
+    if (rc) return rc;
+    g_made.push_back(c);
+    *ctx = c;
+    return MSX_OK;
+}
+
+int msx_ctx_destroy(void* ctx)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = (Ctx*)ctx;
+    if (!known_ctx(c)) return MSX_ERR_ARG;
+    for (size_t i = 0; i < g_made.size(); ++i)
+        if (g_made[i] == c) { g_made.erase(g_made.begin() + (long)i); break; }
+    if (t_use == c) t_use = nullptr;
+    for (Prepared* p : g_prepared)
+        if (p->ctx == c) p->ctx = nullptr;
+    int dev = -1;
+    HIPCHK(hipGetDevice(&dev));
+    if (dev != c->device) HIPCHK(hipSetDevice(c->device));
+    const int rc = destroy_ctx(c);
+    if (dev != c->device) HIPCHK(hipSetDevice(dev));
+    return rc;
+}
+
+int msx_ctx_use(void* ctx)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    if (ctx && !known_ctx((Ctx*)ctx)) return MSX_ERR_ARG;
+    t_use = (Ctx*)ctx;
+    return MSX_OK;
+}
+
+}  // extern "C"
+namespace {
+// null = the context this thread's calls run on
+int ctx_arg(void* ctx, Ctx** out)
+{
+    if (!ctx) return get_ctx(out, false);
+    if (!known_ctx((Ctx*)ctx)) return MSX_ERR_ARG;
+    *out = (Ctx*)ctx;
+    return MSX_OK;
+}
+
+}  // namespace
+extern "C" {
+
+int msx_ctx_reset(void* ctx)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = ctx_arg(ctx, &c);
+    if (rc) return rc;
+    return reset_ctx(c);
+}
+
+int msx_ctx_set_max_blocks(void* ctx, int max_blocks)
+{
+    if (max_blocks < 0) return MSX_ERR_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = ctx_arg(ctx, &c);
+    if (rc) return rc;
+    c->max_blocks = max_blocks;
+    return MSX_OK;
+}
+
+}  // extern "C"
+namespace {
+// the status block of one context, read and cleared; the caller has waited for the work in question
+int take_status(Ctx* c, uint32_t h[8])
+{
+    HIPCHK(hipMemcpy(h, c->d.status, 32, hipMemcpyDeviceToHost));
+    if (h[0] != 0) HIPCHK(hipMemset(c->d.status, 0, 32));
+    if (c->latch) __atomic_store_n(c->latch, 0u, __ATOMIC_RELAXED);
+    return MSX_OK;
+}
+
+int status_code(const uint32_t h[8])
+{
+    if (h[0] == kStatusTimeout) return MSX_ERR_TIMEOUT;
+    if (h[0] == kStatusCapacity) return MSX_ERR_CAPACITY;
+    if (h[0] == kStatusBadIndex) return MSX_ERR_INDEX;
+    return MSX_OK;
+}
+
+}  // namespace
+extern "C" {
+
+int msx_last_status(void* ctx, int* rank, int* site, unsigned* expected, unsigned* seen)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = ctx_arg(ctx, &c);
+    if (rc) return rc;
+    uint32_t h[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if ((rc = take_status(c, h))) return rc;
+    if (rank) *rank = (int)h[1];
+    if (site) *site = (int)h[2];
+    if (expected) *expected = h[3];
+    if (seen) *seen = h[4];
+    if (h[0] != 0) g_status_detail = h[6];
+    return status_code(h);
+}
+
+// ---- routing plans --------------------------------------------------------------------------------
+
+int msx_moe_plan_create(void* ctx, int max_tokens_per_rank, void** plan)
+{
+    if (!plan || max_tokens_per_rank < 1 || max_tokens_per_rank > 65534) return MSX_ERR_ARG;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = ctx_arg(ctx, &c);
+    if (rc) return rc;
+    MoePlan* p = new MoePlan();
+    p->owner = c;
+    p->fixed_size = true;
+    p->slots_bytes = (size_t)kMaxRanks * (size_t)max_tokens_per_rank * 16;
+    if (hipMalloc(&p->slots, p->slots_bytes) != hipSuccess || hipMalloc((void**)&p->base, 64 * 4) != hipSuccess ||
+        hipMemset(p->base, 0, 64 * 4) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        if (p->slots) (void)hipFree(p->slots);
+        if (p->base) (void)hipFree(p->base);
+        delete p;
+        return MSX_ERR_NOMEM;
+    }
+    g_plans.push_back(p);
+    *plan = p;
+    return MSX_OK;
+}
+
+int msx_moe_plan_destroy(void* plan)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    for (size_t i = 0; i < g_plans.size(); ++i)
+        if (g_plans[i] == plan) {
+            MoePlan* p = g_plans[i];
+            g_plans.erase(g_plans.begin() + (long)i);
+            HIPCHK(hipDeviceSynchronize());
+            (void)hipFree(p->slots);
+            (void)hipFree(p->base);
+            delete p;
+            return MSX_OK;
+        }
+    return MSX_ERR_ARG;
+}
+
+// ---- prepared calls ---------------------------------------------------------------------------------
+
+}  // extern "C"
+namespace {
+// Runs `call` (one of the ordinary entry points) with its launches recorded instead of enqueued.
+template <class F> int prepare(void** handle, F call)
+{
+    if (!handle) return MSX_ERR_ARG;
+    if (t_record) return MSX_ERR_UNSUPPORTED;
+    std::unique_ptr<Prepared> p(new Prepared());
+    {
+        std::lock_guard<std::mutex> lk(g_mu);
+        int rc = get_ctx(&p->ctx);
+        if (rc) return rc;
+    }
+    t_record = p.get();
+    const int rc = call();
+    t_record = nullptr;
+    if (rc) {
+        for (void* m : p->owned) (void)hipFree(m);
+        return rc;
+    }
+    p->grid = t_grid; p->block = t_block; p->algo = t_algo;
+    std::lock_guard<std::mutex> lk(g_mu);
+    g_prepared.push_back(p.get());
+    *handle = p.release();
+    return MSX_OK;
+}
+
+}  // namespace
+extern "C" {
+
+int msx_prepare_allreduce(const void* const* send, void* const* recv, const void* const* residual, size_t count,
+                          int dtype, int op, int nranks, int algo, void** handle)
+{
+    return prepare(handle, [&] { return msx_allreduce_ex(send, recv, residual, count, dtype, op, nranks, algo, nullptr); });
+}
+
+int msx_prepare_reducescatter(const void* const* send, void* const* recv, size_t count, int dtype, int op, int nranks,
+                              void** handle)
+{
+    return prepare(handle, [&] { return msx_reducescatter_ex(send, recv, count, dtype, op, nranks, nullptr); });
+}
+
+int msx_prepare_allgather(const void* const* send, void* const* recv, size_t count, int dtype, int nranks, void** handle)
+{
+    return prepare(handle, [&] { return msx_allgather_ex(send, recv, count, dtype, nranks, nullptr); });
+}
+
+int msx_prepare_alltoall(const void* const* send, void* const* recv, size_t count, int dtype, int nranks, void** handle)
+{
+    return prepare(handle, [&] { return msx_alltoall_ex(send, recv, count, dtype, nranks, nullptr); });
+}
+
+int msx_prepare_moe_dispatch(const void* const* tokens, const int32_t* const* topk_idx, int T, int H, int K,
+                             int n_experts, int dtype, int nranks, void* const* recv_tokens,
+                             int32_t* const* recv_src_token, int32_t* recv_counts, size_t recv_capacity_tokens,
+                             void* plan, void** handle)
+{
+    return prepare(handle, [&] {
+        return msx_moe_dispatch(tokens, topk_idx, T, H, K, n_experts, dtype, nranks, recv_tokens, recv_src_token,
+                                recv_counts, recv_capacity_tokens, plan, nullptr);
+    });
+}
+
+int msx_prepare_moe_combine(const void* const* expert_out, void* const* out_tokens, int T, int H, int dtype, int nranks,
+                            size_t capacity_tokens, void* plan, void** handle)
+{
+    return prepare(handle, [&] {
+        return msx_moe_combine(expert_out, out_tokens, T, H, dtype, nranks, capacity_tokens, plan, nullptr);
+    });
+}
+
+int msx_run(void* handle, void* stream)
+{
+    Prepared* p = (Prepared*)handle;
+    if (!p || p->magic != kPreparedMagic || !p->ctx) return MSX_ERR_ARG;
+    int rc = latched(p->ctx);
+    if (rc) return rc;
+    for (auto& step : p->steps) {
+        const hipError_t e = step((hipStream_t)stream);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    t_grid = p->grid; t_block = p->block; t_algo = p->algo;
+    return MSX_OK;
+}
+
+int msx_release(void* handle)
+{
+    Prepared* p = (Prepared*)handle;
+    if (!p) return MSX_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    size_t at = g_prepared.size();
+    for (size_t i = 0; i < g_prepared.size(); ++i)
+        if (g_prepared[i] == p) at = i;
+    if (at == g_prepared.size()) return MSX_ERR_ARG;
+    g_prepared.erase(g_prepared.begin() + (long)at);
+    if (!p->owned.empty()) {
+        HIPCHK(hipDeviceSynchronize());          // a launch of this call may still be using its scratch
+        for (void* m : p->owned) (void)hipFree(m);
+    }
+    p->magic = 0;
+    delete p;
+    return MSX_OK;
 }
 
 int msx_set_option(const char* key, const char* value)
@@ -1528,14 +1957,14 @@ int msx_set_option(const char* key, const char* value)
         g_opt.chaos = (unsigned)u;
     } else if (k == "epoch") {
         Ctx* c = nullptr;
-        int rc = get_ctx(&c);
+        int rc = get_ctx(&c, false);
         if (rc) return rc;
         HIPCHK(hipDeviceSynchronize());
         const unsigned last = (unsigned)u - 1u;   // the next call uses exactly u (or 1 if u is 0)
         HIPCHK(hipMemcpy(c->d.call_state, &last, 4, hipMemcpyHostToDevice));
     } else if (k == "sem_base") {
         Ctx* c = nullptr;
-        int rc = get_ctx(&c);
+        int rc = get_ctx(&c, false);
         if (rc) return rc;
         HIPCHK(hipDeviceSynchronize());
         const size_t ns = (size_t)kMaxRanks * kMaxRanks * kMaxChannels;
@@ -1620,22 +2049,17 @@ int msx_status(void* stream, uint32_t info[6])
     int dev = 0;
     HIPCHK(hipGetDevice(&dev));
     if (dev < 0 || dev >= 64) return MSX_ERR_ARG;
-    Ctx* c = g_ctx[dev];
+    Ctx* c = t_use ? t_use : g_ctx[dev];
+    if (c && t_use && (!known_ctx(c) || c->device != dev)) return MSX_ERR_ARG;
     uint32_t h[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (c) {
-        HIPCHK(hipMemcpy(h, c->d.status, 32, hipMemcpyDeviceToHost));
-        if (h[0] != 0) HIPCHK(hipMemset(c->d.status, 0, 32));
-    }
-    if (h[0] == 0 && g_static[dev]) {        // the fixed context of msx_allreduce_ex_static has a status block of its own
-        HIPCHK(hipMemcpy(h, g_static[dev]->d.status, 32, hipMemcpyDeviceToHost));
-        if (h[0] != 0) HIPCHK(hipMemset(g_static[dev]->d.status, 0, 32));
-    }
+    int rc;
+    if (c && (rc = take_status(c, h))) return rc;
+    // the fixed context of msx_allreduce_ex_static has a status block of its own
+    if (h[0] == 0 && !t_use && g_static[dev] && (rc = take_status(g_static[dev], h))) return rc;
     if (info)
         for (int i = 0; i < 6; ++i) info[i] = h[i];
     if (h[0] != 0) g_status_detail = h[6];
-    if (h[0] == kStatusTimeout) return MSX_ERR_TIMEOUT;
-    if (h[0] == kStatusCapacity) return MSX_ERR_CAPACITY;
-    return MSX_OK;
+    return status_code(h);
 }
 
 int msx_debug_choose(size_t nbytes, int nranks, size_t ll_limit, int* algo, int* unroll, int* want_blocks)
@@ -1698,10 +2122,11 @@ const char* msx_strerror(int err)
         case MSX_ERR_TIMEOUT: return "device-side wait timed out";
         case MSX_ERR_NOMEM: return "scratch too small or allocation failed";
         case MSX_ERR_CAPACITY: return "token dispatch receive buffer overflow";
+        case MSX_ERR_INDEX: return "token dispatch: expert id out of range";
         default: return "unknown error";
     }
 }
 
-const char* msx_version(void) { return "msx 0.1 (gfx950)"; }
+const char* msx_version(void) { return "msx 0.2 (gfx950)"; }
 
 }  // extern "C"

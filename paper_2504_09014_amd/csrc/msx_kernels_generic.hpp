@@ -103,8 +103,9 @@ template <int DT> __device__ __forceinline__ void store_elem_g(void* p, size_t e
     else ((unsigned*)p)[e] = v;
 }
 
-// AllReduce (mode 0: result to every rank, a.count = elements per rank) or ReduceScatter
-// (mode 1: a.count = elements per block, a.out[r] = rank r's block, vec as in k_reducescatter_hb).
+// AllReduce (mode 0: result to every rank, a.count = elements per rank; mode 2: the same element by element,
+// for pointers that are only element-aligned) or ReduceScatter (mode 1: a.count = elements per block,
+// a.out[r] = rank r's block, vec as in k_reducescatter_hb).
 template <int DT, int OP>
 __global__ __launch_bounds__(256) void k_reduce_generic(HbArgs a, DevCtx c, int mode, int vec)
 {
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(256) void k_reduce_generic(HbArgs a, DevCtx c, int 
     if (rank == c.drop_rank) return;
     constexpr size_t epv = (DT == 0 || DT == 3) ? 4 : 8;
     constexpr size_t esz = (DT == 0 || DT == 3) ? 4 : 2;
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, 600, false, false);
+    if (a.barriers && n > 1 && !rank_barrier<true>(c, rank, n, chan, 600, false, false)) return;
     const size_t RT = (size_t)a.chans * blockDim.x;
     const size_t rt = (size_t)chan * blockDim.x + threadIdx.x;
     bool plain_stores = false;
@@ -139,6 +140,17 @@ __global__ __launch_bounds__(256) void k_reduce_generic(HbArgs a, DevCtx c, int 
                 for (int j = 1; j < n; ++j) acc = combine_elem<DT, OP>(acc, load_elem_g<DT>(a.in[j], e));
                 for (int p = 0; p < n; ++p) store_elem_g<DT>(a.out[p], e, acc);
             }
+        }
+    } else if (mode == 2) {
+        // AllReduce element by element, for rows that do not start on 16-byte boundaries: rank r combines its
+        // share of the elements and stores them to every rank (in place is safe: an element is read and
+        // written by one thread only).  Ordinary stores, so the end barrier releases.
+        plain_stores = true;
+        const size_t lo = a.count * (size_t)rank / (size_t)n, hi = a.count * (size_t)(rank + 1) / (size_t)n;
+        for (size_t e = lo + rt; e < hi; e += RT) {
+            auto acc = load_elem_g<DT>(a.in[0], e);
+            for (int j = 1; j < n; ++j) acc = combine_elem<DT, OP>(acc, load_elem_g<DT>(a.in[j], e));
+            for (int p = 0; p < n; ++p) store_elem_g<DT>(a.out[p], e, acc);
         }
     } else {
         const size_t blk = a.count;

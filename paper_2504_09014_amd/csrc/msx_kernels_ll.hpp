@@ -44,7 +44,8 @@ __device__ __forceinline__ void store_words(void* base, size_t k, size_t nbytes,
         if (off + 2 * i + 2 <= nbytes) *(unsigned short*)((char*)base + off + 2 * i) = (unsigned short)h[i];
 }
 
-// Poll packet `pos` of slots j != me (j < n_l) of my scratch until all carry the flag.
+// Poll packet `pos` of slots j != me (j < n_l) of my scratch until all carry the flag.  Used inside the
+// loop over a thread's packets: when the spin budget runs out the thread reports it and leaves that loop.
 #define MSX_LL_POLL_ALL(v, base_off, slot_stride, pos)                                        \
     {                                                                                         \
         bool ready = false;                                                                   \
@@ -62,6 +63,7 @@ __device__ __forceinline__ void store_words(void* base, size_t k, size_t nbytes,
             _Pragma("unroll") for (int j = 0; j < kMaxRanks; ++j)                             \
                 if (j < n_l && j != rank_l && !ll_ready(v[j], tag.flag)) { late = (unsigned)j; seen = v[j].y; } \
             report(c, kStatusTimeout, (unsigned)rank, 100u, tag.flag, seen, late);            \
+            break;                           /* nothing is built from packets that never came */ \
         }                                                                                     \
     }
 
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
             for (int j = 0; j < kMaxRanks; ++j)
                 if (j < n_l && j != rank_l && (unsigned)j * cp + q < P) ready = ready && ll_ready(v[j], tag.flag);
         }
-        if (!ready) report(c, kStatusTimeout, (unsigned)rank, 101u, tag.flag, 0u);
+        if (!ready) { report(c, kStatusTimeout, (unsigned)rank, 101u, tag.flag, 0u); break; }
 #pragma unroll
         for (int j = 0; j < kMaxRanks; ++j)
             if (j < n_l && j != rank_l && (unsigned)j * cp + q < P)

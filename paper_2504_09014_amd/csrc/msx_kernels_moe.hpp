@@ -71,7 +71,10 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
     const int t1 = min(T, t0 + per_thread);
     const int* topk = a.topk[rank];
 
-    // destination marks of a token: one bit per rank that owns one of its K experts
+    // destination marks of a token: one bit per rank that owns one of its K experts; an id outside
+    // [0, n_experts) marks nothing and is reported (the call goes on without it)
+    int bad_id = 0;
+    bool bad = false;
     auto marks = [&](int t) -> unsigned {
         unsigned mask = 0;
         if (K == 8) {                                    // the common case: two 16-byte loads per token
@@ -80,10 +83,12 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
 #pragma unroll
             for (int k = 0; k < 8; ++k)
                 if (e[k] >= 0 && e[k] < a.n_experts) mask |= 1u << (e[k] / a.per_rank);
+                else { bad = true; bad_id = e[k]; }
         } else {
             for (int k = 0; k < K; ++k) {
                 const int e = topk[(size_t)t * K + k];
                 if (e >= 0 && e < a.n_experts) mask |= 1u << (e / a.per_rank);
+                else { bad = true; bad_id = e; }
             }
         }
         return mask;
@@ -113,6 +118,7 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
             cy += (unsigned long long)((mask >> (d + 4)) & 1u) << (16 * d);
         }
     }
+    if (bad) report(c, kStatusBadIndex, (unsigned)rank, 202u, (unsigned)a.n_experts, (unsigned)bad_id);
     unsigned long long totx, toty;
     block_exscan2(cx, cy, scan_lds, totx, toty);   // cx, cy now hold the slots my first token gets
 
@@ -457,7 +463,7 @@ __global__ __launch_bounds__(256) void k_moe_combine(MoeArgs a, DevCtx c)
     const int chan = (int)(blockIdx.x / (unsigned)n);
     const int n_l = per_lane(n);   // per-lane copies for conditions (see per_lane)
     if (rank == c.drop_rank) return;
-    if (n > 1) rank_barrier(c, rank, n, chan, 220, false, false);   // every peer's rows are final
+    if (n > 1 && !rank_barrier<true>(c, rank, n, chan, 220, false, false)) return;   // every peer's rows are final
     const int lane = (int)(threadIdx.x & 63u);
     const int waves = (int)(blockDim.x >> 6);
     const int wave = chan * waves + (int)(threadIdx.x >> 6);

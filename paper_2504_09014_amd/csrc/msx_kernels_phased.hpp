@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
     const size_t V = a.count / epv;
 
     GridBar gb = grid_barrier_begin(c);
-    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, KIND ? 32 : 12, false, false);   // every peer has entered the call
+    if (a.barriers && n > 1) rank_barrier(c, rank, n, chan, KIND ? 32 : 12, false, false);   // every peer has entered the call (unchecked, as in k_allreduce_hb_fused)
 
     // the vectors [lo, hi) of every source belong to this rank
     const void* src[kMaxRanks];

@@ -155,22 +155,14 @@ __global__ __launch_bounds__(256) void k_plan_executor(PlanArgs a, DevCtx c)
     for (const PlanOp* op = list; op->code != kOpEnd; ++op) {
         switch (op->code) {
             case kOpBarrier:
-                rank_barrier(c, rank, n, chan, 400, (op->flags & 1) != 0, (op->flags & 2) != 0);
+                if (!rank_barrier<true>(c, rank, n, chan, 400, (op->flags & 1) != 0, (op->flags & 2) != 0)) return;
                 break;
             case kOpSignal:
                 channel_signal(c, rank, op->peer, chan, 401, (op->flags & 1) != 0);
                 break;
             case kOpWait:
-                if (op->flags & 2) channel_wait(c, rank, op->peer, chan, 402);
-                else {
-                    if (threadIdx.x == 0) {
-                        const unsigned idx = sem_index(rank, op->peer, chan);
-                        const unsigned want = c.expected[idx] + 1u;
-                        c.expected[idx] = want;
-                        sem_spin(c, c.sem + (size_t)idx * kSemStrideWords, want, (unsigned)rank, 403, false);
-                    }
-                    __syncthreads();
-                }
+                // a wait that runs out ends the list: what it guards must not be consumed
+                if (!channel_wait(c, rank, op->peer, chan, (op->flags & 2) ? 402 : 403, (op->flags & 2) != 0)) return;
                 break;
             case kOpDrain:
                 put_drain();

@@ -13,7 +13,7 @@ The kernels avoid the pattern by forming such conditions from per-lane copies of
 rank count (`per_lane` in csrc/msx_device.hpp); this module compiles the device code to assembly
 and reports any place where the pattern is back.
 
-    python -m paper_2504_09014_amd.codegen_audit          # prints findings, exit status 1 if any
+    python tests/codegen_audit.py          # prints findings, exit status 1 if any
 """
 import os
 import re
@@ -21,7 +21,17 @@ import subprocess
 import sys
 import tempfile
 
-from . import build as _build
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+from paper_2504_09014_amd import build as _build  # noqa: E402
+
+# The instruction idioms searched for below are what THIS compiler emits; another version may lower the same
+# source differently, and the scan would then pass without having looked at anything.
+VALIDATED_COMPILER = "roc-7.2.0"
+
+
+def compiler_version():
+    """The hipcc banner (its clang line names the ROCm release the compiler was built from)."""
+    return subprocess.run([_build.HIPCC, "--version"], capture_output=True, text=True, check=True).stdout
 
 _RE_FN = re.compile(r'^(_Z\w+):')
 _RE_LABEL = re.compile(r'^(?:\.L(BB\d+_\d+):|; %bb\.(\d+):)')

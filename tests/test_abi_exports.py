@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(L):
 def test_strerror_and_version(L):
     assert b"gfx950" in L.msx_version()
     assert L.msx_strerror(0) == b"ok"
-    for code in range(-6, 0):
+    for code in range(-7, 0):
         assert L.msx_strerror(code) not in (b"ok", b"unknown error")
     assert L.msx_strerror(-99) == b"unknown error"
 
@@ -48,7 +48,6 @@ def test_argument_errors_need_no_device(L):
     assert L.msx_allreduce(fake, 16, 0, 0, 9, None) == ARG
     assert L.msx_allreduce(None, 16, 0, 0, 8, None) == ARG
     assert L.msx_allreduce(odd, 16, 0, 0, 8, None) == ARG           # alignment
-    assert L.msx_allreduce(fake, 3, 0, 0, 8, None) == ARG           # rows would be misaligned
     assert L.msx_allreduce(fake, 0, 0, 0, 8, None) == 0             # empty is a no-op
     assert L.msx_reducescatter(fake, 12, 0, 0, 8, None) == ARG      # count % nranks
     assert L.msx_alltoall(fake, 12, 1, 0, 8, None) == ARG
@@ -62,9 +61,22 @@ def test_argument_errors_need_no_device(L):
     assert L.msx_allreduce_ex(C.cast(tbl, pp), C.cast(tbl, pp), None, 0, 0, 0, 8, 0, None) == 0
     assert L.msx_alltoall_ex(C.cast(tbl, pp), C.cast(tbl, pp), 64, 0, 8, None) == ARG                 # overlap
     assert L.msx_moe_dispatch(C.cast(tbl, pp), C.cast(tbl, pp), 4, 7, 8, 256, 1, 8, C.cast(tbl, pp), None,
-                              fake, 16, None) == ARG                                                   # row % 16
+                              fake, 16, None, None) == ARG                                             # row % 16
     assert L.msx_moe_dispatch(C.cast(tbl, pp), C.cast(tbl, pp), 70000, 8, 8, 256, 1, 8, C.cast(tbl, pp), None,
-                              fake, 16, None) == UNSUP
+                              fake, 16, None, None) == UNSUP
+    # handles: unknown ones are refused before any device is touched
+    assert L.msx_ctx_use(fake) == ARG
+    assert L.msx_ctx_use(None) == 0
+    assert L.msx_ctx_destroy(fake) == ARG
+    assert L.msx_ctx_set_max_blocks(fake, 8) == ARG
+    assert L.msx_run(None, None) == ARG
+    assert L.msx_release(None) == 0
+    assert L.msx_release(fake) == ARG
+    assert L.msx_moe_plan_destroy(fake) == ARG
+    h = C.c_void_p()
+    assert L.msx_ctx_create(9, 0, C.byref(h)) == ARG
+    assert L.msx_ctx_create(8, 100, C.byref(h)) == ARG                                                # LL size
+    assert L.msx_prepare_allreduce(C.cast(tbl, pp), C.cast(tbl, pp), None, 16, 0, 0, 8, 0, None) == ARG
     assert L.msx_prim_pingpong(10, 1, 0, 0, fake, None) == ARG
     assert L.msx_prim_barrier(1, 9, 1, None, None) == ARG
     assert L.msx_set_option(b"no_such_key", b"1") == ARG
