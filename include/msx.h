@@ -89,9 +89,13 @@ typedef enum {
                                so results differ from the other algorithms in the last bits.  The first
                                call of a new size (re)allocates the ring scratch and blocks. */
     MSX_ALGO_PLAN_2PA_HB = 6, /* MSX_ALGO_2PA_HB run by the generic plan-interpreter kernel (the paper's */
-    MSX_ALGO_PLAN_2PR_HB = 7  /* Executor): same results as the hand-written kernel; count*elemsize must be a
+    MSX_ALGO_PLAN_2PR_HB = 7, /* Executor): same results as the hand-written kernel; count*elemsize must be a
                                multiple of 16*nranks, no residual; the first call of a shape lowers and uploads
-                               the plan (blocks). */
+                               the plan (blocks).  Large messages (where MSX_ALGO_2PA_HB runs in chip-wide read
+                               and write phases) are lowered to that schedule too. */
+    MSX_ALGO_PLAN_1PA_LL = 8, /* MSX_ALGO_1PA_LL and MSX_ALGO_2PA_LL run by the same interpreter from packet */
+    MSX_ALGO_PLAN_2PA_LL = 9  /* operations (put packets, reduce packets, copy packets): any even byte count within
+                               the LL limit, no residual. */
 } msx_algo;
 
 /* ------------------------------------------------------------------------------------
@@ -320,8 +324,8 @@ int msx_ctx_set_max_blocks(void* ctx, int max_blocks);
 int msx_last_status(void* ctx, int* rank, int* site, unsigned* expected, unsigned* seen);
 
 /* Options (strings; numbers in decimal):
- *   "algo"            auto | 1pa_ll | 2pa_ll | 2pa_hb | 2pa_hb_2phase | 2pr_hb | plan_2pa_hb | plan_2pr_hb
- *                     (for the in-place forms)
+ *   "algo"            auto | 1pa_ll | 2pa_ll | 2pa_hb | 2pa_hb_2phase | 2pr_hb | plan_2pa_hb | plan_2pr_hb |
+ *                     plan_1pa_ll | plan_2pa_ll   (for the in-place forms)
  *   "ll_1pa_max_bytes", "ll_2pa_max_bytes"   size thresholds of the automatic choice
  *   "coll_algo"       auto | ll | hb   protocol of allgather / reducescatter (LL needs blocks that
  *                     are multiples of 8 bytes and fit the LL scratch; "ll" fails otherwise)
@@ -367,10 +371,12 @@ int msx_last_launch(int* grid, int* block, int* algo);
  * msx_debug_choose: what the automatic choice would run for `nbytes` per rank given an LL scratch
  * sized for ll_limit bytes, and the HB launch shape (unroll, wanted workgroups per rank; for the phased form
  * the sums a thread holds per phase, and 256 = as many workgroups as are resident).
- * msx_debug_lower_plan: the execution plan the interpreter algorithms run.  ops_out receives
+ * msx_debug_lower_plan(_ex): the execution plan the interpreter algorithms run.  ops_out receives
  * 128-byte records {int code, peer, flags, nsrc, ndst; {int16 kind, rank} src[9], dst[8]; int dst_wt;
- * uint64 first, end, step} (see csrc/msx_kernels_plan.hpp), start_out the nranks*blocks_per_rank+1
- * list offsets.  With ops_out == NULL only *ops_written is set. */
+ * uint32 aux; uint64 first, end, step; uint32 aux2, aux3} (see csrc/msx_kernels_plan.hpp), start_out the
+ * nranks*blocks_per_rank+1 list offsets.  With ops_out == NULL only *ops_written is set.  The _ex form takes
+ * the message size in bytes per rank, any plan algorithm, and `held` (0, or the sums a thread holds per
+ * phase: MSX_ALGO_PLAN_2PA_HB is then lowered to the read phase / write phase schedule). */
 int msx_debug_choose(size_t nbytes, int nranks, size_t ll_limit, int* algo, int* unroll, int* want_blocks);
 /* One step of the controller that paces the write phases of the phased kernels: state = {pace, last pace that
  * was met, frozen, misses in a row} (pace in 10 ns ticks per tile, 0 = unpaced); took_ticks = how long the
@@ -378,6 +384,8 @@ int msx_debug_choose(size_t nbytes, int nranks, size_t ll_limit, int* algo, int*
 int msx_debug_pace_update(uint32_t state[4], uint64_t took_ticks, uint32_t tiles);
 int msx_debug_lower_plan(int algo, int nranks, int blocks_per_rank, size_t vectors_per_rank, int threads,
                          void* ops_out, size_t ops_capacity, uint32_t* start_out, size_t* ops_written);
+int msx_debug_lower_plan_ex(int algo, int nranks, int blocks_per_rank, size_t nbytes, int threads, int held,
+                            void* ops_out, size_t ops_capacity, uint32_t* start_out, size_t* ops_written);
 
 int msx_last_hip_error(void);
 const char* msx_strerror(int err);

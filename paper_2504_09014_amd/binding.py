@@ -9,7 +9,7 @@ import os
 import torch
 
 __all__ = [
-    "F32", "BF16", "F16", "I32", "SUM", "MAX", "MIN", "ALGO_AUTO", "ALGO_1PA_LL", "ALGO_2PA_LL", "ALGO_2PA_HB", "ALGO_2PA_HB_2PHASE", "ALGO_2PR_HB", "ALGO_PLAN_2PA_HB", "ALGO_PLAN_2PR_HB",
+    "F32", "BF16", "F16", "I32", "SUM", "MAX", "MIN", "ALGO_AUTO", "ALGO_1PA_LL", "ALGO_2PA_LL", "ALGO_2PA_HB", "ALGO_2PA_HB_2PHASE", "ALGO_2PR_HB", "ALGO_PLAN_2PA_HB", "ALGO_PLAN_2PR_HB", "ALGO_PLAN_1PA_LL", "ALGO_PLAN_2PA_LL",
     "MsxError", "lib", "lib_path", "init", "reset", "finalize", "set_option", "get_option", "status",
     "check_status", "last_launch", "version", "strerror",
     "allreduce", "reducescatter", "allgather", "alltoall",
@@ -25,7 +25,7 @@ __all__ = [
 F32, BF16, F16, I32 = 0, 1, 2, 3
 SUM, MAX, MIN = 0, 1, 2
 ALGO_AUTO, ALGO_1PA_LL, ALGO_2PA_LL, ALGO_2PA_HB, ALGO_2PA_HB_2PHASE, ALGO_2PR_HB = 0, 1, 2, 3, 4, 5
-ALGO_PLAN_2PA_HB, ALGO_PLAN_2PR_HB = 6, 7
+ALGO_PLAN_2PA_HB, ALGO_PLAN_2PR_HB, ALGO_PLAN_1PA_LL, ALGO_PLAN_2PA_LL = 6, 7, 8, 9
 
 EXPORTS = [
     "msx_allreduce", "msx_reducescatter", "msx_allgather", "msx_alltoall",
@@ -38,7 +38,7 @@ EXPORTS = [
     "msx_prim_ll_roundtrip", "msx_prim_port_put_signal_wait",
     "msx_init", "msx_reset", "msx_finalize", "msx_set_option", "msx_get_option", "msx_status",
     "msx_last_launch", "msx_last_hip_error", "msx_strerror", "msx_version",
-    "msx_debug_choose", "msx_debug_lower_plan", "msx_debug_pace_update",
+    "msx_debug_choose", "msx_debug_lower_plan", "msx_debug_lower_plan_ex", "msx_debug_pace_update",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -107,6 +107,7 @@ def lib():
         L.msx_last_launch.argtypes = [C.POINTER(i), C.POINTER(i), C.POINTER(i)]
         L.msx_debug_choose.argtypes = [sz, i, sz, C.POINTER(i), C.POINTER(i), C.POINTER(i)]
         L.msx_debug_lower_plan.argtypes = [i, i, i, sz, i, vp, sz, C.POINTER(u32), C.POINTER(sz)]
+        L.msx_debug_lower_plan_ex.argtypes = [i, i, i, sz, i, i, vp, sz, C.POINTER(u32), C.POINTER(sz)]
         L.msx_debug_pace_update.argtypes = [C.POINTER(u32), C.c_uint64, u32]
         L.msx_strerror.argtypes = [i]
         L.msx_strerror.restype = C.c_char_p

@@ -480,18 +480,23 @@ template <int DT> struct VecAcc {
     __device__ __forceinline__ u32x4 pack() const { return u32x4{w[0].pack(), w[1].pack(), w[2].pack(), w[3].pack()}; }
 };
 
+// Rank buffers are device memory.  Saying so in the pointer type keeps every access a global one also where
+// the pointer reaches the kernel through a table in LDS (the plan interpreter), where the compiler could not
+// tell and would fall back to flat accesses.
+#define MSX_GLOBAL __attribute__((address_space(1)))
+
 __device__ __forceinline__ u32x4 ld16(const void* base, size_t vec_index)
 {
-    return __builtin_nontemporal_load((const u32x4*)base + vec_index);
+    return __builtin_nontemporal_load((const MSX_GLOBAL u32x4*)base + vec_index);
 }
 // the same load without the streaming hint: the line may stay in the caches
 __device__ __forceinline__ u32x4 ld16_keep(const void* base, size_t vec_index)
 {
-    return *((const u32x4*)base + vec_index);
+    return *((const MSX_GLOBAL u32x4*)base + vec_index);
 }
 __device__ __forceinline__ void st16(void* base, size_t vec_index, u32x4 v)
 {
-    __builtin_nontemporal_store(v, (u32x4*)base + vec_index);
+    __builtin_nontemporal_store(v, (MSX_GLOBAL u32x4*)base + vec_index);
 }
 
 // f(integral_constant<int, 0>) ... f(integral_constant<int, N - 1>), in order: a loop whose index is a constant
@@ -513,6 +518,11 @@ template <int N, class F> __device__ __forceinline__ void static_for(F&& f)
 // small AllGather 4.8 us instead of 3.3 us).  Settling the vector once, before the stores, leaves no load
 // pending at any of them.
 __device__ __forceinline__ void settle(u32x4& v) { asm volatile("" : "+v"(v)); }
+// The same for the payload of an LL packet.  The packet stores are builtins, which the compiler does count,
+// but it cannot carry the count across the per-peer conditions either: without this every peer's store sat
+// behind a wait for ALL earlier memory operations, the previous peer's store included (seven store round trips
+// one after the other in the first phase of 2PA).
+__device__ __forceinline__ void settle(u32x2& v) { asm volatile("" : "+v"(v)); }
 
 // First 16-byte vector of rank r's chunk when V vectors are split over n ranks: the even split rounded down
 // to a whole 128-byte line (8 vectors), so that no two ranks write into the same line and every wave's accesses

@@ -8,6 +8,7 @@
 #include <climits>
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
 #include <cstring>
 #include <functional>
 #include <memory>
@@ -27,6 +28,7 @@
 #include "msx_kernels_ll.hpp"
 #include "msx_kernels_moe.hpp"
 #include "msx_kernels_plan.hpp"
+#include "msx_plan.hpp"
 #include "msx_kernels_generic.hpp"
 #include "msx_port.hpp"
 #include "msx_kernels_prim.hpp"
@@ -96,7 +98,7 @@ struct Ctx {
     int max_blocks = 0;            // workgroups one launch of this context may take (0: all the GPU can hold)
     void* ring = nullptr;          // ring AllReduce: per-rank receive scratch, grown on demand
     size_t ring_bytes = 0;
-    struct Plan { int algo, n, chans; size_t nbytes; PlanOp* ops; unsigned* start; };
+    struct Plan { int algo, n, chans, held; size_t nbytes; PlanOp* ops; unsigned stride; int head; };
     std::vector<Plan> plans;       // lowered execution plans, kept on the device
     Port* port = nullptr;          // created on the first port-channel call
     unsigned* snap = nullptr;  // small device scratch for snapshots
@@ -231,7 +233,7 @@ int destroy_ctx(Ctx* c)
     if (c->d.ll) (void)hipFree(c->d.ll);
     if (c->moe.slots) (void)hipFree(c->moe.slots);
     if (c->ring) (void)hipFree(c->ring);
-    for (auto& p : c->plans) { (void)hipFree(p.ops); (void)hipFree(p.start); }
+    for (auto& p : c->plans) (void)hipFree(p.ops);
     if (c->moe.base) (void)hipFree(c->moe.base);
     if (c->snap) (void)hipFree(c->snap);
     delete c;
@@ -650,22 +652,101 @@ PlanOp plan_reduce_put(std::vector<PlanRef> src, std::vector<PlanRef> dst, int d
     return o;
 }
 
-// Same steps as k_allreduce_hb_fused / k_allreduce_ring, written as data.  nvec = 16-byte vectors per rank.
-void lower_allreduce(int algo, int n, int chans, size_t nvec, int threads, std::vector<PlanOp>* ops,
+// Ring scratch of `need` bytes: the context's own (grown on demand, which waits for the device), or, for a
+// prepared call, an allocation that call owns.
+int ring_scratch(Ctx* c, size_t need, void** out)
+{
+    if (t_record) {
+        void* p = nullptr;
+        if (hipMalloc(&p, need) != hipSuccess) return MSX_ERR_NOMEM;
+        t_record->owned.push_back(p);
+        *out = p;
+        return MSX_OK;
+    }
+    if (need > c->ring_bytes) {
+        HIPCHK(hipDeviceSynchronize());
+        if (c->ring) { HIPCHK(hipFree(c->ring)); c->ring = nullptr; c->ring_bytes = 0; }
+        if (hipMalloc(&c->ring, need) != hipSuccess) return MSX_ERR_NOMEM;
+        c->ring_bytes = need;
+    }
+    *out = c->ring;
+    return MSX_OK;
+}
+
+constexpr size_t kPlanCacheMax = 16;     // lowered plans a context keeps; the oldest goes first
+
+bool plan_algo(int algo)
+{
+    return algo == MSX_ALGO_PLAN_2PA_HB || algo == MSX_ALGO_PLAN_2PR_HB || algo == MSX_ALGO_PLAN_1PA_LL ||
+           algo == MSX_ALGO_PLAN_2PA_LL;
+}
+
+// Same steps as the hand-written kernels, written as data: k_allreduce_hb_fused (held == 0) or
+// k_allreduce_hb_phased (held = sums a thread holds per phase), k_allreduce_ring, k_allreduce_1pa_ll,
+// k_allreduce_2pa_ll.  nbytes = bytes per rank; the HB plans need whole 16-byte vectors split evenly.
+void lower_allreduce(int algo, int n, int chans, size_t nbytes, int threads, int held, std::vector<PlanOp>* ops,
                      std::vector<unsigned>* start)
 {
     start->assign((size_t)n * chans, 0);   // one more entry (the total) is appended at the end
-    const size_t cv = nvec / (size_t)n;
+    const size_t nvec = nbytes / 16, cv = nvec / (size_t)n;
+    const size_t P = (nbytes + 7) / 8, cp = (P + (size_t)n - 1) / (size_t)n;     // LL: packets per rank / per chunk
     for (int b = 0; b < n * chans; ++b) {
         const int rank = b % n, chan = b / n;
         (*start)[b] = (unsigned)ops->size();
         const short r = (short)rank;
-        if (algo == MSX_ALGO_PLAN_2PA_HB) {
+        const int peers = ((1 << n) - 1) & ~(1 << rank);
+        if (algo == MSX_ALGO_PLAN_1PA_LL || algo == MSX_ALGO_PLAN_2PA_LL) {
+            const bool one = algo == MSX_ALGO_PLAN_1PA_LL;
+            const size_t range = one ? P : cp;
+            auto packet_op = [&](int code, int to, unsigned chunk_stride, unsigned region) {
+                PlanOp o = plan_op(code, rank);
+                o.nsrc = o.ndst = 1;
+                o.src[0] = PlanRef{kBufIn, r};
+                o.dst[0] = PlanRef{kBufOut, r};
+                o.dst_wt = to;
+                o.aux = (unsigned)(range * 16);
+                o.aux2 = chunk_stride;
+                o.aux3 = region;
+                o.first = (size_t)chan * threads;
+                o.end = range;
+                o.step = (size_t)chans * threads;
+                return o;
+            };
+            ops->push_back(packet_op(kOpPutPacket, peers, one ? 0u : (unsigned)cp, 0u));
+            ops->push_back(packet_op(kOpReducePacket, one ? 0 : peers, one ? 0u : (unsigned)(rank * cp), 0u));
+            if (!one) ops->push_back(packet_op(kOpCopyPacket, 0, (unsigned)cp, (unsigned)((size_t)n * cp * 16)));
+        } else if (algo == MSX_ALGO_PLAN_2PA_HB) {
             std::vector<PlanRef> src, dst;
             for (short j = 0; j < n; ++j) { src.push_back({kBufIn, j}); dst.push_back({kBufOut, j}); }
             ops->push_back(plan_op(kOpBarrier));
-            ops->push_back(plan_reduce_put(src, dst, (1 << n) - 1, (size_t)rank * cv + (size_t)chan * threads,
-                                           (size_t)(rank + 1) * cv, (size_t)chans * threads));
+            if (held == 0) {
+                ops->push_back(plan_reduce_put(src, dst, (1 << n) - 1, (size_t)rank * cv + (size_t)chan * threads,
+                                               (size_t)(rank + 1) * cv, (size_t)chans * threads));
+            } else {
+                // rounds of a chip-wide read phase and a chip-wide write phase; tiles of `threads` vectors dealt
+                // out one by one over the rank's workgroups; every workgroup takes part in every barrier
+                const size_t tiles = cv / (size_t)threads, per_round = (size_t)chans * held;
+                const size_t rounds = (tiles + per_round - 1) / per_round;
+                for (size_t round = 0; round < rounds; ++round) {
+                    const size_t first = round * per_round + (size_t)chan;
+                    const size_t left = first >= tiles ? 0 : (tiles - first + (size_t)chans - 1) / (size_t)chans;
+                    const unsigned mine = (unsigned)(left < (size_t)held ? left : (size_t)held);
+                    PlanOp rd = plan_reduce_put(src, dst, (1 << n) - 1, (size_t)rank * cv + first * threads, 0,
+                                                (size_t)chans * threads);
+                    rd.code = kOpReduceHold;
+                    rd.aux = mine;
+                    PlanOp wr = rd;
+                    wr.code = kOpPutHeld;
+                    ops->push_back(rd);
+                    ops->push_back(plan_op(kOpGridBarrier, 0, 2));
+                    ops->push_back(wr);
+                    ops->push_back(plan_op(kOpDrain));
+                    ops->push_back(plan_op(kOpGridBarrier, 0, 1));
+                }
+                if (chan == 0 && tiles * threads < cv)      // what is left behind the chunk's last whole tile
+                    ops->push_back(plan_reduce_put(src, dst, (1 << n) - 1, (size_t)rank * cv + tiles * threads,
+                                                   (size_t)(rank + 1) * cv, (size_t)threads));
+            }
             ops->push_back(plan_op(kOpDrain));
             ops->push_back(plan_op(kOpBarrier));
         } else {
@@ -701,68 +782,82 @@ void lower_allreduce(int algo, int n, int chans, size_t nvec, int threads, std::
     start->push_back((unsigned)ops->size());
 }
 
-// Ring scratch of `need` bytes: the context's own (grown on demand, which waits for the device), or, for a
-// prepared call, an allocation that call owns.
-int ring_scratch(Ctx* c, size_t need, void** out)
+// The lists as the interpreter reads them: every workgroup's at a fixed stride, padded with end marks; a rank
+// barrier that every list begins with is taken out (the kernel runs it while the list is on its way) and
+// described by *head (bit 0: there is one; bits 1, 2: its flags).
+void pack_plan(const std::vector<PlanOp>& ops, const std::vector<unsigned>& start, std::vector<PlanOp>* packed,
+               unsigned* stride, int* head)
 {
-    if (t_record) {
-        void* p = nullptr;
-        if (hipMalloc(&p, need) != hipSuccess) return MSX_ERR_NOMEM;
-        t_record->owned.push_back(p);
-        *out = p;
-        return MSX_OK;
+    const size_t lists = start.size() - 1;
+    bool common = lists > 0;
+    for (size_t b = 0; b < lists && common; ++b) {
+        const PlanOp& o = ops[start[b]];
+        common = start[b + 1] - start[b] > 1 && o.code == kOpBarrier && o.flags == ops[start[0]].flags;
     }
-    if (need > c->ring_bytes) {
-        HIPCHK(hipDeviceSynchronize());
-        if (c->ring) { HIPCHK(hipFree(c->ring)); c->ring = nullptr; c->ring_bytes = 0; }
-        if (hipMalloc(&c->ring, need) != hipSuccess) return MSX_ERR_NOMEM;
-        c->ring_bytes = need;
-    }
-    *out = c->ring;
-    return MSX_OK;
+    *head = common ? 1 | (ops[start[0]].flags << 1) : 0;
+    const unsigned skip = common ? 1u : 0u;
+    unsigned longest = 1;
+    for (size_t b = 0; b < lists; ++b) longest = std::max(longest, start[b + 1] - start[b] - skip);
+    *stride = longest;
+    packed->assign(lists * longest, plan_op(kOpEnd));
+    for (size_t b = 0; b < lists; ++b)
+        for (unsigned k = start[b] + skip; k < start[b + 1]; ++k) (*packed)[b * longest + (k - start[b] - skip)] = ops[k];
 }
-
-constexpr size_t kPlanCacheMax = 16;     // lowered plans a context keeps; the oldest goes first
 
 int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nbytes, int dtype, int n, int algo,
                    hipStream_t stream)
 {
-    if (nbytes % (16 * (size_t)n)) return MSX_ERR_UNSUPPORTED;
-    const size_t nvec = nbytes / 16;
-    const void* kp = dtype == MSX_F32 ? (const void*)k_plan_executor<0> : (const void*)k_plan_executor<1>;
-    const int threads = 256;
-    int chans = 1, rc;
     const bool ring = algo == MSX_ALGO_PLAN_2PR_HB;
-    int want = g_opt.hb_blocks, unroll_unused = 1;
-    const size_t per_rank = nvec / (size_t)n;
-    if (!ring) choose_hb_shape(nbytes, n, threads, &unroll_unused, &want);   // same shape as the hand kernel
-    if ((rc = pick_channels(c, kp, threads, n, per_rank, 4, want, ring ? 64 : kMaxChannels, &chans))) return rc;
+    const bool packets = algo == MSX_ALGO_PLAN_1PA_LL || algo == MSX_ALGO_PLAN_2PA_LL;
+    const int threads = 256;
+    int chans = 1, rc, held = 0;
+    const void* kp = dtype == MSX_F32 ? (const void*)k_plan_executor<0, 0> : (const void*)k_plan_executor<1, 0>;
+    if (packets) {
+        if (nbytes % 2) return MSX_ERR_UNSUPPORTED;
+        const size_t P = (nbytes + 7) / 8, cp = (P + (size_t)n - 1) / (size_t)n;
+        const size_t need = algo == MSX_ALGO_PLAN_1PA_LL ? (size_t)n * P * 16 : 2 * (size_t)n * cp * 16;
+        if (need > c->d.ll_rot_stride) return MSX_ERR_NOMEM;
+        const size_t work = algo == MSX_ALGO_PLAN_1PA_LL ? P : cp;
+        if ((rc = pick_channels(c, kp, threads, n, work, 1, g_opt.ll_blocks, 64, &chans))) return rc;
+    } else {
+        if (nbytes % (16 * (size_t)n)) return MSX_ERR_UNSUPPORTED;
+        const size_t per_rank = nbytes / 16 / (size_t)n;
+        int want = g_opt.hb_blocks, unroll_unused = 1;
+        if (!ring) choose_hb_shape(nbytes, n, threads, &unroll_unused, &want);   // same shape as the hand kernel
+        size_t per_thread = 4;
+        int cap = ring ? 64 : kMaxChannels;
+        if (!ring && n == 8 && use_phased(nbytes, n, 0)) {
+            // very large messages: the read phase / write phase schedule, one workgroup per CU
+            held = kPhasedHeld;
+            kp = plan_executor_held(dtype == MSX_F32);
+            want = g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels;
+            per_thread = (size_t)held;
+        }
+        if ((rc = pick_channels(c, kp, threads, n, per_rank, per_thread, want, cap, &chans))) return rc;
+    }
     void* ring_mem = nullptr;
     if (ring && (rc = ring_scratch(c, nbytes * (size_t)n, &ring_mem))) return rc;
-    Ctx::Plan found{algo, n, chans, nbytes, nullptr, nullptr};
+    Ctx::Plan found{algo, n, chans, held, nbytes, nullptr, 0u, 0};
     if (!t_record)
         for (const auto& p : c->plans)
-            if (p.algo == algo && p.n == n && p.chans == chans && p.nbytes == nbytes) found = p;
+            if (p.algo == algo && p.n == n && p.chans == chans && p.held == held && p.nbytes == nbytes) found = p;
     if (!found.ops) {
-        std::vector<PlanOp> ops;
+        std::vector<PlanOp> ops, packed;
         std::vector<unsigned> start;
-        lower_allreduce(algo, n, chans, nvec, threads, &ops, &start);
-        if (hipMalloc((void**)&found.ops, ops.size() * sizeof(PlanOp)) != hipSuccess) return MSX_ERR_NOMEM;
-        if (hipMalloc((void**)&found.start, start.size() * sizeof(unsigned)) != hipSuccess) { (void)hipFree(found.ops); return MSX_ERR_NOMEM; }
+        lower_allreduce(algo, n, chans, nbytes, threads, held, &ops, &start);
+        pack_plan(ops, start, &packed, &found.stride, &found.head);
+        if (hipMalloc((void**)&found.ops, packed.size() * sizeof(PlanOp)) != hipSuccess) return MSX_ERR_NOMEM;
         if (t_record) {                                  // a prepared call keeps its plan for itself
             t_record->owned.push_back(found.ops);
-            t_record->owned.push_back(found.start);
         } else {
             if (c->plans.size() >= kPlanCacheMax) {      // a launch in flight may still be reading the oldest one
                 HIPCHK(hipDeviceSynchronize());
                 (void)hipFree(c->plans.front().ops);
-                (void)hipFree(c->plans.front().start);
                 c->plans.erase(c->plans.begin());
             }
             c->plans.push_back(found);
         }
-        HIPCHK(hipMemcpy(found.ops, ops.data(), ops.size() * sizeof(PlanOp), hipMemcpyHostToDevice));
-        HIPCHK(hipMemcpy(found.start, start.data(), start.size() * sizeof(unsigned), hipMemcpyHostToDevice));
+        HIPCHK(hipMemcpy(found.ops, packed.data(), packed.size() * sizeof(PlanOp), hipMemcpyHostToDevice));
     }
     PlanArgs a{};
     for (int i = 0; i < n; ++i) {
@@ -771,8 +866,12 @@ int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nb
         a.scratch[i] = ring ? (void*)((char*)ring_mem + (size_t)i * nbytes) : nullptr;
     }
     a.ops = found.ops;
-    a.start = found.start;
+    a.nbytes = nbytes;
+    a.stride = found.stride;
     a.n = n;
+    a.head = found.head;
+    a.packets = packets ? 1 : 0;
+    a.pace = g_opt.hb_pace;
     note_launch(n * chans, threads, algo);
     typedef void (*K)(PlanArgs, DevCtx);
     return launch((K)kp, n * chans, threads, stream, a, dev_ctx(c));
@@ -816,7 +915,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
 {
     int rc = check_common(dtype, op, nranks);
     if (rc) return rc;
-    if (algo < MSX_ALGO_AUTO || algo > MSX_ALGO_PLAN_2PR_HB) return MSX_ERR_ARG;
+    if (algo < MSX_ALGO_AUTO || algo > MSX_ALGO_PLAN_2PA_LL) return MSX_ERR_ARG;
     if ((rc = check_table(send, nranks))) return rc;
     if ((rc = check_table((const void* const*)recv, nranks))) return rc;
     if (residual && (rc = check_table(residual, nranks))) return rc;
@@ -828,8 +927,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     if (fixed_ctx) {
         // nothing below may allocate: the ring's and the interpreter's scratch grow on demand, so they are out
         if (nbytes > kStaticMaxBytes) return MSX_ERR_NOMEM;
-        if (algo == MSX_ALGO_2PR_HB || algo == MSX_ALGO_PLAN_2PA_HB || algo == MSX_ALGO_PLAN_2PR_HB)
-            return MSX_ERR_UNSUPPORTED;
+        if (algo == MSX_ALGO_2PR_HB || plan_algo(algo)) return MSX_ERR_UNSUPPORTED;
         if ((rc = get_static_ctx(stream, &c))) return rc;
     } else if ((rc = get_ctx(&c))) return rc;
     const int n = nranks;
@@ -874,11 +972,11 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
         return launch(k, n * chans, threads, stream, a, dev_ctx(c));
     }
 
-    if ((algo == MSX_ALGO_PLAN_2PA_HB || algo == MSX_ALGO_PLAN_2PR_HB) && n > 1) {
+    if (plan_algo(algo) && n > 1) {
         if (residual) return MSX_ERR_UNSUPPORTED;
         return plan_allreduce(c, send, recv, nbytes, dtype, n, algo, stream);
     }
-    if (algo == MSX_ALGO_PLAN_2PA_HB || algo == MSX_ALGO_PLAN_2PR_HB) algo = MSX_ALGO_2PA_HB;
+    if (plan_algo(algo)) algo = MSX_ALGO_2PA_HB;
     if (algo == MSX_ALGO_2PR_HB && n == 1) algo = MSX_ALGO_2PA_HB;
     if (algo == MSX_ALGO_2PR_HB) {
         // two-phase ring: n equal chunks of whole 16-byte vectors, no residual
@@ -1895,6 +1993,8 @@ int msx_set_option(const char* key, const char* value)
         else if (v == "2pr_hb") g_opt.algo = MSX_ALGO_2PR_HB;
         else if (v == "plan_2pa_hb") g_opt.algo = MSX_ALGO_PLAN_2PA_HB;
         else if (v == "plan_2pr_hb") g_opt.algo = MSX_ALGO_PLAN_2PR_HB;
+        else if (v == "plan_1pa_ll") g_opt.algo = MSX_ALGO_PLAN_1PA_LL;
+        else if (v == "plan_2pa_ll") g_opt.algo = MSX_ALGO_PLAN_2PA_LL;
         else return MSX_ERR_ARG;
         return MSX_OK;
     }
@@ -1993,7 +2093,7 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
     unsigned long long u = 0;
     if (k == "algo") {
         static const char* names[] = {"auto", "1pa_ll", "2pa_ll", "2pa_hb", "2pa_hb_2phase", "2pr_hb",
-                                      "plan_2pa_hb", "plan_2pr_hb"};
+                                      "plan_2pa_hb", "plan_2pr_hb", "plan_1pa_ll", "plan_2pa_ll"};
         snprintf(value_out, value_len, "%s", names[g_opt.algo]);
         return MSX_OK;
     }
@@ -2084,22 +2184,32 @@ int msx_debug_pace_update(uint32_t state[4], uint64_t took_ticks, uint32_t tiles
     return MSX_OK;
 }
 
-int msx_debug_lower_plan(int algo, int nranks, int blocks_per_rank, size_t vectors_per_rank, int threads,
-                         void* ops_out, size_t ops_capacity, uint32_t* start_out, size_t* ops_written)
+int msx_debug_lower_plan_ex(int algo, int nranks, int blocks_per_rank, size_t nbytes, int threads, int held,
+                            void* ops_out, size_t ops_capacity, uint32_t* start_out, size_t* ops_written)
 {
-    if ((algo != MSX_ALGO_PLAN_2PA_HB && algo != MSX_ALGO_PLAN_2PR_HB) || nranks < 2 || nranks > kMaxRanks ||
-        blocks_per_rank < 1 || blocks_per_rank > kMaxChannels || threads < 1 || !ops_written ||
-        vectors_per_rank % (size_t)nranks)
+    if (!plan_algo(algo) || nranks < 2 || nranks > kMaxRanks || blocks_per_rank < 1 ||
+        blocks_per_rank > kMaxChannels || threads < 1 || !ops_written || held < 0 || held > 64)
         return MSX_ERR_ARG;
+    const bool packets = algo == MSX_ALGO_PLAN_1PA_LL || algo == MSX_ALGO_PLAN_2PA_LL;
+    if (packets ? (nbytes % 2 != 0 || held != 0) : (nbytes % (16 * (size_t)nranks) != 0)) return MSX_ERR_ARG;
+    if (held && algo != MSX_ALGO_PLAN_2PA_HB) return MSX_ERR_ARG;
     std::vector<PlanOp> ops;
     std::vector<unsigned> start;
-    lower_allreduce(algo, nranks, blocks_per_rank, vectors_per_rank, threads, &ops, &start);
+    lower_allreduce(algo, nranks, blocks_per_rank, nbytes, threads, held, &ops, &start);
     *ops_written = ops.size();
     if (!ops_out || !start_out) return MSX_OK;           // size query
     if (ops.size() > ops_capacity) return MSX_ERR_NOMEM;
     memcpy(ops_out, ops.data(), ops.size() * sizeof(PlanOp));
     memcpy(start_out, start.data(), start.size() * sizeof(unsigned));
     return MSX_OK;
+}
+
+int msx_debug_lower_plan(int algo, int nranks, int blocks_per_rank, size_t vectors_per_rank, int threads,
+                         void* ops_out, size_t ops_capacity, uint32_t* start_out, size_t* ops_written)
+{
+    if (algo != MSX_ALGO_PLAN_2PA_HB && algo != MSX_ALGO_PLAN_2PR_HB) return MSX_ERR_ARG;
+    return msx_debug_lower_plan_ex(algo, nranks, blocks_per_rank, vectors_per_rank * 16, threads, 0, ops_out,
+                                   ops_capacity, start_out, ops_written);
 }
 
 int msx_last_launch(int* grid, int* block, int* algo)

@@ -28,20 +28,22 @@ struct LlArgs {
 __device__ __forceinline__ u32x2 load_words(const void* base, size_t k, size_t nbytes)
 {
     const size_t off = k * 8;
-    if (off + 8 <= nbytes) return *(const u32x2*)((const char*)base + off);
+    const MSX_GLOBAL char* b = (const MSX_GLOBAL char*)base;
+    if (off + 8 <= nbytes) return *(const MSX_GLOBAL u32x2*)(b + off);
     unsigned h[4] = {0, 0, 0, 0};
     for (int i = 0; i < 4; ++i)
-        if (off + 2 * i + 2 <= nbytes) h[i] = *(const unsigned short*)((const char*)base + off + 2 * i);
+        if (off + 2 * i + 2 <= nbytes) h[i] = *(const MSX_GLOBAL unsigned short*)(b + off + 2 * i);
     return u32x2{h[0] | (h[1] << 16), h[2] | (h[3] << 16)};
 }
 
 __device__ __forceinline__ void store_words(void* base, size_t k, size_t nbytes, u32x2 w)
 {
     const size_t off = k * 8;
-    if (off + 8 <= nbytes) { *(u32x2*)((char*)base + off) = w; return; }
+    MSX_GLOBAL char* b = (MSX_GLOBAL char*)base;
+    if (off + 8 <= nbytes) { *(MSX_GLOBAL u32x2*)(b + off) = w; return; }
     const unsigned h[4] = {w.x & 0xffffu, w.x >> 16, w.y & 0xffffu, w.y >> 16};
     for (int i = 0; i < 4; ++i)
-        if (off + 2 * i + 2 <= nbytes) *(unsigned short*)((char*)base + off + 2 * i) = (unsigned short)h[i];
+        if (off + 2 * i + 2 <= nbytes) *(MSX_GLOBAL unsigned short*)(b + off + 2 * i) = (unsigned short)h[i];
 }
 
 // Poll packet `pos` of slots j != me (j < n_l) of my scratch until all carry the flag.  Used inside the
@@ -90,7 +92,8 @@ __global__ __launch_bounds__(1024) void k_allreduce_1pa_ll(LlArgs a, DevCtx c)
 
     // send: my packet k goes to slot `rank` of every peer, all peers before any wait
     for (unsigned k = rt; k < P; k += RT) {
-        const u32x2 w = k == rt ? first : load_words(a.in[rank], k, a.nbytes);
+        u32x2 w = k == rt ? first : load_words(a.in[rank], k, a.nbytes);
+        settle(w);
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
             if (p < n_l && p != rank_l)
@@ -150,6 +153,8 @@ __global__ __launch_bounds__(1024) void k_allreduce_2pa_ll(LlArgs a, DevCtx c)
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
             if (p < n_l && p != rank_l && (unsigned)p * cp + q < P) w[p] = load_words(a.in[rank], (size_t)p * cp + q, a.nbytes);
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p) settle(w[p]);      // one wait for all the loads, none between the stores
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
             if (p < n_l && p != rank_l && (unsigned)p * cp + q < P)
@@ -258,7 +263,8 @@ __global__ __launch_bounds__(1024) void k_allgather_ll(LlCollArgs a, DevCtx c)
     char* const mine = (char*)a.out[rank] + (size_t)rank * a.nbytes;
     chaos_delay(c, 90);
     for (unsigned k = rt; k < P; k += RT) {
-        const u32x2 w = load_words(a.in[rank], k, a.nbytes);
+        u32x2 w = load_words(a.in[rank], k, a.nbytes);
+        settle(w);
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
             if (p < n_l && p != rank_l)
@@ -301,6 +307,8 @@ __global__ __launch_bounds__(1024) void k_reducescatter_ll(LlCollArgs a, DevCtx 
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
             if (p < n_l && p != rank_l) w[p] = load_words((const char*)a.in[rank] + (size_t)p * a.nbytes, k, a.nbytes);
+#pragma unroll
+        for (int p = 0; p < kMaxRanks; ++p) settle(w[p]);
 #pragma unroll
         for (int p = 0; p < kMaxRanks; ++p)
             if (p < n_l && p != rank_l)

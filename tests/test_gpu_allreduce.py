@@ -349,6 +349,51 @@ def test_plan_interpreter_runs_the_same_algorithms(msx, orc, n, dtype):
         msx.set_option("chaos", "0")
 
 
+@pytest.mark.parametrize("n", [1, 2, 3, 5, 7, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_plan_interpreter_runs_the_packet_algorithms(msx, orc, n, dtype):
+    """1PA-LL and 2PA-LL from packet operations: bit-identical to the oracle (and so to the hand kernels),
+    scrambled timing, ragged sizes down to a single element, in place and out of place."""
+    esz = 4 if dtype == torch.float32 else 2
+    for count in [1 if esz == 4 else 2, 6, 510, 4096, 4098, 20000 + 2 * n, 131072 + 26]:
+        x = synth.int_valued_f32(n, count, seed=count) if dtype == torch.float32 else synth.normal(n, count, seed=count)
+        want = _oracle(orc, x)
+        msx.set_option("chaos", str(3 + count))
+        for algo in (8, 9):
+            if algo == 8 and count * esz > 32768:
+                continue
+            for inplace in (False, True):
+                for r, o in enumerate(_run_ex(msx, x, algo, inplace=inplace)):
+                    assert np.array_equal(o.view(np.uint8), want.view(np.uint8)), (algo, n, count, r, inplace)
+        msx.set_option("chaos", "0")
+    # many calls in a row: the flag epoch and the scratch rotation advance as for the hand kernels, which may
+    # be mixed in freely
+    x = synth.normal(n, 3000, seed=77) if dtype == torch.bfloat16 else synth.int_valued_f32(n, 3000, seed=77)
+    want = _oracle(orc, x)
+    for k in range(12):
+        algo = (8, 9, 1, 2)[k % 4]
+        assert np.array_equal(_run_ex(msx, x, algo)[n - 1].view(np.uint8), want.view(np.uint8)), (k, algo)
+
+
+def test_plan_interpreter_runs_the_phased_schedule(phased, orc):
+    """MSX_ALGO_PLAN_2PA_HB at sizes where the hand kernel runs in chip-wide phases: lowered to the same
+    schedule (reduce and hold, chip-wide barrier, put what is held), several rounds, partial last rounds."""
+    msx = phased
+    n = 8
+    for blocks, vecs_per_chunk in [(1, 256 * 64 * 2 + 256 * 5 + 77), (2, 256 * 64 * 2 * 2 + 256 * 64 + 1), (1, 255),
+                                   (2, 256 * 64 * 2), (0, 256 * 70 + 9)]:
+        count = vecs_per_chunk * n * 8
+        msx.set_option("hb_blocks_per_rank", str(blocks))
+        msx.set_option("chaos", str(blocks * 5 + 1))
+        x = synth.normal(n, count, seed=vecs_per_chunk)
+        want = _oracle(orc, x)
+        for inplace in (False, True):
+            outs = _run_ex(msx, x, 6, inplace=inplace)
+            for r in range(n):
+                assert np.array_equal(outs[r], want), (blocks, vecs_per_chunk, r, inplace)
+        assert np.array_equal(_run_ex(msx, x, 3)[5], want)           # the hand kernel on the same launch shape
+
+
 def test_plan_interpreter_argument_checks_and_dead_rank(msx, orc):
     send = [torch.zeros(100, dtype=torch.bfloat16, device="cuda") for _ in range(8)]
     for algo in (6, 7):
@@ -359,7 +404,7 @@ def test_plan_interpreter_argument_checks_and_dead_rank(msx, orc):
     msx.set_option("spin_limit", "2000")
     msx.set_option("drop_rank", "2")
     try:
-        for algo in (6, 7):
+        for algo in (6, 7, 8, 9):
             s_ = [x[r].clone().cuda() for r in range(8)]
             r_ = [torch.empty_like(t) for t in s_]
             msx.allreduce_ex(s_, r_, None, algo=algo)
@@ -377,7 +422,7 @@ def test_plan_interpreter_argument_checks_and_dead_rank(msx, orc):
 
 @pytest.fixture
 def phased(msx):
-    """Forces the phased form of the fused HB kernel at any size (by default it starts at 128 MiB per rank)."""
+    """Forces the phased form of the fused HB kernel at any size (by default it starts at 40 MiB per rank, 8 ranks)."""
     old = msx.get_option("hb_phased_min_bytes")
     msx.set_option("hb_phased_min_bytes", "0")
     yield msx

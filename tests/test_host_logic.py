@@ -15,11 +15,13 @@ class PlanRef(C.Structure):
 
 class PlanOp(C.Structure):
     _fields_ = [("code", C.c_int), ("peer", C.c_int), ("flags", C.c_int), ("nsrc", C.c_int), ("ndst", C.c_int),
-                ("src", PlanRef * 9), ("dst", PlanRef * 8), ("dst_wt", C.c_int),
-                ("first", C.c_uint64), ("end", C.c_uint64), ("step", C.c_uint64), ("_pad", C.c_uint64)]
+                ("src", PlanRef * 9), ("dst", PlanRef * 8), ("dst_wt", C.c_int), ("aux", C.c_uint32),
+                ("first", C.c_uint64), ("end", C.c_uint64), ("step", C.c_uint64),
+                ("aux2", C.c_uint32), ("aux3", C.c_uint32)]
 
 
-END, BARRIER, SIGNAL, WAIT, REDUCE_PUT, DRAIN = range(6)
+END, BARRIER, SIGNAL, WAIT, REDUCE_PUT, DRAIN, PUT_PACKET, REDUCE_PACKET, COPY_PACKET, REDUCE_HOLD, GRID_BARRIER, \
+    PUT_HELD = range(12)
 IN, OUT, SCRATCH = range(3)
 
 
@@ -40,9 +42,24 @@ def lower(L, algo, n, chans, vecs_per_rank, threads):
     return ops, list(start)
 
 
+def lower_ex(L, algo, n, chans, nbytes, threads, held=0):
+    written = C.c_size_t(0)
+    assert L.msx_debug_lower_plan_ex(algo, n, chans, nbytes, threads, held, None, 0, None, C.byref(written)) == 0
+    ops = (PlanOp * written.value)()
+    start = (C.c_uint32 * (n * chans + 1))()
+    assert L.msx_debug_lower_plan_ex(algo, n, chans, nbytes, threads, held, ops, written.value, start,
+                                     C.byref(written)) == 0
+    return ops, list(start)
+
+
 def simulate(ops, start, n, chans, threads, x, ring_order_rounding=None):
-    """x: [n, V] float64 'vectors'.  Returns out [n, V].  Each workgroup runs until it blocks."""
+    """x: [n, V] float64 'vectors' (for packet operations: one value per 8-byte packet).  Returns out [n, V].
+    Each workgroup runs until it blocks.  LL scratch: per rank a dict byte offset -> value (a packet that is
+    there carries the call's flag); the chip-wide barrier: a generation count per workgroup."""
     V = x.shape[1]
+    ll = [dict() for _ in range(n)]
+    grid_gen = [0] * (n * chans)
+    held = [dict() for _ in range(n * chans)]
     bufs = {IN: x.copy(), OUT: np.full((n, V), np.nan), SCRATCH: np.full((n, V), np.nan)}
     sem = np.zeros((n, n, chans), np.int64)          # [recv][send][chan]
     expected = np.zeros((n, n, chans), np.int64)
@@ -99,6 +116,66 @@ def simulate(ops, start, n, chans, threads, x, ring_order_rounding=None):
                         assert op.dst_wt & (1 << k), "remote destination written with an ordinary store"
             elif op.code == DRAIN:
                 pass
+            elif op.code == PUT_PACKET:
+                for t in range(threads):
+                    for q in range(op.first + t, op.end, op.step):
+                        for p_ in range(n):
+                            if (op.dst_wt >> p_) & 1 and op.aux2 * p_ + q < V:
+                                assert p_ != rank
+                                off = op.aux3 + op.peer * op.aux + q * 16
+                                assert off not in ll[p_], "a packet slot written twice in one call"
+                                ll[p_][off] = bufs[op.src[0].kind][op.src[0].rank, op.aux2 * p_ + q]
+            elif op.code == REDUCE_PACKET:
+                qs = [q for t in range(threads) for q in range(op.first + t, op.end, op.step) if op.aux2 + q < V]
+                need = [op.aux3 + j * op.aux + q * 16 for q in qs for j in range(n) if j != op.peer]
+                if not all(o in ll[rank] for o in need):
+                    return progressed                                  # still polling
+                for q in qs:
+                    k = op.aux2 + q
+                    acc = None
+                    for j in range(n):                                 # rank order, mine among them
+                        v = bufs[op.src[0].kind][op.src[0].rank, k] if j == op.peer else ll[rank][op.aux3 + j * op.aux + q * 16]
+                        acc = v if acc is None else acc + v
+                    bufs[op.dst[0].kind][op.dst[0].rank, k] = acc
+                    touched[op.dst[0].kind, op.dst[0].rank, k] += 1
+                    for p_ in range(n):
+                        if (op.dst_wt >> p_) & 1:
+                            off = op.aux3 + n * op.aux + op.peer * op.aux + q * 16
+                            assert off not in ll[p_]
+                            ll[p_][off] = acc
+            elif op.code == COPY_PACKET:
+                want = [(j, q) for t in range(threads) for q in range(op.first + t, op.end, op.step)
+                        for j in range(n) if j != op.peer and op.aux2 * j + q < V]
+                if not all(op.aux3 + j * op.aux + q * 16 in ll[rank] for j, q in want):
+                    return progressed
+                for j, q in want:
+                    bufs[op.dst[0].kind][op.dst[0].rank, op.aux2 * j + q] = ll[rank][op.aux3 + j * op.aux + q * 16]
+                    touched[op.dst[0].kind, op.dst[0].rank, op.aux2 * j + q] += 1
+            elif op.code == REDUCE_HOLD:
+                held[b] = {}
+                for t in range(threads):
+                    for h in range(op.aux):
+                        i = op.first + t + h * op.step
+                        acc = bufs[op.src[0].kind][op.src[0].rank, i]
+                        for k in range(1, op.nsrc):
+                            acc = acc + bufs[op.src[k].kind][op.src[k].rank, i]
+                        held[b][(t, h)] = acc
+            elif op.code == PUT_HELD:
+                for t in range(threads):
+                    for h in range(op.aux):
+                        i = op.first + t + h * op.step
+                        for k in range(op.ndst):
+                            d = op.dst[k]
+                            bufs[d.kind][d.rank, i] = held[b][(t, h)]
+                            touched[d.kind, d.rank, i] += 1
+            elif op.code == GRID_BARRIER:
+                if barrier_phase[b] == 0:
+                    grid_gen[b] += 1
+                    barrier_phase[b] = 1
+                    progressed = True
+                if min(grid_gen) < grid_gen[b]:
+                    return progressed
+                barrier_phase[b] = 0
             else:
                 raise AssertionError(f"unknown op {op.code}")
             pc[b] += 1
@@ -156,6 +233,44 @@ def test_lowered_ring_plan_computes_the_allreduce_in_ring_order(L, n, chans, thr
     assert np.all(touched[SCRATCH].sum(axis=1) == (n - 1) * cv)
 
 
+@pytest.mark.parametrize("n", [2, 3, 8])
+@pytest.mark.parametrize("chans,threads,P", [(1, 4, 1), (3, 4, 7), (2, 8, 64), (5, 16, 333), (1, 64, 8 * 64 + 1)])
+@pytest.mark.parametrize("algo", [8, 9])
+def test_lowered_packet_plans_compute_the_allreduce(L, algo, n, chans, threads, P):
+    """1PA and 2PA over LL packets as lowered plans: every packet slot is written once, every poll is
+    answered, every output packet is produced exactly once, sums are taken in rank order."""
+    ops, start = lower_ex(L, algo, n, chans, P * 8, threads)
+    codes = [ops[k].code for k in range(start[0], start[1])]
+    assert codes == ([PUT_PACKET, REDUCE_PACKET, END] if algo == 8 else [PUT_PACKET, REDUCE_PACKET, COPY_PACKET, END])
+    rng = np.random.default_rng(P + n)
+    x = rng.integers(-1000, 1001, (n, P)).astype(np.float64)
+    out, touched = simulate(ops, start, n, chans, threads, x)
+    assert np.array_equal(out, np.tile(x.sum(0), (n, 1)))
+    assert np.all(touched[OUT] == 1)
+
+
+@pytest.mark.parametrize("chans,threads,held,cv", [(1, 4, 4, 4 * 4 * 3), (3, 4, 4, 4 * 50 + 3), (2, 8, 8, 8 * 8 * 2 * 2),
+                                                   (4, 4, 64, 4 * 300 + 1), (2, 4, 4, 3)])
+def test_lowered_phased_plan_computes_the_allreduce(L, chans, threads, held, cv):
+    """The read phase / write phase schedule as a plan: all workgroups pass the same number of chip-wide
+    barriers, no workgroup holds more than `held` tiles, every output vector is written exactly once."""
+    n = 8
+    V = cv * n
+    ops, start = lower_ex(L, 6, n, chans, V * 16, threads, held)
+    per_wg = []
+    for b in range(n * chans):
+        lst = [ops[k] for k in range(start[b], start[b + 1])]
+        per_wg.append(sum(1 for o in lst if o.code == GRID_BARRIER))
+        assert all(o.aux <= held for o in lst if o.code in (REDUCE_HOLD, PUT_HELD))
+        assert lst[0].code == BARRIER and lst[-2].code == BARRIER and lst[-1].code == END
+    assert len(set(per_wg)) == 1
+    rng = np.random.default_rng(V)
+    x = rng.integers(-1000, 1001, (n, V)).astype(np.float64)
+    out, touched = simulate(ops, start, n, chans, threads, x)
+    assert np.array_equal(out, np.tile(x.sum(0), (n, 1)))
+    assert np.all(touched[OUT] == 1)
+
+
 def test_lower_plan_argument_checks(L):
     w = C.c_size_t(0)
     assert L.msx_debug_lower_plan(3, 8, 1, 64, 256, None, 0, None, C.byref(w)) == -1      # not a plan algorithm
@@ -165,6 +280,10 @@ def test_lower_plan_argument_checks(L):
     ops = (PlanOp * 4)()
     start = (C.c_uint32 * 17)()
     assert L.msx_debug_lower_plan(6, 8, 2, 64, 256, ops, 4, start, C.byref(w)) == -5       # buffer too small
+    assert L.msx_debug_lower_plan_ex(8, 8, 1, 1001, 256, 0, None, 0, None, C.byref(w)) == -1   # odd byte count
+    assert L.msx_debug_lower_plan_ex(9, 8, 1, 1000, 256, 64, None, 0, None, C.byref(w)) == -1  # packets hold nothing
+    assert L.msx_debug_lower_plan_ex(7, 8, 1, 1024, 256, 64, None, 0, None, C.byref(w)) == -1  # the ring neither
+    assert L.msx_debug_lower_plan_ex(8, 8, 1, 1000, 256, 0, None, 0, None, C.byref(w)) == 0 and w.value == 8 * 3
 
 
 def test_automatic_choice_and_launch_shapes(L):
