@@ -93,6 +93,9 @@ def parse(path):
             if "Loop Header" in line:
                 loop = label
             cur = [label, loop]
+            mm = re.search(r'Parent Loop (BB\d+_\d+) Depth', line)    # the outermost parent shares the label's line
+            if mm:
+                parents.setdefault((fn, label), []).append(mm.group(1))
             continue
         if re.match(r'^\s+;', line):            # further comment lines of a loop header block
             if "Loop Header" in line:
@@ -146,7 +149,9 @@ def serialised_store_findings(path, limit=3):
     The write-through stores are inline assembly, so the compiler does not know they are in flight.  When a
     conditional store is the first use of a loaded register it waits for ALL memory operations there, which
     also drains the stores already issued: a sequence of per-peer stores then runs one round trip at a time
-    (`settle()` in csrc/msx_device.hpp consumes the loaded vector once, before the stores).
+    (`settle()` in csrc/msx_device.hpp consumes the loaded vector once, before the stores).  The LL packet
+    stores are builtins, which the compiler counts, but across the per-peer conditions it falls back to the
+    same full wait: they are checked too (the first phase of 2PA-LL ran seven store round trips in a row).
     -> [(function, stores behind a full wait, write-through stores)]"""
     found = []
     fn, prev, stores, waited = None, [], 0, 0
@@ -165,9 +170,13 @@ def serialised_store_findings(path, limit=3):
             continue
         if not t or t.startswith(";") or t.startswith("."):
             continue
-        if t.startswith("global_store_dwordx4") and " sc1" in t:
+        # write-through puts, and the LL packet stores (a packet store sits up to eight instructions behind its
+        # wait: the four moves that assemble {w0, flag, w1, flag} and the descriptor set-up come in between)
+        put = t.startswith("global_store_dwordx4") and " sc1" in t
+        packet = t.startswith("buffer_store_dwordx4") and " sc1" in t
+        if put or packet:
             stores += 1
-            if any(p.startswith("s_waitcnt") and "vmcnt(0)" in p for p in prev[-3:]):
+            if any(p.startswith("s_waitcnt") and "vmcnt(0)" in p for p in prev[-(3 if put else 8):]):
                 waited += 1
         prev.append(t)
     return found
