@@ -94,8 +94,16 @@ typedef enum {
                                the plan (blocks).  Large messages (where MSX_ALGO_2PA_HB runs in chip-wide read
                                and write phases) are lowered to that schedule too. */
     MSX_ALGO_PLAN_1PA_LL = 8, /* MSX_ALGO_1PA_LL and MSX_ALGO_2PA_LL run by the same interpreter from packet */
-    MSX_ALGO_PLAN_2PA_LL = 9  /* operations (put packets, reduce packets, copy packets): any even byte count within
+    MSX_ALGO_PLAN_2PA_LL = 9, /* operations (put packets, reduce packets, copy packets): any even byte count within
                                the LL limit, no residual. */
+    MSX_ALGO_2PR_PORT = 10  /* the two-phase ring over the PortChannel, as in the paper's overlapped ring example:
+                               every chunk travels in two halves, copied by the port (FIFO in host memory, CPU proxy,
+                               runtime device-to-device copies) while the rank's threads reduce the other half.  Same
+                               sums, same order and rounding as MSX_ALGO_2PR_HB (bit-identical results); same size
+                               rule, no residual.  The proxy thread is told of every launch, so the call can be
+                               neither prepared nor captured into a graph (MSX_ERR_UNSUPPORTED), and the stream must
+                               not share a hardware queue with the proxy's own stream (a non-blocking stream the
+                               library creates on first use; the null stream and torch's streams are fine). */
 } msx_algo;
 
 /* ------------------------------------------------------------------------------------
@@ -274,9 +282,12 @@ int msx_prim_put_signal_wait(const void* src, void* staging, void* dst, size_t n
 
 /* PortChannel hand-off (port-mapped I/O, emulated): rank 0 pushes put(src -> staging), signal and
  * flush requests into a FIFO in host memory; a CPU proxy thread of the library carries them out
- * (hipMemcpyAsync device to device on its own stream, semaphore increment after the copy, tail
- * advance on flush); rank 1 waits on the semaphore, then copies staging -> dst with its threads.
- * The first call starts the proxy thread and allocates the FIFO (blocks once). */
+ * (hipMemcpyAsync device to device on its own stream; the signal is a one-wave kernel behind the copy
+ * on that stream, which bumps rank 1's device-side semaphores; the flush is reported once an event
+ * behind the copy has fired); rank 1 waits on its semaphores, then copies staging -> dst with its
+ * threads.  The first call starts the proxy thread and allocates the FIFOs (blocks once).  If the
+ * proxy runs into a HIP error it stops copying and signalling (the waiters time out) and msx_status
+ * returns MSX_ERR_HIP. */
 int msx_prim_port_put_signal_wait(const void* src, void* staging, void* dst, size_t nbytes, void* stream);
 
 /* LL encode only: write ceil(nbytes/8) 16-byte packets {w0, flag, w1, flag} for src into
@@ -325,7 +336,7 @@ int msx_last_status(void* ctx, int* rank, int* site, unsigned* expected, unsigne
 
 /* Options (strings; numbers in decimal):
  *   "algo"            auto | 1pa_ll | 2pa_ll | 2pa_hb | 2pa_hb_2phase | 2pr_hb | plan_2pa_hb | plan_2pr_hb |
- *                     plan_1pa_ll | plan_2pa_ll   (for the in-place forms)
+ *                     plan_1pa_ll | plan_2pa_ll | 2pr_port   (for the in-place forms)
  *   "ll_1pa_max_bytes", "ll_2pa_max_bytes"   size thresholds of the automatic choice
  *   "coll_algo"       auto | ll | hb   protocol of allgather / reducescatter (LL needs blocks that
  *                     are multiples of 8 bytes and fit the LL scratch; "ll" fails otherwise)

@@ -9,7 +9,7 @@ import os
 import torch
 
 __all__ = [
-    "F32", "BF16", "F16", "I32", "SUM", "MAX", "MIN", "ALGO_AUTO", "ALGO_1PA_LL", "ALGO_2PA_LL", "ALGO_2PA_HB", "ALGO_2PA_HB_2PHASE", "ALGO_2PR_HB", "ALGO_PLAN_2PA_HB", "ALGO_PLAN_2PR_HB", "ALGO_PLAN_1PA_LL", "ALGO_PLAN_2PA_LL",
+    "F32", "BF16", "F16", "I32", "SUM", "MAX", "MIN", "ALGO_AUTO", "ALGO_1PA_LL", "ALGO_2PA_LL", "ALGO_2PA_HB", "ALGO_2PA_HB_2PHASE", "ALGO_2PR_HB", "ALGO_PLAN_2PA_HB", "ALGO_PLAN_2PR_HB", "ALGO_PLAN_1PA_LL", "ALGO_PLAN_2PA_LL", "ALGO_2PR_PORT",
     "MsxError", "lib", "lib_path", "init", "reset", "finalize", "set_option", "get_option", "status",
     "check_status", "last_launch", "version", "strerror",
     "allreduce", "reducescatter", "allgather", "alltoall",
@@ -26,6 +26,7 @@ F32, BF16, F16, I32 = 0, 1, 2, 3
 SUM, MAX, MIN = 0, 1, 2
 ALGO_AUTO, ALGO_1PA_LL, ALGO_2PA_LL, ALGO_2PA_HB, ALGO_2PA_HB_2PHASE, ALGO_2PR_HB = 0, 1, 2, 3, 4, 5
 ALGO_PLAN_2PA_HB, ALGO_PLAN_2PR_HB, ALGO_PLAN_1PA_LL, ALGO_PLAN_2PA_LL = 6, 7, 8, 9
+ALGO_2PR_PORT = 10
 
 EXPORTS = [
     "msx_allreduce", "msx_reducescatter", "msx_allgather", "msx_alltoall",

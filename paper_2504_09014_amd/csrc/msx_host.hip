@@ -63,17 +63,20 @@ struct Options {
     unsigned chaos = 0;
 };
 
-// PortChannel emulation: the FIFO in pinned host memory and the CPU proxy thread that serves it.
+// PortChannel emulation: the FIFOs in pinned host memory and the CPU proxy thread that serves them.
 struct Port {
-    PortFifo* fifo = nullptr;
-    unsigned* expected = nullptr;      // device: what the next port wait of each (recv, send) pair needs
+    PortShared* shared = nullptr;      // host address (pinned, mapped)
+    PortShared* shared_dev = nullptr;  // the same memory as the device sees it
+    unsigned* sem = nullptr;           // the context's device-side semaphores (signals land there)
     hipStream_t stream = nullptr;      // the proxy's own stream (default priority)
+    std::vector<hipEvent_t> events;    // for flush requests, reused in turn
+    std::thread thread;
     std::mutex mu;
     std::condition_variable cv;
     unsigned long long announced = 0;  // requests launched kernels will push in total
     unsigned long long consumed = 0;   // requests served so far
     bool stop = false;
-    std::atomic<bool> exited{false};
+    std::atomic<int> hip_error{0};     // first HIP error the proxy ran into (it stops signalling then)
     int device = 0;
 };
 
@@ -128,46 +131,85 @@ int hip_fail(hipError_t e)
 size_t elem_size(int dtype) { return (dtype == MSX_F32 || dtype == MSX_I32) ? 4 : 2; }
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// The proxy: pops requests of every rank's FIFO in order.  put -> a device-to-device copy on the proxy's stream;
+// signal -> a one-wave kernel behind it on the same stream (ordered after the copies, nothing waits on the CPU);
+// flush -> an event behind what has been enqueued, polled until it has fired.  After a HIP error nothing more is
+// copied or signalled: the waiting ranks run into their timeouts, and msx_status names the error.
 void port_proxy(Port* p)
 {
     (void)hipSetDevice(p->device);
+    unsigned long long taken[kMaxRanks] = {};
+    for (int r = 0; r < kMaxRanks; ++r) taken[r] = p->shared->fifo[r].tail;
+    struct Pending { int rank; unsigned long long seq; hipEvent_t ev; };
+    std::vector<Pending> pending;
+    size_t next_event = 0;
+    auto fail = [&](hipError_t e) {
+        int none = 0;
+        p->hip_error.compare_exchange_strong(none, (int)e);
+    };
     for (;;) {
         {
             std::unique_lock<std::mutex> lk(p->mu);
-            p->cv.wait(lk, [&] { return p->stop || p->consumed < p->announced; });
+            p->cv.wait(lk, [&] { return p->stop || p->consumed < p->announced || !pending.empty(); });
             if (p->stop) break;
         }
-        const auto deadline = std::chrono::steady_clock::now() + std::chrono::seconds(20);
+        auto idle_since = std::chrono::steady_clock::now();
         for (;;) {
             {
                 std::lock_guard<std::mutex> lk(p->mu);
-                if (p->stop || p->consumed >= p->announced) break;
+                if (p->stop || (p->consumed >= p->announced && pending.empty())) break;
             }
-            const unsigned long long head = __atomic_load_n(&p->fifo->head, __ATOMIC_ACQUIRE);
-            if (head > p->consumed) {
-                const PortReq r = p->fifo->req[p->consumed % kPortSlots];
-                if (r.type == kPortPut) {
-                    (void)hipMemcpyAsync((void*)r.dst, (const void*)r.src, (size_t)r.bytes, hipMemcpyDeviceToDevice,
-                                         p->stream);
-                } else if (r.type == kPortSignal) {
-                    (void)hipStreamSynchronize(p->stream);      // the copies before the signal have landed
-                    if (r.arg < (unsigned)(kMaxRanks * kMaxRanks))
-                        __atomic_fetch_add(&p->fifo->sem[r.arg], 1u, __ATOMIC_RELEASE);
-                } else {
-                    (void)hipStreamSynchronize(p->stream);
+            bool progress = false;
+            for (int r = 0; r < kMaxRanks; ++r) {
+                PortFifo* f = &p->shared->fifo[r];
+                while (__atomic_load_n(&f->head, __ATOMIC_ACQUIRE) > taken[r]) {
+                    const PortReq q = f->req[taken[r] % kPortSlots];
+                    const unsigned long long seq = ++taken[r];
+                    const bool ok = p->hip_error.load() == 0;
+                    if (q.type == kPortPut) {
+                        if (ok && q.bytes) {
+                            hipError_t e = hipMemcpyAsync((void*)q.dst, (const void*)q.src, (size_t)q.bytes,
+                                                          hipMemcpyDeviceToDevice, p->stream);
+                            if (e != hipSuccess) fail(e);
+                        }
+                    } else if (q.type == kPortSignal) {
+                        const int recv = (int)(q.arg & 0xffu), send = (int)((q.arg >> 8) & 0xffu), nsem = (int)(q.arg >> 16);
+                        if (ok && recv < kMaxRanks && send < kMaxRanks && nsem >= 1 && nsem <= 64) {
+                            hipLaunchKernelGGL(k_port_signal, dim3(1), dim3(64), 0, p->stream, p->sem, recv, send, nsem);
+                            hipError_t e = hipGetLastError();
+                            if (e != hipSuccess) fail(e);
+                        }
+                    } else if (q.type == kPortFlush) {
+                        hipEvent_t ev = p->events[next_event++ % p->events.size()];
+                        hipError_t e = ok ? hipEventRecord(ev, p->stream) : hipErrorUnknown;
+                        if (e == hipSuccess) pending.push_back(Pending{r, seq, ev});
+                        else if (ok) fail(e);
+                    }
+                    __atomic_store_n(&f->tail, seq, __ATOMIC_RELEASE);
+                    std::lock_guard<std::mutex> lk(p->mu);
+                    ++p->consumed;
+                    progress = true;
                 }
-                std::lock_guard<std::mutex> lk(p->mu);
-                ++p->consumed;
-                __atomic_store_n(&p->fifo->tail, p->consumed, __ATOMIC_RELEASE);
-            } else if (std::chrono::steady_clock::now() > deadline) {
-                std::lock_guard<std::mutex> lk(p->mu);   // the kernel never pushed: forget the rest
+            }
+            for (size_t k = 0; k < pending.size();) {
+                const hipError_t e = hipEventQuery(pending[k].ev);
+                if (e == hipErrorNotReady) { ++k; continue; }
+                if (e == hipSuccess) __atomic_store_n(&p->shared->fifo[pending[k].rank].flushed, pending[k].seq, __ATOMIC_RELEASE);
+                else fail(e);
+                pending.erase(pending.begin() + (long)k);
+                progress = true;
+            }
+            if (progress) {
+                idle_since = std::chrono::steady_clock::now();
+            } else if (std::chrono::steady_clock::now() - idle_since > std::chrono::seconds(3)) {
+                std::lock_guard<std::mutex> lk(p->mu);   // the kernels never pushed what they announced: forget the rest
                 p->announced = p->consumed;
+                pending.clear();
             } else {
                 std::this_thread::yield();
             }
         }
     }
-    p->exited.store(true);
 }
 
 void destroy_port(Port* p)
@@ -178,11 +220,10 @@ void destroy_port(Port* p)
         p->stop = true;
     }
     p->cv.notify_all();
-    for (int i = 0; i < 5000 && !p->exited.load(); ++i) std::this_thread::sleep_for(std::chrono::milliseconds(1));
-    if (!p->exited.load()) return;      // never seen: leave everything in place rather than free under a live thread
-    if (p->stream) (void)hipStreamDestroy(p->stream);
-    if (p->fifo) (void)hipHostFree(p->fifo);
-    if (p->expected) (void)hipFree(p->expected);
+    if (p->thread.joinable()) p->thread.join();
+    if (p->stream) { (void)hipStreamSynchronize(p->stream); (void)hipStreamDestroy(p->stream); }
+    for (hipEvent_t e : p->events) (void)hipEventDestroy(e);
+    if (p->shared) (void)hipHostFree(p->shared);
     delete p;
 }
 
@@ -191,22 +232,38 @@ int get_port(Ctx* c, Port** out)
     if (c->port) { *out = c->port; return MSX_OK; }
     Port* p = new Port();
     p->device = c->device;
-    bool ok = hipHostMalloc((void**)&p->fifo, sizeof(PortFifo), hipHostMallocMapped) == hipSuccess;
-    if (ok) memset(p->fifo, 0, sizeof(PortFifo));
-    ok = ok && hipMalloc((void**)&p->expected, kMaxRanks * kMaxRanks * 4) == hipSuccess &&
-         hipMemset(p->expected, 0, kMaxRanks * kMaxRanks * 4) == hipSuccess &&
-         hipStreamCreateWithFlags(&p->stream, hipStreamNonBlocking) == hipSuccess &&
-         hipDeviceSynchronize() == hipSuccess;
+    p->sem = c->d.sem;
+    bool ok = hipHostMalloc((void**)&p->shared, sizeof(PortShared), hipHostMallocMapped) == hipSuccess;
+    if (ok) memset(p->shared, 0, sizeof(PortShared));
+    ok = ok && hipHostGetDevicePointer((void**)&p->shared_dev, p->shared, 0) == hipSuccess &&
+         hipStreamCreateWithFlags(&p->stream, hipStreamNonBlocking) == hipSuccess;
+    for (int k = 0; ok && k < 64; ++k) {
+        hipEvent_t e;
+        ok = hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+        if (ok) p->events.push_back(e);
+    }
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
-        if (p->fifo) (void)hipHostFree(p->fifo);
-        if (p->expected) (void)hipFree(p->expected);
+        for (hipEvent_t e : p->events) (void)hipEventDestroy(e);
+        if (p->stream) (void)hipStreamDestroy(p->stream);
+        if (p->shared) (void)hipHostFree(p->shared);
         delete p;
         return MSX_ERR_NOMEM;
     }
-    std::thread(port_proxy, p).detach();
+    p->thread = std::thread(port_proxy, p);
     c->port = p;
     *out = p;
     return MSX_OK;
+}
+
+// tell the proxy that a launch is about to push `requests` requests
+void port_announce(Port* p, unsigned long long requests)
+{
+    {
+        std::lock_guard<std::mutex> pl(p->mu);
+        p->announced += requests;
+    }
+    p->cv.notify_all();
 }
 
 std::vector<Ctx*> g_made;         // contexts made by msx_ctx_create, any device
@@ -915,7 +972,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
 {
     int rc = check_common(dtype, op, nranks);
     if (rc) return rc;
-    if (algo < MSX_ALGO_AUTO || algo > MSX_ALGO_PLAN_2PA_LL) return MSX_ERR_ARG;
+    if (algo < MSX_ALGO_AUTO || algo > MSX_ALGO_2PR_PORT) return MSX_ERR_ARG;
     if ((rc = check_table(send, nranks))) return rc;
     if ((rc = check_table((const void* const*)recv, nranks))) return rc;
     if (residual && (rc = check_table(residual, nranks))) return rc;
@@ -927,7 +984,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
     if (fixed_ctx) {
         // nothing below may allocate: the ring's and the interpreter's scratch grow on demand, so they are out
         if (nbytes > kStaticMaxBytes) return MSX_ERR_NOMEM;
-        if (algo == MSX_ALGO_2PR_HB || plan_algo(algo)) return MSX_ERR_UNSUPPORTED;
+        if (algo == MSX_ALGO_2PR_HB || algo == MSX_ALGO_2PR_PORT || plan_algo(algo)) return MSX_ERR_UNSUPPORTED;
         if ((rc = get_static_ctx(stream, &c))) return rc;
     } else if ((rc = get_ctx(&c))) return rc;
     const int n = nranks;
@@ -977,7 +1034,40 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
         return plan_allreduce(c, send, recv, nbytes, dtype, n, algo, stream);
     }
     if (plan_algo(algo)) algo = MSX_ALGO_2PA_HB;
-    if (algo == MSX_ALGO_2PR_HB && n == 1) algo = MSX_ALGO_2PA_HB;
+    if ((algo == MSX_ALGO_2PR_HB || algo == MSX_ALGO_2PR_PORT) && n == 1) algo = MSX_ALGO_2PA_HB;
+    if (algo == MSX_ALGO_2PR_PORT) {
+        // two-phase ring whose copies go through the port (FIFO, CPU proxy, runtime copies), overlapped with the
+        // reduction: n equal chunks of whole 16-byte vectors, no residual.  The proxy is told of every launch,
+        // so this is neither a call to prepare nor one to capture.
+        if (residual) return MSX_ERR_UNSUPPORTED;
+        if (nbytes % (16 * (size_t)n)) return MSX_ERR_UNSUPPORTED;
+        if (t_record) return MSX_ERR_UNSUPPORTED;
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (stream && hipStreamIsCapturing(stream, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone)
+            return MSX_ERR_UNSUPPORTED;
+        Port* port = nullptr;
+        if ((rc = get_port(c, &port))) return rc;
+        void* ring_mem = nullptr;
+        if ((rc = ring_scratch(c, nbytes * (size_t)n, &ring_mem))) return rc;
+        const void* kp = dtype == MSX_F32 ? (const void*)k_allreduce_ring_port<0> : (const void*)k_allreduce_ring_port<1>;
+        RingArgs a{};
+        for (int i = 0; i < n; ++i) {
+            a.in[i] = send[i];
+            a.out[i] = recv[i];
+            a.scratch[i] = (char*)ring_mem + (size_t)i * nbytes;
+        }
+        a.chunk_vecs = nbytes / 16 / (size_t)n;
+        a.n = n;
+        int chans = 1;
+        // the reductions want workgroups, the copy kernels of the port want the rest of the chip
+        if ((rc = pick_channels(c, kp, 256, n, a.chunk_vecs / 2 + 1, 8, g_opt.hb_blocks, 32, &chans))) return rc;
+        a.chans = chans;
+        const int pushing = g_opt.drop_rank >= 0 && g_opt.drop_rank < n ? n - 1 : n;
+        port_announce(port, (unsigned long long)pushing * ring_port_requests(n));
+        note_launch(n * chans, 256, algo);
+        typedef void (*K)(RingArgs, PortShared*, DevCtx);
+        return launch((K)kp, n * chans, 256, stream, a, port->shared_dev, dev_ctx(c));
+    }
     if (algo == MSX_ALGO_2PR_HB) {
         // two-phase ring: n equal chunks of whole 16-byte vectors, no residual
         if (residual) return MSX_ERR_UNSUPPORTED;
@@ -1643,16 +1733,12 @@ int msx_prim_port_put_signal_wait(const void* src, void* staging, void* dst, siz
     if (resident < 2) return MSX_ERR_UNSUPPORTED;
     size_t readers = (nbytes + (256 * 16 * 8) - 1) / (256 * 16 * 8);   // 32 KiB per reading workgroup and pass
     if (readers < 1) readers = 1;
-    if (readers > 128) readers = 128;
+    if (readers > 64) readers = 64;
     if ((int)readers + 1 > resident) readers = (size_t)resident - 1;
-    {
-        std::lock_guard<std::mutex> pl(p->mu);
-        p->announced += g_opt.drop_rank == 0 ? 0 : 3;   // put, signal, flush (a dropped sender pushes nothing)
-    }
-    p->cv.notify_all();
+    port_announce(p, g_opt.drop_rank == 0 ? 0 : 3);   // put, signal, flush (a dropped sender pushes nothing)
     note_launch(1 + (int)readers, 256, 0);
-    return launch(k_port_put_signal_wait, 1 + (int)readers, 256, (hipStream_t)stream, dev_ctx(c), p->fifo,
-                  p->expected, src, staging, dst, nbytes, (int)readers);
+    return launch(k_port_put_signal_wait, 1 + (int)readers, 256, (hipStream_t)stream, dev_ctx(c), p->shared_dev, src,
+                  staging, dst, nbytes, (int)readers);
 }
 
 // ---- context, options, status ---------------------------------------------------------------
@@ -1995,6 +2081,7 @@ int msx_set_option(const char* key, const char* value)
         else if (v == "plan_2pr_hb") g_opt.algo = MSX_ALGO_PLAN_2PR_HB;
         else if (v == "plan_1pa_ll") g_opt.algo = MSX_ALGO_PLAN_1PA_LL;
         else if (v == "plan_2pa_ll") g_opt.algo = MSX_ALGO_PLAN_2PA_LL;
+        else if (v == "2pr_port") g_opt.algo = MSX_ALGO_2PR_PORT;
         else return MSX_ERR_ARG;
         return MSX_OK;
     }
@@ -2093,7 +2180,7 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
     unsigned long long u = 0;
     if (k == "algo") {
         static const char* names[] = {"auto", "1pa_ll", "2pa_ll", "2pa_hb", "2pa_hb_2phase", "2pr_hb",
-                                      "plan_2pa_hb", "plan_2pr_hb", "plan_1pa_ll", "plan_2pa_ll"};
+                                      "plan_2pa_hb", "plan_2pr_hb", "plan_1pa_ll", "plan_2pa_ll", "2pr_port"};
         snprintf(value_out, value_len, "%s", names[g_opt.algo]);
         return MSX_OK;
     }
@@ -2159,6 +2246,10 @@ int msx_status(void* stream, uint32_t info[6])
     if (info)
         for (int i = 0; i < 6; ++i) info[i] = h[i];
     if (h[0] != 0) g_status_detail = h[6];
+    if (c && c->port && c->port->hip_error.load() != 0) {      // the port's proxy ran into a HIP error: that is the cause
+        t_hip_err = c->port->hip_error.load();
+        return MSX_ERR_HIP;
+    }
     return status_code(h);
 }
 

@@ -57,7 +57,7 @@ def test_argument_errors_need_no_device(L):
     bad = (C.c_void_p * 8)(*[0x1000 + 0x100 * i for i in range(7)], 0)
     pp = C.POINTER(C.c_void_p)
     assert L.msx_allreduce_ex(C.cast(bad, pp), C.cast(tbl, pp), None, 16, 0, 0, 8, 0, None) == ARG
-    assert L.msx_allreduce_ex(C.cast(tbl, pp), C.cast(tbl, pp), None, 16, 0, 0, 8, 10, None) == ARG  # algo
+    assert L.msx_allreduce_ex(C.cast(tbl, pp), C.cast(tbl, pp), None, 16, 0, 0, 8, 11, None) == ARG  # algo
     assert L.msx_allreduce_ex(C.cast(tbl, pp), C.cast(tbl, pp), None, 0, 0, 0, 8, 0, None) == 0
     assert L.msx_alltoall_ex(C.cast(tbl, pp), C.cast(tbl, pp), 64, 0, 8, None) == ARG                 # overlap
     assert L.msx_moe_dispatch(C.cast(tbl, pp), C.cast(tbl, pp), 4, 7, 8, 256, 1, 8, C.cast(tbl, pp), None,

@@ -311,6 +311,62 @@ def test_ring_allreduce_matches_ring_order_oracle(msx, orc, n, dtype):
             assert np.all(np.abs(got - ref) <= 2e-2 * np.abs(ref) + n * ulp)
 
 
+@pytest.mark.parametrize("n", [2, 3, 5, 8])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_overlapped_ring_over_the_port_channel_matches_ring_order_oracle(msx, orc, n, dtype):
+    """MSX_ALGO_2PR_PORT: every hop is a put + signal (+ flush) request to the port (FIFO, CPU proxy, runtime
+    copies), chunks travel in two halves and the reduction of one half overlaps the copy of the other.  The
+    halves change when an element is added, not the order or the rounding: the bits are the plain ring's."""
+    esz = 4 if dtype == torch.float32 else 2
+    for vecs_per_chunk, blocks in [(1, 0), (3, 0), (64, 0), (1001, 3), (16385, 0), (70000, 5)]:
+        count = vecs_per_chunk * n * 16 // esz
+        if dtype == torch.float32:
+            g = torch.Generator().manual_seed(count)
+            x = torch.randn(n, count, generator=g) * torch.exp(torch.randn(n, count, generator=g) * 3)
+        else:
+            x = synth.normal(n, count, seed=count)
+        want = orc.allreduce_ring(_bits(x))
+        msx.set_option("hb_blocks_per_rank", str(blocks))
+        msx.set_option("chaos", str(3 + vecs_per_chunk))
+        try:
+            for inplace in (False, True):
+                outs = _run_ex(msx, x, 10, inplace=inplace)
+                for r in range(n):
+                    assert np.array_equal(outs[r].view(np.uint8), want.view(np.uint8)), (n, count, r, inplace)
+            assert np.array_equal(_run_ex(msx, x, 5)[n - 1].view(np.uint8), want.view(np.uint8))   # the thread-copy ring between
+        finally:
+            msx.set_option("chaos", "0")
+            msx.set_option("hb_blocks_per_rank", "0")
+
+
+def test_port_ring_refuses_what_it_cannot_serve_and_times_out_without_a_rank(msx, orc):
+    send = [torch.zeros(100, dtype=torch.bfloat16, device="cuda") for _ in range(8)]
+    with pytest.raises(msx.MsxError) as e:
+        msx.allreduce_ex(send, send, None, algo=10)
+    assert e.value.code == -2
+    send = [torch.zeros(1024, dtype=torch.bfloat16, device="cuda") for _ in range(8)]
+    with pytest.raises(msx.MsxError) as e:
+        msx.allreduce_ex(send, send, send, algo=10)
+    assert e.value.code == -2
+    with pytest.raises(msx.MsxError) as e:
+        msx.prepare_allreduce(send, send, None, algo=10)        # the proxy is told of every launch
+    assert e.value.code == -2
+    x = synth.normal(8, 8192, seed=12)
+    msx.set_option("spin_limit", "2000")
+    msx.set_option("drop_rank", "3")
+    try:
+        s_ = [x[r].clone().cuda() for r in range(8)]
+        r_ = [torch.empty_like(t) for t in s_]
+        msx.allreduce_ex(s_, r_, None, algo=10)
+        rc, info = msx.status()
+        assert rc == -4, info
+    finally:
+        msx.set_option("drop_rank", "-1")
+        msx.set_option("spin_limit", str(1 << 20))
+        msx.reset()
+    assert np.array_equal(_run_ex(msx, x, 10)[0], orc.allreduce_ring(_bits(x)))
+
+
 def test_ring_allreduce_integers_equal_the_other_algorithms(msx, orc):
     x = synth.int_valued_f32(8, 262144, seed=0)                 # config 1: every order is exact
     want = orc.allreduce_f32(x.numpy())
