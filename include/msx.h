@@ -355,7 +355,10 @@ int msx_last_status(void* ctx, int* rank, int* site, unsigned* expected, unsigne
  *                     dies finish them together (the schedule is found by the kernels themselves and kept, per
  *                     launch shape, in the context)
  *   "hb_barriers"     0 | 1   start/end rank barriers in the HB kernels
- *   "peer_outer"      0 | 1   two-phase HB all-gather: one put per peer instead of peer-inner
+ *   "peer_outer"      0 | 1 | 2   two-phase HB all-gather: one put per peer instead of peer-inner (1); out-of-place
+ *                     all-to-all: 0 = by block size (block after block with the ranks in step from 4 MiB blocks, the
+ *                     peer loop inside below), 1 / 2 = block after block at any size, without / with the rank
+ *                     barrier between blocks
  *   "barrier_fences"  0..3    msx_prim_barrier only: bit 0 release fence, bit 1 acquire fence
  *   "spin_limit"      polls before a wait gives up
  *   "drop_rank"       -1, or a rank whose workgroups return at once (failure-path tests)
@@ -393,6 +396,9 @@ int msx_debug_choose(size_t nbytes, int nranks, size_t ll_limit, int* algo, int*
  * was met, frozen, misses in a row} (pace in 10 ns ticks per tile, 0 = unpaced); took_ticks = how long the
  * full write phase of `tiles` tiles just took.  The same function the kernels call. */
 int msx_debug_pace_update(uint32_t state[4], uint64_t took_ticks, uint32_t tiles);
+/* The multiplier with which the token plan computes the owner rank of an expert, e / (n_experts / nranks), as
+ * the high word of e * magic; 0 = it divides. */
+int msx_debug_owner_magic(int n_experts, int nranks, uint32_t* magic);
 int msx_debug_lower_plan(int algo, int nranks, int blocks_per_rank, size_t vectors_per_rank, int threads,
                          void* ops_out, size_t ops_capacity, uint32_t* start_out, size_t* ops_written);
 int msx_debug_lower_plan_ex(int algo, int nranks, int blocks_per_rank, size_t nbytes, int threads, int held,

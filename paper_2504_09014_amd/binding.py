@@ -39,7 +39,7 @@ EXPORTS = [
     "msx_prim_ll_roundtrip", "msx_prim_port_put_signal_wait",
     "msx_init", "msx_reset", "msx_finalize", "msx_set_option", "msx_get_option", "msx_status",
     "msx_last_launch", "msx_last_hip_error", "msx_strerror", "msx_version",
-    "msx_debug_choose", "msx_debug_lower_plan", "msx_debug_lower_plan_ex", "msx_debug_pace_update",
+    "msx_debug_choose", "msx_debug_lower_plan", "msx_debug_lower_plan_ex", "msx_debug_pace_update", "msx_debug_owner_magic",
 ]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -110,6 +110,7 @@ def lib():
         L.msx_debug_lower_plan.argtypes = [i, i, i, sz, i, vp, sz, C.POINTER(u32), C.POINTER(sz)]
         L.msx_debug_lower_plan_ex.argtypes = [i, i, i, sz, i, i, vp, sz, C.POINTER(u32), C.POINTER(sz)]
         L.msx_debug_pace_update.argtypes = [C.POINTER(u32), C.c_uint64, u32]
+        L.msx_debug_owner_magic.argtypes = [i, i, C.POINTER(u32)]
         L.msx_strerror.argtypes = [i]
         L.msx_strerror.restype = C.c_char_p
         L.msx_version.restype = C.c_char_p

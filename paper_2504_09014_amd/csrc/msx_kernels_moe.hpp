@@ -24,6 +24,8 @@ struct MoeArgs {
     unsigned* base;         // plan scratch: [n src][8] first row of source s inside destination d
     int T, K, n, per_rank;  // per_rank = experts per rank
     int n_experts;
+    unsigned per_rank_magic; // ceil(2^32 / per_rank) when n_experts < 65536 and per_rank > 1 (e / per_rank is then the
+                             // high word of e * magic), else 0: divide
     unsigned row_vecs;      // 16-byte vectors per row
     unsigned cap;           // rows per destination buffer
     int chans;
@@ -72,9 +74,13 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
     const int* topk = a.topk[rank];
 
     // destination marks of a token: one bit per rank that owns one of its K experts; an id outside
-    // [0, n_experts) marks nothing and is reported (the call goes on without it)
+    // [0, n_experts) marks nothing and is reported (the call goes on without it).  The owner of expert e is
+    // e / per_rank: by multiplication (a division by a run-time value is some thirty instructions, and every
+    // thread does dozens of them: 10 of the kernel's 17 us at 4096 tokens and 8 experts per token)
     int bad_id = 0;
     bool bad = false;
+    const unsigned magic = a.per_rank_magic;
+    auto owner = [&](int e) -> unsigned { return magic ? __umulhi((unsigned)e, magic) : (unsigned)(e / a.per_rank); };
     auto marks = [&](int t) -> unsigned {
         unsigned mask = 0;
         if (K == 8) {                                    // the common case: two 16-byte loads per token
@@ -82,12 +88,12 @@ __global__ __launch_bounds__(kPlanThreads) void k_moe_plan(MoeArgs a, DevCtx c)
             const int e[8] = {(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
 #pragma unroll
             for (int k = 0; k < 8; ++k)
-                if (e[k] >= 0 && e[k] < a.n_experts) mask |= 1u << (e[k] / a.per_rank);
+                if (e[k] >= 0 && e[k] < a.n_experts) mask |= 1u << owner(e[k]);
                 else { bad = true; bad_id = e[k]; }
         } else {
             for (int k = 0; k < K; ++k) {
                 const int e = topk[(size_t)t * K + k];
-                if (e >= 0 && e < a.n_experts) mask |= 1u << (e / a.per_rank);
+                if (e >= 0 && e < a.n_experts) mask |= 1u << owner(e);
                 else { bad = true; bad_id = e; }
             }
         }
@@ -370,6 +376,34 @@ struct MoeFp8Args {
     unsigned groups;        // H / 128
 };
 
+// One lane's 16 consecutive bf16 elements (two input vectors) -> 16 E4M3 codes and the scale of their group of
+// 128 (the 8 lanes of a group share their maximum by shuffles; every one of them returns the group's scale).
+__device__ __forceinline__ u32x4 fp8_quantise16(u32x4 v0, u32x4 v1, float& scale)
+{
+    const unsigned w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+    float x[16];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { x[2 * k] = bf16_lo(w[k]); x[2 * k + 1] = bf16_hi(w[k]); }
+    float amax = 1e-4f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const float m = fabsf(x[k]);
+        amax = m > amax ? m : amax;                  // a NaN never wins the comparison
+    }
+#pragma unroll
+    for (int m = 4; m >= 1; m >>= 1) {
+        const float o = __shfl_xor(amax, m, 64);
+        amax = o > amax ? o : amax;
+    }
+    const float inv = 448.0f / amax;
+    float y[16];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) y[k] = x[k] * inv;
+    scale = amax / 448.0f;
+    return u32x4{e4m3_quad(y[0], y[1], y[2], y[3]), e4m3_quad(y[4], y[5], y[6], y[7]),
+                 e4m3_quad(y[8], y[9], y[10], y[11]), e4m3_quad(y[12], y[13], y[14], y[15])};
+}
+
 __global__ __launch_bounds__(256) void k_moe_pack_fp8(MoeArgs a, MoeFp8Args f, DevCtx c)
 {
     const int n = a.n;
@@ -414,28 +448,8 @@ __global__ __launch_bounds__(256) void k_moe_pack_fp8(MoeArgs a, MoeFp8Args f, D
             const unsigned nx = i + 64u;
             u32x4 n0 = {0u, 0u, 0u, 0u}, n1 = n0;
             if (nx < units) { n0 = ld16(src, 2u * nx); n1 = ld16(src, 2u * nx + 1u); }
-            const unsigned w[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-            float x[16];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) { x[2 * k] = bf16_lo(w[k]); x[2 * k + 1] = bf16_hi(w[k]); }
-            float amax = 1e-4f;
-#pragma unroll
-            for (int k = 0; k < 16; ++k) {
-                const float m = fabsf(x[k]);
-                amax = m > amax ? m : amax;                  // a NaN never wins the comparison
-            }
-#pragma unroll
-            for (int m = 4; m >= 1; m >>= 1) {
-                const float o = __shfl_xor(amax, m, 64);
-                amax = o > amax ? o : amax;
-            }
-            const float inv = 448.0f / amax;
-            float y[16];
-#pragma unroll
-            for (int k = 0; k < 16; ++k) y[k] = x[k] * inv;
-            const u32x4 q = {e4m3_quad(y[0], y[1], y[2], y[3]), e4m3_quad(y[4], y[5], y[6], y[7]),
-                             e4m3_quad(y[8], y[9], y[10], y[11]), e4m3_quad(y[12], y[13], y[14], y[15])};
-            const float scale = amax / 448.0f;
+            float scale;
+            const u32x4 q = fp8_quantise16(v0, v1, scale);
 #pragma unroll
             for (int d = 0; d < kMaxRanks; ++d)
                 if (dq[d]) {

@@ -107,6 +107,31 @@ def test_alltoall_matches_oracle(msx, orc, n, dtype, c):
     assert np.array_equal(_bits(buf).view(np.uint8), _bits(x).view(np.uint8))
 
 
+@pytest.mark.parametrize("n", [2, 5, 8])
+@pytest.mark.parametrize("order", [1, 2])
+def test_alltoall_block_after_block(msx, orc, n, order):
+    """The order the large blocks take (every source on one block at a time, the ranks in step with order 2),
+    forced at sizes the oracle likes: ragged ends, fewer vectors than threads, several passes per block."""
+    msx.set_option("peer_outer", str(order))
+    try:
+        for c, blocks in [(8, 0), (8 * 300 + 16, 2), (8 * 256 * 8 * 3 + 8, 1), (8 * 70001, 4), (1 << 21, 0)]:
+            count = n * c
+            x = synth.normal(n, count, seed=c + order)
+            want = orc.alltoall(_bits(x))
+            send = [x[r].clone().cuda() for r in range(n)]
+            recv = [torch.zeros(count, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            msx.set_option("hb_blocks_per_rank", str(blocks))
+            msx.set_option("chaos", str(c % 97 + 1))
+            msx.alltoall_ex(send, recv)
+            msx.check_status()
+            for r in range(n):
+                assert np.array_equal(_bits(recv[r]), want[r]), (n, c, r)
+    finally:
+        msx.set_option("peer_outer", "0")
+        msx.set_option("hb_blocks_per_rank", "0")
+        msx.set_option("chaos", "0")
+
+
 @pytest.mark.parametrize("n", [2, 3, 8])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("c", [4, 8, 100, 4096, 65536 + 8, 262144])

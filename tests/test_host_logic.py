@@ -361,3 +361,20 @@ def test_write_phase_pacing_controller_finds_and_keeps_the_tightest_schedule(L):
     assert L.msx_debug_pace_update(junk, 10 ** 9, tiles) == 0 and junk[0] == 0      # over a millisecond: ignored
     assert L.msx_debug_pace_update(junk, 99999, 1) == 0 and junk[0] == 0            # would exceed the clamp
     assert L.msx_debug_pace_update(None, 100, tiles) == -1
+
+
+def test_owner_of_an_expert_by_multiplication_equals_the_division(L):
+    """The token plan computes e // (n_experts // nranks) as (e * magic) >> 32: exact for every expert id of
+    every shape the library uses the multiplier for, and the library divides where it would not be."""
+    for nranks in range(1, 9):
+        for per in [1, 2, 3, 7, 31, 32, 33, 100, 255, 256, 1000, 4096, 8191]:
+            n_experts = per * nranks
+            m = C.c_uint32(0)
+            assert L.msx_debug_owner_magic(n_experts, nranks, C.byref(m)) == 0
+            if per == 1 or n_experts >= 65536:
+                assert m.value == 0
+                continue
+            e = np.arange(n_experts, dtype=np.uint64)
+            assert np.array_equal((e * np.uint64(m.value)) >> np.uint64(32), e // np.uint64(per)), (nranks, per)
+    m = C.c_uint32(0)
+    assert L.msx_debug_owner_magic(10, 3, C.byref(m)) == -1
