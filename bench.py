@@ -91,6 +91,349 @@ def pct(v, q):
     return s[min(len(s) - 1, max(0, int(round(q / 100.0 * (len(s) - 1)))))]
 
 
+def run_extras(torch, msx, synth, n):
+    """Every other table of the bench.  Each leg runs on its own: a leg that fails (a time-out of
+    the port proxy under a profiler that serialises dispatches, for one) is recorded as
+    {"error": ...}, the context is reset, and the next leg runs."""
+    import ctypes
+    extras = {}
+
+    def leg(name, fn):
+        t0 = time.perf_counter()
+        try:
+            extras[name] = fn()
+            msx.check_status()
+        except (msx.MsxError, RuntimeError) as e:
+            extras[name] = {"error": str(e)}
+            log(f"[bench] leg {name} failed: {e}")
+            try:
+                torch.cuda.synchronize()
+                msx.ctx_reset()
+            except Exception as e2:            # nothing more to do for this leg
+                log(f"[bench] reset after {name} failed: {e2}")
+        torch.cuda.empty_cache()
+        log(f"[bench] {name}: {time.perf_counter() - t0:.1f} s")
+
+    def bufs(c, seed, recv=True):
+        xs = synth.normal(n, c, seed=seed, device="cuda")
+        s_ = [xs[r] for r in range(n)]
+        r_ = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)] if recv else None
+        return s_, r_
+
+    raw_stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    # ---- config 2: small messages, both protocols, in a graph and launched one by one
+    def config2():
+        lat = {}
+        for kib in [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024]:
+            s_, r_ = bufs(kib * 1024 // 2, kib)
+            ll_algo = msx.ALGO_1PA_LL if kib <= 32 else msx.ALGO_2PA_LL     # the paper's split on A100
+            row = {}
+            for name, a in [("ll_us", ll_algo), ("hb_us", msx.ALGO_2PA_HB), ("auto_us", msx.ALGO_AUTO)]:
+                row[name] = round(graph_us(torch, lambda: msx.allreduce_ex(s_, r_, None, algo=a)), 2)
+            g, b, a = msx.last_launch()
+            # the same call launched one by one (no graph): through the pointer-table form (tables and
+            # checks per call) and through a prepared call (checked and marshalled once, run() only launches)
+            row["auto_plain_us"] = round(median([back_to_back_us(
+                torch, lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO), 100, 10) for _ in range(5)]), 2)
+            prep = msx.prepare_allreduce(s_, r_, None, algo=msx.ALGO_AUTO)
+            row["auto_prepared_us"] = round(median([back_to_back_us(
+                torch, lambda: prep.run(raw_stream), 100, 10) for _ in range(5)]), 2)
+            prep.release()
+            row.update({"ll_algo": ll_algo, "auto_algo": a, "auto_grid": g, "auto_block": b})
+            lat[f"{kib}KiB"] = row
+        return lat
+    leg("config2_bf16_latency", config2)
+
+    # ---- config 4: decode shape with the residual fused (one row shared, and one row per rank)
+    def config4():
+        dec = {}
+        for T in [1, 8, 32, 128, 256]:
+            xs, res = synth.decode_activations(n, T, seed=T)
+            s_ = [xs[r].clone().cuda() for r in range(n)]
+            r_ = [torch.empty_like(t) for t in s_]
+            shared = [res.cuda()] * n
+            per_rank = [(res.float() * (1.0 + r)).to(res.dtype).cuda() for r in range(n)]
+            gus = graph_us(torch, lambda: msx.allreduce_ex(s_, r_, shared, algo=msx.ALGO_AUTO))
+            g, b, a = msx.last_launch()
+            pus = graph_us(torch, lambda: msx.allreduce_ex(s_, r_, per_rank, algo=msx.ALGO_AUTO))
+            g2, b2, a2 = msx.last_launch()
+            # unfused: the same AllReduce without the residual, then one elementwise add over all ranks' outputs
+            flat = torch.stack(s_).contiguous()
+            rrow = res.cuda().reshape(1, -1)
+
+            def unfused():
+                msx.allreduce(flat)
+                flat.add_(rrow)
+            uus = graph_us(torch, unfused)
+            dec[f"T{T}"] = {"us_in_graph": round(gus, 2), "per_rank_residual_us_in_graph": round(pus, 2),
+                            "unfused_us_in_graph": round(uus, 2), "algo": a, "grid": g,
+                            "per_rank_algo": a2, "per_rank_grid": g2}
+        return dec
+    leg("config4_decode_residual", config4)
+
+    # ---- config 1
+    def config1():
+        xi = synth.int_valued_f32(n, 262144, seed=0)
+        s_ = [xi[r].clone().cuda() for r in range(n)]
+        r_ = [torch.empty_like(t) for t in s_]
+        c1 = {}
+        for name, a in [("1pa_ll", 1), ("2pa_ll", 2), ("2pa_hb", 3), ("2pa_hb_2phase", 4)]:
+            c1[name] = round(graph_us(torch, lambda: msx.allreduce_ex(s_, r_, None, algo=a)), 2)
+        return c1
+    leg("config1_fp32_1MiB_us", config1)
+
+    # ---- config 3 at other sizes: the automatic choice (fused) next to the two-phase form
+    def config3():
+        c3 = {}
+        for mib in [64, 256, 1024]:
+            c = mib * (1 << 20) // 2
+            s_, r_ = bufs(c, mib)
+            row = {}
+            for name, a in [("fused", msx.ALGO_AUTO), ("two_phase", msx.ALGO_2PA_HB_2PHASE)]:
+                _, ev = time_calls(torch, lambda: msx.allreduce_ex(s_, r_, None, algo=a), 10, 4)
+                ms = sum(ev) / len(ev) / 1e3
+                # two-phase moves more: the sums also go to scratch and come back (n-1)/n of S each way
+                row[name] = {"ms": round(ms, 4), "GBps": round(16 * c * 2 / ms / 1e6, 1),
+                             "pct_roofline": round(16 * c * 2 / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+            c3[f"{mib}MiB"] = row
+            del s_, r_
+            torch.cuda.empty_cache()
+        return c3
+    leg("config3_fused_vs_two_phase", config3)
+
+    # ---- the whole message-size axis of the paper's AllReduce figures, automatic choice, bf16
+    def sweep_auto():
+        sw = {}
+        for kib in [1, 4, 16, 64, 256, 1024, 4096, 16384, 65536, 262144]:
+            c = kib * 1024 // 2
+            s_, r_ = bufs(c, kib + 5)
+            fn = lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO)
+            us = graph_us(torch, fn, calls=20, replays=5) if kib <= 16384 else median(time_calls(torch, fn, 10, 3)[1])
+            g, b, a = msx.last_launch()
+            sw[f"{kib}KiB"] = {"us": round(us, 2), "algbw_GBps": round(c * 2 / us / 1e3, 1), "algo": a, "grid": g}
+            del s_, r_
+            torch.cuda.empty_cache()
+        return sw
+    leg("allreduce_auto_sweep", sweep_auto)
+
+    # ---- rings: thread-copy hand-offs (MemoryChannel) and hand-offs through the port (FIFO, proxy
+    # thread, runtime copies), next to the all-pairs form
+    def rings():
+        ring = {}
+        for mib in [1, 64, 256, 1024]:
+            c = mib * (1 << 20) // 2
+            s_, r_ = bufs(c, mib + 1)
+            row = {}
+            for name, a in [("ring_thread_copy_us", msx.ALGO_2PR_HB), ("ring_port_us", msx.ALGO_2PR_PORT),
+                            ("allpairs_2pa_us", msx.ALGO_2PA_HB)]:
+                try:
+                    row[name] = round(median(time_calls(
+                        torch, lambda: msx.allreduce_ex(s_, r_, None, algo=a), 6 if mib >= 256 else 10, 2)[1]), 1)
+                    msx.check_status()
+                except (msx.MsxError, RuntimeError) as e:
+                    row[name] = {"error": str(e)}
+                    torch.cuda.synchronize()
+                    msx.ctx_reset()
+            if isinstance(row["ring_port_us"], float) and isinstance(row["ring_thread_copy_us"], float):
+                row["port_over_thread_copy"] = round(row["ring_port_us"] / row["ring_thread_copy_us"], 2)
+            ring[f"{mib}MiB"] = row
+            del s_, r_
+            torch.cuda.empty_cache()
+        return ring
+    leg("ring_thread_copy_vs_port_vs_allpairs", rings)
+
+    # ---- the same algorithms run by the plan-interpreter kernel: overhead over the hand-written kernels
+    def interp():
+        res = {}
+        pairs = [("1pa_ll", msx.ALGO_1PA_LL, msx.ALGO_PLAN_1PA_LL, 32), ("2pa_ll", msx.ALGO_2PA_LL, msx.ALGO_PLAN_2PA_LL, 1024),
+                 ("2pa", msx.ALGO_2PA_HB, msx.ALGO_PLAN_2PA_HB, 1 << 30), ("2pr", msx.ALGO_2PR_HB, msx.ALGO_PLAN_2PR_HB, 1 << 30)]
+        for kib in [1, 8, 64, 1024, 65536, 262144]:
+            c = kib * 1024 // 2
+            s_, r_ = bufs(c, kib + 2)
+            row = {}
+            for name, hand, plan, max_kib in pairs:
+                if kib > max_kib or (name == "2pr" and kib < 64):
+                    continue
+                t = {}
+                for which, a in [("hand", hand), ("plan", plan)]:
+                    fn = lambda: msx.allreduce_ex(s_, r_, None, algo=a)
+                    if kib <= 1024:
+                        t[which] = graph_us(torch, fn, calls=20, replays=5)
+                    else:
+                        t[which] = median(time_calls(torch, fn, 10, 3)[1])
+                row[f"hand_{name}_us"] = round(t["hand"], 2)
+                row[f"plan_{name}_us"] = round(t["plan"], 2)
+                row[f"overhead_{name}_pct"] = round(100 * (t["plan"] / t["hand"] - 1), 1)
+            res[f"{kib}KiB"] = row
+            del s_, r_
+            torch.cuda.empty_cache()
+        return res
+    leg("plan_interpreter_vs_hand_kernels", interp)
+
+    # ---- standalone ReduceScatter / AllGather / AllToAll (HB protocol), 256 MiB rows, and what plain
+    # copies of the AllToAll's bytes take on this GPU (one runtime copy; eight copies of one rank's share)
+    def standalone():
+        other = {}
+        c = 128 << 20                                   # elements per full row (256 MiB of bf16)
+        full = synth.normal(n, c, seed=11, device="cuda")
+        rows_ = [full[r] for r in range(n)]
+        part = [torch.empty(c // n, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        full2 = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        for name, fn, moved in [
+            ("reducescatter", lambda: msx.reducescatter_ex(rows_, part), n * c * 2 + c * 2),
+            ("allgather", lambda: msx.allgather_ex(part, full2), c * 2 + n * c * 2),
+            ("alltoall", lambda: msx.alltoall_ex(rows_, full2), 2 * n * c * 2),
+        ]:
+            _, ev = time_calls(torch, fn, 10, 3)
+            ms = median(ev) / 1e3
+            other[name] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
+                           "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+        msx.check_status()
+        dst = torch.empty_like(full)
+        ms = median(time_calls(torch, lambda: dst.copy_(full), 10, 3)[1]) / 1e3
+        other["runtime_copy_of_the_same_bytes"] = {"ms": round(ms, 4), "GBps": round(2 * n * c * 2 / ms / 1e6, 1)}
+        return other
+    leg("standalone_256MiB_rows", standalone)
+
+    # ---- AllGather / ReduceScatter size sweeps (row = the full buffer of one rank), both protocols
+    def ag_rs():
+        sweep = {}
+        try:
+            for row_kib in [8, 64, 1024, 16384, 262144, 1048576]:
+                c = row_kib * 1024 // 2
+                full = synth.normal(n, c, seed=row_kib, device="cuda")
+                rows_ = [full[r] for r in range(n)]
+                part = [torch.empty(c // n, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+                full2 = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+                row = {}
+                for proto in ("hb", "ll"):
+                    if proto == "ll" and row_kib > 1024:      # packets of larger blocks exceed the LL scratch
+                        continue
+                    msx.set_option("coll_algo", proto)
+                    for name, fn in [("allgather", lambda: msx.allgather_ex(part, full2)),
+                                     ("reducescatter", lambda: msx.reducescatter_ex(rows_, part))]:
+                        if row_kib <= 16384:
+                            us = graph_us(torch, fn, calls=20, replays=5)
+                        else:
+                            us = median(time_calls(torch, fn, 8, 2)[1])
+                        row[f"{name}_{proto}_us"] = round(us, 2)
+                moved_ag = c * 2 + n * c * 2
+                moved_rs = n * c * 2 + c * 2
+                row["allgather_hb_GBps"] = round(moved_ag / row["allgather_hb_us"] / 1e3, 1)
+                row["reducescatter_hb_GBps"] = round(moved_rs / row["reducescatter_hb_us"] / 1e3, 1)
+                sweep[f"{row_kib}KiB"] = row
+                del full, rows_, part, full2
+                torch.cuda.empty_cache()
+        finally:
+            msx.set_option("coll_algo", "auto")
+        return sweep
+    leg("allgather_reducescatter_sweep", ag_rs)
+
+    # ---- config 5: dispatch (bf16 and FP8) and combine, with an explicit routing-plan object
+    def config5():
+        res = {}
+        T, H, K, E = 4096, 7168, 8, 256
+        tok = synth.moe_tokens(n, T, H, seed=0, device="cuda")
+        topk = synth.moe_routing(n, T, K, E, seed=0, device="cuda")
+        cap = 24576
+        rt = [torch.empty((cap, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+        rs = [torch.empty((cap,), dtype=torch.int32, device="cuda") for _ in range(n)]
+        cnt = torch.zeros((n, n), dtype=torch.int32, device="cuda")
+        tk = [tok[r] for r in range(n)]
+        ix = [topk[r].contiguous() for r in range(n)]
+        plan = msx.moe_plan_create(T)
+        try:
+            _, ev = time_calls(torch, lambda: msx.moe_dispatch(tk, ix, E, rt, cnt, rs, plan=plan), 20, 5)
+            msx.check_status()
+            rows = int(cnt.sum().item())
+            ms = sum(ev) / len(ev) / 1e3
+            moved = n * T * H * 2 + rows * H * 2
+            res["dispatch_bf16"] = {"ms": round(ms, 4), "rows_sent": rows, "GBps": round(moved / ms / 1e6, 1),
+                                    "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+            outs = [torch.empty((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+            _, ev = time_calls(torch, lambda: msx.moe_combine(rt, outs, plan=plan), 20, 5)
+            msx.check_status()
+            ms = median(ev) / 1e3
+            moved = rows * H * 2 + n * T * H * 2
+            res["combine_bf16"] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
+                                   "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+            rq = [torch.empty((cap, H), dtype=torch.uint8, device="cuda") for _ in range(n)]
+            rsc = [torch.empty((cap, H // 128), dtype=torch.float32, device="cuda") for _ in range(n)]
+            _, ev = time_calls(torch, lambda: msx.moe_dispatch_fp8(tk, ix, E, rq, rsc, cnt, rs, plan=plan), 20, 5)
+            msx.check_status()
+            ms = median(ev) / 1e3
+            moved = n * T * H * 2 + rows * (H + H // 128 * 4)
+            res["dispatch_fp8"] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
+                                   "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+        finally:
+            torch.cuda.synchronize()
+            msx.moe_plan_destroy(plan)
+        return res
+    leg("config5_moe", config5)
+
+    # ---- primitives against the best achievable (the analogue of the paper's primitive table):
+    # a put -> signal || wait -> read hand-off of 4 KiB (latency) and 1 GiB (throughput) through the
+    # MemoryChannel (thread copy) and through the emulated PortChannel (FIFO + CPU proxy + runtime copy)
+    def handoff():
+        prim = {}
+        for label, nb, blocks in [("4KiB", 4096, 1), ("1GiB", 1 << 30, 128)]:
+            a_ = torch.empty(nb, dtype=torch.uint8, device="cuda").random_()
+            st_ = torch.empty_like(a_)
+            d_ = torch.empty_like(a_)
+            it = 50 if nb <= 4096 else 5
+            row = {}
+            for name, fn in [("memory_channel_us", lambda: msx.prim_put_signal_wait(a_, st_, d_, blocks)),
+                             ("port_channel_us", lambda: msx.prim_port_put_signal_wait(a_, st_, d_)),
+                             ("one_runtime_copy_us", lambda: st_.copy_(a_))]:
+                try:
+                    d_.zero_()
+                    row[name] = round(median(time_calls(torch, fn, it, 3)[1]), 1)
+                    msx.check_status()
+                    if name != "one_runtime_copy_us" and not torch.equal(d_, a_):
+                        row[name] = {"error": "hand-off delivered wrong bytes"}
+                except (msx.MsxError, RuntimeError) as e:
+                    row[name] = {"error": str(e)}
+                    torch.cuda.synchronize()
+                    msx.ctx_reset()
+            prim[label] = row
+            del a_, st_, d_
+        return prim
+    leg("handoff_put_signal_wait_read", handoff)
+
+    leg("hop_ns", lambda: {"signal_wait_round_trip_cross_xcd": round(msx.prim_pingpong(2000, 16, 0, 1), 1),
+                           "signal_wait_round_trip_same_xcd": round(msx.prim_pingpong(2000, 16, 0, 8), 1)})
+
+    # ---- what a call costs on the host when it is not replayed from a graph
+    def host_cost():
+        small = torch.zeros((n, 512), dtype=torch.bfloat16, device="cuda")
+        cargs = (ctypes.c_void_p(small.data_ptr()), ctypes.c_size_t(512), ctypes.c_int(msx.BF16), ctypes.c_int(msx.SUM),
+                 ctypes.c_int(n), raw_stream)
+        cfn = msx.lib().msx_allreduce
+        rows_ = [small[r] for r in range(n)]
+        outs_ = [torch.empty_like(r) for r in rows_]
+        prep = msx.prepare_allreduce(rows_, outs_, None, algo=msx.ALGO_AUTO)
+        crun, chandle = msx.lib().msx_run, prep.handle
+        res = {
+            "python_binding_in_place": round(median([back_to_back_us(torch, lambda: msx.allreduce(small), 100, 10) for _ in range(5)]), 2),
+            "python_prepared_run": round(median([back_to_back_us(torch, lambda: prep.run(raw_stream), 100, 10) for _ in range(5)]), 2),
+            "c_abi_prebuilt_args": round(median([back_to_back_us(torch, lambda: cfn(*cargs), 100, 10) for _ in range(5)]), 2),
+            "c_abi_msx_run": round(median([back_to_back_us(torch, lambda: crun(chandle, raw_stream), 100, 10) for _ in range(5)]), 2),
+        }
+        prep.release()
+        return res
+    leg("plain_launch_us_1KiB", host_cost)
+
+    # ---- floor of one graph node: a one-wave kernel that copies 64 semaphore words, replayed the same way
+    def node_floor():
+        from paper_2504_09014_amd.binding import _stream
+        snap = torch.zeros(64, dtype=torch.int32, device="cuda")
+        return round(graph_us(
+            torch, lambda: msx.lib().msx_prim_barrier(0, n, 1, ctypes.c_void_p(snap.data_ptr()), _stream(None))), 2)
+    leg("graph_node_floor_us", node_floor)
+    return extras
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -234,250 +577,7 @@ def main():
 
     # ---------------------------------------------------------------- extras
     if not args.no_extras:
-        extras = {}
-        lat = {}
-        for kib in [1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024]:
-            c = kib * 1024 // 2
-            xs = synth.normal(n, c, seed=kib)
-            s_ = [xs[r].clone().cuda() for r in range(n)]
-            r_ = [torch.empty_like(t) for t in s_]
-            ll_algo = msx.ALGO_1PA_LL if kib <= 32 else msx.ALGO_2PA_LL     # the paper's split on A100
-            row = {}
-            for name, a in [("ll_us", ll_algo), ("hb_us", msx.ALGO_2PA_HB), ("auto_us", msx.ALGO_AUTO)]:
-                row[name] = round(graph_us(torch, lambda: msx.allreduce_ex(s_, r_, None, algo=a)), 2)
-            g, b, a = msx.last_launch()
-            # the same call launched one by one (no graph): what a caller outside a graph pays
-            row["auto_plain_us"] = round(median([back_to_back_us(
-                torch, lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO), 100, 10) for _ in range(5)]), 2)
-            row.update({"ll_algo": ll_algo, "auto_algo": a, "auto_grid": g, "auto_block": b})
-            lat[f"{kib}KiB"] = row
-        msx.check_status()
-        extras["config2_bf16_latency"] = lat
-        dec = {}
-        for T in [1, 8, 32, 128, 256]:
-            xs, res = synth.decode_activations(n, T, seed=T)
-            s_ = [xs[r].clone().cuda() for r in range(n)]
-            r_ = [torch.empty_like(t) for t in s_]
-            rr = [res.cuda()] * n
-            fn = lambda: msx.allreduce_ex(s_, r_, rr, algo=msx.ALGO_AUTO)
-            gus = graph_us(torch, fn)
-            g, b, a = msx.last_launch()
-            # unfused: the same AllReduce without the residual, then one elementwise add over all ranks' outputs
-            flat = torch.stack(s_).contiguous()
-            rrow = res.cuda().reshape(1, -1)
-
-            def unfused():
-                msx.allreduce(flat)
-                flat.add_(rrow)
-            uus = graph_us(torch, unfused)
-            dec[f"T{T}"] = {"us_in_graph": round(gus, 2), "unfused_us_in_graph": round(uus, 2), "algo": a, "grid": g}
-        msx.check_status()
-        extras["config4_decode_residual"] = dec
-        # config 1
-        xi = synth.int_valued_f32(n, 262144, seed=0)
-        s_ = [xi[r].clone().cuda() for r in range(n)]
-        r_ = [torch.empty_like(t) for t in s_]
-        c1 = {}
-        for name, a in [("1pa_ll", 1), ("2pa_ll", 2), ("2pa_hb", 3), ("2pa_hb_2phase", 4)]:
-            fn = lambda: msx.allreduce_ex(s_, r_, None, algo=a)
-            c1[name] = round(graph_us(torch, fn), 2)
-        msx.check_status()
-        extras["config1_fp32_1MiB_us"] = c1
-        # other HB sizes of config 3
-        c3 = {}
-        for mib in [64, 256]:
-            c = mib * (1 << 20) // 2
-            xs = synth.normal(n, c, seed=mib, device="cuda")
-            s_ = [xs[r] for r in range(n)]
-            r_ = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-            fn = lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO)
-            _, ev = time_calls(torch, fn, 20, 5)
-            ms = sum(ev) / len(ev) / 1e3
-            c3[f"{mib}MiB"] = {"ms": round(ms, 4), "GBps": round(16 * c * 2 / ms / 1e6, 1),
-                               "pct_roofline": round(16 * c * 2 / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
-            del xs, s_, r_
-            torch.cuda.empty_cache()
-        msx.check_status()
-        extras["config3_other_sizes"] = c3
-        # the whole message-size axis of the paper's AllReduce figures, automatic choice, bf16
-        sw = {}
-        for kib in [1, 4, 16, 64, 256, 1024, 4096, 16384, 65536, 262144]:
-            c = kib * 1024 // 2
-            xs = synth.normal(n, c, seed=kib + 5, device="cuda")
-            s_ = [xs[r] for r in range(n)]
-            r_ = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-            fn = lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO)
-            us = graph_us(torch, fn, calls=20, replays=5) if kib <= 16384 else median(time_calls(torch, fn, 10, 3)[1])
-            g, b, a = msx.last_launch()
-            sw[f"{kib}KiB"] = {"us": round(us, 2), "algbw_GBps": round(c * 2 / us / 1e3, 1), "algo": a, "grid": g}
-            del xs, s_, r_
-            torch.cuda.empty_cache()
-        msx.check_status()
-        extras["allreduce_auto_sweep"] = sw
-        # two-phase ring over put/signal/wait hand-offs, next to the all-pairs form
-        ring = {}
-        for mib in [1, 64, 256]:
-            c = mib * (1 << 20) // 2
-            xs = synth.normal(n, c, seed=mib + 1, device="cuda")
-            s_ = [xs[r] for r in range(n)]
-            r_ = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-            row = {}
-            for name, a in [("ring_2pr_us", msx.ALGO_2PR_HB), ("allpairs_2pa_us", msx.ALGO_2PA_HB)]:
-                fn = lambda: msx.allreduce_ex(s_, r_, None, algo=a)
-                row[name] = round(median(time_calls(torch, fn, 10, 3)[1]), 1)
-            ring[f"{mib}MiB"] = row
-            del xs, s_, r_
-            torch.cuda.empty_cache()
-        msx.check_status()
-        extras["ring_vs_allpairs"] = ring
-        # the same algorithms run by the plan-interpreter kernel: overhead over the hand-written kernels
-        interp = {}
-        for kib in [64, 1024, 65536, 262144]:
-            c = kib * 1024 // 2
-            xs = synth.normal(n, c, seed=kib + 2, device="cuda")
-            s_ = [xs[r] for r in range(n)]
-            r_ = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-            row = {}
-            for name, a in [("hand_2pa_us", msx.ALGO_2PA_HB), ("plan_2pa_us", msx.ALGO_PLAN_2PA_HB),
-                            ("hand_2pr_us", msx.ALGO_2PR_HB), ("plan_2pr_us", msx.ALGO_PLAN_2PR_HB)]:
-                fn = lambda: msx.allreduce_ex(s_, r_, None, algo=a)
-                if kib <= 1024:
-                    row[name] = round(graph_us(torch, fn, calls=20, replays=5), 2)
-                else:
-                    row[name] = round(median(time_calls(torch, fn, 10, 3)[1]), 1)
-            row["overhead_2pa_pct"] = round(100 * (row["plan_2pa_us"] / row["hand_2pa_us"] - 1), 1)
-            row["overhead_2pr_pct"] = round(100 * (row["plan_2pr_us"] / row["hand_2pr_us"] - 1), 1)
-            interp[f"{kib}KiB"] = row
-            del xs, s_, r_
-            torch.cuda.empty_cache()
-        msx.check_status()
-        extras["plan_interpreter_vs_hand_kernels"] = interp
-        # standalone ReduceScatter / AllGather / AllToAll (HB protocol), 256 MiB rows
-        other = {}
-        c = 128 << 20                                   # elements per full row (256 MiB of bf16)
-        full = synth.normal(n, c, seed=11, device="cuda")
-        rows_ = [full[r] for r in range(n)]
-        part = [torch.empty(c // n, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-        full2 = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-        for name, fn, moved in [
-            ("reducescatter", lambda: msx.reducescatter_ex(rows_, part), n * c * 2 + c * 2),
-            ("allgather", lambda: msx.allgather_ex(part, full2), c * 2 + n * c * 2),
-            ("alltoall", lambda: msx.alltoall_ex(rows_, full2), 2 * n * c * 2),
-        ]:
-            _, ev = time_calls(torch, fn, 10, 3)
-            ms = median(ev) / 1e3
-            other[name] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
-                           "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
-        msx.check_status()
-        del full, rows_, part, full2
-        torch.cuda.empty_cache()
-        extras["standalone_256MiB_rows"] = other
-        # AllGather / ReduceScatter size sweeps (row = the full buffer of one rank), both protocols
-        sweep = {}
-        for row_kib in [8, 64, 1024, 16384, 262144, 1048576]:
-            c = row_kib * 1024 // 2
-            full = synth.normal(n, c, seed=row_kib, device="cuda")
-            rows_ = [full[r] for r in range(n)]
-            part = [torch.empty(c // n, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-            full2 = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-            row = {}
-            for proto in ("hb", "ll"):
-                if proto == "ll" and row_kib > 1024:      # packets of larger blocks exceed the LL scratch
-                    continue
-                msx.set_option("coll_algo", proto)
-                for name, fn in [("allgather", lambda: msx.allgather_ex(part, full2)),
-                                 ("reducescatter", lambda: msx.reducescatter_ex(rows_, part))]:
-                    if row_kib <= 16384:
-                        us = graph_us(torch, fn, calls=20, replays=5)
-                    else:
-                        us = median(time_calls(torch, fn, 8, 2)[1])
-                    row[f"{name}_{proto}_us"] = round(us, 2)
-            msx.set_option("coll_algo", "auto")
-            moved_ag = c * 2 + n * c * 2
-            moved_rs = n * c * 2 + c * 2
-            row["allgather_hb_GBps"] = round(moved_ag / row["allgather_hb_us"] / 1e3, 1)
-            row["reducescatter_hb_GBps"] = round(moved_rs / row["reducescatter_hb_us"] / 1e3, 1)
-            sweep[f"{row_kib}KiB"] = row
-            del full, rows_, part, full2
-            torch.cuda.empty_cache()
-        msx.check_status()
-        extras["allgather_reducescatter_sweep"] = sweep
-        # config 5
-        T, H, K, E = 4096, 7168, 8, 256
-        tok = synth.moe_tokens(n, T, H, seed=0, device="cuda")
-        topk = synth.moe_routing(n, T, K, E, seed=0, device="cuda")
-        cap = 24576
-        rt = [torch.empty((cap, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-        rs = [torch.empty((cap,), dtype=torch.int32, device="cuda") for _ in range(n)]
-        cnt = torch.zeros((n, n), dtype=torch.int32, device="cuda")
-        tk = [tok[r] for r in range(n)]
-        ix = [topk[r].contiguous() for r in range(n)]
-        fn = lambda: msx.moe_dispatch(tk, ix, E, rt, cnt, rs)
-        _, ev = time_calls(torch, fn, 20, 5)
-        msx.check_status()
-        rows = int(cnt.sum().item())
-        ms = sum(ev) / len(ev) / 1e3
-        moved = n * T * H * 2 + rows * H * 2
-        extras["config5_moe_dispatch"] = {"ms": round(ms, 4), "rows_sent": rows, "GBps": round(moved / ms / 1e6, 1),
-                                          "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
-        outs = [torch.empty((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
-        fnc = lambda: msx.moe_combine(rt, outs)
-        _, ev = time_calls(torch, fnc, 20, 5)
-        msx.check_status()
-        ms = median(ev) / 1e3
-        moved = rows * H * 2 + n * T * H * 2
-        extras["config5_moe_combine"] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
-                                         "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
-        rq = [torch.empty((cap, H), dtype=torch.uint8, device="cuda") for _ in range(n)]
-        rsc = [torch.empty((cap, H // 128), dtype=torch.float32, device="cuda") for _ in range(n)]
-        fn8 = lambda: msx.moe_dispatch_fp8(tk, ix, E, rq, rsc, cnt, rs)
-        _, ev = time_calls(torch, fn8, 20, 5)
-        msx.check_status()
-        ms = median(ev) / 1e3
-        moved = n * T * H * 2 + rows * (H + H // 128 * 4)
-        extras["config5_moe_dispatch_fp8"] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
-                                              "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
-        del rq, rsc
-        # primitives against the best achievable (the analogue of the paper's primitive table):
-        # a put -> signal || wait -> read hand-off of 4 KiB (latency) and 1 GiB (throughput) through the
-        # MemoryChannel (thread copy) and through the emulated PortChannel (FIFO + CPU proxy + runtime copy)
-        prim = {}
-        for label, nb, blocks in [("4KiB", 4096, 1), ("1GiB", 1 << 30, 128)]:
-            a_ = torch.empty(nb, dtype=torch.uint8, device="cuda").random_()
-            st_ = torch.empty_like(a_)
-            d_ = torch.empty_like(a_)
-            it = 50 if nb <= 4096 else 5
-            t_mem = median(time_calls(torch, lambda: msx.prim_put_signal_wait(a_, st_, d_, blocks), it, 3)[1])
-            t_port = median(time_calls(torch, lambda: msx.prim_port_put_signal_wait(a_, st_, d_), it, 3)[1])
-            t_copy = median(time_calls(torch, lambda: st_.copy_(a_), it, 3)[1])
-            prim[label] = {"memory_channel_us": round(t_mem, 1), "port_channel_us": round(t_port, 1),
-                           "one_runtime_copy_us": round(t_copy, 1)}
-            msx.check_status()
-            if not (torch.equal(d_, a_)):
-                print("bench.py: primitive hand-off delivered wrong bytes", file=sys.stderr)
-                sys.exit(1)
-            del a_, st_, d_
-        extras["handoff_put_signal_wait_read"] = prim
-        extras["hop_ns"] = {"signal_wait_round_trip_cross_xcd": round(msx.prim_pingpong(2000, 16, 0, 1), 1),
-                            "signal_wait_round_trip_same_xcd": round(msx.prim_pingpong(2000, 16, 0, 8), 1)}
-        # what a call costs on the host when it is not replayed from a graph: through the Python
-        # binding (tables built per call) and through the C ABI with its arguments built once
-        import ctypes
-        small = torch.zeros((n, 512), dtype=torch.bfloat16, device="cuda")
-        cargs = (ctypes.c_void_p(small.data_ptr()), ctypes.c_size_t(512), ctypes.c_int(msx.BF16), ctypes.c_int(msx.SUM),
-                 ctypes.c_int(n), ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
-        cfn = msx.lib().msx_allreduce
-        extras["plain_launch_us_1KiB"] = {
-            "python_binding": round(median([back_to_back_us(torch, lambda: msx.allreduce(small), 100, 10) for _ in range(5)]), 2),
-            "c_abi_prebuilt_args": round(median([back_to_back_us(torch, lambda: cfn(*cargs), 100, 10) for _ in range(5)]), 2),
-        }
-        # floor of one graph node: a one-wave kernel that copies 64 semaphore words, replayed the same way
-        from paper_2504_09014_amd.binding import _stream
-        snap = torch.zeros(64, dtype=torch.int32, device="cuda")
-        extras["graph_node_floor_us"] = round(graph_us(
-            torch, lambda: msx.lib().msx_prim_barrier(0, n, 1, ctypes.c_void_p(snap.data_ptr()), _stream(None))), 2)
-        msx.check_status()
-        out["extras"] = extras
+        out["extras"] = run_extras(torch, msx, synth, n)
 
     print(json.dumps(out), flush=True)
 

@@ -841,7 +841,8 @@ void lower_allreduce(int algo, int n, int chans, size_t nbytes, int threads, int
 
 // The lists as the interpreter reads them: every workgroup's at a fixed stride, padded with end marks; a rank
 // barrier that every list begins with is taken out (the kernel runs it while the list is on its way) and
-// described by *head (bit 0: there is one; bits 1, 2: its flags).
+// described by *head (bit 0: there is one; bits 1, 2: its flags); a drain right in front of a barrier or a
+// signal becomes a flag of that operation (kPlanDrainFirst): one step of the interpreter less per hand-off.
 void pack_plan(const std::vector<PlanOp>& ops, const std::vector<unsigned>& start, std::vector<PlanOp>* packed,
                unsigned* stride, int* head)
 {
@@ -853,12 +854,23 @@ void pack_plan(const std::vector<PlanOp>& ops, const std::vector<unsigned>& star
     }
     *head = common ? 1 | (ops[start[0]].flags << 1) : 0;
     const unsigned skip = common ? 1u : 0u;
+    std::vector<std::vector<PlanOp>> fused(lists);
     unsigned longest = 1;
-    for (size_t b = 0; b < lists; ++b) longest = std::max(longest, start[b + 1] - start[b] - skip);
+    for (size_t b = 0; b < lists; ++b) {
+        for (unsigned k = start[b] + skip; k < start[b + 1]; ++k) {
+            PlanOp o = ops[k];
+            if (o.code == kOpDrain && k + 1 < start[b + 1] && (ops[k + 1].code == kOpBarrier || ops[k + 1].code == kOpSignal)) {
+                o = ops[++k];
+                o.flags |= kPlanDrainFirst;
+            }
+            fused[b].push_back(o);
+        }
+        longest = std::max(longest, (unsigned)fused[b].size());
+    }
     *stride = longest;
     packed->assign(lists * longest, plan_op(kOpEnd));
     for (size_t b = 0; b < lists; ++b)
-        for (unsigned k = start[b] + skip; k < start[b + 1]; ++k) (*packed)[b * longest + (k - start[b] - skip)] = ops[k];
+        for (size_t k = 0; k < fused[b].size(); ++k) (*packed)[b * longest + k] = fused[b][k];
 }
 
 int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nbytes, int dtype, int n, int algo,
@@ -868,7 +880,10 @@ int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nb
     const bool packets = algo == MSX_ALGO_PLAN_1PA_LL || algo == MSX_ALGO_PLAN_2PA_LL;
     const int threads = 256;
     int chans = 1, rc, held = 0;
-    const void* kp = dtype == MSX_F32 ? (const void*)k_plan_executor<0, 0> : (const void*)k_plan_executor<1, 0>;
+    // one instantiation per operation family (channel operations / packet operations)
+    const void* kp = packets ? (n == 8 ? (dtype == MSX_F32 ? (const void*)k_plan_executor<0, 0, 1, 8> : (const void*)k_plan_executor<1, 0, 1, 8>)
+                                       : (dtype == MSX_F32 ? (const void*)k_plan_executor<0, 0, 1, 0> : (const void*)k_plan_executor<1, 0, 1, 0>))
+                             : (dtype == MSX_F32 ? (const void*)k_plan_executor<0, 0, 0> : (const void*)k_plan_executor<1, 0, 0>);
     if (packets) {
         if (nbytes % 2) return MSX_ERR_UNSUPPORTED;
         const size_t P = (nbytes + 7) / 8, cp = (P + (size_t)n - 1) / (size_t)n;
@@ -903,6 +918,12 @@ int plan_allreduce(Ctx* c, const void* const* send, void* const* recv, size_t nb
         std::vector<unsigned> start;
         lower_allreduce(algo, n, chans, nbytes, threads, held, &ops, &start);
         pack_plan(ops, start, &packed, &found.stride, &found.head);
+        for (const PlanOp& o : packed) {                 // the kernel chosen above carries one family only
+            const bool pkt_op = o.code == kOpPutPacket || o.code == kOpReducePacket || o.code == kOpCopyPacket;
+            const bool chan_op = o.code == kOpBarrier || o.code == kOpSignal || o.code == kOpWait || o.code == kOpReducePut ||
+                                 o.code == kOpDrain;
+            if ((packets && (chan_op || (found.head & 1))) || (!packets && pkt_op)) return MSX_ERR_UNSUPPORTED;
+        }
         if (hipMalloc((void**)&found.ops, packed.size() * sizeof(PlanOp)) != hipSuccess) return MSX_ERR_NOMEM;
         if (t_record) {                                  // a prepared call keeps its plan for itself
             t_record->owned.push_back(found.ops);

@@ -37,6 +37,8 @@ enum PlanCode : int {
     kOpPutHeld = 11       // store held[h] to vector first + t + h * step of every destination, paced
 };
 
+constexpr int kPlanDrainFirst = 4;    // flag of a barrier or a signal: wait for this workgroup's stores first
+
 enum BufKind : int { kBufIn = 0, kBufOut = 1, kBufScratch = 2 };
 
 struct PlanRef { short kind; short rank; };   // which buffer: kind of rank
@@ -334,9 +336,16 @@ __device__ __forceinline__ void plan_put_held(const PlanPtrs& bufs, const PlanOp
 // 64 fills the register file, one workgroup per CU).  The instantiation with held sums runs the operations of
 // the read phase / write phase schedule only (barriers, drain, the held pair, a plain reduce-put for ragged
 // ends): whatever else sat in its loop would compete with the sums for registers.
-template <int DT, int HELD>
+// FAM picks the operation families an instantiation carries, by what a plan contains (the host looks): 0 the
+// channel operations (barrier, signal, wait, drain, reduce-put), 1 the packet operations, 2 both (no lowering
+// here mixes them, so 2 is not instantiated and the host refuses such a plan).  NR: the rank count the packet
+// operations are compiled for (8, or 0 = any, read from the arguments), again so that a call carries one copy.  The code of
+// the families a plan does not use is still in the way of the ones it does: a small message spends its time
+// fetching instructions, and the two-family kernel took 0.4 us longer per call than the one-family kernels.
+template <int DT, int HELD, int FAM = 0, int NR = 0>
 __global__ __launch_bounds__(256) void k_plan_executor(PlanArgs a, DevCtx c)
 {
+    constexpr bool kChan = HELD == 0 && FAM != 1, kPkt = HELD == 0 && FAM != 0;
     const int n = a.n;
     const int rank = (int)(blockIdx.x % (unsigned)n);
     const int chan = (int)(blockIdx.x / (unsigned)n);
@@ -349,21 +358,25 @@ __global__ __launch_bounds__(256) void k_plan_executor(PlanArgs a, DevCtx c)
     __shared__ PlanBufs bufs;
     const unsigned n_ops = a.stride < kLdsOps ? a.stride : kLdsOps;     // longer lists come in windows of kLdsOps
     const u32x4* g = (const u32x4*)(a.ops + (size_t)blockIdx.x * a.stride);
-    u32x4 early = {0u, 0u, 0u, 0u};
-    if (threadIdx.x < n_ops * kVecsPerOp) early = g[threadIdx.x];
-    if (threadIdx.x < (unsigned)kMaxRanks) {
-#pragma unroll
-        for (int r = 0; r < kMaxRanks; ++r)
-            if ((int)threadIdx.x == r) {
-                bufs.p[kBufIn][r] = a.in[r];
-                bufs.p[kBufOut][r] = a.out[r];
-                bufs.p[kBufScratch][r] = a.scratch[r];
-            }
-    }
+    // (no branch around the load - surplus threads fetch the last vector again - so that everything the
+    // kernel asks of its arguments up to here is requested, and waited for, together)
+    const unsigned early_vecs = n_ops * kVecsPerOp;
+    const u32x4 early = g[threadIdx.x < early_vecs ? threadIdx.x : early_vecs - 1u];
+    // Lane t of the first 24 keeps pointer t of the three tables, fetched with one vector load straight from
+    // the kernel-argument segment (the explicit arguments start at its offset 0, and the tables are the first
+    // members of the first argument).  Through scalar registers the 24 pointers were fetched, and waited for,
+    // in several goes in front of the first barrier: 0.6 us.
+    static_assert(offsetof(PlanArgs, in) == 0 && offsetof(PlanArgs, out) == sizeof(void*) * kMaxRanks &&
+                  offsetof(PlanArgs, scratch) == 2 * sizeof(void*) * kMaxRanks, "table layout");
+    const void* mine = nullptr;
+    if (threadIdx.x < 3u * (unsigned)kMaxRanks)
+        mine = ((const void* const MSX_GLOBAL*)__builtin_amdgcn_kernarg_segment_ptr())[threadIdx.x];
     PlanLl ll{CallTag{0u, 0u, 0u, 0u}, n, rank, a.nbytes};
-    if (a.packets) ll.tag = call_begin(c);
+    if constexpr (kPkt)
+        if (a.packets) ll.tag = call_begin(c);
     if (rank == c.drop_rank) {
-        if (a.packets) call_end(c, ll.tag);
+        if constexpr (kPkt)
+            if (a.packets) call_end(c, ll.tag);
         return;
     }
     [[maybe_unused]] GridBar gb{0u, 0u, true};
@@ -377,7 +390,8 @@ __global__ __launch_bounds__(256) void k_plan_executor(PlanArgs a, DevCtx c)
         pace = a.pace ? ctl.pace : 0u;
     }
     bool alive = true;
-    if (a.head & 1) alive = rank_barrier<true>(c, rank, n, chan, 400, (a.head & 2) != 0, (a.head & 4) != 0);
+    if constexpr (kChan || HELD > 0)
+        if (a.head & 1) alive = rank_barrier<true>(c, rank, n, chan, 400, (a.head & 2) != 0, (a.head & 4) != 0);
     // every buffer the `count` operations in the window name, looked up once (workgroup-collective)
     auto resolve = [&](unsigned count) {
         __syncthreads();
@@ -390,6 +404,7 @@ __global__ __launch_bounds__(256) void k_plan_executor(PlanArgs a, DevCtx c)
         __syncthreads();
     };
     {
+        if (threadIdx.x < 3u * (unsigned)kMaxRanks) (&bufs.p[0][0])[threadIdx.x] = mine;
         u32x4* l = (u32x4*)lds_ops;
         if (threadIdx.x < n_ops * kVecsPerOp) l[threadIdx.x] = early;
         for (unsigned i = threadIdx.x + 256u; i < n_ops * kVecsPerOp; i += 256u) l[i] = g[i];
@@ -411,14 +426,17 @@ __global__ __launch_bounds__(256) void k_plan_executor(PlanArgs a, DevCtx c)
         if (code == kOpEnd) break;
         switch (code) {
             case kOpBarrier:
-                alive = rank_barrier<true>(c, rank, n, chan, 400, (op->flags & 1) != 0, (op->flags & 2) != 0);
+                if (op->flags & kPlanDrainFirst) put_drain();
+                if constexpr (kChan || HELD > 0)
+                    alive = rank_barrier<true>(c, rank, n, chan, 400, (op->flags & 1) != 0, (op->flags & 2) != 0);
                 break;
             case kOpSignal:
-                if constexpr (HELD == 0) channel_signal(c, rank, op->peer, chan, 401, (op->flags & 1) != 0);
+                if (op->flags & kPlanDrainFirst) put_drain();
+                if constexpr (kChan) channel_signal(c, rank, op->peer, chan, 401, (op->flags & 1) != 0);
                 break;
             case kOpWait:
                 // a wait that runs out ends the list: what it guards must not be consumed
-                if constexpr (HELD == 0)
+                if constexpr (kChan)
                     alive = channel_wait(c, rank, op->peer, chan, (op->flags & 2) ? 402 : 403, (op->flags & 2) != 0);
                 break;
             case kOpDrain:
@@ -428,7 +446,7 @@ __global__ __launch_bounds__(256) void k_plan_executor(PlanArgs a, DevCtx c)
                 const int ns = op->nsrc, nd = op->ndst, wt = op->dst_wt;
                 if constexpr (HELD > 0) {
                     plan_reduce_put_any<DT>(lds_ptrs[pc % kLdsOps], op);    // a chunk's ragged end only: less than one vector per thread
-                } else {
+                } else if constexpr (kChan) {
                     if (ns == 8 && nd == 8 && wt == 0xff) plan_reduce_put_run<DT, 8, 8, true>(lds_ptrs[pc % kLdsOps], op);
                     else if (ns == 1 && nd == 1 && wt == 1) plan_reduce_put_run<DT, 1, 1, true>(lds_ptrs[pc % kLdsOps], op);
                     else if (ns == 2 && nd == 1 && wt == 1) plan_reduce_put_run<DT, 2, 1, true>(lds_ptrs[pc % kLdsOps], op);
@@ -438,18 +456,18 @@ __global__ __launch_bounds__(256) void k_plan_executor(PlanArgs a, DevCtx c)
                 break;
             }
             case kOpPutPacket:
-                if constexpr (HELD == 0) {
-                    if (n == 8) plan_put_packet<8>(lds_ptrs[pc % kLdsOps], op, c, ll); else plan_put_packet<0>(lds_ptrs[pc % kLdsOps], op, c, ll);
+                if constexpr (kPkt) {
+                    plan_put_packet<NR>(lds_ptrs[pc % kLdsOps], op, c, ll);
                 }
                 break;
             case kOpReducePacket:
-                if constexpr (HELD == 0) {
-                    if (n == 8) plan_reduce_packet<DT, 8>(lds_ptrs[pc % kLdsOps], op, c, ll); else plan_reduce_packet<DT, 0>(lds_ptrs[pc % kLdsOps], op, c, ll);
+                if constexpr (kPkt) {
+                    plan_reduce_packet<DT, NR>(lds_ptrs[pc % kLdsOps], op, c, ll);
                 }
                 break;
             case kOpCopyPacket:
-                if constexpr (HELD == 0) {
-                    if (n == 8) plan_copy_packet<8>(lds_ptrs[pc % kLdsOps], op, c, ll); else plan_copy_packet<0>(lds_ptrs[pc % kLdsOps], op, c, ll);
+                if constexpr (kPkt) {
+                    plan_copy_packet<NR>(lds_ptrs[pc % kLdsOps], op, c, ll);
                 }
                 break;
             case kOpReduceHold:
@@ -507,7 +525,8 @@ __global__ __launch_bounds__(256) void k_plan_executor(PlanArgs a, DevCtx c)
         if (a.pace && blockIdx.x == 0 && threadIdx.x == 0) pace_save(c, ctl, key);
         grid_barrier_end(c, gb, gen);
     }
-    if (a.packets) call_end(c, ll.tag);
+    if constexpr (kPkt)
+        if (a.packets) call_end(c, ll.tag);
 }
 
 }  // namespace msx
