@@ -91,7 +91,7 @@ def pct(v, q):
     return s[min(len(s) - 1, max(0, int(round(q / 100.0 * (len(s) - 1)))))]
 
 
-def run_extras(torch, msx, synth, n):
+def run_extras(torch, msx, synth, n, port=True):
     """Every other table of the bench.  Each leg runs on its own: a leg that fails (a time-out of
     the port proxy under a profiler that serialises dispatches, for one) is recorded as
     {"error": ...}, the context is reset, and the next leg runs."""
@@ -227,6 +227,9 @@ def run_extras(torch, msx, synth, n):
             row = {}
             for name, a in [("ring_thread_copy_us", msx.ALGO_2PR_HB), ("ring_port_us", msx.ALGO_2PR_PORT),
                             ("allpairs_2pa_us", msx.ALGO_2PA_HB)]:
+                if a == msx.ALGO_2PR_PORT and not port:
+                    row[name] = None
+                    continue
                 try:
                     row[name] = round(median(time_calls(
                         torch, lambda: msx.allreduce_ex(s_, r_, None, algo=a), 6 if mib >= 256 else 10, 2)[1]), 1)
@@ -235,7 +238,7 @@ def run_extras(torch, msx, synth, n):
                     row[name] = {"error": str(e)}
                     torch.cuda.synchronize()
                     msx.ctx_reset()
-            if isinstance(row["ring_port_us"], float) and isinstance(row["ring_thread_copy_us"], float):
+            if isinstance(row.get("ring_port_us"), float) and isinstance(row.get("ring_thread_copy_us"), float):
                 row["port_over_thread_copy"] = round(row["ring_port_us"] / row["ring_thread_copy_us"], 2)
             ring[f"{mib}MiB"] = row
             del s_, r_
@@ -289,6 +292,14 @@ def run_extras(torch, msx, synth, n):
             ms = median(ev) / 1e3
             other[name] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1),
                            "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
+        msx.check_status()
+        # the all-to-all with the peer loop inside at every size (the order the small blocks take), for comparison
+        msx.set_option("a2a_blocks_min_bytes", str(1 << 60))
+        try:
+            ms = median(time_calls(torch, lambda: msx.alltoall_ex(rows_, full2), 10, 3)[1]) / 1e3
+        finally:
+            msx.set_option("a2a_blocks_min_bytes", str(4 << 20))
+        other["alltoall_peer_loop_inside"] = {"ms": round(ms, 4), "GBps": round(2 * n * c * 2 / ms / 1e6, 1)}
         msx.check_status()
         dst = torch.empty_like(full)
         ms = median(time_calls(torch, lambda: dst.copy_(full), 10, 3)[1]) / 1e3
@@ -372,6 +383,26 @@ def run_extras(torch, msx, synth, n):
         return res
     leg("config5_moe", config5)
 
+    # ---- what this GPU's memory sustains for plain streams (the yardstick for every bandwidth figure above)
+    def streams():
+        res = {}
+        nb = 2 << 30
+        a_ = torch.empty(nb, dtype=torch.uint8, device="cuda").random_()
+        b_ = torch.empty_like(a_)
+        for name, mode, moved in [("read_only", 0, nb), ("write_only", 1, nb), ("copy", 2, 2 * nb)]:
+            best = None
+            for blocks in (256, 512, 1024, 2048, 4096, 8192, 16384):
+                us = median(time_calls(torch, lambda: msx.prim_stream(mode, a_, b_, blocks), 6, 2)[1])
+                if best is None or us < best[0]:
+                    best = (us, blocks)
+            res[name] = {"GBps": round(moved / best[0] / 1e3, 1), "blocks": best[1]}
+        us = median(time_calls(torch, lambda: b_.copy_(a_), 8, 2)[1])
+        res["runtime_copy"] = {"GBps": round(2 * nb / us / 1e3, 1)}
+        if not torch.equal(a_, b_):
+            res["error"] = "copy delivered wrong bytes"
+        return res
+    leg("hbm_stream_ceilings_2GiB", streams)
+
     # ---- primitives against the best achievable (the analogue of the paper's primitive table):
     # a put -> signal || wait -> read hand-off of 4 KiB (latency) and 1 GiB (throughput) through the
     # MemoryChannel (thread copy) and through the emulated PortChannel (FIFO + CPU proxy + runtime copy)
@@ -386,6 +417,9 @@ def run_extras(torch, msx, synth, n):
             for name, fn in [("memory_channel_us", lambda: msx.prim_put_signal_wait(a_, st_, d_, blocks)),
                              ("port_channel_us", lambda: msx.prim_port_put_signal_wait(a_, st_, d_)),
                              ("one_runtime_copy_us", lambda: st_.copy_(a_))]:
+                if name == "port_channel_us" and not port:
+                    row[name] = None
+                    continue
                 try:
                     d_.zero_()
                     row[name] = round(median(time_calls(torch, fn, it, 3)[1]), 1)
@@ -442,6 +476,9 @@ def main():
     ap.add_argument("--mib", type=int, default=1024, help="bf16 MiB per rank of the headline AllReduce")
     ap.add_argument("--no-extras", action="store_true", help="skip latency / decode / dispatch tables")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-port", action="store_true",
+                    help="skip the legs that need the port's proxy copies to run beside a waiting kernel "
+                         "(they cannot under a profiler that serialises dispatches, and would time out)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, to scale "
                          "hardware byte counters against)")
@@ -577,7 +614,7 @@ def main():
 
     # ---------------------------------------------------------------- extras
     if not args.no_extras:
-        out["extras"] = run_extras(torch, msx, synth, n)
+        out["extras"] = run_extras(torch, msx, synth, n, port=not args.no_port)
 
     print(json.dumps(out), flush=True)
 

@@ -280,6 +280,12 @@ int msx_prim_barrier(int rounds, int nranks, int blocks_per_rank, uint32_t* sem_
 int msx_prim_put_signal_wait(const void* src, void* staging, void* dst, size_t nbytes,
                              int blocks_per_rank, void* stream);
 
+/* Plain streams, the yardstick for the bandwidth kernels (no passage of the paper: a measurement aid).
+ * mode 0 reads nbytes from src, 1 writes nbytes to dst, 2 copies src -> dst, with `blocks` workgroups of 256
+ * threads and streaming 16-byte accesses.  src, dst: device, 16-byte aligned (the unused one may be NULL);
+ * nbytes a multiple of 16.  Mode 1 fills dst with a pattern of no meaning. */
+int msx_prim_stream(int mode, const void* src, void* dst, size_t nbytes, int blocks, void* stream);
+
 /* PortChannel hand-off (port-mapped I/O, emulated): rank 0 pushes put(src -> staging), signal and
  * flush requests into a FIFO in host memory; a CPU proxy thread of the library carries them out
  * (hipMemcpyAsync device to device on its own stream; the signal is a one-wave kernel behind the copy
@@ -359,6 +365,7 @@ int msx_last_status(void* ctx, int* rank, int* site, unsigned* expected, unsigne
  *                     all-to-all: 0 = by block size (block after block with the ranks in step from 4 MiB blocks, the
  *                     peer loop inside below), 1 / 2 = block after block at any size, without / with the rank
  *                     barrier between blocks
+ *   "a2a_blocks_min_bytes"  that block size (default 4 MiB; a huge value keeps the peer loop inside at any size)
  *   "barrier_fences"  0..3    msx_prim_barrier only: bit 0 release fence, bit 1 acquire fence
  *   "spin_limit"      polls before a wait gives up
  *   "drop_rank"       -1, or a rank whose workgroups return at once (failure-path tests)

@@ -18,7 +18,7 @@ __all__ = [
     "moe_plan_create", "moe_plan_destroy",
     "prepare_allreduce", "prepare_reducescatter", "prepare_allgather", "prepare_alltoall",
     "prepare_moe_dispatch", "prepare_moe_combine", "run", "release", "Prepared",
-    "prim_pingpong", "prim_barrier", "prim_put_signal_wait", "prim_ll_encode", "prim_ll_roundtrip", "prim_port_put_signal_wait",
+    "prim_pingpong", "prim_barrier", "prim_put_signal_wait", "prim_ll_encode", "prim_ll_roundtrip", "prim_port_put_signal_wait", "prim_stream",
     "EXPORTS",
 ]
 
@@ -36,7 +36,7 @@ EXPORTS = [
     "msx_prepare_moe_dispatch", "msx_prepare_moe_combine", "msx_run", "msx_release",
     "msx_ctx_create", "msx_ctx_destroy", "msx_ctx_reset", "msx_ctx_use", "msx_ctx_set_max_blocks", "msx_last_status",
     "msx_prim_pingpong", "msx_prim_barrier", "msx_prim_put_signal_wait", "msx_prim_ll_encode",
-    "msx_prim_ll_roundtrip", "msx_prim_port_put_signal_wait",
+    "msx_prim_ll_roundtrip", "msx_prim_port_put_signal_wait", "msx_prim_stream",
     "msx_init", "msx_reset", "msx_finalize", "msx_set_option", "msx_get_option", "msx_status",
     "msx_last_launch", "msx_last_hip_error", "msx_strerror", "msx_version",
     "msx_debug_choose", "msx_debug_lower_plan", "msx_debug_lower_plan_ex", "msx_debug_pace_update", "msx_debug_owner_magic",
@@ -102,6 +102,7 @@ def lib():
         L.msx_prim_port_put_signal_wait.argtypes = [vp, vp, vp, sz, vp]
         L.msx_prim_ll_encode.argtypes = [vp, sz, u32, vp, vp]
         L.msx_prim_ll_roundtrip.argtypes = [vp, vp, sz, i, vp]
+        L.msx_prim_stream.argtypes = [i, vp, vp, sz, i, vp]
         L.msx_set_option.argtypes = [C.c_char_p, C.c_char_p]
         L.msx_get_option.argtypes = [C.c_char_p, C.c_char_p, sz]
         L.msx_status.argtypes = [vp, C.POINTER(u32)]
@@ -515,3 +516,12 @@ def prim_ll_roundtrip(src, dst, blocks_per_rank=1, stream=None):
     nbytes = src.numel() * src.element_size()
     _ck(lib().msx_prim_ll_roundtrip(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), nbytes,
                                     blocks_per_rank, _stream(stream)), "msx_prim_ll_roundtrip")
+
+
+def prim_stream(mode, src, dst, blocks=2048, stream=None):
+    """mode 0: read src, 1: write dst, 2: copy src -> dst (the unused tensor may be None)."""
+    t = src if src is not None else dst
+    nbytes = t.numel() * t.element_size()
+    _ck(lib().msx_prim_stream(mode, C.c_void_p(src.data_ptr()) if src is not None else None,
+                              C.c_void_p(dst.data_ptr()) if dst is not None else None, nbytes, blocks,
+                              _stream(stream)), "msx_prim_stream")

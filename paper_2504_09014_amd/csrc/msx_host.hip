@@ -52,6 +52,7 @@ struct Options {
     // write phases (k_allreduce_hb_phased).  -1 = automatic: 8 ranks from 40 MiB (see use_phased; with fewer
     // ranks, whose phases are smaller, it loses), never otherwise
     long long hb_phased_min = -1;
+    size_t a2a_blocks_min = (size_t)4 << 20;   // all-to-all: block after block from blocks of this many bytes
     int hb_barriers = 1;
     int hb_pace = 1;          // phased kernels: pace the write phase (see k_allreduce_hb_phased)
     int peer_outer = 0;
@@ -174,8 +175,8 @@ void port_proxy(Port* p)
                         }
                     } else if (q.type == kPortSignal) {
                         const int recv = (int)(q.arg & 0xffu), send = (int)((q.arg >> 8) & 0xffu), nsem = (int)(q.arg >> 16);
-                        if (ok && recv < kMaxRanks && send < kMaxRanks && nsem >= 1 && nsem <= 64) {
-                            hipLaunchKernelGGL(k_port_signal, dim3(1), dim3(64), 0, p->stream, p->sem, recv, send, nsem);
+                        if (ok && recv < kMaxRanks && send < kMaxRanks && nsem >= 1 && nsem <= kMaxChannels) {
+                            hipLaunchKernelGGL(k_port_signal, dim3(1), dim3(nsem <= 64 ? 64 : 256), 0, p->stream, p->sem, recv, send, nsem);
                             hipError_t e = hipGetLastError();
                             if (e != hipSuccess) fail(e);
                         }
@@ -1270,7 +1271,7 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     a.barriers = g_opt.hb_barriers;
     // all-to-all of large blocks: block after block, the ranks in step (see k_alltoall_hb); "peer_outer" 1 / 2
     // force that order for any size (1: without the rank barrier between the blocks)
-    if (which == kA2A) a.peer_outer = g_opt.peer_outer ? g_opt.peer_outer : (count_or_bytes >= ((size_t)4 << 20) ? 2 : 0);
+    if (which == kA2A) a.peer_outer = g_opt.peer_outer ? g_opt.peer_outer : (count_or_bytes >= g_opt.a2a_blocks_min ? 2 : 0);
     note_launch(n * chans, threads, MSX_ALGO_2PA_HB);
     const DevCtx d = dev_ctx(c);
     switch (which) {
@@ -1722,6 +1723,23 @@ int msx_prim_put_signal_wait(const void* src, void* staging, void* dst, size_t n
                   nbytes, blocks_per_rank);
 }
 
+int msx_prim_stream(int mode, const void* src, void* dst, size_t nbytes, int blocks, void* stream)
+{
+    if (mode < 0 || mode > 2 || blocks < 1 || blocks > 65536 || nbytes % 16) return MSX_ERR_ARG;
+    if ((mode != 1 && (!src || !aligned16(src))) || (mode != 0 && (!dst || !aligned16(dst)))) return MSX_ERR_ARG;
+    if (nbytes == 0) return MSX_OK;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Ctx* c = nullptr;
+    int rc = get_ctx(&c);
+    if (rc) return rc;
+    note_launch(blocks, 256, 0);
+    const size_t nvec = nbytes / 16;
+    unsigned* sink = c->d.status + 15;     // a word of the status block nothing reads; written only if the data is all ones
+    if (mode == 0) return launch(k_stream<0>, blocks, 256, (hipStream_t)stream, (const u32x4*)src, (u32x4*)nullptr, nvec, sink);
+    if (mode == 1) return launch(k_stream<1>, blocks, 256, (hipStream_t)stream, (const u32x4*)nullptr, (u32x4*)dst, nvec, sink);
+    return launch(k_stream<2>, blocks, 256, (hipStream_t)stream, (const u32x4*)src, (u32x4*)dst, nvec, sink);
+}
+
 int msx_prim_ll_encode(const void* src, size_t nbytes, uint32_t flag, void* packets_out, void* stream)
 {
     if (nbytes == 0) return MSX_OK;
@@ -1768,7 +1786,7 @@ int msx_prim_port_put_signal_wait(const void* src, void* staging, void* dst, siz
     if (resident < 2) return MSX_ERR_UNSUPPORTED;
     size_t readers = (nbytes + (256 * 16 * 8) - 1) / (256 * 16 * 8);   // 32 KiB per reading workgroup and pass
     if (readers < 1) readers = 1;
-    if (readers > 64) readers = 64;
+    if (readers > 128) readers = 128;      // half of the CUs: the proxy's copy kernel needs the others while these wait
     if ((int)readers + 1 > resident) readers = (size_t)resident - 1;
     port_announce(p, g_opt.drop_rank == 0 ? 0 : 3);   // put, signal, flush (a dropped sender pushes nothing)
     note_launch(1 + (int)readers, 256, 0);
@@ -2144,6 +2162,7 @@ int msx_set_option(const char* key, const char* value)
     if (k == "ll_1pa_max_bytes") g_opt.ll_1pa_max = (size_t)u;
     else if (k == "ll_2pa_max_bytes") g_opt.ll_2pa_max = (size_t)u;
     else if (k == "coll_ll_max_bytes") g_opt.coll_ll_max = (size_t)u;
+    else if (k == "a2a_blocks_min_bytes") g_opt.a2a_blocks_min = (size_t)u;
     else if (k == "hb_phased_min_bytes") g_opt.hb_phased_min = u > (unsigned long long)LLONG_MAX ? LLONG_MAX : (long long)u;
     else if (k == "ll_max_bytes") {
         if (u < 4096 || u > (16u << 20)) return MSX_ERR_ARG;
@@ -2228,6 +2247,7 @@ int msx_get_option(const char* key, char* value_out, size_t value_len)
     if (k == "ll_1pa_max_bytes") u = g_opt.ll_1pa_max;
     else if (k == "ll_2pa_max_bytes") u = g_opt.ll_2pa_max;
     else if (k == "coll_ll_max_bytes") u = g_opt.coll_ll_max;
+    else if (k == "a2a_blocks_min_bytes") u = g_opt.a2a_blocks_min;
     else if (k == "hb_phased_min_bytes") {
         if (g_opt.hb_phased_min < 0) { snprintf(value_out, value_len, "auto"); return MSX_OK; }
         u = (unsigned long long)g_opt.hb_phased_min;

@@ -73,6 +73,46 @@ __global__ __launch_bounds__(256) void k_put_signal_wait(DevCtx c, const void* s
     }
 }
 
+// ---- plain streams: what this GPU's memory sustains for one-directional and 1:1 traffic ------------------
+// MODE 0: read nvec 16-byte vectors (their XOR goes to sink[0] only if it is all ones in every lane, which
+// keeps the loads alive without a store per thread), 1: write nvec vectors, 2: copy.  Streaming accesses,
+// grid-stride, U vectors in flight per thread (8 when only reading): the yardstick the bandwidth kernels are
+// held against.
+template <int MODE>
+__global__ __launch_bounds__(256) void k_stream(const u32x4* src, u32x4* dst, size_t nvec, unsigned* sink)
+{
+    constexpr int U = MODE == 0 ? 8 : 4;
+    const size_t T = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    const u32x4 fill = {(unsigned)i, 1u, 2u, 3u};
+    for (; i + (U - 1) * T < nvec; i += U * T) {
+        if constexpr (MODE == 1) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) __builtin_nontemporal_store(fill, dst + i + u * T);
+        } else {
+            u32x4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * T);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                if constexpr (MODE == 0) acc ^= v[u];
+                else __builtin_nontemporal_store(v[u], dst + i + u * T);
+            }
+        }
+    }
+    for (; i < nvec; i += T) {
+        if constexpr (MODE == 1) __builtin_nontemporal_store(fill, dst + i);
+        else {
+            const u32x4 v = __builtin_nontemporal_load(src + i);
+            if constexpr (MODE == 0) acc ^= v;
+            else __builtin_nontemporal_store(v, dst + i);
+        }
+    }
+    if constexpr (MODE == 0)
+        if ((acc.x & acc.y & acc.z & acc.w) == 0xffffffffu && sink) sink[0] = 1u;
+}
+
 // LL encode into caller memory (byte image check against the CPU encoder)
 __global__ __launch_bounds__(256) void k_ll_encode(const void* src, size_t nbytes, unsigned flag, u32x4* packets)
 {

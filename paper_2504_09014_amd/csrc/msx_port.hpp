@@ -91,8 +91,8 @@ __device__ __forceinline__ bool port_flush(const DevCtx& c, PortFifo* f, unsigne
     return false;
 }
 
-// The kernel the proxy enqueues for a signal request: one wave, one semaphore per lane.
-__global__ __launch_bounds__(64) void k_port_signal(unsigned* sem, int recv, int send, int nsem)
+// The kernel the proxy enqueues for a signal request: one semaphore per thread (one wave up to 64 channels).
+__global__ __launch_bounds__(256) void k_port_signal(unsigned* sem, int recv, int send, int nsem)
 {
     if ((int)threadIdx.x < nsem)
         __hip_atomic_fetch_add(sem + (size_t)sem_index(recv, send, (int)threadIdx.x) * kSemStrideWords, 1u,

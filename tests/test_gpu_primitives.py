@@ -68,6 +68,29 @@ def test_put_signal_wait_hands_over_the_bytes(msx, nbytes, chans):
     assert torch.equal(staging.cpu(), src_h)
 
 
+@pytest.mark.parametrize("nvec", [1, 255, 1024 * 4 + 3, 1 << 18])
+@pytest.mark.parametrize("blocks", [1, 3, 64])
+def test_stream_probe_copies_and_stays_inside_its_buffers(msx, nvec, blocks):
+    """the copy mode moves every vector; read and write modes touch nothing outside [0, nbytes)"""
+    nbytes = nvec * 16
+    pad = 256
+    src_h = _rand_bytes(nbytes + 2 * pad, nvec)
+    src = src_h.cuda()
+    dst = torch.full((nbytes + 2 * pad,), 0x5A, dtype=torch.uint8, device="cuda")
+    msx.prim_stream(2, src[pad:pad + nbytes], dst[pad:pad + nbytes], blocks)
+    msx.check_status()
+    got = dst.cpu()
+    assert torch.equal(got[pad:pad + nbytes], src_h[pad:pad + nbytes])
+    assert torch.all(got[:pad] == 0x5A) and torch.all(got[pad + nbytes:] == 0x5A)
+    msx.prim_stream(0, src[pad:pad + nbytes], None, blocks)
+    dst.fill_(0x5A)
+    msx.prim_stream(1, None, dst[pad:pad + nbytes], blocks)
+    msx.check_status()
+    got = dst.cpu()
+    assert torch.all(got[:pad] == 0x5A) and torch.all(got[pad + nbytes:] == 0x5A)
+    assert torch.equal(src.cpu(), src_h)
+
+
 @pytest.mark.parametrize("nbytes", [1, 3, 4, 5, 8, 9, 16, 17, 1024, 1027, 100_001])
 def test_ll_encode_is_byte_identical_to_the_cpu_encoder(msx, orc, nbytes):
     payload = _rand_bytes(nbytes, 77 + nbytes)
