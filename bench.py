@@ -217,6 +217,23 @@ def run_extras(torch, msx, synth, n, port=True):
         return sw
     leg("allreduce_auto_sweep", sweep_auto)
 
+    # ---- rank counts other than 8 at a bandwidth size (256 MiB per rank), automatic choice
+    def rank_counts():
+        res = {}
+        c = 128 << 20
+        for nr in (2, 3, 4, 5, 6, 7, 8):
+            xs = synth.normal(nr, c, seed=70 + nr, device="cuda")
+            s_ = [xs[r] for r in range(nr)]
+            r_ = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(nr)]
+            ms = median(time_calls(torch, lambda: msx.allreduce_ex(s_, r_, None, algo=msx.ALGO_AUTO), 10, 6)[1]) / 1e3
+            g, b, a = msx.last_launch()
+            res[f"n{nr}"] = {"ms": round(ms, 4), "GBps": round(2 * nr * c * 2 / ms / 1e6, 1),
+                             "pct_roofline": round(2 * nr * c * 2 / ms / 1e6 / HBM_PEAK_GBPS * 100, 1), "grid": g}
+            del xs, s_, r_
+            torch.cuda.empty_cache()
+        return res
+    leg("allreduce_256MiB_by_rank_count", rank_counts)
+
     # ---- rings: thread-copy hand-offs (MemoryChannel) and hand-offs through the port (FIFO, proxy
     # thread, runtime copies), next to the all-pairs form
     def rings():

@@ -49,8 +49,8 @@ struct Options {
     int hb_unroll = 0;        // 0 = by size
     int cache_mode = -1;      // -1 = by footprint, else 0 | 1 | 2 (see choose_cache_mode)
     // fused HB AllReduce: from this many bytes per rank on, the launch alternates between chip-wide read and
-    // write phases (k_allreduce_hb_phased).  -1 = automatic: 8 ranks from 40 MiB (see use_phased; with fewer
-    // ranks, whose phases are smaller, it loses), never otherwise
+    // write phases (k_allreduce_hb_phased).  -1 = automatic: 8 ranks from 40 MiB, the AllReduce of 4 ranks from
+    // 64 MiB (see use_phased), never otherwise
     long long hb_phased_min = -1;
     size_t a2a_blocks_min = (size_t)4 << 20;   // all-to-all: block after block from blocks of this many bytes
     int hb_barriers = 1;
@@ -601,10 +601,15 @@ HbKernel hb_fused_kernel(int dt, int u, int n, int res, int cache)
 // measured against the free-running kernels, TB/s: AllReduce 32 MiB 5.3 / 5.6-5.9, 40 MiB 5.6 / 4.9, 48 MiB
 // 5.9 / 5.0, 64 MiB 6.0-6.2 / 5.2; AllGather 32 MiB 5.2 / 5.5, 40 MiB 5.3 / 4.75, 64 MiB 6.0 / 4.5;
 // ReduceScatter 32 MiB 4.3 / 4.35, 40 MiB 4.7 / 4.6, 64 MiB 5.55 / 4.9.
-bool use_phased(size_t nbytes, int n, int res_mode)
+// Four ranks (AllReduce without a residual only: the kernel with the rank count as a template argument), from
+// 64 MiB per rank: 64 MiB 5.0 / 4.6, 256 MiB 6.15 / 5.1, 1 GiB 5.7 / 5.25.  Two ranks: 4.0 / 3.7, 5.4 / 5.25,
+// 5.2 / 5.6 - no clear gain, left to the free-running kernel.
+bool use_phased(size_t nbytes, int n, int res_mode, bool allreduce = false)
 {
     if (n < 2 || res_mode == 2 || g_opt.hb_unroll != 0) return false;
-    return g_opt.hb_phased_min < 0 ? n == 8 && nbytes >= ((size_t)40 << 20) : nbytes >= (size_t)g_opt.hb_phased_min;
+    if (g_opt.hb_phased_min >= 0) return nbytes >= (size_t)g_opt.hb_phased_min;
+    if (n == 8) return nbytes >= ((size_t)40 << 20);
+    return allreduce && n == 4 && res_mode == 0 && nbytes >= ((size_t)64 << 20);
 }
 HbKernel hb_2phase_kernel(int dt, int u, int n)
 {
@@ -1128,7 +1133,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
                                          : hb_2phase_kernel(dtype, U, n);
     // very large messages: the same sums in chip-wide read and write phases, one workgroup per CU (as many
     // as are resident; an explicit hb_blocks_per_rank still counts)
-    if (algo == MSX_ALGO_2PA_HB && use_phased(nbytes, n, res_mode)) {
+    if (algo == MSX_ALGO_2PA_HB && use_phased(nbytes, n, res_mode, true)) {
         k = phased_reduce_kernel(dtype == MSX_F32, n, res_mode, 0);
         U = kPhasedHeld;
         want = g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels;

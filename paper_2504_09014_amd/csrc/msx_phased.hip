@@ -9,6 +9,7 @@ namespace msx {
 PhasedKernel phased_reduce_kernel(bool f32, int nranks, int res, int kind)
 {
     if (kind == 1) return phased_reducescatter(f32, nranks);
+    if (res == 0 && (nranks == 2 || nranks == 4)) return phased_allreduce_2_or_4(f32, nranks);
     return f32 ? phased_allreduce_f32(nranks, res) : phased_allreduce_bf16(nranks, res);
 }
 

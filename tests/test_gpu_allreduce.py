@@ -487,7 +487,7 @@ def phased(msx):
     msx.set_option("chaos", "0")
 
 
-@pytest.mark.parametrize("n", [2, 3, 7, 8])
+@pytest.mark.parametrize("n", [2, 3, 4, 7, 8])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_phased_fused_hb_matches_oracle_over_rounds_and_ragged_ends(phased, orc, n, dtype):
     msx = phased
@@ -597,6 +597,26 @@ def test_phased_fused_hb_survives_barrier_counter_wraparound(phased, orc):
             assert np.array_equal(got[i], _oracle(orc, x)), i
     finally:
         msx.reset()
+
+
+def test_paced_shapes_that_share_a_schedule_slot_evict_each_other_harmlessly(phased, orc):
+    """The learnt schedules live in seven direct-mapped slots tagged with the launch's shape.  Ten shapes taken in
+    turn, three times over, must collide (pigeonhole): a shape that finds another one's entry starts from
+    scratch, and no schedule learnt for one shape may hold back, or corrupt, a launch of another."""
+    msx = phased
+    n = 8
+    msx.set_option("hb_blocks_per_rank", "1")
+    shapes = []
+    for k in range(10):
+        count = 8 * (256 * 64 * (3 + k % 4) + 9 * k + 1) * 8        # 3..6 rounds with one workgroup per rank, ragged ends
+        x = synth.normal(n, count, seed=400 + k)
+        shapes.append((x, _oracle(orc, x)))
+    for sweep in range(3):
+        for k, (x, want) in enumerate(shapes):
+            got = _run_ex(msx, x, 3)
+            for r in (0, 3, 7):
+                assert np.array_equal(got[r], want), (sweep, k, r)
+    msx.check_status()
 
 
 def test_phased_fused_hb_with_paced_write_phases(phased, orc):

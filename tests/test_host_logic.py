@@ -363,6 +363,22 @@ def test_write_phase_pacing_controller_finds_and_keeps_the_tightest_schedule(L):
     assert L.msx_debug_pace_update(None, 100, tiles) == -1
 
 
+def test_write_phase_pacing_controller_stays_inside_its_clamp_on_any_input(L):
+    """Whatever a phase reports (clock glitches, a phase that took no time, one tile, thousands of tiles, a state
+    left behind by another shape), the pace stays within [0, 1500] ticks per tile and the remembered good
+    schedule too: a wave is never told to wait longer than 15 us per tile."""
+    L.msx_debug_pace_update.argtypes = [C.POINTER(C.c_uint32), C.c_uint64, C.c_uint32]
+    rng = np.random.default_rng(11)
+    for trial in range(200):
+        state = (C.c_uint32 * 4)(*[int(v) for v in rng.integers(0, 1501, 2)], int(rng.integers(0, 2)), int(rng.integers(0, 3)))
+        # pace, good (<= 1500, as pace_load leaves them), frozen, misses
+        for _ in range(60):
+            took = int(rng.choice([0, 1, int(rng.integers(0, 2000)), int(rng.integers(0, 99999)), 99999, 100000, 2 ** 40]))
+            tiles = int(rng.choice([1, 2, 16, 63, 64, int(rng.integers(1, 5000))]))
+            assert L.msx_debug_pace_update(state, took, tiles) == 0
+            assert state[0] <= 1500 and state[1] <= 1500 and state[2] <= 1 and state[3] <= 3, (trial, list(state), took, tiles)
+
+
 def test_owner_of_an_expert_by_multiplication_equals_the_division(L):
     """The token plan computes e // (n_experts // nranks) as (e * magic) >> 32: exact for every expert id of
     every shape the library uses the multiplier for, and the library divides where it would not be."""
