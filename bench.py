@@ -375,9 +375,10 @@ def run_extras(torch, msx, synth, n, port=True):
             _, ev = time_calls(torch, lambda: msx.moe_dispatch(tk, ix, E, rt, cnt, rs, plan=plan), 20, 5)
             msx.check_status()
             rows = int(cnt.sum().item())
-            ms = sum(ev) / len(ev) / 1e3
+            ms = median(ev) / 1e3
             moved = n * T * H * 2 + rows * H * 2
-            res["dispatch_bf16"] = {"ms": round(ms, 4), "rows_sent": rows, "GBps": round(moved / ms / 1e6, 1),
+            res["dispatch_bf16"] = {"ms": round(ms, 4), "ms_mean": round(sum(ev) / len(ev) / 1e3, 4), "rows_sent": rows,
+                                    "GBps": round(moved / ms / 1e6, 1),
                                     "pct_roofline": round(moved / ms / 1e6 / HBM_PEAK_GBPS * 100, 1)}
             outs = [torch.empty((T, H), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
             _, ev = time_calls(torch, lambda: msx.moe_combine(rt, outs, plan=plan), 20, 5)
@@ -554,12 +555,15 @@ def main():
     phased = msx.get_option("hb_phased_min_bytes") == "auto" and n == 8 and S >= (40 << 20)
     kernel_name = "k_allreduce_hb_phased<bf16, 8 ranks, 64 sums held>" if phased else "k_allreduce_hb_fused<bf16>"
     traffic = None
+    traffic_source = None      # hardware counters cannot be read from inside this process: the figure is the
+                               # committed rocprofv3 measurement of this same command (see profiles/)
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
             t = json.load(open(tpath)).get(f"allreduce_hb_{'phased' if phased else 'fused'}_{args.mib}MiB")
             if t:
                 traffic = t["fetch_bytes"] + t["write_bytes"]
+                traffic_source = t.get("source")
         except Exception:
             traffic = None
 
@@ -587,7 +591,7 @@ def main():
         },
         "roofline": {
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+            "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_source,
             "kernel": kernel_name, "algorithmic_bytes": alg_bytes,
             "kernel_ms_avg": round(kern_avg, 4), "kernel_ms_min": round(min(kern_ms), 4),
             "kernel_ms_p10": round(pct(kern_ms, 10), 4), "kernel_ms_median": round(median(kern_ms), 4),

@@ -401,7 +401,7 @@ int msx_last_launch(int* grid, int* block, int* algo);
  * phase: MSX_ALGO_PLAN_2PA_HB is then lowered to the read phase / write phase schedule). */
 int msx_debug_choose(size_t nbytes, int nranks, size_t ll_limit, int* algo, int* unroll, int* want_blocks);
 /* One step of the controller that paces the write phases of the phased kernels: state = {pace, last pace that
- * was met, frozen, misses in a row} (pace in 10 ns ticks per tile, 0 = unpaced); took_ticks = how long the
+ * was met, frozen, misses in a row | phases met since frozen << 8} (pace in 10 ns ticks per tile, 0 = unpaced); took_ticks = how long the
  * full write phase of `tiles` tiles just took.  The same function the kernels call. */
 int msx_debug_pace_update(uint32_t state[4], uint64_t took_ticks, uint32_t tiles);
 /* The multiplier with which the token plan computes the owner rank of an expert, e / (n_experts / nranks), as

@@ -196,7 +196,8 @@ struct GridBar { unsigned base, per_gen; bool ok; };   // lanes 0..7 of the firs
 
 constexpr int kGridBarBaseWord = 8 * kSemStrideWords;
 constexpr int kGridBarPaceWord = kGridBarBaseWord + kSemStrideWords;     // a word of its own line: the write-phase schedule
-constexpr size_t kGridBarBytes = (size_t)(kGridBarPaceWord + kSemStrideWords) * 4;
+constexpr unsigned kPaceSlots = 31;    // remembered shapes: word 0 of the first line is the running launch's pace, 4 words per slot behind it
+constexpr size_t kGridBarBytes = (size_t)(kGridBarPaceWord + 4 + 4 * kPaceSlots) * 4;
 
 // Workgroup-collective; first thing (before any arrival of this call can have happened: an arrival
 // needs this workgroup's own).
@@ -282,29 +283,34 @@ __device__ __forceinline__ void wait_until(unsigned long long target)
 //   schedule missed (too tight: nobody is held back any more and the slow dies are late again): back to the
 //   last one that was met, and stop tightening; missed three times in a row: learn again from scratch; missed
 //   before any was met: loosen by 1/16
-// The state outlives the call (beside the barrier counters, seven slots tagged with the shape of the launch), so
+//   frozen and met 256 times in a row: tighten once more (conditions may have changed since the miss that froze
+//   it - another launch beside it, a colder chip - and a schedule that is merely met is never found too loose
+//   otherwise); a miss sends it straight back to the last good one
+// The state outlives the call (beside the barrier counters, 31 slots tagged with the shape of the launch), so
 // a call of a shape seen before starts from the schedule that one ended with.
-struct PaceCtl { unsigned pace, good, frozen, misses; };
+struct PaceCtl { unsigned pace, good, frozen, misses, age; };
+constexpr unsigned kPaceRetryAfter = 256;
 
 // no schedule is slower than this many ticks per tile (15 us; a phase of 64 tiles then lasts a millisecond):
 // whatever the words in memory say, a wave never waits longer
 constexpr unsigned kMaxPace = 1500;
 __host__ __device__ __forceinline__ unsigned pace_clamp(unsigned pace) { return pace > kMaxPace ? 0u : pace; }
 
-// word 0 of the line: the pace of the launch that is running; words 4..31: seven remembered shapes, direct-mapped
+// word 0 of the first line: the pace of the launch that is running; behind it kPaceSlots remembered shapes,
+// direct-mapped (a bench run alone meets a dozen shapes; with seven slots they kept evicting each other)
 __device__ __forceinline__ PaceCtl pace_load(const DevCtx& c, unsigned key)
 {
-    const unsigned* w = c.gbar + kGridBarPaceWord + 4u + ((key >> 7) % 7u) * 4u;
-    PaceCtl p{0u, 0u, 0u, 0u};
-    if (w[1] == key) { p.pace = pace_clamp(w[0]); p.good = pace_clamp(w[2]); p.frozen = w[3] & 1u; p.misses = (w[3] >> 8) & 3u; }
+    const unsigned* w = c.gbar + kGridBarPaceWord + 4u + ((key >> 7) % kPaceSlots) * 4u;
+    PaceCtl p{0u, 0u, 0u, 0u, 0u};
+    if (w[1] == key) { p.pace = pace_clamp(w[0]); p.good = pace_clamp(w[2]); p.frozen = w[3] & 1u; p.misses = (w[3] >> 8) & 3u; p.age = (w[3] >> 16) & 0x1ffu; }
     return p;
 }
 
 // workgroup 0, one thread, after the call's last barrier
 __device__ __forceinline__ void pace_save(const DevCtx& c, const PaceCtl& p, unsigned key)
 {
-    unsigned* w = c.gbar + kGridBarPaceWord + 4u + ((key >> 7) % 7u) * 4u;
-    w[0] = p.pace; w[1] = key; w[2] = p.good; w[3] = (p.frozen & 1u) | (p.misses << 8);
+    unsigned* w = c.gbar + kGridBarPaceWord + 4u + ((key >> 7) % kPaceSlots) * 4u;
+    w[0] = p.pace; w[1] = key; w[2] = p.good; w[3] = (p.frozen & 1u) | (p.misses << 8) | (p.age << 16);
 }
 
 __host__ __device__ __forceinline__ void pace_update(PaceCtl& p, unsigned long long took, unsigned tiles)
@@ -319,14 +325,15 @@ __host__ __device__ __forceinline__ void pace_update(PaceCtl& p, unsigned long l
         if (t <= sched + sched / 16u + 300u) {
             p.good = p.pace;
             p.misses = 0;
-            if (!p.frozen) p.pace = p.pace * 12u / 13u;
+            if (!p.frozen) { p.pace = p.pace * 12u / 13u; p.age = 0; }
+            else if (++p.age >= kPaceRetryAfter) { p.age = 0; p.frozen = 0; }
         } else if (!p.good) {
             // no schedule has been met yet: this one is too tight, try a looser one (never looser than what the
             // unpaced phase just took, which is met by definition and ends the search)
             const unsigned looser = p.pace + p.pace / 16u + 1u, unpaced = t / tiles + 1u;
             p.pace = pace_clamp(looser < unpaced ? looser : unpaced);
         } else if (++p.misses >= 3u) {
-            p = PaceCtl{fresh, 0u, 0u, 0u};
+            p = PaceCtl{fresh, 0u, 0u, 0u, 0u};
         } else {
             p.pace = p.good;
             p.frozen = 1u;

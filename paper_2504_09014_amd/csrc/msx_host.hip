@@ -2336,9 +2336,9 @@ int msx_debug_owner_magic(int n_experts, int nranks, uint32_t* magic)
 int msx_debug_pace_update(uint32_t state[4], uint64_t took_ticks, uint32_t tiles)
 {
     if (!state || tiles == 0) return MSX_ERR_ARG;
-    PaceCtl p{state[0], state[1], state[2], state[3]};
+    PaceCtl p{state[0], state[1], state[2], state[3] & 3u, (state[3] >> 8) & 0x1ffu};
     pace_update(p, took_ticks, tiles);
-    state[0] = p.pace; state[1] = p.good; state[2] = p.frozen; state[3] = p.misses;
+    state[0] = p.pace; state[1] = p.good; state[2] = p.frozen; state[3] = p.misses | (p.age << 8);
     return MSX_OK;
 }
 

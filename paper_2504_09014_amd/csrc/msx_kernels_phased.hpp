@@ -68,7 +68,9 @@ __global__ __launch_bounds__(256) void k_allreduce_hb_phased(HbArgs a, DevCtx c)
     const bool pacing = a.pace && rounds >= kPacedRounds;
     unsigned gen = 0;
     // what the schedule is remembered under from call to call: the shape of the launch
-    const unsigned key = ((unsigned)a.count ^ (unsigned)(a.count >> 32)) * 2654435761u + gridDim.x * 64u + (unsigned)(DT * 8 + RES * 2 + KIND) + 1u;
+    // (the rank count is part of the shape: four ranks put to half as many destinations per tile as eight, and a
+    // schedule inherited from an 8-rank call of the same size was met, hence kept, and 50 % too slow)
+    const unsigned key = ((unsigned)a.count ^ (unsigned)(a.count >> 32)) * 2654435761u + gridDim.x * 64u + (unsigned)(DT * 8 + RES * 2 + KIND) + 1u + (unsigned)n * 7919u * 128u;
     PaceCtl ctl = pace_load(c, key);   // every workgroup reads it; workgroup 0 keeps it up to date
     unsigned pace = pacing ? ctl.pace : 0u;   // wall-clock ticks between the puts of two tiles in a full write phase (0: unpaced)
     // Tiles of a round: the AllReduce deals them out one by one (workgroup c of the rank takes every chans-th),
@@ -240,7 +242,7 @@ __global__ __launch_bounds__(256) void k_allgather_hb_phased(HbArgs a, DevCtx c)
     const unsigned rounds = (unsigned)((tiles + per_round - 1) / per_round);
     const bool pacing = a.pace && rounds >= kPacedRounds;
     unsigned gen = 0;
-    const unsigned key = ((unsigned)a.count ^ (unsigned)(a.count >> 32)) * 2654435761u + gridDim.x * 64u + 32u + 1u;
+    const unsigned key = ((unsigned)a.count ^ (unsigned)(a.count >> 32)) * 2654435761u + gridDim.x * 64u + 32u + 1u + (unsigned)n * 7919u * 128u;
     PaceCtl ctl = pace_load(c, key);
     unsigned pace = pacing ? ctl.pace : 0u;   // wall-clock ticks between the puts of two tiles (0: unpaced)
     const size_t tstep = (size_t)a.chans * 256;      // tiles dealt out one by one, as in the AllReduce

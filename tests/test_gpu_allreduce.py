@@ -600,18 +600,18 @@ def test_phased_fused_hb_survives_barrier_counter_wraparound(phased, orc):
 
 
 def test_paced_shapes_that_share_a_schedule_slot_evict_each_other_harmlessly(phased, orc):
-    """The learnt schedules live in seven direct-mapped slots tagged with the launch's shape.  Ten shapes taken in
-    turn, three times over, must collide (pigeonhole): a shape that finds another one's entry starts from
-    scratch, and no schedule learnt for one shape may hold back, or corrupt, a launch of another."""
+    """The learnt schedules live in 31 direct-mapped slots tagged with the launch's shape.  34 shapes taken in
+    turn, twice over, must collide (pigeonhole): a shape that finds another one's entry starts from scratch, and
+    no schedule learnt for one shape may hold back, or corrupt, a launch of another."""
     msx = phased
     n = 8
     msx.set_option("hb_blocks_per_rank", "1")
     shapes = []
-    for k in range(10):
-        count = 8 * (256 * 64 * (3 + k % 4) + 9 * k + 1) * 8        # 3..6 rounds with one workgroup per rank, ragged ends
+    for k in range(34):
+        count = 8 * (256 * 64 * 3 + 9 * k + 1) * 8                  # 3 rounds and a ragged end with one workgroup per rank
         x = synth.normal(n, count, seed=400 + k)
         shapes.append((x, _oracle(orc, x)))
-    for sweep in range(3):
+    for sweep in range(2):
         for k, (x, want) in enumerate(shapes):
             got = _run_ex(msx, x, 3)
             for r in (0, 3, 7):

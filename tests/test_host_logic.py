@@ -349,6 +349,13 @@ def test_write_phase_pacing_controller_finds_and_keeps_the_tightest_schedule(L):
     held = state[0]
     run(state, cliff=7000, rounds=8)
     assert state[0] == held                                     # frozen: stays
+    # ... but not for ever: after 256 phases that met it, it tries one step tighter, misses, and is back
+    log = run(state, cliff=7000, rounds=300)
+    assert state[0] == held and state[2] == 1 and sum(t == unpaced for t in log) == 1
+    # a frozen schedule that has become far too loose (the cliff moved down) is found out the same way
+    loose = (C.c_uint32 * 4)(held, held, 1, 0)
+    run(loose, cliff=3500, rounds=256 * 9)
+    assert 3500 <= loose[0] * tiles <= 3500 * 13 // 12 + tiles, loose[0]
     log = run(state, cliff=9000, rounds=12)                     # conditions change: the old schedule is too tight now
     assert sum(t == unpaced for t in log) <= 6 and 9000 <= state[0] * tiles <= 9000 * 13 // 12 + tiles
     # a system on which pacing gains nothing (no schedule below the unpaced time can be met): the search ends
@@ -376,7 +383,8 @@ def test_write_phase_pacing_controller_stays_inside_its_clamp_on_any_input(L):
             took = int(rng.choice([0, 1, int(rng.integers(0, 2000)), int(rng.integers(0, 99999)), 99999, 100000, 2 ** 40]))
             tiles = int(rng.choice([1, 2, 16, 63, 64, int(rng.integers(1, 5000))]))
             assert L.msx_debug_pace_update(state, took, tiles) == 0
-            assert state[0] <= 1500 and state[1] <= 1500 and state[2] <= 1 and state[3] <= 3, (trial, list(state), took, tiles)
+            assert state[0] <= 1500 and state[1] <= 1500 and state[2] <= 1 and (state[3] & 0xff) <= 3 and (state[3] >> 8) < 256, \
+                (trial, list(state), took, tiles)
 
 
 def test_owner_of_an_expert_by_multiplication_equals_the_division(L):
