@@ -49,8 +49,8 @@ struct Options {
     int hb_unroll = 0;        // 0 = by size
     int cache_mode = -1;      // -1 = by footprint, else 0 | 1 | 2 (see choose_cache_mode)
     // fused HB AllReduce: from this many bytes per rank on, the launch alternates between chip-wide read and
-    // write phases (k_allreduce_hb_phased).  -1 = automatic: 8 ranks from 40 MiB, the AllReduce of 4 ranks from
-    // 64 MiB (see use_phased), never otherwise
+    // write phases (k_allreduce_hb_phased).  -1 = automatic: 8 ranks from 40 MiB, the AllReduce of 3 to 7 ranks
+    // from 64 or 128 MiB (see use_phased), never otherwise
     long long hb_phased_min = -1;
     size_t a2a_blocks_min = (size_t)4 << 20;   // all-to-all: block after block from blocks of this many bytes
     int hb_barriers = 1;
@@ -601,15 +601,18 @@ HbKernel hb_fused_kernel(int dt, int u, int n, int res, int cache)
 // measured against the free-running kernels, TB/s: AllReduce 32 MiB 5.3 / 5.6-5.9, 40 MiB 5.6 / 4.9, 48 MiB
 // 5.9 / 5.0, 64 MiB 6.0-6.2 / 5.2; AllGather 32 MiB 5.2 / 5.5, 40 MiB 5.3 / 4.75, 64 MiB 6.0 / 4.5;
 // ReduceScatter 32 MiB 4.3 / 4.35, 40 MiB 4.7 / 4.6, 64 MiB 5.55 / 4.9.
-// Four ranks (AllReduce without a residual only: the kernel with the rank count as a template argument), from
-// 64 MiB per rank: 64 MiB 5.0 / 4.6, 256 MiB 6.15 / 5.1, 1 GiB 5.7 / 5.25.  Two ranks: 4.0 / 3.7, 5.4 / 5.25,
-// 5.2 / 5.6 - no clear gain, left to the free-running kernel.
+// Other rank counts (AllReduce without a residual only: the kernels with the rank count as a template argument),
+// phased / free-running TB/s at 64 MiB and 256 MiB per rank: 3 ranks 4.55 / 4.8 and 5.75 / 5.25; 4 ranks 5.0 / 4.6
+// and 6.15 / 5.1 (1 GiB 5.7 / 5.25); 5 ranks 5.3 / 4.8 and 6.2 / 4.9; 6 ranks 5.3 / 4.75 and 5.75 / 5.05; 7 ranks
+// 5.4 / 4.8 and 6.1 / 4.95.  So: 4 to 7 ranks from 64 MiB, 3 ranks from 128 MiB.  Two ranks: 4.0 / 3.7, 5.4 / 5.25,
+// 5.2 / 5.6 (1 GiB) - no clear gain, left to the free-running kernel.
 bool use_phased(size_t nbytes, int n, int res_mode, bool allreduce = false)
 {
     if (n < 2 || res_mode == 2 || g_opt.hb_unroll != 0) return false;
     if (g_opt.hb_phased_min >= 0) return nbytes >= (size_t)g_opt.hb_phased_min;
     if (n == 8) return nbytes >= ((size_t)40 << 20);
-    return allreduce && n == 4 && res_mode == 0 && nbytes >= ((size_t)64 << 20);
+    if (!allreduce || res_mode != 0 || n < 3) return false;
+    return nbytes >= ((size_t)(n == 3 ? 128 : 64) << 20);
 }
 HbKernel hb_2phase_kernel(int dt, int u, int n)
 {

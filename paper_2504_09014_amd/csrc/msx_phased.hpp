@@ -10,7 +10,7 @@ typedef void (*PhasedKernel)(HbArgs, DevCtx);
 constexpr int kPhasedHeld = 64;
 
 // dt: MSX_F32 or MSX_BF16; kind 0 AllReduce (res: 0 none, 1 one residual shared by all ranks), 1 ReduceScatter.
-// The rank count is a template argument for 8 ranks (and, for the AllReduce without a residual, for 2 and 4)
+// The rank count is a template argument for 8 ranks (and, for the AllReduce without a residual, for 2 to 7)
 // and a run-time value otherwise.
 PhasedKernel phased_reduce_kernel(bool f32, int nranks, int res, int kind);
 PhasedKernel phased_allgather_kernel(int nranks);
@@ -19,6 +19,7 @@ PhasedKernel phased_allgather_kernel(int nranks);
 PhasedKernel phased_allreduce_f32(int nranks, int res);
 PhasedKernel phased_allreduce_bf16(int nranks, int res);
 PhasedKernel phased_reducescatter(bool f32, int nranks);
-PhasedKernel phased_allreduce_2_or_4(bool f32, int nranks);    // no residual; nullptr for other rank counts
+PhasedKernel phased_allreduce_2_to_4(bool f32, int nranks);    // no residual; nullptr for other rank counts
+PhasedKernel phased_allreduce_5_to_7(bool f32, int nranks);
 
 }  // namespace msx

@@ -487,7 +487,7 @@ def phased(msx):
     msx.set_option("chaos", "0")
 
 
-@pytest.mark.parametrize("n", [2, 3, 4, 7, 8])
+@pytest.mark.parametrize("n", [2, 3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_phased_fused_hb_matches_oracle_over_rounds_and_ragged_ends(phased, orc, n, dtype):
     msx = phased
