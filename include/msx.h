@@ -356,8 +356,9 @@ int msx_last_status(void* ctx, int* rank, int* site, unsigned* expected, unsigne
  *                     shared by all ranks) runs in chip-wide read and write phases, one workgroup per CU; auto:
  *                     8 ranks from 40 MiB (per rank; rows, for ReduceScatter / AllGather), the AllReduce of 4 to 7
  *                     ranks without a residual from 64 MiB and of 3 ranks from 128 MiB, never otherwise; an
- *                     explicit value applies to every rank count.  The token pack of msx_moe_dispatch has such
- *                     a form for rows of whole multiples of 1 KiB: auto from 32 MiB of tokens per rank (8 ranks)
+ *                     explicit value applies to every rank count.  The token pack of msx_moe_dispatch and
+ *                     msx_moe_combine have such a form for rows of whole multiples of 1 KiB (the combine also needs
+ *                     T x H to be a whole number of 4 KiB tiles): auto from 32 MiB of tokens per rank (8 ranks)
  *   "hb_pace"         0 | 1   phased kernels: hold the write phases to a common wall-clock schedule, so that all
  *                     dies finish them together (the schedule is found by the kernels themselves and kept, per
  *                     launch shape, in the context)

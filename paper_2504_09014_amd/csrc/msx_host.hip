@@ -29,6 +29,7 @@
 #include "msx_kernels_moe.hpp"
 #include "msx_kernels_plan.hpp"
 #include "msx_plan.hpp"
+#include "msx_combine.hpp"
 #include "msx_kernels_generic.hpp"
 #include "msx_port.hpp"
 #include "msx_kernels_prim.hpp"
@@ -1661,6 +1662,24 @@ int msx_moe_combine(const void* const* expert_out, void* const* out_tokens, int 
     a.n = n;
     a.row_vecs = (unsigned)(row_bytes / 16);
     a.cap = (unsigned)capacity_tokens;
+    // many rows of whole multiples of 64 vectors: chip-wide read and write phases, one workgroup per CU (see
+    // k_moe_combine_dealt).  Automatic for 8 ranks from 32 MiB of tokens per rank, like the token pack; an explicit
+    // hb_phased_min_bytes counts for every rank count.
+    const size_t token_bytes = (size_t)T * row_bytes;
+    const unsigned long long out_vecs = (unsigned long long)T * a.row_vecs;
+    if (a.row_vecs % 64u == 0 && out_vecs % 256u == 0 && out_vecs < (1ull << 32) &&
+        (unsigned long long)a.cap * row_bytes <= 0xE0000000ull &&
+        (g_opt.hb_phased_min < 0 ? n == 8 && token_bytes >= ((size_t)32 << 20)
+                                 : token_bytes >= (size_t)g_opt.hb_phased_min)) {
+        CombineKernel kd = combine_dealt_kernel(dtype == MSX_F32);
+        int dch = 1;
+        if ((rc = pick_channels(c, (const void*)kd, 256, n, (size_t)out_vecs, (size_t)kCombineHeld,
+                                g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels, kMaxChannels, &dch)))
+            return rc;
+        a.chans = dch;
+        note_launch(n * dch, 256, MSX_ALGO_2PA_HB);
+        return launch(kd, n * dch, 256, (hipStream_t)stream, a, dev_ctx(c));
+    }
     const void* kp = dtype == MSX_F32 ? (const void*)k_moe_combine<0> : (const void*)k_moe_combine<1>;
     int chans = 1;
     // read-heavy like the reduce-scatter: 32 workgroups per rank beat more (measured at 8 x 4096 rows of 7168:

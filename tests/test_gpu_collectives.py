@@ -400,6 +400,49 @@ def test_moe_combine_small_shapes(msx, orc, n, T, H, K, E):
         assert np.array_equal(_bits(out[s]), want[s]), s
 
 
+@pytest.mark.parametrize("n,T,H,K,E,blocks", [(8, 1000, 512, 8, 256, 1), (8, 300, 7168, 8, 256, 2), (4, 332, 8192, 2, 16, 0),
+                                              (2, 76, 1536, 1, 4, 1), (8, 4, 512, 8, 64, 1), (8, 64, 512, 3, 8, 3)])
+def test_moe_combine_in_read_and_write_phases(msx, orc, n, T, H, K, E, blocks):
+    """The combine that alternates between chip-wide read and write phases (by default: 8 ranks, 32 MiB of tokens
+    per rank; rows of whole multiples of 64 vectors, outputs of whole tiles), forced here; one to three
+    workgroups per rank make many rounds, the last one partial.  A tile's absent rows are read as zeros from
+    beyond the buffer and added as -0.0, so the "expert output" carries what that could get wrong: -0.0 and +0.0
+    in all rows of a token, NaNs, infinities."""
+    tokens = synth.moe_tokens(n, T, H, seed=31)
+    topk = synth.moe_routing(n, T, K, E, seed=31)
+    cap = n * T
+    recv, src, counts, rc, info = _dispatch(msx, tokens, topk, E, cap)
+    assert rc == 0, info
+    y = synth.normal(n, cap * H, seed=78).view(n, cap, H).clone()
+    yb = y.view(torch.int16)
+    yb[:, :, 0] = -32768                                       # -0.0 in every row: the sum must stay -0.0
+    yb[:, :, 1] = 0                                            # +0.0 in every row
+    yb[:, ::2, 2] = -32768                                     # mixed zeros
+    yb[:, ::2, 3] = 0x7FC0                                     # NaN in some rows
+    yb[:, ::3, 4] = 0x7F80                                     # +inf in some rows
+    ydev = [y[d].clone().cuda() for d in range(n)]
+    out = [torch.full((T, H), float("nan"), dtype=torch.bfloat16, device="cuda") for _ in range(n)]
+    want, orc_rc = orc.moe_combine_bf16(_bits(y), topk.numpy(), E)
+    assert orc_rc == 0
+    old = msx.get_option("hb_phased_min_bytes")
+    msx.set_option("hb_phased_min_bytes", "0")
+    msx.set_option("hb_blocks_per_rank", str(blocks))
+    msx.set_option("chaos", "21")
+    try:
+        for rep in range(2):
+            msx.moe_combine(ydev, out)
+            grid = msx.last_launch()[0]
+            assert grid == n * blocks if blocks else (grid % n == 0 and 200 <= grid <= 256), (grid, n, blocks)
+            msx.check_status()
+            for s_ in range(n):
+                assert np.array_equal(_bits(out[s_]), want[s_]), (rep, s_)
+                out[s_].fill_(float("nan"))
+    finally:
+        msx.set_option("hb_phased_min_bytes", old)
+        msx.set_option("hb_blocks_per_rank", "0")
+        msx.set_option("chaos", "0")
+
+
 def test_moe_combine_needs_a_matching_dispatch(msx):
     y = [torch.zeros((16, 8), dtype=torch.bfloat16, device="cuda") for _ in range(8)]
     out = [torch.zeros((12345, 8), dtype=torch.bfloat16, device="cuda") for _ in range(8)]
