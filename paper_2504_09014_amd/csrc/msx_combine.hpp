@@ -4,9 +4,8 @@
 
 namespace msx {
 
-// sums (vectors) a thread holds per phase: beside them it keeps eight row offsets per tile, so a few less than
-// the 64 of the phased AllReduce fit without spilling
-constexpr int kCombineHeld = 56;
+// sums (vectors) a thread holds per phase, as many as the phased AllReduce
+constexpr int kCombineHeld = 64;
 
 typedef void (*CombineKernel)(MoeArgs, DevCtx);
 CombineKernel combine_dealt_kernel(bool f32);

@@ -564,6 +564,12 @@ __device__ __forceinline__ void st16_wt_keep(void* base, size_t vec_index, u32x4
     u32x4* p = (u32x4*)base + vec_index;
     asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
 }
+// the same with the address as a wave-uniform base (scalar registers) plus a 32-bit byte offset per lane: one
+// vector register of address instead of two, where registers are what a kernel runs out of
+__device__ __forceinline__ void st16_wt_keep_at(const void* uniform_base, unsigned byte_off, u32x4 v)
+{
+    asm volatile("global_store_dwordx4 %0, %1, %2 sc1\n\ts_nop 1" : : "v"(byte_off), "v"(v), "s"(uniform_base) : "memory");
+}
 __device__ __forceinline__ void st8_wt(void* addr, u32x2 v)
 {
     asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(addr), "v"(v) : "memory");

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void k_moe_combine_dealt(MoeArgs a, DevCtx c)
         // under the next read phase; short, so nobody waits behind it
         static_for<H>([&](auto k) {
             constexpr unsigned h = (unsigned)decltype(k)::value;
-            if (h < mine) st16_wt_keep(out, (size_t)v0 + (size_t)h * tstep + lane, held[h]);
+            if (h < mine) st16_wt_keep_at(out + ((size_t)v0 + (size_t)h * tstep) * 16, lane_bytes, held[h]);
         });
         put_drain();
     }
