@@ -355,7 +355,8 @@ int msx_last_status(void* ctx, int* rank, int* site, unsigned* expected, unsigne
  *   "hb_phased_min_bytes"   auto | bytes per rank from which the fused HB AllReduce (no residual, or one
  *                     shared by all ranks) runs in chip-wide read and write phases, one workgroup per CU; auto:
  *                     8 ranks from 40 MiB (per rank; rows, for ReduceScatter / AllGather), the AllReduce of 4 to 7
- *                     ranks without a residual from 64 MiB and of 3 ranks from 128 MiB, never otherwise; an
+ *                     ranks without a residual from 64 MiB and of 3 ranks from 128 MiB, the AllGather of 3 to 7
+ *                     ranks from 128 MiB rows and of 2 ranks from 256 MiB rows, never otherwise; an
  *                     explicit value applies to every rank count.  The token pack of msx_moe_dispatch and
  *                     msx_moe_combine have such a form for rows of whole multiples of 1 KiB (the combine also needs
  *                     T x H to be a whole number of 4 KiB tiles): auto from 32 MiB of tokens per rank (8 ranks)

@@ -607,12 +607,19 @@ HbKernel hb_fused_kernel(int dt, int u, int n, int res, int cache)
 // and 6.15 / 5.1 (1 GiB 5.7 / 5.25); 5 ranks 5.3 / 4.8 and 6.2 / 4.9; 6 ranks 5.3 / 4.75 and 5.75 / 5.05; 7 ranks
 // 5.4 / 4.8 and 6.1 / 4.95.  So: 4 to 7 ranks from 64 MiB, 3 ranks from 128 MiB.  Two ranks: 4.0 / 3.7, 5.4 / 5.25,
 // 5.2 / 5.6 (1 GiB) - no clear gain, left to the free-running kernel.
-bool use_phased(size_t nbytes, int n, int res_mode, bool allreduce = false)
+// AllGather with other rank counts (its phased kernel takes the rank count at run time), phased / free-running
+// TB/s by row size: 4 ranks 64 MiB 5.55 / 5.4, 128 MiB 6.0 / 4.6, 256 MiB 6.2 / 4.8, 1 GiB 5.6 / 5.1; 6 ranks 64 MiB
+// 4.8 / 4.4, 128 MiB 5.7 / 4.7, 256 MiB 5.9 / 4.8; 3, 5, 7 ranks at 256 MiB 5.3 / 4.8, 5.7 / 4.7, 5.6 / 4.7; 2 ranks
+// 128 MiB 4.95 / 5.7, 256 MiB 5.6 / 5.25, 1 GiB 5.35 / 5.25.  So: 3 to 7 ranks from 128 MiB rows, 2 ranks from 256 MiB.
+// The ReduceScatter of other rank counts stays free-running (5.6 against 5.2 TB/s at 4 ranks, 4.1 / 3.8 at 2).
+enum PhasedKind { kPhasedOther = 0, kPhasedAllReduce = 1, kPhasedAllGather = 2 };
+bool use_phased(size_t nbytes, int n, int res_mode, int kind = kPhasedOther)
 {
     if (n < 2 || res_mode == 2 || g_opt.hb_unroll != 0) return false;
     if (g_opt.hb_phased_min >= 0) return nbytes >= (size_t)g_opt.hb_phased_min;
     if (n == 8) return nbytes >= ((size_t)40 << 20);
-    if (!allreduce || res_mode != 0 || n < 3) return false;
+    if (kind == kPhasedAllGather) return nbytes >= ((size_t)(n == 2 ? 256 : 128) << 20);
+    if (kind != kPhasedAllReduce || res_mode != 0 || n < 3) return false;
     return nbytes >= ((size_t)(n == 3 ? 128 : 64) << 20);
 }
 HbKernel hb_2phase_kernel(int dt, int u, int n)
@@ -1137,7 +1144,7 @@ int allreduce_impl(const void* const* send, void* const* recv, const void* const
                                          : hb_2phase_kernel(dtype, U, n);
     // very large messages: the same sums in chip-wide read and write phases, one workgroup per CU (as many
     // as are resident; an explicit hb_blocks_per_rank still counts)
-    if (algo == MSX_ALGO_2PA_HB && use_phased(nbytes, n, res_mode, true)) {
+    if (algo == MSX_ALGO_2PA_HB && use_phased(nbytes, n, res_mode, kPhasedAllReduce)) {
         k = phased_reduce_kernel(dtype == MSX_F32, n, res_mode, 0);
         U = kPhasedHeld;
         want = g_opt.hb_blocks > 0 ? g_opt.hb_blocks : kMaxChannels;
@@ -1243,7 +1250,7 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     }
     // large blocks, 8 ranks: chip-wide read and write phases, one workgroup per CU (see k_allreduce_hb_phased)
     const size_t row_bytes = (which == kRS ? count_or_bytes * elem_size(dtype) : count_or_bytes) * (size_t)n;
-    if ((which == kRS || which == kAG) && vec && use_phased(row_bytes, n, 0)) {
+    if ((which == kRS || which == kAG) && vec && use_phased(row_bytes, n, 0, which == kAG ? kPhasedAllGather : kPhasedOther)) {
         HbKernel pk = which == kRS ? phased_reduce_kernel(dtype == MSX_F32, n, 0, 1) : phased_allgather_kernel(n);
         int pch = 1;
         if ((rc = pick_channels(c, (const void*)pk, threads, n, work_units, kPhasedHeld,
@@ -1266,7 +1273,10 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     // mid sizes are latency bound: 64 KiB rows 4.8 -> 4.2 us reduce-scatter, 7.9 -> 5.4 us all-gather); for
     // large inputs the read-heavy reduce-scatter runs best with few workgroups per rank (32; 64 up to
     // 64 MiB blocks), the write-heavy copies with many
-    const int cap = which == kRS ? (work_units <= ((size_t)4 << 20) ? 64 : 32) : 128;
+    // (the sweeps were run with 8 ranks; what counts is the total over the chip, so fewer ranks get more each:
+    // with the per-rank figures of 8 ranks a 2-rank reduce-scatter ran on 64 workgroups, at 1.2 TB/s)
+    const int total = which == kRS ? (work_units <= ((size_t)4 << 20) ? 512 : 256) : 1024;
+    const int cap = std::min(kMaxChannels, std::max(1, total / n));
     int chans = 1;
     if ((rc = pick_channels(c, kp, threads, n, work_units, 1, g_opt.hb_blocks, cap, &chans))) return rc;
     HbArgs a{};
