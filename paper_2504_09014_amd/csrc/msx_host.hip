@@ -503,6 +503,9 @@ int resident_blocks(Ctx* c, const void* k, int threads, int* out)
 }
 
 // channels (workgroups per rank) for `work` items per rank handled `per_thread` at a time
+// A cap on workgroups per rank that was found with 8 ranks, as a total over the chip shared out over n ranks.
+int per_rank_cap(int total, int n) { return std::min(kMaxChannels, std::max(1, total / std::max(1, n))); }
+
 int pick_channels(Ctx* c, const void* k, int threads, int n, size_t work, size_t per_thread, int want,
                   int cap, int* chans)
 {
@@ -991,7 +994,7 @@ int reduce_generic(Ctx* c, const void* const* in, void* const* out, size_t count
     const size_t per_rank = mode == 0 ? (vecs + (size_t)n - 1) / (size_t)n
                             : mode == 2 ? (count + (size_t)n - 1) / (size_t)n : (vec ? vecs : count);
     int chans = 1, rc;
-    if ((rc = pick_channels(c, (const void*)k, 256, n, per_rank, 1, g_opt.hb_blocks, 128, &chans))) return rc;
+    if ((rc = pick_channels(c, (const void*)k, 256, n, per_rank, 1, g_opt.hb_blocks, per_rank_cap(1024, n), &chans))) return rc;
     HbArgs a{};
     for (int i = 0; i < n; ++i) {
         a.in[i] = in[i];
@@ -1276,7 +1279,7 @@ int hb_other(HbOther which, const void* const* in, void* const* out, size_t coun
     // (the sweeps were run with 8 ranks; what counts is the total over the chip, so fewer ranks get more each:
     // with the per-rank figures of 8 ranks a 2-rank reduce-scatter ran on 64 workgroups, at 1.2 TB/s)
     const int total = which == kRS ? (work_units <= ((size_t)4 << 20) ? 512 : 256) : 1024;
-    const int cap = std::min(kMaxChannels, std::max(1, total / n));
+    const int cap = per_rank_cap(total, n);
     int chans = 1;
     if ((rc = pick_channels(c, kp, threads, n, work_units, 1, g_opt.hb_blocks, cap, &chans))) return rc;
     HbArgs a{};
@@ -1402,7 +1405,7 @@ int moe_dispatch_impl(const void* const* tokens, const int32_t* const* topk_idx,
 
     int chans = 1;
     // one wave per token row, 4 waves per workgroup, a few rows per wave
-    if ((rc = pick_channels(c, (const void*)k_moe_pack, 256, n, (size_t)T * 64, 4, g_opt.hb_blocks, 128, &chans)))
+    if ((rc = pick_channels(c, (const void*)k_moe_pack, 256, n, (size_t)T * 64, 4, g_opt.hb_blocks, per_rank_cap(1024, n), &chans)))
         return rc;
     a.chans = chans;
     plan->T = T;
@@ -1694,7 +1697,7 @@ int msx_moe_combine(const void* const* expert_out, void* const* out_tokens, int 
     int chans = 1;
     // read-heavy like the reduce-scatter: 32 workgroups per rank beat more (measured at 8 x 4096 rows of 7168:
     // 0.56 ms against 0.585 ms with 128)
-    if ((rc = pick_channels(c, kp, 256, n, (size_t)T * 64, 4, g_opt.hb_blocks, 32, &chans))) return rc;
+    if ((rc = pick_channels(c, kp, 256, n, (size_t)T * 64, 4, g_opt.hb_blocks, per_rank_cap(256, n), &chans))) return rc;
     a.chans = chans;
     note_launch(n * chans, 256, MSX_ALGO_2PA_HB);
     typedef void (*K)(MoeArgs, DevCtx);
