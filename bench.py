@@ -234,6 +234,27 @@ def run_extras(torch, msx, synth, n, port=True):
         return res
     leg("allreduce_256MiB_by_rank_count", rank_counts)
 
+    # ---- ReduceScatter / AllGather with other rank counts (256 MiB rows), automatic choice
+    def rs_ag_rank_counts():
+        res = {}
+        for nr in (2, 4, 6, 8):
+            c = (128 << 20) // (nr * 64) * (nr * 64)
+            full = synth.normal(nr, c, seed=90 + nr, device="cuda")
+            rows_ = [full[r] for r in range(nr)]
+            part = [torch.empty(c // nr, dtype=torch.bfloat16, device="cuda") for _ in range(nr)]
+            full2 = [torch.empty(c, dtype=torch.bfloat16, device="cuda") for _ in range(nr)]
+            row = {}
+            for name, fn in [("reducescatter", lambda: msx.reducescatter_ex(rows_, part)),
+                             ("allgather", lambda: msx.allgather_ex(part, full2))]:
+                ms = median(time_calls(torch, fn, 8, 6)[1]) / 1e3
+                moved = nr * c * 2 + c * 2
+                row[name] = {"ms": round(ms, 4), "GBps": round(moved / ms / 1e6, 1), "grid": msx.last_launch()[0]}
+            res[f"n{nr}"] = row
+            del full, rows_, part, full2
+            torch.cuda.empty_cache()
+        return res
+    leg("reducescatter_allgather_256MiB_rows_by_rank_count", rs_ag_rank_counts)
+
     # ---- rings: thread-copy hand-offs (MemoryChannel) and hand-offs through the port (FIFO, proxy
     # thread, runtime copies), next to the all-pairs form
     def rings():
