@@ -589,7 +589,7 @@ def main():
             traffic = None
 
     out = {
-        "metric": "emulated 8-rank AllReduce GB/s (% HBM roofline) + small-msg latency us",
+        "metric": "emulated 8-rank AllReduce GB/s (% HBM roofline) + small-msg latency \u00b5s",
         "value": round(value, 1),
         "unit": "GB/s",
         "n_gpus": 1,
