@@ -4,6 +4,7 @@ by a small sequential simulator over numpy buffers (one float per 16-byte vector
 scheduler that advances workgroups until they block, so the test also shows that the plan cannot
 deadlock and that every wait is matched by exactly one signal."""
 import ctypes as C
+import os
 
 import numpy as np
 import pytest
@@ -402,3 +403,24 @@ def test_owner_of_an_expert_by_multiplication_equals_the_division(L):
             assert np.array_equal((e * np.uint64(m.value)) >> np.uint64(32), e // np.uint64(per)), (nranks, per)
     m = C.c_uint32(0)
     assert L.msx_debug_owner_magic(10, 3, C.byref(m)) == -1
+
+
+def test_bench_refuses_more_than_one_gpu_and_names_the_reason():
+    """The ranks are emulated inside one GPU: `bench.py --gpus N` with N above 1 must exit with a message that
+    says so, before anything touches a device."""
+    import subprocess
+    import sys as _sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([_sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bench_metric_is_the_baseline_metric():
+    import json
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = open(os.path.join(root, "bench.py")).read()
+    m = re.search(r'"metric": ("[^\n]*?"),', src)
+    assert m and json.loads(m.group(1)) == json.load(open(os.path.join(root, "BASELINE.json")))["metric"]
